@@ -1,0 +1,135 @@
+/*
+ * pilc.h -- C ABI of libpilc: the entropy-coding stage of PILC (arXiv 2206.05279)
+ * for AMD MI355X (gfx950).
+ *
+ * The stage turns uint8 subpixels plus per-subpixel distribution parameters into a
+ * bitstream and back (Sec. 3.1 "Compress"/"Decompress": the coder receives the symbols
+ * and the predicted logistic parameters; the decoder regenerates the same parameters and
+ * recovers the symbols losslessly).
+ *
+ * Conventions for every entry point
+ *   - All `*_dev` pointers and the pointers inside pilc_params are DEVICE memory owned by
+ *     the caller; pilc_geom, pilc_params and `*_host` pointers are HOST memory.
+ *   - The library never allocates or frees device memory on behalf of a call: images,
+ *     parameters, workspace and output are caller-owned.  (Three small constant tables
+ *     live in the library's own device globals and are filled on first use per device.)
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default
+ *     stream).  Every call synchronises that stream before it returns, so the status and
+ *     all outputs are final on return.
+ *   - Return value: 0 on success, a negative PILC_E_* code otherwise.  No exceptions, no
+ *     global mutable state besides the constant tables; calls on different streams may run
+ *     concurrently if they use different workspaces.
+ *   - Tensors are dense, row-major, channel-interleaved: index ((i*h + y)*w + x)*3 + c.
+ */
+#ifndef PILC_H
+#define PILC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PILC_VERSION 1u
+
+enum {
+    PILC_OK = 0,
+    PILC_E_ARG = -1,       /* null / misaligned pointer, bad geometry                      */
+    PILC_E_WORKSPACE = -2, /* workspace smaller than pilc_workspace_size reports            */
+    PILC_E_CAPACITY = -3,  /* coded output does not fit coded_capacity (nothing usable out) */
+    PILC_E_TOO_LARGE = -4, /* payload would reach 4 GiB (32-bit lane offsets)               */
+    PILC_E_FORMAT = -5,    /* decode: bad magic / version / geometry mismatch / size        */
+    PILC_E_CORRUPT = -6,   /* decode: offsets not monotone or out of bounds, a lane runs
+                              past its end, or does not return to its initial state         */
+    PILC_E_HIP = -7        /* HIP runtime failure (see pilc_last_hip_error)                 */
+};
+
+/* Geometry of a batch.  M = prec_bits is the constant of Sec. 3.2 for which every
+ * symbol's integer masses sum to 2^M (the paper uses 10..15 for 8-bit data; 16 is also
+ * accepted here).  A "lane" is one independent rANS stream:
+ *   lane_mode 0: lane j codes the flat pixel range [j*lane_a, min((j+1)*lane_a, n*h*w));
+ *                lane_a must divide h*w or be a multiple of it.
+ *   lane_mode 1: lane j codes one tile of lane_a rows x lane_b columns; tiles are numbered
+ *                row-major inside an image, images in order; edge tiles are clipped.
+ * Inside a lane the decode order is raster order of its pixels, R,G,B inside a pixel. */
+typedef struct {
+    uint32_t n, h, w;   /* images, rows, columns; 3 interleaved channels */
+    uint32_t prec_bits; /* M, 10..16 */
+    uint32_t lane_mode; /* 0 or 1 */
+    uint32_t lane_a, lane_b;
+} pilc_geom;
+
+/* Per-subpixel logistic parameters (Sec. 3.1 eq. (7), Sec. 3.3) in fixed point, plus the
+ * per-image coefficients that condition G on R and B on R,G of the same pixel (Sec. 3.1
+ * eqs. (3)-(4), applied as  mu'_G = mu_G + a_GR*(x_R-mu_R),
+ * mu'_B = mu_B + a_BR*(x_R-mu_R) + a_BG*(x_G-mu_G), each product rounded to Q8.8). */
+typedef struct {
+    const uint16_t *mu;        /* device [n,h,w,3]  Q8.8 unsigned                          */
+    const int16_t *log_scale;  /* device [n,h,w,3]  Q4.12, natural log of the scale;
+                                  values outside [-4, 6) act as the nearest bound         */
+    const int16_t *chan_coef;  /* device [n,3]      Q2.14: a_GR, a_BR, a_BG                */
+} pilc_params;
+
+/* Number of lanes of a geometry (Sec. 3.2's independent coder instances, "one thread per
+ * piece" in Sec. 4.3); 0 if the geometry is invalid. */
+uint64_t pilc_lane_count(const pilc_geom *geom);
+
+/* Sizes a caller must provide: bytes of device workspace for encode and decode of this
+ * geometry, and an upper bound of the container size (64-byte header + 4*(lanes+1) offset
+ * table + per lane 4 bytes of state + at most one 16-bit word per symbol).
+ * Errors: PILC_E_ARG. */
+int pilc_workspace_size(const pilc_geom *geom, size_t *workspace_bytes_host,
+                        size_t *max_coded_bytes_host);
+
+/* Compress (Sec. 3.1 "Compress", coder part; Sec. 3.2 tables; App. A eq. (11) per symbol).
+ *   img_dev        uint8 [n,h,w,3]
+ *   params         see pilc_params
+ *   workspace_dev  >= workspace_bytes from pilc_workspace_size, 256-byte aligned; contents
+ *                  are scratch, undefined afterwards
+ *   coded_dev      output container, 16-byte aligned, capacity coded_capacity bytes
+ *   coded_bytes_host  receives the container size
+ * Container (little endian): 64-byte header {"PILC", version, n, h, w, 3, M, lane_mode,
+ * lane_a, lane_b, lanes, 0, payload_bytes u64, 0 u64}; u32 offsets[lanes+1] (exclusive
+ * prefix sum of lane byte counts, relative to the payload); payload = for each lane its
+ * final 32-bit state followed by its 16-bit words in the order the decoder reads them.
+ * Errors: PILC_E_ARG, PILC_E_WORKSPACE, PILC_E_CAPACITY (coded_dev contents undefined),
+ * PILC_E_TOO_LARGE, PILC_E_HIP. */
+int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params *params,
+                void *workspace_dev, size_t workspace_bytes, uint8_t *coded_dev,
+                size_t coded_capacity, uint64_t *coded_bytes_host, void *hip_stream);
+
+/* Decompress (Sec. 3.1 "Decompress", coder part; App. A eq. (12) per symbol, the symbol
+ * being the x with C_x <= S mod 2^M < C_x + P_x).  The geometry and parameters must be the
+ * ones used to encode.  img_out_dev uint8 [n,h,w,3]; on error its contents are undefined.
+ * Errors: PILC_E_ARG, PILC_E_WORKSPACE, PILC_E_FORMAT, PILC_E_CORRUPT, PILC_E_HIP. */
+int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_bytes,
+                const pilc_params *params, void *workspace_dev, size_t workspace_bytes,
+                uint8_t *img_out_dev, void *hip_stream);
+
+/* The integer tables of Sec. 3.2 for the symbols actually present: for every subpixel (image
+ * layout [n,h,w,3]) its cumulative count C_x and mass P_x (sum_x P_x = 2^M, P_x >= 1).
+ * cum_out_dev, freq_out_dev: device uint32 [n,h,w,3].  A verification entry point: encode
+ * computes the same values on the fly and never materialises them.
+ * Errors: PILC_E_ARG, PILC_E_HIP. */
+int pilc_symbol_tables(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params *params,
+                       uint32_t *cum_out_dev, uint32_t *freq_out_dev, void *hip_stream);
+
+/* Per-kernel timing, off by default.  When enabled, pilc_encode / pilc_decode bracket each
+ * kernel with HIP events on the stream the kernel is launched on.  pilc_last_timing returns
+ * the durations in milliseconds of the most recent call on the calling thread: index 0 is
+ * the whole GPU part of the call, 1.. are its kernels in launch order (pilc_timing_name
+ * gives their names).  Returns the number of entries written (<= capacity), 0 if timing
+ * was off. */
+void pilc_set_timing(int enabled);
+int pilc_last_timing(float *ms_out_host, int capacity);
+const char *pilc_timing_name(int index_in_last_call);
+
+const char *pilc_strerror(int code);
+const char *pilc_last_hip_error(void); /* text of the last HIP failure on this thread */
+uint32_t pilc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

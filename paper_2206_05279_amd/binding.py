@@ -1,0 +1,176 @@
+"""Thin Python binding of libpilc's C ABI: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; PyTorch supplies device
+memory and streams.  There is no CPU fallback: if the library has not been built, or
+no GPU is present, the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpilc.so")
+
+PILC_OK = 0
+PILC_E_ARG = -1
+PILC_E_WORKSPACE = -2
+PILC_E_CAPACITY = -3
+PILC_E_TOO_LARGE = -4
+PILC_E_FORMAT = -5
+PILC_E_CORRUPT = -6
+PILC_E_HIP = -7
+
+EXPORTS = [
+    "pilc_lane_count", "pilc_workspace_size", "pilc_encode", "pilc_decode", "pilc_symbol_tables",
+    "pilc_set_timing", "pilc_last_timing", "pilc_timing_name", "pilc_strerror",
+    "pilc_last_hip_error", "pilc_version",
+]
+
+
+class pilc_geom(C.Structure):
+    _fields_ = [("n", C.c_uint32), ("h", C.c_uint32), ("w", C.c_uint32), ("prec_bits", C.c_uint32),
+                ("lane_mode", C.c_uint32), ("lane_a", C.c_uint32), ("lane_b", C.c_uint32)]
+
+
+class pilc_params(C.Structure):
+    _fields_ = [("mu", C.c_void_p), ("log_scale", C.c_void_p), ("chan_coef", C.c_void_p)]
+
+
+class PilcError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = lib().pilc_strerror(code).decode()
+        if code == PILC_E_HIP:
+            msg += ": " + lib().pilc_last_hip_error().decode()
+        super().__init__("%s failed: %s (%d)" % (where, msg, code))
+
+
+_lib = None
+
+
+def lib():
+    """Loads libpilc.so (building it first only if no built library exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from . import build
+            build.build_lib()
+        L = C.CDLL(LIB_PATH)
+        gp, pp = C.POINTER(pilc_geom), C.POINTER(pilc_params)
+        L.pilc_lane_count.restype = C.c_uint64
+        L.pilc_lane_count.argtypes = [gp]
+        L.pilc_workspace_size.restype = C.c_int
+        L.pilc_workspace_size.argtypes = [gp, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        L.pilc_encode.restype = C.c_int
+        L.pilc_encode.argtypes = [gp, C.c_void_p, pp, C.c_void_p, C.c_size_t, C.c_void_p,
+                                  C.c_size_t, C.POINTER(C.c_uint64), C.c_void_p]
+        L.pilc_decode.restype = C.c_int
+        L.pilc_decode.argtypes = [gp, C.c_void_p, C.c_size_t, pp, C.c_void_p, C.c_size_t,
+                                  C.c_void_p, C.c_void_p]
+        L.pilc_symbol_tables.restype = C.c_int
+        L.pilc_symbol_tables.argtypes = [gp, C.c_void_p, pp, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.pilc_set_timing.restype = None
+        L.pilc_set_timing.argtypes = [C.c_int]
+        L.pilc_last_timing.restype = C.c_int
+        L.pilc_last_timing.argtypes = [C.POINTER(C.c_float), C.c_int]
+        L.pilc_timing_name.restype = C.c_char_p
+        L.pilc_timing_name.argtypes = [C.c_int]
+        L.pilc_strerror.restype = C.c_char_p
+        L.pilc_strerror.argtypes = [C.c_int]
+        L.pilc_last_hip_error.restype = C.c_char_p
+        L.pilc_version.restype = C.c_uint32
+        _lib = L
+    return _lib
+
+
+def make_geom(n, h, w, prec_bits, lane_mode, lane_a, lane_b=0) -> pilc_geom:
+    return pilc_geom(int(n), int(h), int(w), int(prec_bits), int(lane_mode), int(lane_a), int(lane_b))
+
+
+def _dev_ptr(t: Optional[torch.Tensor], dtype, what: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError("%s must be a contiguous %s device tensor" % (what, dtype))
+    return t.data_ptr()
+
+
+def _params(mu, log_scale, chan_coef) -> pilc_params:
+    return pilc_params(_dev_ptr(mu, torch.uint16, "mu"), _dev_ptr(log_scale, torch.int16, "log_scale"),
+                       _dev_ptr(chan_coef, torch.int16, "chan_coef"))
+
+
+def _stream_handle(stream: Optional[torch.cuda.Stream]) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def pilc_lane_count(geom: pilc_geom) -> int:
+    return int(lib().pilc_lane_count(C.byref(geom)))
+
+
+def pilc_workspace_size(geom: pilc_geom) -> Tuple[int, int]:
+    """Returns (workspace_bytes, max_coded_bytes)."""
+    ws, mc = C.c_size_t(0), C.c_size_t(0)
+    rc = lib().pilc_workspace_size(C.byref(geom), C.byref(ws), C.byref(mc))
+    if rc != PILC_OK:
+        raise PilcError(rc, "pilc_workspace_size")
+    return int(ws.value), int(mc.value)
+
+
+def pilc_encode(geom: pilc_geom, img, mu, log_scale, chan_coef, workspace, coded,
+                stream: Optional[torch.cuda.Stream] = None, check: bool = True) -> Tuple[int, int]:
+    """Runs pilc_encode; returns (rc, coded_bytes).  workspace / coded are uint8 device tensors."""
+    nbytes = C.c_uint64(0)
+    par = _params(mu, log_scale, chan_coef)
+    rc = lib().pilc_encode(C.byref(geom), _dev_ptr(img, torch.uint8, "img"), C.byref(par),
+                           _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+                           _dev_ptr(coded, torch.uint8, "coded"), coded.numel(), C.byref(nbytes),
+                           _stream_handle(stream))
+    if check and rc != PILC_OK:
+        raise PilcError(rc, "pilc_encode")
+    return rc, int(nbytes.value)
+
+
+def pilc_decode(geom: pilc_geom, coded, coded_bytes: int, mu, log_scale, chan_coef, workspace,
+                img_out, stream: Optional[torch.cuda.Stream] = None, check: bool = True) -> int:
+    par = _params(mu, log_scale, chan_coef)
+    rc = lib().pilc_decode(C.byref(geom), _dev_ptr(coded, torch.uint8, "coded"), int(coded_bytes),
+                           C.byref(par), _dev_ptr(workspace, torch.uint8, "workspace"),
+                           workspace.numel(), _dev_ptr(img_out, torch.uint8, "img_out"),
+                           _stream_handle(stream))
+    if check and rc != PILC_OK:
+        raise PilcError(rc, "pilc_decode")
+    return rc
+
+
+def pilc_symbol_tables(geom: pilc_geom, img, mu, log_scale, chan_coef, cum_out, freq_out,
+                       stream: Optional[torch.cuda.Stream] = None) -> None:
+    par = _params(mu, log_scale, chan_coef)
+    rc = lib().pilc_symbol_tables(C.byref(geom), _dev_ptr(img, torch.uint8, "img"), C.byref(par),
+                                  _dev_ptr(cum_out, torch.uint32, "cum_out"),
+                                  _dev_ptr(freq_out, torch.uint32, "freq_out"), _stream_handle(stream))
+    if rc != PILC_OK:
+        raise PilcError(rc, "pilc_symbol_tables")
+
+
+def pilc_set_timing(enabled: bool) -> None:
+    lib().pilc_set_timing(1 if enabled else 0)
+
+
+def pilc_last_timing() -> List[Tuple[str, float]]:
+    buf = (C.c_float * 16)()
+    k = lib().pilc_last_timing(buf, 16)
+    return [(lib().pilc_timing_name(i).decode(), float(buf[i])) for i in range(k)]
+
+
+def pilc_strerror(code: int) -> str:
+    return lib().pilc_strerror(int(code)).decode()
+
+
+def pilc_version() -> int:
+    return int(lib().pilc_version())

@@ -1,0 +1,770 @@
+// libpilc: kernels and C ABI of the PILC entropy-coding stage for gfx950 (arXiv 2206.05279).
+//
+// Path per call
+//   encode: lane kernel (mean shift -> (cum,freq) -> rANS, words to per-lane scratch slots)
+//           -> 3-step prefix scan of lane byte counts (offset table + header)
+//           -> pack (lane streams copied to their offsets)
+//   decode: header check -> lane kernel (search of the symbol, state update, refill)
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+
+#include "../../include/pilc.h"
+#include "pilc_device.hpp"
+
+namespace pilc {
+
+__device__ uint2 g_sig_cell[kSigEntries];
+__device__ uint32_t g_exp_hi[kExpHiEntries];
+__device__ uint32_t g_exp_lo[kExpLoEntries];
+
+constexpr uint32_t kHeaderBytes = 64;
+constexpr uint32_t kRansLow = 1u << 16;
+
+// status word kinds (device side), mapped to PILC_E_* on the host
+enum : int { ST_OK = 0, ST_TOO_LARGE = 4, ST_FORMAT = 5, ST_CORRUPT = 6, ST_CAPACITY = 3 };
+
+struct Status {
+    int code;
+    int pad;
+    unsigned long long payload_bytes;
+};
+
+// --------------------------------------------------------------------------------------------
+// Per-pixel helper: effective means of the three channels (Sec. 3.1 eqs. (3)-(4), innovation
+// form).  e_G uses the unshifted mu_G so the three means are independent of each other.
+// --------------------------------------------------------------------------------------------
+__device__ __forceinline__ void mean_shift(const int x[3], const int m[3], int a_gr, int a_br,
+                                           int a_bg, int out[3])
+{
+    int e_r = x[0] * 256 - m[0];
+    int e_g = x[1] * 256 - m[1];
+    out[0] = m[0];
+    out[1] = m[1] + rsh14(a_gr * e_r);
+    out[2] = m[2] + rsh14(a_br * e_r) + rsh14(a_bg * e_g);
+}
+
+// --------------------------------------------------------------------------------------------
+// pilc_symbol_tables: one thread per pixel.
+// --------------------------------------------------------------------------------------------
+__global__ void k_symbol_tables(Geo g, const uint8_t *__restrict__ img,
+                                const uint16_t *__restrict__ mu, const int16_t *__restrict__ ls,
+                                const int16_t *__restrict__ coef, uint32_t *__restrict__ cum_out,
+                                uint32_t *__restrict__ freq_out)
+{
+    __shared__ LdsTables tab;
+    load_tables(tab);
+    uint32_t p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= g.total_px) return;
+    size_t s = (size_t)p * 3;
+    uint32_t im = p / g.hw;
+    int x[3] = {img[s], img[s + 1], img[s + 2]};
+    int m[3] = {mu[s], mu[s + 1], mu[s + 2]};
+    int me[3];
+    mean_shift(x, m, coef[3 * im], coef[3 * im + 1], coef[3 * im + 2], me);
+    for (int c = 0; c < 3; ++c) {
+        uint32_t inv_s = inv_scale(ls[s + c], tab);
+        uint32_t lo = cum_at(x[c], me[c], inv_s, g.prec_bits, tab);
+        uint32_t hi = cum_at(x[c] + 1, me[c], inv_s, g.prec_bits, tab);
+        cum_out[s + c] = lo;
+        freq_out[s + c] = hi - lo;
+    }
+}
+
+// --------------------------------------------------------------------------------------------
+// Encode, one thread per lane.  Symbols are pushed last-first (App. A eq. (11)); the 16-bit
+// words go to the lane's scratch slot from its end downwards, so that they finish in the
+// order the decoder reads them.
+// --------------------------------------------------------------------------------------------
+__global__ void k_encode_lanes(Geo g, const uint8_t *__restrict__ img,
+                               const uint16_t *__restrict__ mu, const int16_t *__restrict__ ls,
+                               const int16_t *__restrict__ coef, uint16_t *__restrict__ scratch,
+                               uint32_t *__restrict__ lane_words, uint32_t *__restrict__ lane_state)
+{
+    __shared__ LdsTables tab;
+    load_tables(tab);
+    uint32_t lane = blockIdx.x * blockDim.x + threadIdx.x;
+    if (lane >= g.lanes) return;
+    const LaneShape sh = lane_shape(g, lane);
+    const uint32_t m_bits = g.prec_bits;
+    const uint32_t spread = (1u << m_bits) - 256u;
+
+    // last pixel of the lane
+    uint32_t rows = sh.npx / sh.tw;
+    uint32_t col = sh.tw - 1;
+    uint32_t p = sh.first + (rows - 1) * g.w + col;
+    uint32_t im = p / g.hw;
+    uint32_t left_in_img = p - im * g.hw;  // pixels before p inside its image
+    int a_gr = coef[3 * im], a_br = coef[3 * im + 1], a_bg = coef[3 * im + 2];
+
+    uint16_t *wp = scratch + (size_t)sh.sym_base + 3u * sh.npx;  // one past the slot end
+    uint32_t nwords = 0;
+    uint32_t S = kRansLow;
+
+    for (uint32_t t = 0; t < sh.npx; ++t) {
+        size_t s = (size_t)p * 3;
+        int x[3] = {img[s], img[s + 1], img[s + 2]};
+        int m[3] = {mu[s], mu[s + 1], mu[s + 2]};
+        int me[3];
+        mean_shift(x, m, a_gr, a_br, a_bg, me);
+#pragma unroll
+        for (int c = 2; c >= 0; --c) {
+            uint32_t inv_s = inv_scale(ls[s + c], tab);
+            uint32_t lo = x[c] == 0 ? 0u : cum_inner(x[c], me[c], inv_s, spread, tab);
+            uint32_t hi = x[c] == 255 ? (1u << m_bits) : cum_inner(x[c] + 1, me[c], inv_s, spread, tab);
+            uint32_t f = hi - lo;
+            if (S >= (f << (32 - m_bits))) {
+                *--wp = (uint16_t)(S & 0xFFFFu);
+                ++nwords;
+                S >>= 16;
+            }
+            uint32_t q = S / f;
+            S = (q << m_bits) + (S - q * f) + lo;
+        }
+        // step to the previous pixel of the lane
+        if (col == 0) {
+            col = sh.tw - 1;
+            p -= g.w - sh.tw + 1;
+            // (only tile lanes have several rows, and a tile never leaves its image)
+            left_in_img -= g.w - sh.tw + 1;
+        } else {
+            --col;
+            --p;
+            if (left_in_img == 0) {
+                if (t + 1 < sh.npx) {
+                    --im;
+                    left_in_img = g.hw - 1;
+                    a_gr = coef[3 * im];
+                    a_br = coef[3 * im + 1];
+                    a_bg = coef[3 * im + 2];
+                }
+            } else {
+                --left_in_img;
+            }
+        }
+    }
+    lane_words[lane] = nwords;
+    lane_state[lane] = S;
+}
+
+// --------------------------------------------------------------------------------------------
+// Prefix scan of lane byte counts (4 + 2*words) into the container's offset table.
+// --------------------------------------------------------------------------------------------
+constexpr int kScanThreads = 256;
+constexpr int kScanItems = 4;
+constexpr int kScanTile = kScanThreads * kScanItems;
+
+__device__ __forceinline__ unsigned long long block_exclusive_scan(unsigned long long v,
+                                                                   unsigned long long *total)
+{
+    __shared__ unsigned long long wave_sum[kScanThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned long long inc = v;
+    for (int d = 1; d < 64; d <<= 1) {
+        unsigned long long o = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += o;
+    }
+    if (lane == 63) wave_sum[wave] = inc;
+    __syncthreads();
+    unsigned long long base = 0, all = 0;
+    for (int i = 0; i < kScanThreads / 64; ++i) {
+        if (i < wave) base += wave_sum[i];
+        all += wave_sum[i];
+    }
+    __syncthreads();
+    *total = all;
+    return base + inc - v;
+}
+
+__global__ void k_scan_partials(uint32_t lanes, const uint32_t *__restrict__ lane_words,
+                                unsigned long long *__restrict__ block_sums)
+{
+    uint32_t base = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
+    unsigned long long v = 0;
+    for (int i = 0; i < kScanItems; ++i)
+        if (base + i < lanes) v += 4ull + 2ull * lane_words[base + i];
+    unsigned long long total;
+    block_exclusive_scan(v, &total);
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
+}
+
+// Single workgroup: exclusive scan of the block sums in place; writes the header.
+__global__ void k_scan_spine(Geo g, uint32_t nblocks, unsigned long long *__restrict__ block_sums,
+                             uint8_t *__restrict__ coded, unsigned long long coded_capacity,
+                             Status *__restrict__ status)
+{
+    unsigned long long carry = 0;
+    for (uint32_t b0 = 0; b0 < nblocks; b0 += kScanThreads) {
+        uint32_t i = b0 + threadIdx.x;
+        unsigned long long v = i < nblocks ? block_sums[i] : 0ull, total;
+        unsigned long long ex = block_exclusive_scan(v, &total);
+        if (i < nblocks) block_sums[i] = carry + ex;
+        carry += total;
+    }
+    if (threadIdx.x == 0) {
+        status->payload_bytes = carry;
+        unsigned long long need = kHeaderBytes + 4ull * ((unsigned long long)g.lanes + 1ull) + carry;
+        if (carry >= (1ull << 32))
+            status->code = ST_TOO_LARGE;
+        else if (need > coded_capacity)
+            status->code = ST_CAPACITY;
+        uint32_t *h = reinterpret_cast<uint32_t *>(coded);
+        h[0] = 0x434C4950u;  // "PILC"
+        h[1] = PILC_VERSION;
+        h[2] = g.n;
+        h[3] = g.h;
+        h[4] = g.w;
+        h[5] = 3u;
+        h[6] = g.prec_bits;
+        h[7] = g.lane_mode;
+        h[8] = g.lane_a;
+        h[9] = g.lane_b;
+        h[10] = g.lanes;
+        h[11] = 0u;
+        h[12] = (uint32_t)carry;
+        h[13] = (uint32_t)(carry >> 32);
+        h[14] = 0u;
+        h[15] = 0u;
+    }
+}
+
+__global__ void k_scan_apply(uint32_t lanes, const uint32_t *__restrict__ lane_words,
+                             const unsigned long long *__restrict__ block_sums,
+                             uint32_t *__restrict__ offsets)
+{
+    uint32_t base = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
+    unsigned long long item[kScanItems], v = 0;
+    for (int i = 0; i < kScanItems; ++i) {
+        item[i] = base + i < lanes ? 4ull + 2ull * lane_words[base + i] : 0ull;
+        v += item[i];
+    }
+    unsigned long long total;
+    unsigned long long ex = block_exclusive_scan(v, &total) + block_sums[blockIdx.x];
+    for (int i = 0; i < kScanItems; ++i) {
+        if (base + i < lanes) offsets[base + i] = (uint32_t)ex;
+        ex += item[i];
+        // the closing entry offsets[lanes] = payload size
+        if (base + i + 1 == lanes) offsets[lanes] = (uint32_t)ex;
+    }
+}
+
+// --------------------------------------------------------------------------------------------
+// Pack: every workgroup fills a fixed range of payload words; each word finds its lane by a
+// search in the offset table, then reads the lane's state or scratch slot.
+// --------------------------------------------------------------------------------------------
+constexpr uint32_t kPackWords = 8192;
+
+__device__ __forceinline__ uint32_t find_lane(const uint32_t *offsets, uint32_t lo, uint32_t hi,
+                                              uint32_t byte)
+{
+    // largest l in [lo, hi] with offsets[l] <= byte
+    while (lo < hi) {
+        uint32_t mid = lo + (hi - lo + 1) / 2;
+        if (offsets[mid] <= byte)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    return lo;
+}
+
+__global__ void k_pack(Geo g, const uint16_t *__restrict__ scratch,
+                       const uint32_t *__restrict__ lane_state, const uint32_t *__restrict__ offsets,
+                       uint16_t *__restrict__ payload, const Status *__restrict__ status)
+{
+    if (status->code != ST_OK) return;
+    const unsigned long long total_words = status->payload_bytes >> 1;
+    const unsigned long long w0 = (unsigned long long)blockIdx.x * kPackWords;
+    if (w0 >= total_words) return;
+    const uint32_t w1 = (uint32_t)min(w0 + kPackWords, total_words);
+    __shared__ uint32_t s_lo, s_hi;
+    if (threadIdx.x == 0) {
+        s_lo = find_lane(offsets, 0, g.lanes - 1, (uint32_t)w0 * 2u);
+        s_hi = find_lane(offsets, s_lo, g.lanes - 1, (w1 - 1) * 2u);
+    }
+    __syncthreads();
+    const uint32_t lo = s_lo, hi = s_hi;
+    for (uint32_t wi = (uint32_t)w0 + threadIdx.x; wi < w1; wi += blockDim.x) {
+        uint32_t byte = wi * 2u;
+        uint32_t lane = find_lane(offsets, lo, hi, byte);
+        uint32_t begin = offsets[lane];
+        uint32_t local = byte - begin;
+        uint16_t v;
+        if (local < 4u) {
+            v = (uint16_t)(lane_state[lane] >> (8u * local));
+        } else {
+            uint32_t nwords = (offsets[lane + 1] - begin - 4u) >> 1;
+            LaneShape sh = lane_shape(g, lane);
+            size_t slot_end = (size_t)sh.sym_base + 3u * sh.npx;
+            v = scratch[slot_end - nwords + ((local - 4u) >> 1)];
+        }
+        payload[wi] = v;
+    }
+}
+
+// --------------------------------------------------------------------------------------------
+// Decode.
+// --------------------------------------------------------------------------------------------
+__global__ void k_init_status(Status *status)
+{
+    status->code = ST_OK;
+    status->pad = 0;
+    status->payload_bytes = 0;
+}
+
+__global__ void k_check_header(Geo g, const uint8_t *__restrict__ coded,
+                               unsigned long long coded_bytes, Status *__restrict__ status)
+{
+    const uint32_t *h = reinterpret_cast<const uint32_t *>(coded);
+    int st = ST_OK;
+    unsigned long long payload = (unsigned long long)h[12] | ((unsigned long long)h[13] << 32);
+    if (h[0] != 0x434C4950u || h[1] != PILC_VERSION) st = ST_FORMAT;
+    if (h[2] != g.n || h[3] != g.h || h[4] != g.w || h[5] != 3u || h[6] != g.prec_bits ||
+        h[7] != g.lane_mode || h[8] != g.lane_a || h[9] != g.lane_b || h[10] != g.lanes)
+        st = ST_FORMAT;
+    if (coded_bytes != kHeaderBytes + 4ull * ((unsigned long long)g.lanes + 1ull) + payload)
+        st = ST_FORMAT;
+    if (st == ST_OK) {
+        const uint32_t *offsets = h + kHeaderBytes / 4;
+        if (payload >= (1ull << 32) || offsets[0] != 0u || offsets[g.lanes] != (uint32_t)payload)
+            st = ST_CORRUPT;
+    }
+    status->code = st;
+    status->payload_bytes = payload;
+}
+
+__global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
+                               const uint16_t *__restrict__ mu, const int16_t *__restrict__ ls,
+                               const int16_t *__restrict__ coef, uint8_t *__restrict__ out,
+                               Status *__restrict__ status)
+{
+    __shared__ LdsTables tab;
+    load_tables(tab);
+    if (status->code != ST_OK) return;  // uniform: written by an earlier kernel
+    uint32_t lane = blockIdx.x * blockDim.x + threadIdx.x;
+    if (lane >= g.lanes) return;
+    const LaneShape sh = lane_shape(g, lane);
+    const uint32_t m_bits = g.prec_bits;
+    const uint32_t spread = (1u << m_bits) - 256u;
+    const uint32_t mask = (1u << m_bits) - 1u;
+    const uint32_t payload_bytes = (uint32_t)status->payload_bytes;
+
+    const uint32_t *offsets = reinterpret_cast<const uint32_t *>(coded + kHeaderBytes);
+    const uint16_t *payload =
+        reinterpret_cast<const uint16_t *>(coded + kHeaderBytes + 4ull * ((size_t)g.lanes + 1));
+    uint32_t begin = offsets[lane], end = offsets[lane + 1];
+    if (end < begin || end > payload_bytes || end - begin < 4u || ((begin | end) & 1u)) {
+        atomicMax(&status->code, (int)ST_CORRUPT);
+        return;
+    }
+    uint32_t pos = begin >> 1, stop = end >> 1;  // in 16-bit words
+    uint32_t S = (uint32_t)payload[pos] | ((uint32_t)payload[pos + 1] << 16);
+    pos += 2;
+    bool bad = false;
+
+    uint32_t p = sh.first, col = 0;
+    uint32_t im = p / g.hw;
+    uint32_t left_in_img = g.hw - (p - im * g.hw);  // pixels from p to the end of its image
+    int a_gr = coef[3 * im], a_br = coef[3 * im + 1], a_bg = coef[3 * im + 2];
+
+    for (uint32_t t = 0; t < sh.npx; ++t) {
+        size_t s = (size_t)p * 3;
+        int m[3] = {mu[s], mu[s + 1], mu[s + 2]};
+        int x[3] = {0, 0, 0};
+        int me = m[0];
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            if (c == 1) me = m[1] + rsh14(a_gr * (x[0] * 256 - m[0]));
+            if (c == 2) me = m[2] + rsh14(a_br * (x[0] * 256 - m[0])) + rsh14(a_bg * (x[1] * 256 - m[1]));
+            uint32_t inv_s = inv_scale(ls[s + c], tab);
+            uint32_t slot = S & mask;
+            // the value v with C(v) <= slot < C(v+1), by bisection on v
+            int lo = 0, hi = 256;
+            uint32_t c_lo = 0u, c_hi = 1u << m_bits;
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                int mid = (lo + hi) >> 1;
+                uint32_t cm = cum_inner(mid, me, inv_s, spread, tab);
+                bool ge = cm <= slot;
+                lo = ge ? mid : lo;
+                c_lo = ge ? cm : c_lo;
+                hi = ge ? hi : mid;
+                c_hi = ge ? c_hi : cm;
+            }
+            x[c] = lo;
+            // App. A eq. (12)
+            S = (c_hi - c_lo) * (S >> m_bits) + slot - c_lo;
+            if (S < kRansLow) {
+                if (pos < stop) {
+                    S = (S << 16) | payload[pos];
+                    ++pos;
+                } else {
+                    bad = true;
+                    S |= kRansLow;  // keep the state in range; the lane is already condemned
+                }
+            }
+        }
+        out[s] = (uint8_t)x[0];
+        out[s + 1] = (uint8_t)x[1];
+        out[s + 2] = (uint8_t)x[2];
+        // step to the next pixel of the lane
+        ++col;
+        if (col == sh.tw) {
+            col = 0;
+            p += g.w - sh.tw + 1;
+        } else {
+            ++p;
+        }
+        if (--left_in_img == 0 && t + 1 < sh.npx && g.lane_mode == 0) {
+            ++im;
+            left_in_img = g.hw;
+            a_gr = coef[3 * im];
+            a_br = coef[3 * im + 1];
+            a_bg = coef[3 * im + 2];
+        }
+    }
+    if (bad || S != kRansLow || pos != stop) atomicMax(&status->code, (int)ST_CORRUPT);
+}
+
+// --------------------------------------------------------------------------------------------
+// Host side
+// --------------------------------------------------------------------------------------------
+thread_local char t_hip_error[256] = "";
+thread_local float t_timing_ms[16];
+thread_local const char *t_timing_name[16];
+thread_local int t_timing_count = 0;
+static int g_timing_enabled = 0;
+
+static int hip_fail(hipError_t e, const char *what)
+{
+    snprintf(t_hip_error, sizeof(t_hip_error), "%s: %s", what, hipGetErrorString(e));
+    return PILC_E_HIP;
+}
+
+#define HIP_TRY(expr)                                   \
+    do {                                                \
+        hipError_t e_ = (expr);                         \
+        if (e_ != hipSuccess) return hip_fail(e_, #expr); \
+    } while (0)
+
+static std::mutex g_table_mutex;
+static bool g_table_ready[64] = {false};
+
+static int ensure_tables()
+{
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return PILC_E_ARG;
+    std::lock_guard<std::mutex> lock(g_table_mutex);
+    if (g_table_ready[dev]) return PILC_OK;
+    static uint32_t sig[kSigEntries + 1];
+    static uint2 cell[kSigEntries];
+    static uint32_t eh[kExpHiEntries], el[kExpLoEntries];
+    for (int i = 0; i <= kSigEntries; ++i)
+        sig[i] = (uint32_t)std::llround(std::ldexp(1.0 / (1.0 + std::exp(-(i - 1024) / 64.0)), 24));
+    for (int i = 0; i < kSigEntries; ++i) cell[i] = make_uint2(sig[i], sig[i + 1] - sig[i]);
+    for (int i = 0; i < kExpHiEntries; ++i)
+        eh[i] = (uint32_t)std::llround(std::ldexp(std::exp(4.0 - i / 64.0), 26));
+    for (int i = 0; i < kExpLoEntries; ++i)
+        el[i] = (uint32_t)std::llround(std::ldexp(std::exp(-i / 4096.0), 31));
+    HIP_TRY(hipMemcpyToSymbol(HIP_SYMBOL(g_sig_cell), cell, sizeof(cell)));
+    HIP_TRY(hipMemcpyToSymbol(HIP_SYMBOL(g_exp_hi), eh, sizeof(eh)));
+    HIP_TRY(hipMemcpyToSymbol(HIP_SYMBOL(g_exp_lo), el, sizeof(el)));
+    HIP_TRY(hipDeviceSynchronize());
+    g_table_ready[dev] = true;
+    return PILC_OK;
+}
+
+static uint64_t ceil_div64(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+
+// Validates a geometry and derives the kernel-side view.  Returns PILC_OK / PILC_E_*.
+static int make_geo(const pilc_geom *in, Geo *g)
+{
+    if (!in || in->n == 0 || in->h == 0 || in->w == 0) return PILC_E_ARG;
+    if (in->prec_bits < 10 || in->prec_bits > 16) return PILC_E_ARG;
+    uint64_t hw = (uint64_t)in->h * in->w;
+    uint64_t total = hw * in->n;
+    uint64_t lanes;
+    if (in->lane_mode == 0) {
+        if (in->lane_a == 0) return PILC_E_ARG;
+        if (hw % in->lane_a != 0 && in->lane_a % hw != 0) return PILC_E_ARG;
+        lanes = ceil_div64(total, in->lane_a);
+    } else if (in->lane_mode == 1) {
+        if (in->lane_a == 0 || in->lane_b == 0) return PILC_E_ARG;
+        lanes = (uint64_t)in->n * ceil_div64(in->h, in->lane_a) * ceil_div64(in->w, in->lane_b);
+    } else {
+        return PILC_E_ARG;
+    }
+    // 32-bit symbol indices and lane numbers inside the kernels
+    if (total * 3 >= (1ull << 32) - 4096 || lanes >= (1ull << 31)) return PILC_E_TOO_LARGE;
+    g->n = in->n;
+    g->h = in->h;
+    g->w = in->w;
+    g->hw = (uint32_t)hw;
+    g->prec_bits = in->prec_bits;
+    g->lane_mode = in->lane_mode;
+    g->lane_a = in->lane_a;
+    g->lane_b = in->lane_b;
+    g->tiles_x = in->lane_mode == 1 ? (uint32_t)ceil_div64(in->w, in->lane_b) : 1u;
+    g->tiles_per_img =
+        in->lane_mode == 1 ? (uint32_t)(ceil_div64(in->h, in->lane_a) * g->tiles_x) : 1u;
+    g->total_px = (uint32_t)total;
+    g->lanes = (uint32_t)lanes;
+    return PILC_OK;
+}
+
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct Workspace {
+    size_t status_off, words_off, state_off, sums_off, scratch_off, total;
+    uint32_t scan_blocks;
+};
+
+static Workspace layout(const Geo &g)
+{
+    Workspace w;
+    w.scan_blocks = (uint32_t)ceil_div64(g.lanes, kScanTile);
+    size_t off = 0;
+    w.status_off = off;
+    off = align256(off + sizeof(Status));
+    w.words_off = off;
+    off = align256(off + 4 * (size_t)g.lanes);
+    w.state_off = off;
+    off = align256(off + 4 * (size_t)g.lanes);
+    w.sums_off = off;
+    off = align256(off + 8 * (size_t)w.scan_blocks);
+    w.scratch_off = off;
+    off = align256(off + 2 * (size_t)g.total_px * 3);
+    w.total = off;
+    return w;
+}
+
+static int status_to_error(int st)
+{
+    switch (st) {
+    case ST_OK: return PILC_OK;
+    case ST_CAPACITY: return PILC_E_CAPACITY;
+    case ST_TOO_LARGE: return PILC_E_TOO_LARGE;
+    case ST_FORMAT: return PILC_E_FORMAT;
+    default: return PILC_E_CORRUPT;
+    }
+}
+
+// Optional per-kernel event timing on the caller's stream.
+struct Timer {
+    hipStream_t stream;
+    hipEvent_t ev[17];
+    const char *name[16];
+    int n = 0;
+    bool on;
+    explicit Timer(hipStream_t s) : stream(s), on(g_timing_enabled != 0)
+    {
+        t_timing_count = 0;
+        if (on) {
+            for (auto &e : ev) (void)hipEventCreate(&e);
+            (void)hipEventRecord(ev[0], stream);
+        }
+    }
+    void mark(const char *what)
+    {
+        if (on && n < 16) {
+            name[n] = what;
+            (void)hipEventRecord(ev[++n], stream);
+        }
+    }
+    void finish()  // call after the stream has been synchronised
+    {
+        if (!on) return;
+        t_timing_name[0] = "total";
+        (void)hipEventElapsedTime(&t_timing_ms[0], ev[0], ev[n]);
+        for (int i = 0; i < n && i < 15; ++i) {
+            t_timing_name[i + 1] = name[i];
+            (void)hipEventElapsedTime(&t_timing_ms[i + 1], ev[i], ev[i + 1]);
+        }
+        t_timing_count = n + 1 > 16 ? 16 : n + 1;
+    }
+    ~Timer()
+    {
+        if (on)
+            for (auto &e : ev) (void)hipEventDestroy(e);
+    }
+};
+
+static int lane_block_threads(const Geo &g) { return g.lanes >= (1u << 18) ? 256 : 64; }
+
+}  // namespace pilc
+
+using namespace pilc;
+
+extern "C" {
+
+uint32_t pilc_version(void) { return PILC_VERSION; }
+
+const char *pilc_strerror(int code)
+{
+    switch (code) {
+    case PILC_OK: return "success";
+    case PILC_E_ARG: return "invalid argument (null or misaligned pointer, or bad geometry)";
+    case PILC_E_WORKSPACE: return "workspace too small";
+    case PILC_E_CAPACITY: return "coded output does not fit the given capacity";
+    case PILC_E_TOO_LARGE: return "batch too large for 32-bit offsets";
+    case PILC_E_FORMAT: return "container header does not match (magic, version, geometry or size)";
+    case PILC_E_CORRUPT: return "container is corrupt (offsets, lane overrun or final state)";
+    case PILC_E_HIP: return "HIP runtime failure";
+    default: return "unknown error code";
+    }
+}
+
+const char *pilc_last_hip_error(void) { return t_hip_error; }
+
+void pilc_set_timing(int enabled) { g_timing_enabled = enabled; }
+
+int pilc_last_timing(float *ms_out_host, int capacity)
+{
+    int k = t_timing_count < capacity ? t_timing_count : capacity;
+    for (int i = 0; i < k; ++i) ms_out_host[i] = t_timing_ms[i];
+    return k;
+}
+
+const char *pilc_timing_name(int i)
+{
+    return (i >= 0 && i < t_timing_count) ? t_timing_name[i] : "";
+}
+
+uint64_t pilc_lane_count(const pilc_geom *geom)
+{
+    Geo g;
+    return make_geo(geom, &g) == PILC_OK ? g.lanes : 0;
+}
+
+int pilc_workspace_size(const pilc_geom *geom, size_t *workspace_bytes_host,
+                        size_t *max_coded_bytes_host)
+{
+    Geo g;
+    int rc = make_geo(geom, &g);
+    if (rc != PILC_OK) return rc;
+    if (workspace_bytes_host) *workspace_bytes_host = layout(g).total;
+    if (max_coded_bytes_host)
+        *max_coded_bytes_host = kHeaderBytes + 4 * ((size_t)g.lanes + 1) + 4 * (size_t)g.lanes +
+                                2 * (size_t)g.total_px * 3;
+    return PILC_OK;
+}
+
+static bool params_ok(const pilc_params *p)
+{
+    return p && p->mu && p->log_scale && p->chan_coef && ((uintptr_t)p->mu & 1) == 0 &&
+           ((uintptr_t)p->log_scale & 1) == 0 && ((uintptr_t)p->chan_coef & 1) == 0;
+}
+
+int pilc_symbol_tables(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params *params,
+                       uint32_t *cum_out_dev, uint32_t *freq_out_dev, void *hip_stream)
+{
+    Geo g;
+    int rc = make_geo(geom, &g);
+    if (rc != PILC_OK) return rc;
+    if (!img_dev || !params_ok(params) || !cum_out_dev || !freq_out_dev ||
+        ((uintptr_t)cum_out_dev & 3) || ((uintptr_t)freq_out_dev & 3))
+        return PILC_E_ARG;
+    if ((rc = ensure_tables()) != PILC_OK) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    uint32_t blocks = (uint32_t)ceil_div64(g.total_px, 256);
+    k_symbol_tables<<<blocks, 256, 0, stream>>>(g, img_dev, params->mu, params->log_scale,
+                                                params->chan_coef, cum_out_dev, freq_out_dev);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(stream));
+    return PILC_OK;
+}
+
+int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params *params,
+                void *workspace_dev, size_t workspace_bytes, uint8_t *coded_dev,
+                size_t coded_capacity, uint64_t *coded_bytes_host, void *hip_stream)
+{
+    Geo g;
+    int rc = make_geo(geom, &g);
+    if (rc != PILC_OK) return rc;
+    if (!img_dev || !params_ok(params) || !workspace_dev || !coded_dev || !coded_bytes_host)
+        return PILC_E_ARG;
+    if (((uintptr_t)workspace_dev & 255) || ((uintptr_t)coded_dev & 15)) return PILC_E_ARG;
+    const Workspace ws = layout(g);
+    if (workspace_bytes < ws.total) return PILC_E_WORKSPACE;
+    const size_t table_end = kHeaderBytes + 4 * ((size_t)g.lanes + 1);
+    if (coded_capacity < table_end) return PILC_E_CAPACITY;
+    if ((rc = ensure_tables()) != PILC_OK) return rc;
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+    uint8_t *base = static_cast<uint8_t *>(workspace_dev);
+    Status *status = reinterpret_cast<Status *>(base + ws.status_off);
+    uint32_t *lane_words = reinterpret_cast<uint32_t *>(base + ws.words_off);
+    uint32_t *lane_state = reinterpret_cast<uint32_t *>(base + ws.state_off);
+    unsigned long long *sums = reinterpret_cast<unsigned long long *>(base + ws.sums_off);
+    uint16_t *scratch = reinterpret_cast<uint16_t *>(base + ws.scratch_off);
+    uint32_t *offsets = reinterpret_cast<uint32_t *>(coded_dev + kHeaderBytes);
+    uint16_t *payload = reinterpret_cast<uint16_t *>(coded_dev + table_end);
+
+    Timer timer(stream);
+    k_init_status<<<1, 1, 0, stream>>>(status);
+    const int bt = lane_block_threads(g);
+    k_encode_lanes<<<(uint32_t)ceil_div64(g.lanes, bt), bt, 0, stream>>>(
+        g, img_dev, params->mu, params->log_scale, params->chan_coef, scratch, lane_words,
+        lane_state);
+    timer.mark("encode_lanes");
+    k_scan_partials<<<ws.scan_blocks, kScanThreads, 0, stream>>>(g.lanes, lane_words, sums);
+    k_scan_spine<<<1, kScanThreads, 0, stream>>>(g, ws.scan_blocks, sums, coded_dev,
+                                                 (unsigned long long)coded_capacity, status);
+    k_scan_apply<<<ws.scan_blocks, kScanThreads, 0, stream>>>(g.lanes, lane_words, sums, offsets);
+    timer.mark("scan");
+    // worst case payload that fits the capacity; workgroups past the real size exit at once
+    const size_t max_payload = 4 * (size_t)g.lanes + 2 * (size_t)g.total_px * 3;
+    const size_t room = coded_capacity - table_end;
+    const size_t pack_bytes = max_payload < room ? max_payload : room;
+    const uint32_t pack_blocks = (uint32_t)ceil_div64(pack_bytes / 2, kPackWords);
+    if (pack_blocks)
+        k_pack<<<pack_blocks, 256, 0, stream>>>(g, scratch, lane_state, offsets, payload, status);
+    timer.mark("pack");
+    HIP_TRY(hipGetLastError());
+    Status host_status;
+    HIP_TRY(hipMemcpyAsync(&host_status, status, sizeof(Status), hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    timer.finish();
+    if (host_status.code != ST_OK) return status_to_error(host_status.code);
+    *coded_bytes_host = table_end + host_status.payload_bytes;
+    return PILC_OK;
+}
+
+int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_bytes,
+                const pilc_params *params, void *workspace_dev, size_t workspace_bytes,
+                uint8_t *img_out_dev, void *hip_stream)
+{
+    Geo g;
+    int rc = make_geo(geom, &g);
+    if (rc != PILC_OK) return rc;
+    if (!coded_dev || !params_ok(params) || !workspace_dev || !img_out_dev) return PILC_E_ARG;
+    if (((uintptr_t)workspace_dev & 255) || ((uintptr_t)coded_dev & 15)) return PILC_E_ARG;
+    const Workspace ws = layout(g);
+    if (workspace_bytes < ws.total) return PILC_E_WORKSPACE;
+    const size_t table_end = kHeaderBytes + 4 * ((size_t)g.lanes + 1);
+    if (coded_bytes < table_end) return PILC_E_FORMAT;  // cannot even hold header + offsets
+    if ((rc = ensure_tables()) != PILC_OK) return rc;
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+    Status *status = reinterpret_cast<Status *>(static_cast<uint8_t *>(workspace_dev) + ws.status_off);
+
+    Timer timer(stream);
+    k_check_header<<<1, 1, 0, stream>>>(g, coded_dev, (unsigned long long)coded_bytes, status);
+    timer.mark("check_header");
+    const int bt = lane_block_threads(g);
+    k_decode_lanes<<<(uint32_t)ceil_div64(g.lanes, bt), bt, 0, stream>>>(
+        g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev, status);
+    timer.mark("decode_lanes");
+    HIP_TRY(hipGetLastError());
+    Status host_status;
+    HIP_TRY(hipMemcpyAsync(&host_status, status, sizeof(Status), hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    timer.finish();
+    return status_to_error(host_status.code);
+}
+
+}  // extern "C"

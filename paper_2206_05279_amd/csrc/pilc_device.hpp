@@ -1,0 +1,124 @@
+// Device-side arithmetic shared by the libpilc kernels (gfx950 only).
+//
+// Everything here is integer and must produce, bit for bit, the tables that Sec. 3.2 of
+// arXiv 2206.05279 asks for (integer masses summing to 2^M with C_x their running sum) from a
+// logistic law with location mu and scale s on 0..255 (Sec. 3.1 eq. (7), Sec. 3.3), after the
+// channel conditioning of Sec. 3.1 eqs. (3)-(4).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pilc {
+
+constexpr int kSigEntries = 2048;  // interpolation cells of the sigmoid table
+constexpr int kExpHiEntries = 640;
+constexpr int kExpLoEntries = 64;
+
+// Constant tables in device globals, filled by the host once per device.
+//   g_sig_cell[i] = { T[i], T[i+1]-T[i] },  T[i] = round(2^24 * sigmoid((i-1024)/64))
+//   g_exp_hi[i]   = round(2^26 * exp(4 - i/64)),  g_exp_lo[j] = round(2^31 * exp(-j/4096))
+extern __device__ uint2 g_sig_cell[kSigEntries];
+extern __device__ uint32_t g_exp_hi[kExpHiEntries];
+extern __device__ uint32_t g_exp_lo[kExpLoEntries];
+
+// LDS copy of the tables; every coding kernel stages them once per workgroup.
+struct LdsTables {
+    uint2 sig[kSigEntries];
+    uint32_t exp_hi[kExpHiEntries];
+    uint32_t exp_lo[kExpLoEntries];
+};
+
+__device__ __forceinline__ void load_tables(LdsTables &t)
+{
+    for (int i = threadIdx.x; i < kSigEntries; i += blockDim.x) t.sig[i] = g_sig_cell[i];
+    for (int i = threadIdx.x; i < kExpHiEntries; i += blockDim.x) t.exp_hi[i] = g_exp_hi[i];
+    for (int i = threadIdx.x; i < kExpLoEntries; i += blockDim.x) t.exp_lo[i] = g_exp_lo[i];
+    __syncthreads();
+}
+
+// Batch geometry as the kernels see it (derived on the host from pilc_geom).
+struct Geo {
+    uint32_t n, h, w, hw;
+    uint32_t prec_bits;
+    uint32_t lane_mode, lane_a, lane_b;
+    uint32_t tiles_x, tiles_per_img;  // mode 1
+    uint32_t total_px;                // n*h*w   (< 2^32 / 3)
+    uint32_t lanes;
+};
+
+// One lane's pixel set: `npx` pixels starting at flat pixel `first`, laid out as rows of `tw`
+// pixels with a stride of `w` pixels between row starts (flat lanes are a single row).
+struct LaneShape {
+    uint32_t first, npx, tw;
+    uint32_t sym_base;  // symbols of all lanes before this one (lane-major order)
+};
+
+__device__ __forceinline__ LaneShape lane_shape(const Geo &g, uint32_t lane)
+{
+    LaneShape s;
+    if (g.lane_mode == 0) {
+        uint64_t first = (uint64_t)lane * g.lane_a;
+        uint64_t last = first + g.lane_a;
+        if (last > g.total_px) last = g.total_px;
+        s.first = (uint32_t)first;
+        s.npx = (uint32_t)(last - first);
+        s.tw = s.npx;
+        s.sym_base = 3u * s.first;
+    } else {
+        uint32_t img = lane / g.tiles_per_img;
+        uint32_t r = lane - img * g.tiles_per_img;
+        uint32_t ty = r / g.tiles_x, tx = r - ty * g.tiles_x;
+        uint32_t y0 = ty * g.lane_a, x0 = tx * g.lane_b;
+        uint32_t th = min(g.lane_a, g.h - y0);
+        uint32_t tw = min(g.lane_b, g.w - x0);
+        s.first = (img * g.h + y0) * g.w + x0;
+        s.npx = th * tw;
+        s.tw = tw;
+        // tiles above cover y0 full rows; tiles to the left in this tile row are th high
+        s.sym_base = 3u * (img * g.hw + y0 * g.w + x0 * th);
+    }
+    return s;
+}
+
+// Rounded Q2.14 * Q8.8 product: floor((v + 2^13) / 2^14).
+__device__ __forceinline__ int rsh14(int v) { return (v + 8192) >> 14; }
+
+// Q6.25 value of exp(-log_scale); log_scale Q4.12 clamped to [-4, 6).
+__device__ __forceinline__ uint32_t inv_scale(int ls, const LdsTables &t)
+{
+    int u = min(max(ls, -16384), 24575) + 16384;
+    return __umulhi(t.exp_hi[u >> 6], t.exp_lo[u & 63]);
+}
+
+// F(k) in 24 bits at the edge k - 1/2:  d = 256*k - 128 - mu'  (Q8.8), inv_s Q6.25 < 2^31.
+__device__ __forceinline__ uint32_t edge_cdf(int d, uint32_t inv_s, const LdsTables &t)
+{
+    long long p = (long long)d * (long long)(int)inv_s;  // Q.33
+    long long z = p >> 17;                               // Q.16, floor
+    z = z < -(1ll << 20) ? -(1ll << 20) : z;
+    z = z > (1ll << 20) - 1 ? (1ll << 20) - 1 : z;
+    uint32_t w = (uint32_t)((int)z + (1 << 20));
+    uint2 cell = t.sig[w >> 10];
+    return cell.x + ((cell.y * (w & 1023u)) >> 10);
+}
+
+// C(k), 1 <= k <= 255:  k + floor(F(k) * (2^M - 256) / 2^24).
+__device__ __forceinline__ uint32_t cum_inner(int k, int mu_eff, uint32_t inv_s, uint32_t spread,
+                                              const LdsTables &t)
+{
+    uint32_t f = edge_cdf(256 * k - 128 - mu_eff, inv_s, t);
+    return (uint32_t)k + __umulhi(f << 8, spread);
+}
+
+// C(k) for any k in 0..256.
+__device__ __forceinline__ uint32_t cum_at(int k, int mu_eff, uint32_t inv_s, uint32_t prec_bits,
+                                           const LdsTables &t)
+{
+    uint32_t spread = (1u << prec_bits) - 256u;
+    if (k <= 0) return 0u;
+    if (k >= 256) return 1u << prec_bits;
+    return cum_inner(k, mu_eff, inv_s, spread, t);
+}
+
+}  // namespace pilc

@@ -1,0 +1,78 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.  The oracle
+cannot afford whole 150-200 MB sets inside a test, so: (i) lanes are independent streams (pinned
+on the CPU), hence sampled lanes are encoded one by one by the oracle and compared byte for byte
+with the GPU container; (ii) offsets must be the exclusive scan of lane sizes; (iii) the GPU
+decode must return the original image exactly."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pilc_oracle as orc
+from paper_2206_05279_amd import binding as pb
+from paper_2206_05279_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import DeviceWorkload, parse_container  # noqa: E402
+
+
+def _oracle_lane_bytes(wl, lane):
+    """Container bytes of one lane, from the oracle run on that lane's pixels alone."""
+    n, h, w, m, mode, la, lb = wl.geom
+    hw = h * w
+    if mode == 0 and la % hw == 0:            # lane = whole images
+        k = la // hw
+        i0, i1 = lane * k, min((lane + 1) * k, n)
+        g = orc.make_geom(i1 - i0, h, w, m, 0, la, 0)
+        sl = slice(i0, i1)
+        rc, coded = orc.encode(g, wl.img[sl].copy(), wl.mu[sl].copy(), wl.log_scale[sl].copy(),
+                               wl.chan_coef[sl].copy())
+        assert rc == orc.OK
+        return parse_container(coded)[3]
+    if mode == 0:                             # lane inside one image: encode the image, pick the lane
+        per = hw // la
+        i = lane // per
+        g = orc.make_geom(1, h, w, m, 0, la, 0)
+    else:
+        per = -(-h // la) * -(-w // lb)
+        i = lane // per
+        g = orc.make_geom(1, h, w, m, 1, la, lb)
+    sl = slice(i, i + 1)
+    rc, coded = orc.encode(g, wl.img[sl].copy(), wl.mu[sl].copy(), wl.log_scale[sl].copy(),
+                           wl.chan_coef[sl].copy())
+    assert rc == orc.OK
+    _, _, offs, body = parse_container(coded)
+    j = lane - i * per
+    return body[offs[j]:offs[j + 1]]
+
+
+FULL = [
+    ("cfg1-full", lambda: synth.make_workload(1), 12),
+    ("cfg2-full", lambda: synth.make_workload(2), 6),
+    ("cfg3-full", lambda: synth.make_workload(3), 2),
+    ("cfg4-M12-L64-256img", lambda: synth.make_workload(4, 256, prec_bits=12, lanes_per_image=64), 4),
+]
+
+
+@pytest.mark.parametrize("name,make,samples", FULL, ids=[c[0] for c in FULL])
+def test_full_size_sampled_parity(name, make, samples):
+    print("generating", name, flush=True)
+    wl = make()
+    d = DeviceWorkload(wl)
+    print("encoding", name, wl.geom, flush=True)
+    _, nbytes = d.encode()
+    coded = d.coded_numpy()
+    lanes, payload, offs, body = parse_container(coded)
+    assert lanes == pb.pilc_lane_count(d.geom) and nbytes == 64 + 4 * (lanes + 1) + payload
+    sizes = np.diff(offs.astype(np.int64))
+    assert offs[0] == 0 and offs[-1] == payload and sizes.min() >= 4 and not np.any(sizes & 1)
+    rng = np.random.default_rng(99)
+    picks = sorted(set([0, lanes - 1] + [int(v) for v in rng.integers(0, lanes, size=samples)]))
+    for lane in picks:
+        want = _oracle_lane_bytes(wl, lane)
+        got = body[offs[lane]:offs[lane + 1]]
+        assert np.array_equal(got, want), "lane %d differs" % lane
+    print("decoding", name, flush=True)
+    assert d.decode() == pb.PILC_OK
+    assert torch.equal(d.out, d.img)
+    print("bits/subpixel %.4f" % (8.0 * nbytes / wl.subpixels), flush=True)
