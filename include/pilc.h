@@ -125,6 +125,12 @@ void pilc_set_timing(int enabled);
 int pilc_last_timing(float *ms_out_host, int capacity);
 const char *pilc_timing_name(int index_in_last_call);
 
+/* Which lane kernels encode and decode use: 0 = chosen from the lane count (default), 1 = one
+ * thread per lane, 2 = one wavefront per lane.  All choices produce the same bytes; the knob
+ * exists for tuning and for testing both kernel families on the same input.  Process-wide.
+ * Errors: PILC_E_ARG for any other value. */
+int pilc_set_kernel_policy(int policy);
+
 const char *pilc_strerror(int code);
 const char *pilc_last_hip_error(void); /* text of the last HIP failure on this thread */
 uint32_t pilc_version(void);

@@ -26,7 +26,7 @@ PILC_E_HIP = -7
 
 EXPORTS = [
     "pilc_lane_count", "pilc_workspace_size", "pilc_encode", "pilc_decode", "pilc_symbol_tables",
-    "pilc_set_timing", "pilc_last_timing", "pilc_timing_name", "pilc_strerror",
+    "pilc_set_timing", "pilc_set_kernel_policy", "pilc_last_timing", "pilc_timing_name", "pilc_strerror",
     "pilc_last_hip_error", "pilc_version",
 ]
 
@@ -75,6 +75,8 @@ def lib():
         L.pilc_symbol_tables.argtypes = [gp, C.c_void_p, pp, C.c_void_p, C.c_void_p, C.c_void_p]
         L.pilc_set_timing.restype = None
         L.pilc_set_timing.argtypes = [C.c_int]
+        L.pilc_set_kernel_policy.restype = C.c_int
+        L.pilc_set_kernel_policy.argtypes = [C.c_int]
         L.pilc_last_timing.restype = C.c_int
         L.pilc_last_timing.argtypes = [C.POINTER(C.c_float), C.c_int]
         L.pilc_timing_name.restype = C.c_char_p
@@ -160,6 +162,12 @@ def pilc_symbol_tables(geom: pilc_geom, img, mu, log_scale, chan_coef, cum_out, 
 
 def pilc_set_timing(enabled: bool) -> None:
     lib().pilc_set_timing(1 if enabled else 0)
+
+
+def pilc_set_kernel_policy(policy: int) -> None:
+    rc = lib().pilc_set_kernel_policy(int(policy))
+    if rc != PILC_OK:
+        raise PilcError(rc, "pilc_set_kernel_policy")
 
 
 def pilc_last_timing() -> List[Tuple[str, float]]:

@@ -429,9 +429,25 @@ __global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
     if (bad || S != kRansLow || pos != stop) atomicMax(&status->code, (int)ST_CORRUPT);
 }
 
+}  // namespace pilc
+
+#include "pilc_wave_kernels.hpp"
+
+namespace pilc {
+
 // --------------------------------------------------------------------------------------------
 // Host side
 // --------------------------------------------------------------------------------------------
+static int g_kernel_policy = 0;  // 0 auto, 1 thread per lane, 2 wavefront per lane
+
+// A wavefront per lane pays off while there are too few lanes to fill the chip with one thread
+// each (256 CUs x 4 SIMDs x 64 threads = 65,536 threads for a single wave per SIMD).
+static bool use_wave_kernels(const Geo &g)
+{
+    if (g_kernel_policy == 1) return false;
+    if (g_kernel_policy == 2) return true;
+    return g.lanes <= 16384u;
+}
 thread_local char t_hip_error[256] = "";
 thread_local float t_timing_ms[16];
 thread_local const char *t_timing_name[16];
@@ -622,6 +638,13 @@ const char *pilc_last_hip_error(void) { return t_hip_error; }
 
 void pilc_set_timing(int enabled) { g_timing_enabled = enabled; }
 
+int pilc_set_kernel_policy(int policy)
+{
+    if (policy < 0 || policy > 2) return PILC_E_ARG;
+    g_kernel_policy = policy;
+    return PILC_OK;
+}
+
 int pilc_last_timing(float *ms_out_host, int capacity)
 {
     int k = t_timing_count < capacity ? t_timing_count : capacity;
@@ -706,10 +729,16 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
 
     Timer timer(stream);
     k_init_status<<<1, 1, 0, stream>>>(status);
-    const int bt = lane_block_threads(g);
-    k_encode_lanes<<<(uint32_t)ceil_div64(g.lanes, bt), bt, 0, stream>>>(
-        g, img_dev, params->mu, params->log_scale, params->chan_coef, scratch, lane_words,
-        lane_state);
+    if (use_wave_kernels(g)) {
+        k_encode_wave<<<(uint32_t)ceil_div64(g.lanes, kWavesPerBlock), 64 * kWavesPerBlock, 0, stream>>>(
+            g, img_dev, params->mu, params->log_scale, params->chan_coef, scratch, lane_words,
+            lane_state);
+    } else {
+        const int bt = lane_block_threads(g);
+        k_encode_lanes<<<(uint32_t)ceil_div64(g.lanes, bt), bt, 0, stream>>>(
+            g, img_dev, params->mu, params->log_scale, params->chan_coef, scratch, lane_words,
+            lane_state);
+    }
     timer.mark("encode_lanes");
     k_scan_partials<<<ws.scan_blocks, kScanThreads, 0, stream>>>(g.lanes, lane_words, sums);
     k_scan_spine<<<1, kScanThreads, 0, stream>>>(g, ws.scan_blocks, sums, coded_dev,
@@ -755,9 +784,15 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
     Timer timer(stream);
     k_check_header<<<1, 1, 0, stream>>>(g, coded_dev, (unsigned long long)coded_bytes, status);
     timer.mark("check_header");
-    const int bt = lane_block_threads(g);
-    k_decode_lanes<<<(uint32_t)ceil_div64(g.lanes, bt), bt, 0, stream>>>(
-        g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev, status);
+    if (use_wave_kernels(g)) {
+        k_decode_wave<<<(uint32_t)ceil_div64(g.lanes, kWavesPerBlock), 64 * kWavesPerBlock, 0, stream>>>(
+            g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev,
+            &status->code, &status->payload_bytes);
+    } else {
+        const int bt = lane_block_threads(g);
+        k_decode_lanes<<<(uint32_t)ceil_div64(g.lanes, bt), bt, 0, stream>>>(
+            g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev, status);
+    }
     timer.mark("decode_lanes");
     HIP_TRY(hipGetLastError());
     Status host_status;

@@ -17,6 +17,14 @@ def _ogeom(wl):
     return orc.make_geom(*wl.geom)
 
 
+@pytest.fixture(params=[1, 2], ids=["thread-per-lane", "wave-per-lane"])
+def policy(request):
+    """Runs a test once with each lane-kernel family forced."""
+    pb.pilc_set_kernel_policy(request.param)
+    yield request.param
+    pb.pilc_set_kernel_policy(0)
+
+
 SMALL_CASES = [
     ("cfg0-full", lambda: synth.make_workload(0)),
     ("cfg1-70-lanes", lambda: synth.make_workload(1, 16 * 70)),
@@ -51,9 +59,9 @@ def test_symbol_tables_match_oracle(name, make):
 
 
 @pytest.mark.parametrize("name,make", SMALL_CASES, ids=[c[0] for c in SMALL_CASES])
-def test_container_and_image_match_oracle(name, make):
+def test_container_and_image_match_oracle(name, make, policy):
     wl = make()
-    print("case", name, wl.geom, flush=True)
+    print("case", name, wl.geom, "policy", policy, flush=True)
     d = DeviceWorkload(wl)
     rc, nbytes = d.encode()
     o_rc, o_coded = orc.encode(_ogeom(wl), wl.img, wl.mu, wl.log_scale, wl.chan_coef)
@@ -89,7 +97,7 @@ def test_exact_capacity_is_enough_and_one_byte_less_is_not():
     assert rc == pb.PILC_E_WORKSPACE
 
 
-def test_damaged_containers_give_error_codes_never_faults():
+def test_damaged_containers_give_error_codes_never_faults(policy):
     wl = synth.make_workload(0, 4)
     d = DeviceWorkload(wl)
     _, nbytes = d.encode()
