@@ -432,6 +432,7 @@ __global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
 }  // namespace pilc
 
 #include "pilc_wave_kernels.hpp"
+#include "pilc_block_encode.hpp"
 
 namespace pilc {
 
@@ -515,7 +516,7 @@ static int make_geo(const pilc_geom *in, Geo *g)
         return PILC_E_ARG;
     }
     // 32-bit symbol indices and lane numbers inside the kernels
-    if (total * 3 >= (1ull << 32) - 4096 || lanes >= (1ull << 31)) return PILC_E_TOO_LARGE;
+    if (total * 3 + lanes + 4096 >= (1ull << 32)) return PILC_E_TOO_LARGE;
     g->n = in->n;
     g->h = in->h;
     g->w = in->w;
@@ -553,7 +554,8 @@ static Workspace layout(const Geo &g)
     w.sums_off = off;
     off = align256(off + 8 * (size_t)w.scan_blocks);
     w.scratch_off = off;
-    off = align256(off + 2 * (size_t)g.total_px * 3);
+    // one 16-bit word per symbol, plus one dump word per lane for the branch-free encoder
+    off = align256(off + 2 * ((size_t)g.total_px * 3 + g.lanes + 64));
     w.total = off;
     return w;
 }
@@ -730,9 +732,9 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
     Timer timer(stream);
     k_init_status<<<1, 1, 0, stream>>>(status);
     if (use_wave_kernels(g)) {
-        k_encode_wave<<<(uint32_t)ceil_div64(g.lanes, kWavesPerBlock), 64 * kWavesPerBlock, 0, stream>>>(
-            g, img_dev, params->mu, params->log_scale, params->chan_coef, scratch, lane_words,
-            lane_state);
+        k_encode_block<<<(uint32_t)ceil_div64(g.lanes, kEncLanes), kEncThreads, 0, stream>>>(
+            g, img_dev, params->mu, params->log_scale, params->chan_coef, scratch, g.total_px * 3u,
+            lane_words, lane_state);
     } else {
         const int bt = lane_block_threads(g);
         k_encode_lanes<<<(uint32_t)ceil_div64(g.lanes, bt), bt, 0, stream>>>(

@@ -38,33 +38,69 @@ __device__ __forceinline__ uint32_t lane_pixel(const Geo &g, const LaneShape &sh
 
 // --------------------------------------------------------------------------------------------
 // Decode, one wavefront per lane.
+//
+// Per symbol the 64 threads evaluate C(k) at the 64 candidates k = base..base+63 of a window
+// centred on the predicted mean; a ballot of C(k) <= slot counts how many lie at or below the
+// slot, which names the symbol (App. A: the x with C_x <= S mod 2^M < C_x + P_x).  The common
+// case (window inside 1..255 and within 2^15 Q8.8 units of the mean, symbol inside the window)
+// takes a short exact evaluation with 24-bit multiplies; everything else goes through
+// find_symbol_slow, which walks windows with the general 64-bit evaluation.
 // --------------------------------------------------------------------------------------------
+struct Found {
+    uint32_t x, c_lo, c_hi;
+};
+
+__device__ __noinline__ Found find_symbol_slow(int me, uint32_t inv_s, uint32_t slot,
+                                               uint32_t m_bits, const LdsTables &tab)
+{
+    const int lane_id = (int)(threadIdx.x & 63u);
+    const uint32_t spread = (1u << m_bits) - 256u, top = 1u << m_bits;
+    int base = min(max(((me + 128) >> 8) - 31, 0), 193);
+    uint32_t cv, cnt;
+    for (;;) {
+        const int k = base + lane_id;  // 0..256
+        cv = cum_inner(min(max(k, 1), 255), me, inv_s, spread, tab);
+        cv = k <= 0 ? 0u : cv;
+        cv = k >= 256 ? top : cv;
+        cnt = (uint32_t)__popcll(__ballot(cv <= slot));
+        if (cnt == 0u)
+            base = max(base - 63, 0);    // C(0) = 0 <= slot ends this at base 0
+        else if (cnt == 64u)
+            base = min(base + 63, 193);  // C(256) = 2^M > slot ends this at base 193
+        else
+            break;
+    }
+    Found r;
+    r.x = (uint32_t)base + cnt - 1u;
+    r.c_lo = read_lane(cv, cnt - 1u);
+    r.c_hi = read_lane(cv, cnt);
+    return r;
+}
+
+// Wave-wide buffer of the next 64 stream words, one per thread.
 struct WaveReader {
     const uint16_t *payload;
-    uint32_t pos, stop;   // 16-bit word indices into the payload (uniform)
-    uint32_t base;        // first word held in `buf` (even, uniform)
-    uint32_t buf;         // per thread: words base+2j (low half) and base+2j+1 (high half)
+    uint32_t pos, stop;  // 16-bit word indices into the payload (uniform)
+    uint32_t base;       // word index held by thread 0 (uniform)
+    uint32_t buf;        // this thread's word
     uint32_t lane_id;
 
+    // words past `stop` read as 0: an overrun is detected at the end of the lane (pos != stop)
     __device__ __forceinline__ void fill(uint32_t from)
     {
-        base = from & ~1u;
-        uint32_t a = base + 2u * lane_id;
-        uint32_t lo = a < stop ? payload[a] : 0u;
-        uint32_t hi = a + 1u < stop ? payload[a + 1u] : 0u;
-        buf = lo | (hi << 16);
+        base = from;
+        uint32_t a = base + lane_id;
+        buf = a < stop ? (uint32_t)payload[a] : 0u;
     }
-    // next word of the lane (caller checked pos < stop)
     __device__ __forceinline__ uint32_t next()
     {
         uint32_t idx = pos - base;
-        if (idx >= 128u) {
+        if (idx >= 64u) {
             fill(pos);
-            idx = pos - base;
+            idx = 0u;
         }
-        uint32_t w = read_lane(buf, idx >> 1);
         ++pos;
-        return (idx & 1u) ? (w >> 16) : (w & 0xFFFFu);
+        return read_lane(buf, idx);
     }
 };
 
@@ -83,7 +119,6 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_decode_wave(
     const uint32_t m_bits = g.prec_bits;
     const uint32_t spread = (1u << m_bits) - 256u;
     const uint32_t mask = (1u << m_bits) - 1u;
-    const uint32_t top = 1u << m_bits;
     const uint32_t payload_bytes = (uint32_t)*status_payload;
 
     const uint32_t *offsets = reinterpret_cast<const uint32_t *>(coded + 64);
@@ -97,11 +132,52 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_decode_wave(
     }
     rd.pos = begin >> 1;
     rd.stop = end >> 1;
-    uint32_t S = (uint32_t)rd.payload[rd.pos] | ((uint32_t)rd.payload[rd.pos + 1] << 16);
-    S = uniform(S);
+    uint32_t S = uniform((uint32_t)rd.payload[rd.pos] | ((uint32_t)rd.payload[rd.pos + 1] << 16));
     rd.pos += 2;
     rd.fill(rd.pos);
-    bool bad = false;
+
+    const int d0 = 256 * (int)lane_id - 128;  // candidate edge j - 1/2 relative to the window base
+
+    // One symbol.  `win` packs the window chosen for mean `me`: bits 0..7 base (1..192),
+    // bit 8 set when the short evaluation is valid for this window.
+    auto decode_symbol = [&](int me, uint32_t win, uint32_t inv_s, uint32_t inv_a,
+                             uint32_t inv_b) -> uint32_t {
+        const uint32_t slot = S & mask;
+        const int base = (int)(win & 0xFFu);
+        const int d = d0 + ((base << 8) - me);
+        // z = floor(d * inv_s / 2^17) with inv_s = inv_a * 2^16 + inv_b, |d| <= 2^15
+        const int t = __mul24(d, (int)inv_b) >> 16;
+        int w = ((__mul24(d, (int)inv_a) + t) >> 1) + (1 << 20);
+        w = min(max(w, 0), (1 << 21) - 1);
+        const uint2 cell = tab.sig[w >> 10];
+        const uint32_t f24 = cell.x + (__umul24(cell.y, (uint32_t)w & 1023u) >> 10);
+        const uint32_t cv = (uint32_t)base + lane_id + __umulhi(f24 << 8, spread);
+        const uint32_t cnt = (uint32_t)__popcll(__ballot(cv <= slot));
+        uint32_t x, c_lo, c_hi;
+        if (__builtin_expect((win & 0x100u) != 0u && cnt - 1u < 63u, 1)) {
+            x = (uint32_t)base + cnt - 1u;
+            c_lo = read_lane(cv, cnt - 1u);
+            c_hi = read_lane(cv, cnt);
+        } else {
+            Found r = find_symbol_slow(me, inv_s, slot, m_bits, tab);
+            // keep the chain in scalar registers: the call returns through vector registers
+            x = uniform(r.x);
+            c_lo = uniform(r.c_lo);
+            c_hi = uniform(r.c_hi);
+        }
+        // App. A eq. (12)
+        S = (c_hi - c_lo) * (S >> m_bits) + slot - c_lo;
+        if (S < (1u << 16)) S = (S << 16) | rd.next();
+        return x;
+    };
+    // window for a mean: base = clamp(round(mean) - 31, 1, 192); the short evaluation needs
+    // |256*k - 128 - mean| <= 2^15 for k in the window, true when the unclamped base is in
+    // [-63, 255]
+    auto window_of = [](int me) -> uint32_t {
+        const int b0 = ((me + 128) >> 8) - 31;
+        const uint32_t ok = (uint32_t)(b0 + 63) <= 318u ? 0x100u : 0u;
+        return (uint32_t)min(max(b0, 1), 192) | ok;
+    };
 
     for (uint32_t t0 = 0; t0 < sh.npx; t0 += 64u) {
         const uint32_t nb = min(64u, sh.npx - t0);
@@ -111,60 +187,32 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_decode_wave(
         const size_t s = (size_t)p * 3;
         const uint32_t im = p / g.hw;
         const uint32_t v_m01 = (uint32_t)mu[s] | ((uint32_t)mu[s + 1] << 16);
-        const uint32_t v_m2 = mu[s + 2];
+        const uint32_t v_m2 = (uint32_t)mu[s + 2] | (window_of((int)mu[s]) << 16);
         const uint32_t v_i0 = inv_scale(ls[s], tab);
         const uint32_t v_i1 = inv_scale(ls[s + 1], tab);
         const uint32_t v_i2 = inv_scale(ls[s + 2], tab);
-        const uint32_t v_a01 = (uint32_t)(uint16_t)coef[3 * im] | ((uint32_t)(uint16_t)coef[3 * im + 1] << 16);
+        const uint32_t v_a01 =
+            (uint32_t)(uint16_t)coef[3 * im] | ((uint32_t)(uint16_t)coef[3 * im + 1] << 16);
         const uint32_t v_a2 = (uint32_t)(int)coef[3 * im + 2];
         uint32_t v_out = 0;
 
         // ---- serial part: one pixel after the other, all values wave-uniform ----
         for (uint32_t i = 0; i < nb; ++i) {
-            const uint32_t m01 = read_lane(v_m01, i);
-            const int m_r = (int)(m01 & 0xFFFFu), m_g = (int)(m01 >> 16);
-            const int m_b = (int)read_lane(v_m2, i);
+            const uint32_t m01 = read_lane(v_m01, i), m2w = read_lane(v_m2, i);
+            const int m_r = (int)(m01 & 0xFFFFu), m_g = (int)(m01 >> 16), m_b = (int)(m2w & 0xFFFFu);
             const uint32_t a01 = read_lane(v_a01, i);
-            const int a_gr = (int)(short)(a01 & 0xFFFFu), a_br = (int)(short)(a01 >> 16);
+            const int a_gr = (int)(short)(a01 & 0xFFFFu), a_br = (int)a01 >> 16;
             const int a_bg = (int)read_lane(v_a2, i);
-            uint32_t inv[3] = {read_lane(v_i0, i), read_lane(v_i1, i), read_lane(v_i2, i)};
-            int x[3] = {0, 0, 0};
-#pragma unroll
-            for (int c = 0; c < 3; ++c) {
-                int me = m_r;
-                if (c == 1) me = m_g + rsh14(a_gr * (x[0] * 256 - m_r));
-                if (c == 2) me = m_b + rsh14(a_br * (x[0] * 256 - m_r)) + rsh14(a_bg * (x[1] * 256 - m_g));
-                const uint32_t slot = S & mask;
-                // 64 candidates C(base + j); the symbol is base + (#candidates <= slot) - 1
-                int base = min(max(((me + 128) >> 8) - 31, 0), 193);
-                uint32_t cv, cnt;
-                for (;;) {
-                    const int k = base + (int)lane_id;
-                    cv = cum_inner(min(max(k, 1), 255), me, inv[c], spread, tab);
-                    cv = k <= 0 ? 0u : cv;
-                    cv = k >= 256 ? top : cv;
-                    cnt = (uint32_t)__popcll(__ballot(cv <= slot));
-                    if (cnt == 0u)
-                        base = max(base - 63, 0);      // C(0) = 0 <= slot ends this at base 0
-                    else if (cnt == 64u)
-                        base = min(base + 63, 193);    // C(256) = 2^M > slot ends this at base 193
-                    else
-                        break;
-                }
-                x[c] = base + (int)cnt - 1;
-                const uint32_t c_lo = read_lane(cv, cnt - 1u), c_hi = read_lane(cv, cnt);
-                // App. A eq. (12)
-                S = (c_hi - c_lo) * (S >> m_bits) + slot - c_lo;
-                if (S < (1u << 16)) {
-                    if (rd.pos < rd.stop) {
-                        S = (S << 16) | rd.next();
-                    } else {
-                        bad = true;
-                        S |= 1u << 16;
-                    }
-                }
-            }
-            v_out = write_lane((uint32_t)x[0] | ((uint32_t)x[1] << 8) | ((uint32_t)x[2] << 16), i, v_out);
+            const uint32_t i0 = read_lane(v_i0, i), i1 = read_lane(v_i1, i), i2 = read_lane(v_i2, i);
+
+            const uint32_t x_r = decode_symbol(m_r, m2w >> 16, i0, i0 >> 16, i0 & 0xFFFFu);
+            const int e_r = (int)(x_r << 8) - m_r;
+            const int me_g = m_g + rsh14(a_gr * e_r);
+            const uint32_t x_g = decode_symbol(me_g, window_of(me_g), i1, i1 >> 16, i1 & 0xFFFFu);
+            const int e_g = (int)(x_g << 8) - m_g;
+            const int me_b = m_b + rsh14(a_br * e_r) + rsh14(a_bg * e_g);
+            const uint32_t x_b = decode_symbol(me_b, window_of(me_b), i2, i2 >> 16, i2 & 0xFFFFu);
+            v_out = write_lane(x_r | (x_g << 8) | (x_b << 16), i, v_out);
         }
         if (valid) {
             out[s] = (uint8_t)v_out;
@@ -172,7 +220,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_decode_wave(
             out[s + 2] = (uint8_t)(v_out >> 16);
         }
     }
-    if ((bad || S != (1u << 16) || rd.pos != rd.stop) && lane_id == 0) atomicMax(status_code, 6);
+    if ((S != (1u << 16) || rd.pos != rd.stop) && lane_id == 0) atomicMax(status_code, 6);
 }
 
 // --------------------------------------------------------------------------------------------
