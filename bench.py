@@ -5,19 +5,34 @@ A step is one pass of the whole path over one batch of synthetic input: pilc_enc
 fixed-point CDF -> (cum,freq), rANS lanes, offset scan, pack) followed by pilc_decode of the
 container it produced.  Inputs are resident in HBM before the timed region starts.  Prints one
 JSON line.
+
+Besides the contract fields the line carries
+  roofline      dominant kernel of the step: algorithmic bytes / its HIP-event duration against
+                the 8 TB/s HBM peak, and `traffic` = HBM bytes of one launch read from two
+                rocprofv3 --pmc child runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same
+                counter reports for a plain device copy of known size in the same child run;
+  cpu_baseline  the CPU oracle timed on the host cores on a bounded prefix of the workload;
+  other_workloads  compress / decompress MB/s of the other single-GPU workloads (fewer steps).
 """
 from __future__ import annotations
 
 import argparse
+import csv
 import json
 import os
+import shutil
+import signal
+import subprocess
 import sys
+import tempfile
 import time
 from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+HERE = os.path.dirname(os.path.abspath(__file__))
+METRIC = "compress & decompress MB/s (raw uint8) on 1 MI355X; bits/subpixel"
 
 
 def parse_args():
@@ -30,11 +45,75 @@ def parse_args():
     ap.add_argument("--images", type=int, default=None, help="first N images only (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-images", type=int, default=None)
+    ap.add_argument("--no-traffic", action="store_true",
+                    help="skip the two rocprofv3 --pmc child runs that measure HBM traffic")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
+    ap.add_argument("--pmc-child", action="store_true",
+                    help="internal: one warm-up and one step plus a device copy, no report extras")
     return ap.parse_args()
 
 
+# ----------------------------------------------------------------------------------------------
+# HBM traffic from rocprofv3 counters (child processes, started before this process touches HIP)
+# ----------------------------------------------------------------------------------------------
+def _run_pmc(counter: str, config: int, images):
+    """Returns {kernel name prefix: [values in KiB per dispatch]} for one counter, or None."""
+    exe = shutil.which("rocprofv3") or "/opt/rocm/bin/rocprofv3"
+    if not os.path.exists(exe):
+        return None
+    out_dir = tempfile.mkdtemp(prefix="pilc_pmc_", dir="/tmp")
+    cmd = [exe, "--pmc", counter, "-d", out_dir, "-o", "pmc", "--output-format", "csv", "--",
+           sys.executable, os.path.join(HERE, "bench.py"), "--pmc-child", "--config", str(config)]
+    if images is not None:
+        cmd += ["--images", str(images)]
+    env = dict(os.environ, TMPDIR="/tmp")
+    try:
+        proc = subprocess.Popen(cmd, cwd="/tmp", env=env, stdout=subprocess.DEVNULL,
+                                stderr=subprocess.DEVNULL, start_new_session=True)
+        try:
+            proc.wait(timeout=240)
+        except subprocess.TimeoutExpired:
+            os.killpg(proc.pid, signal.SIGKILL)
+            proc.wait()
+            return None
+        if proc.returncode != 0:
+            return None
+        rows = {}
+        for root, _, files in os.walk(out_dir):
+            for f in files:
+                if f.endswith("counter_collection.csv"):
+                    with open(os.path.join(root, f)) as fh:
+                        for r in csv.DictReader(fh):
+                            if r["Counter_Name"] == counter:
+                                name = r["Kernel_Name"].split("(")[0]
+                                rows.setdefault(name, []).append(float(r["Counter_Value"]))
+        return rows
+    except OSError:
+        return None
+    finally:
+        shutil.rmtree(out_dir, ignore_errors=True)
+
+
+def measure_traffic(config: int, images):
+    """HBM bytes per launch of every pilc kernel: counter value (KiB) x 1024 x scale, where
+    scale = known bytes of a plain device copy / what the counter read for that copy."""
+    result = {}
+    for counter, key in (("FETCH_SIZE", "read"), ("WRITE_SIZE", "write")):
+        rows = _run_pmc(counter, config, images)
+        if not rows:
+            return None
+        copies = rows.get("__amd_rocclr_copyBuffer", [])
+        if not copies:
+            return None
+        result[key] = rows
+        result[key + "_copy_kib"] = max(copies)
+    return result
+
+
+# ----------------------------------------------------------------------------------------------
+# CPU baseline: the oracle as it stands
+# ----------------------------------------------------------------------------------------------
 def cpu_baseline(wl, sample_images):
-    """Times the oracle (as it stands) on a prefix of the same workload, on the host cores."""
     from oracle import pilc_oracle as orc
 
     n, h, w, m, mode, la, lb = wl.geom
@@ -70,8 +149,7 @@ def cpu_baseline(wl, sample_images):
         list(pool.map(dec, zip(jobs, coded)))
         t2 = time.perf_counter()
     raw_mb = k * hw * 3 / 1e6
-    # one core, on the first slab only
-    j0 = jobs[0]
+    j0 = jobs[0]  # one core, on the first slab only
     t3 = time.perf_counter()
     c0 = enc(j0)
     t4 = time.perf_counter()
@@ -88,6 +166,73 @@ def cpu_baseline(wl, sample_images):
     }
 
 
+# ----------------------------------------------------------------------------------------------
+# One workload on the GPU
+# ----------------------------------------------------------------------------------------------
+class Run:
+    def __init__(self, config, images):
+        import torch
+        from paper_2206_05279_amd import binding as pb
+        from paper_2206_05279_amd import synth
+
+        self.torch, self.pb = torch, pb
+        dev = torch.device("cuda:0")
+        t = time.perf_counter()
+        self.wl = wl = synth.make_workload(config, images)
+        self.gen_s = time.perf_counter() - t
+        self.geom = pb.make_geom(*wl.geom)
+        self.img = torch.from_numpy(wl.img).to(dev)
+        self.mu = torch.from_numpy(wl.mu).to(dev)
+        self.ls = torch.from_numpy(wl.log_scale).to(dev)
+        self.coef = torch.from_numpy(wl.chan_coef).to(dev)
+        ws_bytes, max_coded = pb.pilc_workspace_size(self.geom)
+        self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self.coded = torch.empty(max_coded, dtype=torch.uint8, device=dev)
+        self.out = torch.empty_like(self.img)
+        self.name = "cfg%d %s: %d x %dx%dx3 uint8, M=%d, %d lanes" % (
+            config, wl.name, wl.n, wl.h, wl.w, wl.prec_bits, pb.pilc_lane_count(self.geom))
+
+    def encode(self):
+        return self.pb.pilc_encode(self.geom, self.img, self.mu, self.ls, self.coef, self.workspace,
+                                   self.coded)[1]
+
+    def decode(self, nbytes):
+        self.pb.pilc_decode(self.geom, self.coded, nbytes, self.mu, self.ls, self.coef,
+                            self.workspace, self.out)
+
+    def timed(self, steps, warmup):
+        torch, pb = self.torch, self.pb
+        for _ in range(warmup):
+            self.decode(self.encode())
+        torch.cuda.synchronize()
+        # timed region: exactly `steps` steps; per-kernel HIP events are recorded inside the
+        # library on the stream the kernels are launched on
+        pb.pilc_set_timing(True)
+        kernel_ms, enc_ms, dec_ms = {}, 0.0, 0.0
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            nbytes = self.encode()
+            te = pb.pilc_last_timing()
+            self.decode(nbytes)
+            td = pb.pilc_last_timing()
+            enc_ms += te[0][1]
+            dec_ms += td[0][1]
+            for name, ms in te[1:] + td[1:]:
+                kernel_ms[name] = kernel_ms.get(name, 0.0) + ms
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        pb.pilc_set_timing(False)
+        raw = self.wl.subpixels
+        return {
+            "elapsed": elapsed, "nbytes": int(nbytes), "raw": raw,
+            "kernel_ms": {k: v / steps for k, v in kernel_ms.items()},
+            "compress_MB_s": raw / 1e6 / (enc_ms / steps * 1e-3),
+            "decompress_MB_s": raw / 1e6 / (dec_ms / steps * 1e-3),
+            "ok": bool(torch.equal(self.out, self.img)),
+        }
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -95,101 +240,99 @@ def main():
               "part of it", file=sys.stderr)
         sys.exit(2)
 
+    # children first: this process has not initialised HIP yet
+    traffic = None
+    if not (args.no_traffic or args.pmc_child):
+        traffic = measure_traffic(args.config, args.images)
+
     import torch
     from paper_2206_05279_amd import binding as pb
-    from paper_2206_05279_amd import synth
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     pb.lib()
-    dev = torch.device("cuda:0")
-    t_gen = time.perf_counter()
-    wl = synth.make_workload(args.config, args.images)
-    t_gen = time.perf_counter() - t_gen
-    geom = pb.make_geom(*wl.geom)
-    img = torch.from_numpy(wl.img).to(dev)
-    mu = torch.from_numpy(wl.mu).to(dev)
-    ls = torch.from_numpy(wl.log_scale).to(dev)
-    coef = torch.from_numpy(wl.chan_coef).to(dev)
-    ws_bytes, max_coded = pb.pilc_workspace_size(geom)
-    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    coded = torch.empty(max_coded, dtype=torch.uint8, device=dev)
-    out = torch.empty_like(img)
-    raw_bytes = wl.subpixels
 
-    def step():
-        _, nb = pb.pilc_encode(geom, img, mu, ls, coef, workspace, coded)
-        pb.pilc_decode(geom, coded, nb, mu, ls, coef, workspace, out)
-        return nb
-
-    for _ in range(args.warmup):
-        nbytes = step()
-    torch.cuda.synchronize()
-    if args.warmup and not torch.equal(out, img):
-        print("bench.py: round trip mismatch", file=sys.stderr)
-        sys.exit(4)
-
-    # timed region: exactly --steps steps; per-kernel HIP events are recorded inside the library
-    # on the stream the kernels are launched on
-    pb.pilc_set_timing(True)
-    kernel_ms = {}
-    enc_ms = dec_ms = 0.0
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        _, nbytes = pb.pilc_encode(geom, img, mu, ls, coef, workspace, coded)
-        te = pb.pilc_last_timing()
-        pb.pilc_decode(geom, coded, nbytes, mu, ls, coef, workspace, out)
-        td = pb.pilc_last_timing()
-        enc_ms += te[0][1]
-        dec_ms += td[0][1]
-        for name, ms in te[1:] + td[1:]:
-            kernel_ms[name] = kernel_ms.get(name, 0.0) + ms
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    pb.pilc_set_timing(False)
-    ok = bool(torch.equal(out, img))
-
-    ms_per_step = 1e3 * elapsed / args.steps
-    kernel_ms = {k: v / args.steps for k, v in kernel_ms.items()}
+    run = Run(args.config, args.images)
+    if args.pmc_child:
+        run.timed(1, 1)
+        probe = torch.empty_like(run.mu)   # plain device copy of known size: 2 bytes/subpixel
+        probe.copy_(run.mu)
+        torch.cuda.synchronize()
+        return
+    r = run.timed(args.steps, args.warmup)
+    raw_bytes, nbytes, kernel_ms = r["raw"], r["nbytes"], r["kernel_ms"]
     dom = max(kernel_ms, key=kernel_ms.get)
     # algorithmic bytes of one launch of either lane kernel: 1 B pixel + 2 B mu + 2 B log-scale per
     # subpixel, plus the container (payload + offset table + header)
     algo_bytes = 5.0 * raw_bytes + nbytes
     achieved = algo_bytes / (kernel_ms[dom] * 1e-3) / 1e9
+    traffic_bytes, traffic_detail = None, None
+    if traffic:
+        copy_bytes = 2.0 * raw_bytes  # the probe copies the mu tensor
+        detail = {}
+        for key in ("read", "write"):
+            scale = copy_bytes / (traffic[key + "_copy_kib"] * 1024.0)
+            vals = [v for name, rows in traffic[key].items() if name.endswith("::" + dom) for v in rows]
+            if vals:
+                detail[key + "_bytes"] = sum(vals) / len(vals) * 1024.0 * scale
+                detail[key + "_scale"] = scale
+        if "read_bytes" in detail and "write_bytes" in detail:
+            traffic_bytes = detail["read_bytes"] + detail["write_bytes"]
+            traffic_detail = detail
     result = {
-        "metric": "compress & decompress MB/s (raw uint8) on 1 MI355X; bits/subpixel",
-        "value": raw_bytes / 1e6 / (elapsed / args.steps),
+        "metric": METRIC,
+        "value": raw_bytes / 1e6 / (r["elapsed"] / args.steps),
         "unit": "MB/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": 1e3 * r["elapsed"] / args.steps,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "u32",
         "data": "synthetic",
-        "config": {"workload": "cfg%d %s: %d x %dx%dx3 uint8, M=%d, %d lanes" % (
-            args.config, wl.name, wl.n, wl.h, wl.w, wl.prec_bits, pb.pilc_lane_count(geom)),
-            "step": "pilc_encode + pilc_decode of the whole batch"},
-        "compress_MB_s": raw_bytes / 1e6 / (enc_ms / args.steps * 1e-3),
-        "decompress_MB_s": raw_bytes / 1e6 / (dec_ms / args.steps * 1e-3),
+        "config": {"workload": run.name, "step": "pilc_encode + pilc_decode of the whole batch"},
+        "compress_MB_s": r["compress_MB_s"],
+        "decompress_MB_s": r["decompress_MB_s"],
         "bits_per_subpixel": 8.0 * nbytes / raw_bytes,
-        "coded_bytes": int(nbytes),
-        "round_trip_exact": ok,
+        "coded_bytes": nbytes,
+        "round_trip_exact": r["ok"],
         "kernel_ms": kernel_ms,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "algorithmic_bytes": algo_bytes, "avg_ms": kernel_ms[dom]},
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_bytes,
+                     "traffic_detail": traffic_detail, "algorithmic_bytes": algo_bytes,
+                     "avg_ms": kernel_ms[dom]},
         "paper_context": "PILC reports about 200 MB/s end to end and 675/672 MB/s for its coder "
                          "phases on one V100 (table-driven coder, different workload)",
-        "input_generation_s": t_gen,
+        "input_generation_s": run.gen_s,
     }
+    ok = r["ok"]
     if not args.no_cpu_baseline:
         sample = args.cpu_sample_images or {0: 64, 1: 21504, 2: 5376, 3: 10, 4: 336}[args.config]
-        result["cpu_baseline"] = cpu_baseline(wl, sample)
+        result["cpu_baseline"] = cpu_baseline(run.wl, sample)
+    if not args.no_extra and args.images is None:
+        extra = {}
+        del run
+        torch.cuda.empty_cache()
+        for cfg in (2, 3):
+            if cfg == args.config:
+                continue
+            other = Run(cfg, None)
+            o = other.timed(max(2, args.steps // 3), 1)
+            dk = max(o["kernel_ms"], key=o["kernel_ms"].get)
+            ab = 5.0 * o["raw"] + o["nbytes"]
+            extra[other.name] = {
+                "compress_MB_s": o["compress_MB_s"], "decompress_MB_s": o["decompress_MB_s"],
+                "bits_per_subpixel": 8.0 * o["nbytes"] / o["raw"], "round_trip_exact": o["ok"],
+                "kernel_ms": o["kernel_ms"],
+                "dominant_kernel_hbm_frac": ab / (o["kernel_ms"][dk] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            }
+            ok = ok and o["ok"]
+            del other
+            torch.cuda.empty_cache()
+        result["other_workloads"] = extra
     print(json.dumps(result))
     if not ok:
         sys.exit(4)

@@ -119,7 +119,7 @@ int pilc_symbol_tables(const pilc_geom *geom, const uint8_t *img_dev, const pilc
  * kernel with HIP events on the stream the kernel is launched on.  pilc_last_timing returns
  * the durations in milliseconds of the most recent call on the calling thread: index 0 is
  * the whole GPU part of the call, 1.. are its kernels in launch order (pilc_timing_name
- * gives their names).  Returns the number of entries written (<= capacity), 0 if timing
+ * gives the kernel's function name; "scan" covers the three scan kernels).  Returns the number of entries written (<= capacity), 0 if timing
  * was off. */
 void pilc_set_timing(int enabled);
 int pilc_last_timing(float *ms_out_host, int capacity);

@@ -731,7 +731,8 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
 
     Timer timer(stream);
     k_init_status<<<1, 1, 0, stream>>>(status);
-    if (use_wave_kernels(g)) {
+    const bool few_lanes = use_wave_kernels(g);
+    if (few_lanes) {
         k_encode_block<<<(uint32_t)ceil_div64(g.lanes, kEncLanes), kEncThreads, 0, stream>>>(
             g, img_dev, params->mu, params->log_scale, params->chan_coef, scratch, g.total_px * 3u,
             lane_words, lane_state);
@@ -741,7 +742,7 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
             g, img_dev, params->mu, params->log_scale, params->chan_coef, scratch, lane_words,
             lane_state);
     }
-    timer.mark("encode_lanes");
+    timer.mark(few_lanes ? "k_encode_block" : "k_encode_lanes");
     k_scan_partials<<<ws.scan_blocks, kScanThreads, 0, stream>>>(g.lanes, lane_words, sums);
     k_scan_spine<<<1, kScanThreads, 0, stream>>>(g, ws.scan_blocks, sums, coded_dev,
                                                  (unsigned long long)coded_capacity, status);
@@ -754,7 +755,7 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
     const uint32_t pack_blocks = (uint32_t)ceil_div64(pack_bytes / 2, kPackWords);
     if (pack_blocks)
         k_pack<<<pack_blocks, 256, 0, stream>>>(g, scratch, lane_state, offsets, payload, status);
-    timer.mark("pack");
+    timer.mark("k_pack");
     HIP_TRY(hipGetLastError());
     Status host_status;
     HIP_TRY(hipMemcpyAsync(&host_status, status, sizeof(Status), hipMemcpyDeviceToHost, stream));
@@ -785,8 +786,9 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
 
     Timer timer(stream);
     k_check_header<<<1, 1, 0, stream>>>(g, coded_dev, (unsigned long long)coded_bytes, status);
-    timer.mark("check_header");
-    if (use_wave_kernels(g)) {
+    timer.mark("k_check_header");
+    const bool few_lanes = use_wave_kernels(g);
+    if (few_lanes) {
         k_decode_wave<<<(uint32_t)ceil_div64(g.lanes, kWavesPerBlock), 64 * kWavesPerBlock, 0, stream>>>(
             g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev,
             &status->code, &status->payload_bytes);
@@ -795,7 +797,7 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
         k_decode_lanes<<<(uint32_t)ceil_div64(g.lanes, bt), bt, 0, stream>>>(
             g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev, status);
     }
-    timer.mark("decode_lanes");
+    timer.mark(few_lanes ? "k_decode_wave" : "k_decode_lanes");
     HIP_TRY(hipGetLastError());
     Status host_status;
     HIP_TRY(hipMemcpyAsync(&host_status, status, sizeof(Status), hipMemcpyDeviceToHost, stream));
