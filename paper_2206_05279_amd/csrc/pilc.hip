@@ -433,22 +433,38 @@ __global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
 
 #include "pilc_wave_kernels.hpp"
 #include "pilc_block_encode.hpp"
+#include "pilc_group_decode.hpp"
 
 namespace pilc {
 
 // --------------------------------------------------------------------------------------------
 // Host side
 // --------------------------------------------------------------------------------------------
-static int g_kernel_policy = 0;  // 0 auto, 1 thread per lane, 2 wavefront per lane
+// 0 auto, 1 thread per lane, 2 few-lane kernels; 3/4/5 few-lane with 64/32/16 threads per lane
+// in decode, 6 few-lane with the scalar-state wave-per-lane decoder
+static int g_kernel_policy = 0;
 
 // A wavefront per lane pays off while there are too few lanes to fill the chip with one thread
 // each (256 CUs x 4 SIMDs x 64 threads = 65,536 threads for a single wave per SIMD).
 static bool use_wave_kernels(const Geo &g)
 {
     if (g_kernel_policy == 1) return false;
-    if (g_kernel_policy == 2) return true;
+    if (g_kernel_policy >= 2) return true;
     return g.lanes <= 16384u;
 }
+
+// Threads per lane of the few-lane decoder: enough lanes per wavefront that no SIMD has to host
+// more than two wavefronts (1024 SIMDs), as few as possible otherwise (wider candidate windows).
+static int decode_group_size(const Geo &g)
+{
+    if (g_kernel_policy == 3) return 64;
+    if (g_kernel_policy == 4) return 32;
+    if (g_kernel_policy == 5) return 16;
+    if (g.lanes <= 2048u) return 64;
+    if (g.lanes <= 4096u) return 32;
+    return 16;
+}
+
 thread_local char t_hip_error[256] = "";
 thread_local float t_timing_ms[16];
 thread_local const char *t_timing_name[16];
@@ -642,7 +658,7 @@ void pilc_set_timing(int enabled) { g_timing_enabled = enabled; }
 
 int pilc_set_kernel_policy(int policy)
 {
-    if (policy < 0 || policy > 2) return PILC_E_ARG;
+    if (policy < 0 || policy > 6) return PILC_E_ARG;
     g_kernel_policy = policy;
     return PILC_OK;
 }
@@ -789,15 +805,32 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
     timer.mark("k_check_header");
     const bool few_lanes = use_wave_kernels(g);
     if (few_lanes) {
-        k_decode_wave<<<(uint32_t)ceil_div64(g.lanes, kWavesPerBlock), 64 * kWavesPerBlock, 0, stream>>>(
-            g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev,
-            &status->code, &status->payload_bytes);
+        const int gs = decode_group_size(g);
+        const uint32_t waves = (uint32_t)ceil_div64(g.lanes, 64 / gs);
+        const uint32_t blocks = (uint32_t)ceil_div64(waves, kGroupWavesPerBlock);
+        const int bt = 64 * kGroupWavesPerBlock;
+        if (g_kernel_policy == 6)
+            k_decode_wave<<<(uint32_t)ceil_div64(g.lanes, kWavesPerBlock), 64 * kWavesPerBlock, 0, stream>>>(
+                g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev,
+                &status->code, &status->payload_bytes);
+        else if (gs == 64)
+            k_decode_group<64><<<blocks, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
+                                                          params->chan_coef, img_out_dev, &status->code,
+                                                          &status->payload_bytes);
+        else if (gs == 32)
+            k_decode_group<32><<<blocks, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
+                                                          params->chan_coef, img_out_dev, &status->code,
+                                                          &status->payload_bytes);
+        else
+            k_decode_group<16><<<blocks, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
+                                                          params->chan_coef, img_out_dev, &status->code,
+                                                          &status->payload_bytes);
     } else {
         const int bt = lane_block_threads(g);
         k_decode_lanes<<<(uint32_t)ceil_div64(g.lanes, bt), bt, 0, stream>>>(
             g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev, status);
     }
-    timer.mark(few_lanes ? "k_decode_wave" : "k_decode_lanes");
+    timer.mark(few_lanes ? (g_kernel_policy == 6 ? "k_decode_wave" : "k_decode_group") : "k_decode_lanes");
     HIP_TRY(hipGetLastError());
     Status host_status;
     HIP_TRY(hipMemcpyAsync(&host_status, status, sizeof(Status), hipMemcpyDeviceToHost, stream));
