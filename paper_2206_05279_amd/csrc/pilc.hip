@@ -5,6 +5,8 @@
 //           -> 3-step prefix scan of lane byte counts (offset table + header)
 //           -> pack (lane streams copied to their offsets)
 //   decode: header check -> lane kernel (search of the symbol, state update, refill)
+// Lane kernels: pilc_lane_kernels.hpp (thread per lane), pilc_block_encode.hpp and
+// pilc_group_decode.hpp / pilc_wave_kernels.hpp (few long lanes).
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -22,7 +24,6 @@ __device__ uint32_t g_exp_hi[kExpHiEntries];
 __device__ uint32_t g_exp_lo[kExpLoEntries];
 
 constexpr uint32_t kHeaderBytes = 64;
-constexpr uint32_t kRansLow = 1u << 16;
 
 // status word kinds (device side), mapped to PILC_E_* on the host
 enum : int { ST_OK = 0, ST_TOO_LARGE = 4, ST_FORMAT = 5, ST_CORRUPT = 6, ST_CAPACITY = 3 };
@@ -72,82 +73,6 @@ __global__ void k_symbol_tables(Geo g, const uint8_t *__restrict__ img,
         cum_out[s + c] = lo;
         freq_out[s + c] = hi - lo;
     }
-}
-
-// --------------------------------------------------------------------------------------------
-// Encode, one thread per lane.  Symbols are pushed last-first (App. A eq. (11)); the 16-bit
-// words go to the lane's scratch slot from its end downwards, so that they finish in the
-// order the decoder reads them.
-// --------------------------------------------------------------------------------------------
-__global__ void k_encode_lanes(Geo g, const uint8_t *__restrict__ img,
-                               const uint16_t *__restrict__ mu, const int16_t *__restrict__ ls,
-                               const int16_t *__restrict__ coef, uint16_t *__restrict__ scratch,
-                               uint32_t *__restrict__ lane_words, uint32_t *__restrict__ lane_state)
-{
-    __shared__ LdsTables tab;
-    load_tables(tab);
-    uint32_t lane = blockIdx.x * blockDim.x + threadIdx.x;
-    if (lane >= g.lanes) return;
-    const LaneShape sh = lane_shape(g, lane);
-    const uint32_t m_bits = g.prec_bits;
-    const uint32_t spread = (1u << m_bits) - 256u;
-
-    // last pixel of the lane
-    uint32_t rows = sh.npx / sh.tw;
-    uint32_t col = sh.tw - 1;
-    uint32_t p = sh.first + (rows - 1) * g.w + col;
-    uint32_t im = p / g.hw;
-    uint32_t left_in_img = p - im * g.hw;  // pixels before p inside its image
-    int a_gr = coef[3 * im], a_br = coef[3 * im + 1], a_bg = coef[3 * im + 2];
-
-    uint16_t *wp = scratch + (size_t)sh.sym_base + 3u * sh.npx;  // one past the slot end
-    uint32_t nwords = 0;
-    uint32_t S = kRansLow;
-
-    for (uint32_t t = 0; t < sh.npx; ++t) {
-        size_t s = (size_t)p * 3;
-        int x[3] = {img[s], img[s + 1], img[s + 2]};
-        int m[3] = {mu[s], mu[s + 1], mu[s + 2]};
-        int me[3];
-        mean_shift(x, m, a_gr, a_br, a_bg, me);
-#pragma unroll
-        for (int c = 2; c >= 0; --c) {
-            uint32_t inv_s = inv_scale(ls[s + c], tab);
-            uint32_t lo = x[c] == 0 ? 0u : cum_inner(x[c], me[c], inv_s, spread, tab);
-            uint32_t hi = x[c] == 255 ? (1u << m_bits) : cum_inner(x[c] + 1, me[c], inv_s, spread, tab);
-            uint32_t f = hi - lo;
-            if (S >= (f << (32 - m_bits))) {
-                *--wp = (uint16_t)(S & 0xFFFFu);
-                ++nwords;
-                S >>= 16;
-            }
-            uint32_t q = S / f;
-            S = (q << m_bits) + (S - q * f) + lo;
-        }
-        // step to the previous pixel of the lane
-        if (col == 0) {
-            col = sh.tw - 1;
-            p -= g.w - sh.tw + 1;
-            // (only tile lanes have several rows, and a tile never leaves its image)
-            left_in_img -= g.w - sh.tw + 1;
-        } else {
-            --col;
-            --p;
-            if (left_in_img == 0) {
-                if (t + 1 < sh.npx) {
-                    --im;
-                    left_in_img = g.hw - 1;
-                    a_gr = coef[3 * im];
-                    a_br = coef[3 * im + 1];
-                    a_bg = coef[3 * im + 2];
-                }
-            } else {
-                --left_in_img;
-            }
-        }
-    }
-    lane_words[lane] = nwords;
-    lane_state[lane] = S;
 }
 
 // --------------------------------------------------------------------------------------------
@@ -336,101 +261,9 @@ __global__ void k_check_header(Geo g, const uint8_t *__restrict__ coded,
     status->payload_bytes = payload;
 }
 
-__global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
-                               const uint16_t *__restrict__ mu, const int16_t *__restrict__ ls,
-                               const int16_t *__restrict__ coef, uint8_t *__restrict__ out,
-                               Status *__restrict__ status)
-{
-    __shared__ LdsTables tab;
-    load_tables(tab);
-    if (status->code != ST_OK) return;  // uniform: written by an earlier kernel
-    uint32_t lane = blockIdx.x * blockDim.x + threadIdx.x;
-    if (lane >= g.lanes) return;
-    const LaneShape sh = lane_shape(g, lane);
-    const uint32_t m_bits = g.prec_bits;
-    const uint32_t spread = (1u << m_bits) - 256u;
-    const uint32_t mask = (1u << m_bits) - 1u;
-    const uint32_t payload_bytes = (uint32_t)status->payload_bytes;
-
-    const uint32_t *offsets = reinterpret_cast<const uint32_t *>(coded + kHeaderBytes);
-    const uint16_t *payload =
-        reinterpret_cast<const uint16_t *>(coded + kHeaderBytes + 4ull * ((size_t)g.lanes + 1));
-    uint32_t begin = offsets[lane], end = offsets[lane + 1];
-    if (end < begin || end > payload_bytes || end - begin < 4u || ((begin | end) & 1u)) {
-        atomicMax(&status->code, (int)ST_CORRUPT);
-        return;
-    }
-    uint32_t pos = begin >> 1, stop = end >> 1;  // in 16-bit words
-    uint32_t S = (uint32_t)payload[pos] | ((uint32_t)payload[pos + 1] << 16);
-    pos += 2;
-    bool bad = false;
-
-    uint32_t p = sh.first, col = 0;
-    uint32_t im = p / g.hw;
-    uint32_t left_in_img = g.hw - (p - im * g.hw);  // pixels from p to the end of its image
-    int a_gr = coef[3 * im], a_br = coef[3 * im + 1], a_bg = coef[3 * im + 2];
-
-    for (uint32_t t = 0; t < sh.npx; ++t) {
-        size_t s = (size_t)p * 3;
-        int m[3] = {mu[s], mu[s + 1], mu[s + 2]};
-        int x[3] = {0, 0, 0};
-        int me = m[0];
-#pragma unroll
-        for (int c = 0; c < 3; ++c) {
-            if (c == 1) me = m[1] + rsh14(a_gr * (x[0] * 256 - m[0]));
-            if (c == 2) me = m[2] + rsh14(a_br * (x[0] * 256 - m[0])) + rsh14(a_bg * (x[1] * 256 - m[1]));
-            uint32_t inv_s = inv_scale(ls[s + c], tab);
-            uint32_t slot = S & mask;
-            // the value v with C(v) <= slot < C(v+1), by bisection on v
-            int lo = 0, hi = 256;
-            uint32_t c_lo = 0u, c_hi = 1u << m_bits;
-#pragma unroll
-            for (int it = 0; it < 8; ++it) {
-                int mid = (lo + hi) >> 1;
-                uint32_t cm = cum_inner(mid, me, inv_s, spread, tab);
-                bool ge = cm <= slot;
-                lo = ge ? mid : lo;
-                c_lo = ge ? cm : c_lo;
-                hi = ge ? hi : mid;
-                c_hi = ge ? c_hi : cm;
-            }
-            x[c] = lo;
-            // App. A eq. (12)
-            S = (c_hi - c_lo) * (S >> m_bits) + slot - c_lo;
-            if (S < kRansLow) {
-                if (pos < stop) {
-                    S = (S << 16) | payload[pos];
-                    ++pos;
-                } else {
-                    bad = true;
-                    S |= kRansLow;  // keep the state in range; the lane is already condemned
-                }
-            }
-        }
-        out[s] = (uint8_t)x[0];
-        out[s + 1] = (uint8_t)x[1];
-        out[s + 2] = (uint8_t)x[2];
-        // step to the next pixel of the lane
-        ++col;
-        if (col == sh.tw) {
-            col = 0;
-            p += g.w - sh.tw + 1;
-        } else {
-            ++p;
-        }
-        if (--left_in_img == 0 && t + 1 < sh.npx && g.lane_mode == 0) {
-            ++im;
-            left_in_img = g.hw;
-            a_gr = coef[3 * im];
-            a_br = coef[3 * im + 1];
-            a_bg = coef[3 * im + 2];
-        }
-    }
-    if (bad || S != kRansLow || pos != stop) atomicMax(&status->code, (int)ST_CORRUPT);
-}
-
 }  // namespace pilc
 
+#include "pilc_lane_kernels.hpp"
 #include "pilc_wave_kernels.hpp"
 #include "pilc_block_encode.hpp"
 #include "pilc_group_decode.hpp"
@@ -627,6 +460,16 @@ struct Timer {
     }
 };
 
+// True when every 8-pixel chunk of every lane starts at a multiple of 8 pixels, never straddles
+// two images, and the arrays allow 16-byte (parameters) / 8-byte (pixels) vector accesses.
+static bool chunks_aligned(const Geo &g, const void *img, const pilc_params *p)
+{
+    const bool geo = g.lane_mode == 0 ? (g.lane_a % 8 == 0 && g.hw % 8 == 0)
+                                      : (g.w % 8 == 0 && g.lane_b % 8 == 0);
+    return geo && ((uintptr_t)img & 7) == 0 && ((uintptr_t)p->mu & 15) == 0 &&
+           ((uintptr_t)p->log_scale & 15) == 0;
+}
+
 static int lane_block_threads(const Geo &g) { return g.lanes >= (1u << 18) ? 256 : 64; }
 
 }  // namespace pilc
@@ -754,9 +597,13 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
             lane_words, lane_state);
     } else {
         const int bt = lane_block_threads(g);
-        k_encode_lanes<<<(uint32_t)ceil_div64(g.lanes, bt), bt, 0, stream>>>(
-            g, img_dev, params->mu, params->log_scale, params->chan_coef, scratch, lane_words,
-            lane_state);
+        const uint32_t nb = (uint32_t)ceil_div64(g.lanes, bt);
+        if (chunks_aligned(g, img_dev, params))
+            k_encode_lanes<true><<<nb, bt, 0, stream>>>(g, img_dev, params->mu, params->log_scale,
+                                                        params->chan_coef, scratch, lane_words, lane_state);
+        else
+            k_encode_lanes<false><<<nb, bt, 0, stream>>>(g, img_dev, params->mu, params->log_scale,
+                                                         params->chan_coef, scratch, lane_words, lane_state);
     }
     timer.mark(few_lanes ? "k_encode_block" : "k_encode_lanes");
     k_scan_partials<<<ws.scan_blocks, kScanThreads, 0, stream>>>(g.lanes, lane_words, sums);
@@ -827,8 +674,15 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
                                                           &status->payload_bytes);
     } else {
         const int bt = lane_block_threads(g);
-        k_decode_lanes<<<(uint32_t)ceil_div64(g.lanes, bt), bt, 0, stream>>>(
-            g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev, status);
+        const uint32_t nb = (uint32_t)ceil_div64(g.lanes, bt);
+        if (chunks_aligned(g, img_out_dev, params))
+            k_decode_lanes<true><<<nb, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
+                                                        params->chan_coef, img_out_dev, &status->code,
+                                                        &status->payload_bytes);
+        else
+            k_decode_lanes<false><<<nb, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
+                                                         params->chan_coef, img_out_dev, &status->code,
+                                                         &status->payload_bytes);
     }
     timer.mark(few_lanes ? (g_kernel_policy == 6 ? "k_decode_wave" : "k_decode_group") : "k_decode_lanes");
     HIP_TRY(hipGetLastError());

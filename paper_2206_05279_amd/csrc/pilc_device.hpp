@@ -92,15 +92,17 @@ __device__ __forceinline__ uint32_t inv_scale(int ls, const LdsTables &t)
 }
 
 // F(k) in 24 bits at the edge k - 1/2:  d = 256*k - 128 - mu'  (Q8.8), inv_s Q6.25 < 2^31.
+// z = clamp(floor(d * inv_s / 2^17), -2^20, 2^20 - 1) is taken from the 64-bit product as its bits
+// 17..48; it saturates exactly when the product's high word leaves [-32, 31].
 __device__ __forceinline__ uint32_t edge_cdf(int d, uint32_t inv_s, const LdsTables &t)
 {
-    long long p = (long long)d * (long long)(int)inv_s;  // Q.33
-    long long z = p >> 17;                               // Q.16, floor
-    z = z < -(1ll << 20) ? -(1ll << 20) : z;
-    z = z > (1ll << 20) - 1 ? (1ll << 20) - 1 : z;
-    uint32_t w = (uint32_t)((int)z + (1 << 20));
-    uint2 cell = t.sig[w >> 10];
-    return cell.x + ((cell.y * (w & 1023u)) >> 10);
+    const long long p = (long long)d * (long long)(int)inv_s;  // Q.33
+    const int hi = (int)(p >> 32);
+    int w = (int)__builtin_amdgcn_alignbit((uint32_t)hi, (uint32_t)p, 17) + (1 << 20);
+    w = hi >= 32 ? (1 << 21) - 1 : w;
+    w = hi < -32 ? 0 : w;
+    const uint2 cell = t.sig[(uint32_t)w >> 10];
+    return cell.x + (__umul24(cell.y, (uint32_t)w & 1023u) >> 10);
 }
 
 // C(k), 1 <= k <= 255:  k + floor(F(k) * (2^M - 256) / 2^24).

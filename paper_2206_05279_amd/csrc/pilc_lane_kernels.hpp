@@ -1,0 +1,272 @@
+// One thread per lane: the kernels for batches with many lanes (gfx950).
+//
+// Every thread walks its own lane (App. A eqs. (11)-(12) of arXiv 2206.05279 are serial per
+// lane), so neighbouring threads read memory a whole lane apart.  To keep the L2->L1 traffic
+// near the useful bytes, a lane is consumed in chunks of 8 pixels held in registers: when the
+// geometry keeps every chunk 8-pixel aligned (kVec) the 24 + 48 + 48 bytes of a chunk arrive as
+// 64- and 128-bit loads, and decoded pixels leave as 64-bit stores; otherwise, and for ragged
+// chunk tails, the same registers are filled element by element.
+#pragma once
+
+#include "pilc_device.hpp"
+
+namespace pilc {
+
+constexpr int kChunk = 8;  // pixels per chunk
+
+struct Chunk {
+    int x[kChunk][3];   // pixel values (encode)
+    int m[kChunk][3];   // mu, Q8.8
+    int l[kChunk][3];   // log-scale, Q4.12
+};
+
+__device__ __forceinline__ int byte_of(const uint32_t *w, int i) { return (w[i >> 2] >> (8 * (i & 3))) & 0xFF; }
+__device__ __forceinline__ int half_of(const uint32_t *w, int i) { return (w[i >> 1] >> (16 * (i & 1))) & 0xFFFF; }
+
+// Fills `c` with the pixels p .. p+len-1 (len <= 8).  kVec: p is a multiple of 8 and the arrays
+// are 16-byte aligned, so a full chunk is 3 x 8 bytes of pixels and 3 x 16 bytes of each parameter.
+template <bool kVec, bool kPixels>
+__device__ __forceinline__ void load_chunk(Chunk &c, uint32_t p, uint32_t len,
+                                           const uint8_t *__restrict__ img,
+                                           const uint16_t *__restrict__ mu,
+                                           const int16_t *__restrict__ ls)
+{
+    const size_t s = (size_t)p * 3;
+    if (kVec && len == (uint32_t)kChunk) {
+        uint32_t wm[12], wl[12];
+        const uint4 *pm = reinterpret_cast<const uint4 *>(mu + s);
+        const uint4 *pl = reinterpret_cast<const uint4 *>(ls + s);
+#pragma unroll
+        for (int q = 0; q < 3; ++q) {
+            const uint4 a = pm[q], b = pl[q];
+            wm[4 * q] = a.x; wm[4 * q + 1] = a.y; wm[4 * q + 2] = a.z; wm[4 * q + 3] = a.w;
+            wl[4 * q] = b.x; wl[4 * q + 1] = b.y; wl[4 * q + 2] = b.z; wl[4 * q + 3] = b.w;
+        }
+        uint32_t wx[6] = {0, 0, 0, 0, 0, 0};
+        if (kPixels) {
+            const uint2 *px = reinterpret_cast<const uint2 *>(img + s);
+#pragma unroll
+            for (int q = 0; q < 3; ++q) {
+                const uint2 a = px[q];
+                wx[2 * q] = a.x; wx[2 * q + 1] = a.y;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i)
+#pragma unroll
+            for (int ch = 0; ch < 3; ++ch) {
+                if (kPixels) c.x[i][ch] = byte_of(wx, 3 * i + ch);
+                c.m[i][ch] = half_of(wm, 3 * i + ch);
+                c.l[i][ch] = (int)(short)half_of(wl, 3 * i + ch);
+            }
+    } else {
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i)
+#pragma unroll
+            for (int ch = 0; ch < 3; ++ch) {
+                const bool in = (uint32_t)i < len;
+                const size_t e = in ? s + 3 * i + ch : s;
+                if (kPixels) c.x[i][ch] = img[e];
+                c.m[i][ch] = mu[e];
+                c.l[i][ch] = ls[e];
+            }
+    }
+}
+
+// floor(n / f) and the remainder for f < 2^16 and n / f < 2^22 (true after the renormalisation
+// of the encoder): a float estimate is within [-2, +1] of the quotient, then fixed up exactly.
+__device__ __forceinline__ uint32_t div_small(uint32_t n, uint32_t f, uint32_t &rem)
+{
+    uint32_t q = (uint32_t)((float)n * __builtin_amdgcn_rcpf((float)f));
+    int r = (int)(n - q * f);
+    if (r < 0) { r += (int)f; q -= 1u; }
+    if (r >= (int)f) { r -= (int)f; q += 1u; }
+    if (r >= (int)f) { r -= (int)f; q += 1u; }
+    rem = (uint32_t)r;
+    return q;
+}
+
+// Chunk c of a lane: rows of sh.tw pixels, g.w apart, each cut into pieces of 8 pixels.
+struct ChunkPos {
+    uint32_t p, len;
+};
+__device__ __forceinline__ ChunkPos chunk_pos(const Geo &g, const LaneShape &sh, uint32_t per_row,
+                                              uint32_t c)
+{
+    const uint32_t row = c / per_row, k = c - row * per_row;
+    ChunkPos r;
+    r.p = sh.first + row * g.w + k * kChunk;
+    r.len = min((uint32_t)kChunk, sh.tw - k * kChunk);
+    return r;
+}
+
+// --------------------------------------------------------------------------------------------
+// Encode.  Symbols are pushed last-first (App. A eq. (11)); the 16-bit words go to the lane's
+// scratch slot from its end downwards, so that they finish in the order the decoder reads them.
+// --------------------------------------------------------------------------------------------
+template <bool kVec>
+__global__ void k_encode_lanes(Geo g, const uint8_t *__restrict__ img,
+                               const uint16_t *__restrict__ mu, const int16_t *__restrict__ ls,
+                               const int16_t *__restrict__ coef, uint16_t *__restrict__ scratch,
+                               uint32_t *__restrict__ lane_words, uint32_t *__restrict__ lane_state)
+{
+    __shared__ LdsTables tab;
+    load_tables(tab);
+    const uint32_t lane = blockIdx.x * blockDim.x + threadIdx.x;
+    if (lane >= g.lanes) return;
+    const LaneShape sh = lane_shape(g, lane);
+    const uint32_t m_bits = g.prec_bits;
+    const uint32_t spread = (1u << m_bits) - 256u, top = 1u << m_bits;
+    const uint32_t per_row = (sh.tw + kChunk - 1) / kChunk;
+    const uint32_t chunks = per_row * (sh.npx / sh.tw);
+
+    const uint32_t slot_end = sh.sym_base + 3u * sh.npx;
+    uint32_t wpos = slot_end;
+    uint32_t S = 1u << 16;
+
+    for (uint32_t c = chunks; c-- > 0u;) {
+        const ChunkPos cp = chunk_pos(g, sh, per_row, c);
+        Chunk ck;
+        load_chunk<kVec, true>(ck, cp.p, cp.len, img, mu, ls);
+        // a chunk never straddles two images when kVec; otherwise take the image per pixel
+        uint32_t im = cp.p / g.hw;
+        int a_gr = coef[3 * im], a_br = coef[3 * im + 1], a_bg = coef[3 * im + 2];
+#pragma unroll
+        for (int i = kChunk - 1; i >= 0; --i) {
+            if ((uint32_t)i < cp.len) {
+                if (!kVec) {
+                    const uint32_t im_i = (cp.p + i) / g.hw;
+                    if (im_i != im) {
+                        im = im_i;
+                        a_gr = coef[3 * im]; a_br = coef[3 * im + 1]; a_bg = coef[3 * im + 2];
+                    }
+                }
+                const int e_r = ck.x[i][0] * 256 - ck.m[i][0], e_g = ck.x[i][1] * 256 - ck.m[i][1];
+                const int me[3] = {ck.m[i][0], ck.m[i][1] + rsh14(a_gr * e_r),
+                                   ck.m[i][2] + rsh14(a_br * e_r) + rsh14(a_bg * e_g)};
+#pragma unroll
+                for (int ch = 2; ch >= 0; --ch) {
+                    const int x = ck.x[i][ch];
+                    const uint32_t inv_s = inv_scale(ck.l[i][ch], tab);
+                    const uint32_t lo = x == 0 ? 0u : cum_inner(x, me[ch], inv_s, spread, tab);
+                    const uint32_t hi = x == 255 ? top : cum_inner(x + 1, me[ch], inv_s, spread, tab);
+                    const uint32_t f = hi - lo;
+                    if (S >= (f << (32u - m_bits))) {
+                        scratch[--wpos] = (uint16_t)(S & 0xFFFFu);
+                        S >>= 16;
+                    }
+                    uint32_t rem;
+                    const uint32_t q = div_small(S, f, rem);
+                    S = (q << m_bits) + rem + lo;
+                }
+            }
+        }
+    }
+    lane_words[lane] = slot_end - wpos;
+    lane_state[lane] = S;
+}
+
+// --------------------------------------------------------------------------------------------
+// Decode.  The symbol is found by an 8-step bisection on C(k) (App. A: "binary search").
+// --------------------------------------------------------------------------------------------
+template <bool kVec>
+__global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
+                               const uint16_t *__restrict__ mu, const int16_t *__restrict__ ls,
+                               const int16_t *__restrict__ coef, uint8_t *__restrict__ out,
+                               int *__restrict__ status_code,
+                               const unsigned long long *__restrict__ status_payload)
+{
+    __shared__ LdsTables tab;
+    load_tables(tab);
+    if (*status_code != 0) return;  // uniform: written by an earlier kernel
+    const uint32_t lane = blockIdx.x * blockDim.x + threadIdx.x;
+    if (lane >= g.lanes) return;
+    const LaneShape sh = lane_shape(g, lane);
+    const uint32_t m_bits = g.prec_bits;
+    const uint32_t spread = (1u << m_bits) - 256u, mask = (1u << m_bits) - 1u;
+    const uint32_t payload_bytes = (uint32_t)*status_payload;
+    const uint32_t per_row = (sh.tw + kChunk - 1) / kChunk;
+    const uint32_t chunks = per_row * (sh.npx / sh.tw);
+
+    const uint32_t *offsets = reinterpret_cast<const uint32_t *>(coded + 64);
+    const uint16_t *payload =
+        reinterpret_cast<const uint16_t *>(coded + 64 + 4ull * ((size_t)g.lanes + 1));
+    const uint32_t begin = offsets[lane], end = offsets[lane + 1];
+    if (end < begin || end > payload_bytes || end - begin < 4u || ((begin | end) & 1u)) {
+        atomicMax(status_code, 6);
+        return;
+    }
+    uint32_t pos = begin >> 1;
+    const uint32_t stop = end >> 1;  // in 16-bit words
+    uint32_t S = (uint32_t)payload[pos] | ((uint32_t)payload[pos + 1] << 16);
+    pos += 2;
+
+    for (uint32_t c = 0; c < chunks; ++c) {
+        const ChunkPos cp = chunk_pos(g, sh, per_row, c);
+        Chunk ck;
+        load_chunk<kVec, false>(ck, cp.p, cp.len, nullptr, mu, ls);
+        uint32_t im = cp.p / g.hw;
+        int a_gr = coef[3 * im], a_br = coef[3 * im + 1], a_bg = coef[3 * im + 2];
+        uint32_t wout[6] = {0, 0, 0, 0, 0, 0};  // the chunk's 24 decoded bytes
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i) {
+            if ((uint32_t)i < cp.len) {
+                if (!kVec) {
+                    const uint32_t im_i = (cp.p + i) / g.hw;
+                    if (im_i != im) {
+                        im = im_i;
+                        a_gr = coef[3 * im]; a_br = coef[3 * im + 1]; a_bg = coef[3 * im + 2];
+                    }
+                }
+                int x[3] = {0, 0, 0};
+#pragma unroll
+                for (int ch = 0; ch < 3; ++ch) {
+                    int me = ck.m[i][0];
+                    if (ch == 1) me = ck.m[i][1] + rsh14(a_gr * (x[0] * 256 - ck.m[i][0]));
+                    if (ch == 2)
+                        me = ck.m[i][2] + rsh14(a_br * (x[0] * 256 - ck.m[i][0])) +
+                             rsh14(a_bg * (x[1] * 256 - ck.m[i][1]));
+                    const uint32_t inv_s = inv_scale(ck.l[i][ch], tab);
+                    const uint32_t slot = S & mask;
+                    int lo = 0, hi = 256;
+                    uint32_t c_lo = 0u, c_hi = 1u << m_bits;
+#pragma unroll
+                    for (int it = 0; it < 8; ++it) {
+                        const int mid = (lo + hi) >> 1;
+                        const uint32_t cm = cum_inner(mid, me, inv_s, spread, tab);
+                        const bool ge = cm <= slot;
+                        lo = ge ? mid : lo;
+                        c_lo = ge ? cm : c_lo;
+                        hi = ge ? hi : mid;
+                        c_hi = ge ? c_hi : cm;
+                    }
+                    x[ch] = lo;
+                    // App. A eq. (12)
+                    S = (c_hi - c_lo) * (S >> m_bits) + slot - c_lo;
+                    if (S < (1u << 16)) {
+                        // a lane that runs past its end reads zeros and fails the final check
+                        const uint32_t wd = pos < stop ? (uint32_t)payload[pos] : 0u;
+                        S = (S << 16) | wd;
+                        ++pos;
+                    }
+                    const int b = 3 * i + ch;
+                    wout[b >> 2] |= (uint32_t)lo << (8 * (b & 3));
+                }
+            }
+        }
+        const size_t s = (size_t)cp.p * 3;
+        if (kVec && cp.len == (uint32_t)kChunk) {
+            uint2 *po = reinterpret_cast<uint2 *>(out + s);
+            po[0] = make_uint2(wout[0], wout[1]);
+            po[1] = make_uint2(wout[2], wout[3]);
+            po[2] = make_uint2(wout[4], wout[5]);
+        } else {
+#pragma unroll
+            for (int b = 0; b < 3 * kChunk; ++b)
+                if ((uint32_t)b < 3u * cp.len) out[s + b] = (uint8_t)(wout[b >> 2] >> (8 * (b & 3)));
+        }
+    }
+    if (S != (1u << 16) || pos != stop) atomicMax(status_code, 6);
+}
+
+}  // namespace pilc
