@@ -470,7 +470,7 @@ static bool chunks_aligned(const Geo &g, const void *img, const pilc_params *p)
            ((uintptr_t)p->log_scale & 15) == 0;
 }
 
-static int lane_block_threads(const Geo &g) { return g.lanes >= (1u << 18) ? 256 : 64; }
+static int lane_block_threads(const Geo &g) { return g.lanes >= (1u << 16) ? 256 : 64; }
 
 }  // namespace pilc
 

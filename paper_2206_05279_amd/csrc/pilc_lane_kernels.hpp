@@ -74,11 +74,12 @@ __device__ __forceinline__ void load_chunk(Chunk &c, uint32_t p, uint32_t len,
 }
 
 // floor(n / f) and the remainder for f < 2^16 and n / f < 2^22 (true after the renormalisation
-// of the encoder): a float estimate is within [-2, +1] of the quotient, then fixed up exactly.
-__device__ __forceinline__ uint32_t div_small(uint32_t n, uint32_t f, uint32_t &rem)
+// of the encoder), given rf ~ 1/f to float accuracy: the float estimate is within [-2, +1] of the
+// quotient and is fixed up exactly.
+__device__ __forceinline__ uint32_t div_small(uint32_t n, uint32_t f, float rf, uint32_t &rem)
 {
-    uint32_t q = (uint32_t)((float)n * __builtin_amdgcn_rcpf((float)f));
-    int r = (int)(n - q * f);
+    uint32_t q = (uint32_t)((float)n * rf);
+    int r = (int)(n - __umul24(q, f));
     if (r < 0) { r += (int)f; q -= 1u; }
     if (r >= (int)f) { r -= (int)f; q += 1u; }
     if (r >= (int)f) { r -= (int)f; q += 1u; }
@@ -131,34 +132,44 @@ __global__ void k_encode_lanes(Geo g, const uint8_t *__restrict__ img,
         // a chunk never straddles two images when kVec; otherwise take the image per pixel
         uint32_t im = cp.p / g.hw;
         int a_gr = coef[3 * im], a_br = coef[3 * im + 1], a_bg = coef[3 * im + 2];
+        // Phase 1: (cum | freq << 16) and 1/freq of the chunk's 24 symbols.  Nothing here depends on
+        // the state, so the 24 evaluations overlap freely.
+        uint32_t cf[3 * kChunk];
+        float rf[3 * kChunk];
 #pragma unroll
-        for (int i = kChunk - 1; i >= 0; --i) {
-            if ((uint32_t)i < cp.len) {
-                if (!kVec) {
-                    const uint32_t im_i = (cp.p + i) / g.hw;
-                    if (im_i != im) {
-                        im = im_i;
-                        a_gr = coef[3 * im]; a_br = coef[3 * im + 1]; a_bg = coef[3 * im + 2];
-                    }
+        for (int i = 0; i < kChunk; ++i) {
+            if (!kVec && (uint32_t)i < cp.len) {
+                const uint32_t im_i = (cp.p + i) / g.hw;
+                if (im_i != im) {
+                    im = im_i;
+                    a_gr = coef[3 * im]; a_br = coef[3 * im + 1]; a_bg = coef[3 * im + 2];
                 }
-                const int e_r = ck.x[i][0] * 256 - ck.m[i][0], e_g = ck.x[i][1] * 256 - ck.m[i][1];
-                const int me[3] = {ck.m[i][0], ck.m[i][1] + rsh14(a_gr * e_r),
-                                   ck.m[i][2] + rsh14(a_br * e_r) + rsh14(a_bg * e_g)};
+            }
+            const int e_r = ck.x[i][0] * 256 - ck.m[i][0], e_g = ck.x[i][1] * 256 - ck.m[i][1];
+            const int me[3] = {ck.m[i][0], ck.m[i][1] + rsh14(a_gr * e_r),
+                               ck.m[i][2] + rsh14(a_br * e_r) + rsh14(a_bg * e_g)};
 #pragma unroll
-                for (int ch = 2; ch >= 0; --ch) {
-                    const int x = ck.x[i][ch];
-                    const uint32_t inv_s = inv_scale(ck.l[i][ch], tab);
-                    const uint32_t lo = x == 0 ? 0u : cum_inner(x, me[ch], inv_s, spread, tab);
-                    const uint32_t hi = x == 255 ? top : cum_inner(x + 1, me[ch], inv_s, spread, tab);
-                    const uint32_t f = hi - lo;
-                    if (S >= (f << (32u - m_bits))) {
-                        scratch[--wpos] = (uint16_t)(S & 0xFFFFu);
-                        S >>= 16;
-                    }
-                    uint32_t rem;
-                    const uint32_t q = div_small(S, f, rem);
-                    S = (q << m_bits) + rem + lo;
+            for (int ch = 0; ch < 3; ++ch) {
+                const int x = ck.x[i][ch];
+                const uint32_t inv_s = inv_scale(ck.l[i][ch], tab);
+                const uint32_t lo = x == 0 ? 0u : cum_inner(x, me[ch], inv_s, spread, tab);
+                const uint32_t hi = x == 255 ? top : cum_inner(x + 1, me[ch], inv_s, spread, tab);
+                cf[3 * i + ch] = lo | ((hi - lo) << 16);  // cum < 2^16, freq <= 2^16 - 255
+                rf[3 * i + ch] = __builtin_amdgcn_rcpf((float)(hi - lo));
+            }
+        }
+        // Phase 2: the serial chain (App. A eq. (11)), last symbol first.
+#pragma unroll
+        for (int k = 3 * kChunk - 1; k >= 0; --k) {
+            if ((uint32_t)k < 3u * cp.len) {
+                const uint32_t f = cf[k] >> 16, lo = cf[k] & 0xFFFFu;
+                if (S >= (f << (32u - m_bits))) {
+                    scratch[--wpos] = (uint16_t)(S & 0xFFFFu);
+                    S >>= 16;
                 }
+                uint32_t rem;
+                const uint32_t q = div_small(S, f, rf[k], rem);
+                S = (q << m_bits) + rem + lo;
             }
         }
     }
