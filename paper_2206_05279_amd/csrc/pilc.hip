@@ -177,56 +177,48 @@ __global__ void k_scan_apply(uint32_t lanes, const uint32_t *__restrict__ lane_w
 }
 
 // --------------------------------------------------------------------------------------------
-// Pack: every workgroup fills a fixed range of payload words; each word finds its lane by a
-// search in the offset table, then reads the lane's state or scratch slot.
+// Pack: a workgroup copies the streams of a run of consecutive lanes (their bytes are contiguous
+// in the payload).  Offsets, scratch positions and states of the run sit in LDS; each payload
+// word finds its lane by bisection there.
 // --------------------------------------------------------------------------------------------
-constexpr uint32_t kPackWords = 8192;
+constexpr int kPackMaxLanes = 256;
 
-__device__ __forceinline__ uint32_t find_lane(const uint32_t *offsets, uint32_t lo, uint32_t hi,
-                                              uint32_t byte)
-{
-    // largest l in [lo, hi] with offsets[l] <= byte
-    while (lo < hi) {
-        uint32_t mid = lo + (hi - lo + 1) / 2;
-        if (offsets[mid] <= byte)
-            lo = mid;
-        else
-            hi = mid - 1;
-    }
-    return lo;
-}
-
-__global__ void k_pack(Geo g, const uint16_t *__restrict__ scratch,
-                       const uint32_t *__restrict__ lane_state, const uint32_t *__restrict__ offsets,
-                       uint16_t *__restrict__ payload, const Status *__restrict__ status)
+__global__ __launch_bounds__(256) void k_pack(Geo g, uint32_t lanes_per_block,
+                                              const uint16_t *__restrict__ scratch,
+                                              const uint32_t *__restrict__ lane_state,
+                                              const uint32_t *__restrict__ offsets,
+                                              uint16_t *__restrict__ payload,
+                                              const Status *__restrict__ status)
 {
     if (status->code != ST_OK) return;
-    const unsigned long long total_words = status->payload_bytes >> 1;
-    const unsigned long long w0 = (unsigned long long)blockIdx.x * kPackWords;
-    if (w0 >= total_words) return;
-    const uint32_t w1 = (uint32_t)min(w0 + kPackWords, total_words);
-    __shared__ uint32_t s_lo, s_hi;
-    if (threadIdx.x == 0) {
-        s_lo = find_lane(offsets, 0, g.lanes - 1, (uint32_t)w0 * 2u);
-        s_hi = find_lane(offsets, s_lo, g.lanes - 1, (w1 - 1) * 2u);
+    __shared__ uint32_t s_off[kPackMaxLanes + 1];
+    __shared__ uint32_t s_src[kPackMaxLanes];    // scratch index of the lane's first word
+    __shared__ uint32_t s_state[kPackMaxLanes];
+    const uint32_t l0 = blockIdx.x * lanes_per_block;
+    const uint32_t n = min(lanes_per_block, g.lanes - l0);
+    for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) {
+        const uint32_t begin = offsets[l0 + i], end = offsets[l0 + i + 1];
+        const LaneShape sh = lane_shape(g, l0 + i);
+        s_off[i] = begin;
+        if (i + 1 == n) s_off[n] = end;
+        s_src[i] = sh.sym_base + 3u * sh.npx - ((end - begin - 4u) >> 1);
+        s_state[i] = lane_state[l0 + i];
     }
     __syncthreads();
-    const uint32_t lo = s_lo, hi = s_hi;
-    for (uint32_t wi = (uint32_t)w0 + threadIdx.x; wi < w1; wi += blockDim.x) {
-        uint32_t byte = wi * 2u;
-        uint32_t lane = find_lane(offsets, lo, hi, byte);
-        uint32_t begin = offsets[lane];
-        uint32_t local = byte - begin;
-        uint16_t v;
-        if (local < 4u) {
-            v = (uint16_t)(lane_state[lane] >> (8u * local));
-        } else {
-            uint32_t nwords = (offsets[lane + 1] - begin - 4u) >> 1;
-            LaneShape sh = lane_shape(g, lane);
-            size_t slot_end = (size_t)sh.sym_base + 3u * sh.npx;
-            v = scratch[slot_end - nwords + ((local - 4u) >> 1)];
+    const uint32_t w_begin = s_off[0] >> 1, w_end = s_off[n] >> 1;
+    for (uint32_t w = w_begin + threadIdx.x; w < w_end; w += blockDim.x) {
+        const uint32_t byte = 2u * w;
+        uint32_t lo = 0, hi = n - 1;  // largest i with s_off[i] <= byte
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi + 1) >> 1;
+            if (s_off[mid] <= byte)
+                lo = mid;
+            else
+                hi = mid - 1;
         }
-        payload[wi] = v;
+        const uint32_t local = byte - s_off[lo];
+        payload[w] = local < 4u ? (uint16_t)(s_state[lo] >> (8u * local))
+                                : scratch[s_src[lo] + ((local - 4u) >> 1)];
     }
 }
 
@@ -611,13 +603,14 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
                                                  (unsigned long long)coded_capacity, status);
     k_scan_apply<<<ws.scan_blocks, kScanThreads, 0, stream>>>(g.lanes, lane_words, sums, offsets);
     timer.mark("scan");
-    // worst case payload that fits the capacity; workgroups past the real size exit at once
-    const size_t max_payload = 4 * (size_t)g.lanes + 2 * (size_t)g.total_px * 3;
-    const size_t room = coded_capacity - table_end;
-    const size_t pack_bytes = max_payload < room ? max_payload : room;
-    const uint32_t pack_blocks = (uint32_t)ceil_div64(pack_bytes / 2, kPackWords);
-    if (pack_blocks)
-        k_pack<<<pack_blocks, 256, 0, stream>>>(g, scratch, lane_state, offsets, payload, status);
+    // a run of lanes per workgroup: about 16K symbols' worth, at most 256 lanes
+    const uint64_t lane_sym =
+        3ull * (g.lane_mode == 0 ? (uint64_t)(g.lane_a < g.total_px ? g.lane_a : g.total_px)
+                                 : (uint64_t)g.lane_a * g.lane_b);
+    uint32_t pack_lanes = (uint32_t)(16384 / (lane_sym ? lane_sym : 1));
+    pack_lanes = pack_lanes < 1 ? 1 : (pack_lanes > (uint32_t)kPackMaxLanes ? kPackMaxLanes : pack_lanes);
+    k_pack<<<(uint32_t)ceil_div64(g.lanes, pack_lanes), 256, 0, stream>>>(
+        g, pack_lanes, scratch, lane_state, offsets, payload, status);
     timer.mark("k_pack");
     HIP_TRY(hipGetLastError());
     Status host_status;
