@@ -273,7 +273,8 @@ def main():
         detail = {}
         for key in ("read", "write"):
             scale = copy_bytes / (traffic[key + "_copy_kib"] * 1024.0)
-            vals = [v for name, rows in traffic[key].items() if name.endswith("::" + dom) for v in rows]
+            vals = [v for name, rows in traffic[key].items()
+                    if ("::" + dom) in name and name.split("::" + dom)[1][:1] in ("", "<") for v in rows]
             if vals:
                 detail[key + "_bytes"] = sum(vals) / len(vals) * 1024.0 * scale
                 detail[key + "_scale"] = scale
