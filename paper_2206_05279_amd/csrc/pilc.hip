@@ -266,7 +266,8 @@ namespace pilc {
 // Host side
 // --------------------------------------------------------------------------------------------
 // 0 auto, 1 thread per lane, 2 few-lane kernels; 3/4/5 few-lane with 64/32/16 threads per lane
-// in decode, 6 few-lane with the scalar-state wave-per-lane decoder
+// in decode, 6 few-lane with the scalar-state wave-per-lane decoder, 7 few-lane with 16 threads
+// per lane and two candidates per thread
 static int g_kernel_policy = 0;
 
 // A wavefront per lane pays off while there are too few lanes to fill the chip with one thread
@@ -285,6 +286,7 @@ static int decode_group_size(const Geo &g)
     if (g_kernel_policy == 3) return 64;
     if (g_kernel_policy == 4) return 32;
     if (g_kernel_policy == 5) return 16;
+    if (g_kernel_policy == 7) return 17;
     if (g.lanes <= 2048u) return 64;
     if (g.lanes <= 4096u) return 32;
     return 16;
@@ -493,7 +495,7 @@ void pilc_set_timing(int enabled) { g_timing_enabled = enabled; }
 
 int pilc_set_kernel_policy(int policy)
 {
-    if (policy < 0 || policy > 6) return PILC_E_ARG;
+    if (policy < 0 || policy > 7) return PILC_E_ARG;
     g_kernel_policy = policy;
     return PILC_OK;
 }
@@ -645,8 +647,8 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
     timer.mark("k_check_header");
     const bool few_lanes = use_wave_kernels(g);
     if (few_lanes) {
-        const int gs = decode_group_size(g);
-        const uint32_t waves = (uint32_t)ceil_div64(g.lanes, 64 / gs);
+        const int gs = decode_group_size(g);  // 17: 16 threads per lane with two candidates each
+        const uint32_t waves = (uint32_t)ceil_div64(g.lanes, gs == 17 ? 4 : 64 / gs);
         const uint32_t blocks = (uint32_t)ceil_div64(waves, kGroupWavesPerBlock);
         const int bt = 64 * kGroupWavesPerBlock;
         if (g_kernel_policy == 6)
@@ -654,17 +656,21 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
                 g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev,
                 &status->code, &status->payload_bytes);
         else if (gs == 64)
-            k_decode_group<64><<<blocks, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
+            k_decode_group<64, 1><<<blocks, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
                                                           params->chan_coef, img_out_dev, &status->code,
                                                           &status->payload_bytes);
         else if (gs == 32)
-            k_decode_group<32><<<blocks, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
+            k_decode_group<32, 1><<<blocks, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
                                                           params->chan_coef, img_out_dev, &status->code,
                                                           &status->payload_bytes);
+        else if (gs == 16)
+            k_decode_group<16, 1><<<blocks, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
+                                                             params->chan_coef, img_out_dev, &status->code,
+                                                             &status->payload_bytes);
         else
-            k_decode_group<16><<<blocks, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
-                                                          params->chan_coef, img_out_dev, &status->code,
-                                                          &status->payload_bytes);
+            k_decode_group<16, 2><<<blocks, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
+                                                             params->chan_coef, img_out_dev, &status->code,
+                                                             &status->payload_bytes);
     } else {
         const int bt = lane_block_threads(g);
         const uint32_t nb = (uint32_t)ceil_div64(g.lanes, bt);

@@ -24,18 +24,27 @@ __device__ __forceinline__ uint32_t from_next_thread(uint32_t v)
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x130 /* wave_shl:1 */, 0xF, 0xF, false);
 }
 
-template <int G>
+// thread i of a 16-thread row receives the value of thread (i + 1) mod 16 of the same row
+__device__ __forceinline__ uint32_t from_next_in_row(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x12F /* row_ror:15 */, 0xF, 0xF, false);
+}
+
+// G threads per lane, C candidates per thread: the window of a symbol is W = G * C values wide.
+template <int G, int C>
 __global__ __launch_bounds__(64 * kGroupWavesPerBlock) void k_decode_group(
     Geo g, const uint8_t *__restrict__ coded, const uint16_t *__restrict__ mu,
     const int16_t *__restrict__ ls, const int16_t *__restrict__ coef, uint8_t *__restrict__ out,
     int *__restrict__ status_code, const unsigned long long *__restrict__ status_payload)
 {
     static_assert(G == 16 || G == 32 || G == 64, "threads per lane");
+    static_assert(C == 1 || (C == 2 && G == 16), "two candidates per thread only with 16-thread rows");
     constexpr int L = 64 / G;
-    constexpr int kBaseMax = 256 - G;            // candidates stay within 1..255
-    constexpr int kHalf = G / 2 - 1;             // window starts this far below the rounded mean
-    constexpr int kOkLo = 256 * G - 32895;       // means for which |256 k - 128 - mean| <= 2^15
-    constexpr int kOkHi = 98176 - 256 * G;       //   holds over the whole (clamped) window
+    constexpr int W = G * C;                     // candidates per symbol
+    constexpr int kBaseMax = 256 - W;            // candidates stay within 1..255
+    constexpr int kHalf = W / 2 - 1;             // window starts this far below the rounded mean
+    constexpr int kOkLo = 256 * W - 32895;       // means for which |256 k - 128 - mean| <= 2^15
+    constexpr int kOkHi = 98176 - 256 * W;       //   holds over the whole (clamped) window
     __shared__ LdsTables tab;
     load_tables(tab);
     if (*status_code != 0) return;
@@ -71,7 +80,8 @@ __global__ __launch_bounds__(64 * kGroupWavesPerBlock) void k_decode_group(
     uint32_t wbuf = wbase + j < stop ? (uint32_t)payload[wbase + j] : 0u;
     uint32_t widx = gbase;  // wavefront thread that holds the lane's next word
 
-    const int d0 = 256 * (int)j - 128;  // candidate edge j - 1/2 relative to the window base
+    // candidate edge relative to the window base: thread j holds candidates j and (C == 2) j + G
+    const int d0 = 256 * (int)j - 128;
 
     auto bperm = [](uint32_t src_thread, uint32_t v) -> uint32_t {
         return (uint32_t)__builtin_amdgcn_ds_bpermute((int)(src_thread << 2), (int)v);
@@ -103,43 +113,72 @@ __global__ __launch_bounds__(64 * kGroupWavesPerBlock) void k_decode_group(
         const int sc = (int)pk >> 9;
         // candidates of a window the short form cannot evaluate compare against 2^32 - 1: a miss
         const uint32_t slot_eff = slot | (uint32_t)((int)(pk << 23) >> 31);
-        const int d = d0 + sc;
-        // z = floor(d * inv_s / 2^17) with inv_s = a * 2^16 + b and |d| <= 2^15
-        const int t = __mul24(d, (int)(inv_s & 0xFFFFu)) >> 16;
-        int w = ((__mul24(d, (int)(inv_s >> 16)) + t) >> 1) + (1 << 20);
-        w = min(max(w, 0), (1 << 21) - 1);
-        const uint2 cell = tab.sig[w >> 10];
-        uint32_t spec = next((uint32_t)base + j);
-        const uint32_t f24 = cell.x + (__umul24(cell.y, (uint32_t)w & 1023u) >> 10);
-        uint32_t cv = (uint32_t)base + j + __umulhi(f24 << 8, spread);
-        uint32_t cnt = group_count(cv <= slot_eff);
-        bool bad = cnt - 1u >= (uint32_t)(G - 1);
+        uint32_t cv[C], spec[C];
+        uint32_t cnt = 0;
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const int d = d0 + 256 * G * c + sc;
+            // z = floor(d * inv_s / 2^17) with inv_s = a * 2^16 + b and |d| <= 2^15
+            const int t = __mul24(d, (int)(inv_s & 0xFFFFu)) >> 16;
+            // clamp z to [-2^20, 2^20 - 1]; the table cell is 1024 + (z >> 10), the fraction z & 1023
+            const int z = min(max((__mul24(d, (int)(inv_s >> 16)) + t) >> 1, -(1 << 20)), (1 << 20) - 1);
+            const uint2 cell = (tab.sig + 1024)[z >> 10];
+            spec[c] = next((uint32_t)base + j + (uint32_t)(G * c));
+            const uint32_t f24 = cell.x + (__umul24(cell.y, (uint32_t)z & 1023u) >> 10);
+            cv[c] = (uint32_t)base + j + (uint32_t)(G * c) + __umulhi(f24 << 8, spread);
+        }
+#pragma unroll
+        for (int c = 0; c < C; ++c) cnt += group_count(cv[c] <= slot_eff);
+        bool bad = cnt - 1u >= (uint32_t)(W - 1);
         if (ragged) bad = bad && act;
         if (__builtin_expect(__any(bad), 0)) {
             // general evaluation; windows walk towards the slot: C(0) = 0 <= slot ends a walk
-            // down at base 0, C(256) = 2^M > slot ends a walk up at base 257 - G
+            // down at base 0, C(256) = 2^M > slot ends a walk up at base 257 - W
             const int me = (base << 8) - sc;
             const bool redo = bad;
-            int step = (pk & 0x100u) != 0u ? 0 : (cnt == 0u ? -(G - 1) : (G - 1));
+            int step = (pk & 0x100u) != 0u ? 0 : (cnt == 0u ? -(W - 1) : (W - 1));
             do {
                 if (bad) {
-                    base = min(max(base + step, 0), 257 - G);
-                    cv = cum_at(base + (int)j, me, inv_s, m_bits, tab);
+                    base = min(max(base + step, 0), 257 - W);
+#pragma unroll
+                    for (int c = 0; c < C; ++c)
+                        cv[c] = cum_at(base + (int)j + G * c, me, inv_s, m_bits, tab);
                 }
-                cnt = group_count(redo ? cv <= slot : cv <= slot_eff);
+                uint32_t n = 0;
+#pragma unroll
+                for (int c = 0; c < C; ++c) n += group_count(redo ? cv[c] <= slot : cv[c] <= slot_eff);
+                cnt = n;
                 if (bad) {
-                    bad = cnt - 1u >= (uint32_t)(G - 1);
-                    step = cnt == 0u ? -(G - 1) : (G - 1);
+                    bad = cnt - 1u >= (uint32_t)(W - 1);
+                    step = cnt == 0u ? -(W - 1) : (W - 1);
                 }
             } while (__any(bad));
-            if (redo) spec = next((uint32_t)base + j);
+            if (redo) {
+#pragma unroll
+                for (int c = 0; c < C; ++c) spec[c] = next((uint32_t)base + j + (uint32_t)(G * c));
+            }
         }
-        // App. A eq. (12), computed by every thread as if its own candidate were the symbol
-        const uint32_t cvn = from_next_thread(cv);
-        const uint32_t sj = __umul24(cvn - cv, S >> m_bits) + (slot - cv);
-        const uint32_t winner = gbase + cnt - 1u;
+        // App. A eq. (12), computed by every thread as if its own candidates were the symbol
+        const uint32_t q = S >> m_bits;
+        uint32_t sj, sp, winner;
+        if (C == 1) {
+            const uint32_t cvn = from_next_thread(cv[0]);
+            sj = __umul24(cvn - cv[0], q) + (slot - cv[0]);
+            sp = spec[0];
+            winner = gbase + cnt - 1u;
+        } else {
+            // candidate j + G follows candidate j of the row's next thread; candidate G follows G - 1
+            const uint32_t n0 = from_next_in_row(cv[0]), n1 = from_next_in_row(cv[C - 1]);
+            const uint32_t cvn0 = j == (uint32_t)(G - 1) ? n1 : n0;
+            const uint32_t s0 = __umul24(cvn0 - cv[0], q) + (slot - cv[0]);
+            const uint32_t s1 = __umul24(n1 - cv[C - 1], q) + (slot - cv[C - 1]);
+            const bool upper = cnt > (uint32_t)G;  // the symbol is one of the second candidates
+            sj = upper ? s1 : s0;
+            sp = upper ? spec[C - 1] : spec[0];
+            winner = gbase + ((cnt - 1u) & (uint32_t)(G - 1));
+        }
         uint32_t s_new = bperm(winner, sj);
-        pk_next = bperm(winner, spec);
+        pk_next = bperm(winner, sp);
         const bool refill = s_new < (1u << 16);
         s_new = refill ? (s_new << 16) | wnext : s_new;
         if (ragged) {
