@@ -134,6 +134,66 @@ const char *pilc_timing_name(int index_in_last_call);
  * Process-wide.  Errors: PILC_E_ARG for any other value. */
 int pilc_set_kernel_policy(int policy);
 
+/* ------------------------------------------------------------------------------------------
+ * The paper's own coder variant: ANS-AI (Sec. 3.2, Alg. 3 "Encode x", Alg. 4 "Decode one
+ * symbol"), the table-driven form of the modified rANS of Alg. 1 / Alg. 2.  The state lives in
+ * [2^M, 2^(M+1)); every symbol carries the index d of one of D fixed distributions over X
+ * symbols; encode looks up delta[d,x], phi[d,x], decode looks up Theta[d,S], B[d,S], N[d,S].
+ * A "piece" is one independent coder instance of `count` symbols (Sec. 4.3: one thread per
+ * piece).  Readings the paper leaves open: a piece is encoded last symbol first so that decode
+ * returns the symbols in order; the state starts at 2^M and decode must return there with the
+ * stream used up; a pushed group of bits keeps its order, bit 0 of S first.
+ * Container (little endian): 64-byte header {"PANS", 1, pieces, count, M, D, X, 0.., payload
+ * bytes u64 at byte 48, 0}; u32 offsets[pieces+1] (bytes, relative to the payload); per piece
+ * {final state u32, bit count u32, ceil(bits/32) words of 32 bits, bit i of the stream at bit
+ * i%32 of word i/32}.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+    uint32_t pieces, count; /* independent pieces, symbols per piece; rounded-up pieces*count < 2^32 */
+    uint32_t prec_bits;     /* M, 1..15, 2^M >= num_sym */
+    uint32_t num_dist;      /* D, 1..256 */
+    uint32_t num_sym;       /* X, 2..256 */
+} pilc_ansai_shape;
+
+/* Bytes of device memory pilc_ansai_build_tables fills for these M, D, X (0 if invalid):
+ * 8*D*X for delta and phi plus 3*D*2^M (5*D*2^M when M > 12) for Theta, B, N, plus padding. */
+size_t pilc_ansai_table_bytes(uint32_t prec_bits, uint32_t num_dist, uint32_t num_sym);
+
+/* Builds the tables of Sec. 3.2 on the device from integer masses.
+ *   mass_dev    device uint32 [D, X], every P_x >= 1, each row summing to 2^M
+ *   tables_dev  device, 256-byte aligned, tables_bytes >= pilc_ansai_table_bytes(); opaque to
+ *               the caller, valid for any number of encode / decode calls with the same M, D, X
+ * Errors: PILC_E_ARG (bad sizes or pointers, or masses that break the two conditions above:
+ * the blob is then marked unusable), PILC_E_WORKSPACE (tables_bytes too small), PILC_E_HIP. */
+int pilc_ansai_build_tables(uint32_t prec_bits, uint32_t num_dist, uint32_t num_sym,
+                            const uint32_t *mass_dev, void *tables_dev, size_t tables_bytes,
+                            void *hip_stream);
+
+/* Device workspace needed by pilc_ansai_encode / pilc_ansai_decode and an upper bound of the
+ * container size (header + offsets + per piece 8 bytes and ceil(count*M/32) words).
+ * Errors: PILC_E_ARG, PILC_E_TOO_LARGE. */
+int pilc_ansai_workspace_size(const pilc_ansai_shape *shape, size_t *workspace_bytes_host,
+                              size_t *max_coded_bytes_host);
+
+/* Alg. 3 over a batch.  sym_dev, dist_dev: device uint8 [pieces, count], 16-byte aligned;
+ * workspace_dev 256-byte aligned scratch; coded_dev 16-byte aligned output.
+ * Errors: PILC_E_ARG (also: a symbol >= X or an index >= D in the data, or tables built for
+ * other M, D, X), PILC_E_WORKSPACE, PILC_E_CAPACITY, PILC_E_TOO_LARGE, PILC_E_HIP; on error
+ * the contents of coded_dev are undefined. */
+int pilc_ansai_encode(const pilc_ansai_shape *shape, const uint8_t *sym_dev, const uint8_t *dist_dev,
+                      const void *tables_dev, void *workspace_dev, size_t workspace_bytes,
+                      uint8_t *coded_dev, size_t coded_capacity, uint64_t *coded_bytes_host,
+                      void *hip_stream);
+
+/* Alg. 4 over a batch; dist_dev must hold the indices used to encode.  sym_out_dev: device
+ * uint8 [pieces, count], 16-byte aligned; on error its contents are undefined.
+ * Errors: PILC_E_ARG (as above), PILC_E_WORKSPACE, PILC_E_FORMAT (header does not match the
+ * shape or coded_bytes), PILC_E_CORRUPT (bad offsets or record, a piece that runs out of bits,
+ * keeps some, or does not return to the initial state), PILC_E_HIP. */
+int pilc_ansai_decode(const pilc_ansai_shape *shape, const uint8_t *coded_dev, size_t coded_bytes,
+                      const uint8_t *dist_dev, const void *tables_dev, void *workspace_dev,
+                      size_t workspace_bytes, uint8_t *sym_out_dev, void *hip_stream);
+
 const char *pilc_strerror(int code);
 const char *pilc_last_hip_error(void); /* text of the last HIP failure on this thread */
 uint32_t pilc_version(void);

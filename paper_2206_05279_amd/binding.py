@@ -28,6 +28,8 @@ EXPORTS = [
     "pilc_lane_count", "pilc_workspace_size", "pilc_encode", "pilc_decode", "pilc_symbol_tables",
     "pilc_set_timing", "pilc_set_kernel_policy", "pilc_last_timing", "pilc_timing_name", "pilc_strerror",
     "pilc_last_hip_error", "pilc_version",
+    "pilc_ansai_table_bytes", "pilc_ansai_build_tables", "pilc_ansai_workspace_size", "pilc_ansai_encode",
+    "pilc_ansai_decode",
 ]
 
 
@@ -38,6 +40,11 @@ class pilc_geom(C.Structure):
 
 class pilc_params(C.Structure):
     _fields_ = [("mu", C.c_void_p), ("log_scale", C.c_void_p), ("chan_coef", C.c_void_p)]
+
+
+class pilc_ansai_shape(C.Structure):
+    _fields_ = [("pieces", C.c_uint32), ("count", C.c_uint32), ("prec_bits", C.c_uint32),
+                ("num_dist", C.c_uint32), ("num_sym", C.c_uint32)]
 
 
 class PilcError(RuntimeError):
@@ -85,6 +92,20 @@ def lib():
         L.pilc_strerror.argtypes = [C.c_int]
         L.pilc_last_hip_error.restype = C.c_char_p
         L.pilc_version.restype = C.c_uint32
+        sp = C.POINTER(pilc_ansai_shape)
+        L.pilc_ansai_table_bytes.restype = C.c_size_t
+        L.pilc_ansai_table_bytes.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32]
+        L.pilc_ansai_build_tables.restype = C.c_int
+        L.pilc_ansai_build_tables.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p,
+                                              C.c_size_t, C.c_void_p]
+        L.pilc_ansai_workspace_size.restype = C.c_int
+        L.pilc_ansai_workspace_size.argtypes = [sp, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        L.pilc_ansai_encode.restype = C.c_int
+        L.pilc_ansai_encode.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                        C.c_void_p, C.c_size_t, C.POINTER(C.c_uint64), C.c_void_p]
+        L.pilc_ansai_decode.restype = C.c_int
+        L.pilc_ansai_decode.argtypes = [sp, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_size_t, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -182,3 +203,57 @@ def pilc_strerror(code: int) -> str:
 
 def pilc_version() -> int:
     return int(lib().pilc_version())
+
+
+# ---------------------------------------------------------------- the table-driven coder (ANS-AI)
+def make_ansai_shape(pieces, count, prec_bits, num_dist, num_sym=256) -> pilc_ansai_shape:
+    return pilc_ansai_shape(int(pieces), int(count), int(prec_bits), int(num_dist), int(num_sym))
+
+
+def pilc_ansai_table_bytes(prec_bits: int, num_dist: int, num_sym: int = 256) -> int:
+    return int(lib().pilc_ansai_table_bytes(int(prec_bits), int(num_dist), int(num_sym)))
+
+
+def pilc_ansai_build_tables(prec_bits: int, num_dist: int, num_sym: int, mass, tables,
+                            stream: Optional[torch.cuda.Stream] = None, check: bool = True) -> int:
+    """mass: uint32 device tensor [D, X]; tables: uint8 device tensor of pilc_ansai_table_bytes()."""
+    rc = lib().pilc_ansai_build_tables(int(prec_bits), int(num_dist), int(num_sym),
+                                       _dev_ptr(mass, torch.uint32, "mass"),
+                                       _dev_ptr(tables, torch.uint8, "tables"), tables.numel(),
+                                       _stream_handle(stream))
+    if check and rc != PILC_OK:
+        raise PilcError(rc, "pilc_ansai_build_tables")
+    return rc
+
+
+def pilc_ansai_workspace_size(shape: pilc_ansai_shape) -> Tuple[int, int]:
+    """Returns (workspace_bytes, max_coded_bytes)."""
+    ws, mc = C.c_size_t(0), C.c_size_t(0)
+    rc = lib().pilc_ansai_workspace_size(C.byref(shape), C.byref(ws), C.byref(mc))
+    if rc != PILC_OK:
+        raise PilcError(rc, "pilc_ansai_workspace_size")
+    return int(ws.value), int(mc.value)
+
+
+def pilc_ansai_encode(shape: pilc_ansai_shape, sym, dist, tables, workspace, coded,
+                      stream: Optional[torch.cuda.Stream] = None, check: bool = True) -> Tuple[int, int]:
+    nbytes = C.c_uint64(0)
+    rc = lib().pilc_ansai_encode(C.byref(shape), _dev_ptr(sym, torch.uint8, "sym"),
+                                 _dev_ptr(dist, torch.uint8, "dist"), _dev_ptr(tables, torch.uint8, "tables"),
+                                 _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                 _dev_ptr(coded, torch.uint8, "coded"), coded.numel(), C.byref(nbytes),
+                                 _stream_handle(stream))
+    if check and rc != PILC_OK:
+        raise PilcError(rc, "pilc_ansai_encode")
+    return rc, int(nbytes.value)
+
+
+def pilc_ansai_decode(shape: pilc_ansai_shape, coded, coded_bytes: int, dist, tables, workspace, sym_out,
+                      stream: Optional[torch.cuda.Stream] = None, check: bool = True) -> int:
+    rc = lib().pilc_ansai_decode(C.byref(shape), _dev_ptr(coded, torch.uint8, "coded"), int(coded_bytes),
+                                 _dev_ptr(dist, torch.uint8, "dist"), _dev_ptr(tables, torch.uint8, "tables"),
+                                 _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                 _dev_ptr(sym_out, torch.uint8, "sym_out"), _stream_handle(stream))
+    if check and rc != PILC_OK:
+        raise PilcError(rc, "pilc_ansai_decode")
+    return rc

@@ -11,6 +11,7 @@
 
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 
@@ -76,7 +77,7 @@ __global__ void k_symbol_tables(Geo g, const uint8_t *__restrict__ img,
 }
 
 // --------------------------------------------------------------------------------------------
-// Prefix scan of lane byte counts (4 + 2*words) into the container's offset table.
+// Prefix scan of per-item byte counts into a container's offset table.
 // --------------------------------------------------------------------------------------------
 constexpr int kScanThreads = 256;
 constexpr int kScanItems = 4;
@@ -104,20 +105,36 @@ __device__ __forceinline__ unsigned long long block_exclusive_scan(unsigned long
     return base + inc - v;
 }
 
-__global__ void k_scan_partials(uint32_t lanes, const uint32_t *__restrict__ lane_words,
+// Bytes an item (a lane, a piece) takes in the payload, from the count its coder left behind:
+// base + unit * ((count + add) >> shift).
+struct ItemBytes {
+    uint32_t base, unit, add, shift;
+    __device__ __forceinline__ unsigned long long operator()(uint32_t count) const
+    {
+        return (unsigned long long)base + (unsigned long long)unit * ((count + add) >> shift);
+    }
+};
+
+// The first twelve 32-bit words of a container header (the payload size follows them).
+struct HeaderWords {
+    uint32_t w[12];
+};
+
+__global__ void k_scan_partials(uint32_t items, ItemBytes bytes, const uint32_t *__restrict__ counts,
                                 unsigned long long *__restrict__ block_sums)
 {
     uint32_t base = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
     unsigned long long v = 0;
     for (int i = 0; i < kScanItems; ++i)
-        if (base + i < lanes) v += 4ull + 2ull * lane_words[base + i];
+        if (base + i < items) v += bytes(counts[base + i]);
     unsigned long long total;
     block_exclusive_scan(v, &total);
     if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
 }
 
 // Single workgroup: exclusive scan of the block sums in place; writes the header.
-__global__ void k_scan_spine(Geo g, uint32_t nblocks, unsigned long long *__restrict__ block_sums,
+__global__ void k_scan_spine(HeaderWords head, uint32_t items, uint32_t nblocks,
+                             unsigned long long *__restrict__ block_sums,
                              uint8_t *__restrict__ coded, unsigned long long coded_capacity,
                              Status *__restrict__ status)
 {
@@ -131,24 +148,15 @@ __global__ void k_scan_spine(Geo g, uint32_t nblocks, unsigned long long *__rest
     }
     if (threadIdx.x == 0) {
         status->payload_bytes = carry;
-        unsigned long long need = kHeaderBytes + 4ull * ((unsigned long long)g.lanes + 1ull) + carry;
-        if (carry >= (1ull << 32))
-            status->code = ST_TOO_LARGE;
-        else if (need > coded_capacity)
-            status->code = ST_CAPACITY;
+        unsigned long long need = kHeaderBytes + 4ull * ((unsigned long long)items + 1ull) + carry;
+        if (status->code == ST_OK) {  // an earlier error stays
+            if (carry >= (1ull << 32))
+                status->code = ST_TOO_LARGE;
+            else if (need > coded_capacity)
+                status->code = ST_CAPACITY;
+        }
         uint32_t *h = reinterpret_cast<uint32_t *>(coded);
-        h[0] = 0x434C4950u;  // "PILC"
-        h[1] = PILC_VERSION;
-        h[2] = g.n;
-        h[3] = g.h;
-        h[4] = g.w;
-        h[5] = 3u;
-        h[6] = g.prec_bits;
-        h[7] = g.lane_mode;
-        h[8] = g.lane_a;
-        h[9] = g.lane_b;
-        h[10] = g.lanes;
-        h[11] = 0u;
+        for (int i = 0; i < 12; ++i) h[i] = head.w[i];
         h[12] = (uint32_t)carry;
         h[13] = (uint32_t)(carry >> 32);
         h[14] = 0u;
@@ -156,23 +164,23 @@ __global__ void k_scan_spine(Geo g, uint32_t nblocks, unsigned long long *__rest
     }
 }
 
-__global__ void k_scan_apply(uint32_t lanes, const uint32_t *__restrict__ lane_words,
+__global__ void k_scan_apply(uint32_t items, ItemBytes bytes, const uint32_t *__restrict__ counts,
                              const unsigned long long *__restrict__ block_sums,
                              uint32_t *__restrict__ offsets)
 {
     uint32_t base = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
     unsigned long long item[kScanItems], v = 0;
     for (int i = 0; i < kScanItems; ++i) {
-        item[i] = base + i < lanes ? 4ull + 2ull * lane_words[base + i] : 0ull;
+        item[i] = base + i < items ? bytes(counts[base + i]) : 0ull;
         v += item[i];
     }
     unsigned long long total;
     unsigned long long ex = block_exclusive_scan(v, &total) + block_sums[blockIdx.x];
     for (int i = 0; i < kScanItems; ++i) {
-        if (base + i < lanes) offsets[base + i] = (uint32_t)ex;
+        if (base + i < items) offsets[base + i] = (uint32_t)ex;
         ex += item[i];
-        // the closing entry offsets[lanes] = payload size
-        if (base + i + 1 == lanes) offsets[lanes] = (uint32_t)ex;
+        // the closing entry offsets[items] = payload size
+        if (base + i + 1 == items) offsets[items] = (uint32_t)ex;
     }
 }
 
@@ -600,10 +608,14 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
                                                          params->chan_coef, scratch, lane_words, lane_state);
     }
     timer.mark(few_lanes ? "k_encode_block" : "k_encode_lanes");
-    k_scan_partials<<<ws.scan_blocks, kScanThreads, 0, stream>>>(g.lanes, lane_words, sums);
-    k_scan_spine<<<1, kScanThreads, 0, stream>>>(g, ws.scan_blocks, sums, coded_dev,
+    const ItemBytes lane_bytes = {4u, 2u, 0u, 0u};  // a 32-bit state and 16-bit words
+    const HeaderWords head = {{0x434C4950u /* "PILC" */, PILC_VERSION, g.n, g.h, g.w, 3u, g.prec_bits,
+                               g.lane_mode, g.lane_a, g.lane_b, g.lanes, 0u}};
+    k_scan_partials<<<ws.scan_blocks, kScanThreads, 0, stream>>>(g.lanes, lane_bytes, lane_words, sums);
+    k_scan_spine<<<1, kScanThreads, 0, stream>>>(head, g.lanes, ws.scan_blocks, sums, coded_dev,
                                                  (unsigned long long)coded_capacity, status);
-    k_scan_apply<<<ws.scan_blocks, kScanThreads, 0, stream>>>(g.lanes, lane_words, sums, offsets);
+    k_scan_apply<<<ws.scan_blocks, kScanThreads, 0, stream>>>(g.lanes, lane_bytes, lane_words, sums,
+                                                              offsets);
     timer.mark("scan");
     // a run of lanes per workgroup: about 16K symbols' worth, at most 256 lanes
     const uint64_t lane_sym =
@@ -693,3 +705,5 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
 }
 
 }  // extern "C"
+
+#include "pilc_ansai.hpp"

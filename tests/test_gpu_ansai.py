@@ -1,0 +1,240 @@
+"""GPU parity of the table-driven coder (Sec. 3.2 Algs. 3-4) against the CPU reference: the
+tables entry by entry, the container byte for byte, the decoded symbols, and the error codes,
+through the C ABI, on shapes that span several wavefronts, ragged rows and every table path."""
+import struct
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ansai_oracle as ao
+from paper_2206_05279_amd import binding as pb
+from paper_2206_05279_amd import synth_pieces as sp
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import DevicePieces, first_difference  # noqa: E402
+
+
+def _logistic(m, d, x=256):
+    return lambda rng: sp.logistic_masses(m, d, x)
+
+
+def _random(m, d, x, conc=0.3):
+    return lambda rng: sp.random_masses(rng, m, d, x, conc)
+
+
+# name, M, masses, pieces, count, uniform symbols
+CASES = [
+    ("one symbol", 12, _logistic(12, 8), 1, 1, False),
+    ("one wavefront", 12, _logistic(12, 8), 64, 64, False),
+    ("ragged pieces and rows", 12, _logistic(12, 8), 65, 1000, False),
+    ("odd count", 10, _logistic(10, 3), 130, 257, False),
+    ("short rows", 12, _logistic(12, 8), 7, 33, False),
+    ("count 1, many pieces", 12, _logistic(12, 8), 300, 1, False),
+    ("count 3", 12, _logistic(12, 8), 129, 3, False),
+    ("M15 tables in global memory", 15, _logistic(15, 2), 200, 999, False),
+    ("M13 wide entries in LDS", 13, _logistic(13, 1), 100, 500, False),
+    ("5 symbols", 6, _random(6, 3, 5), 96, 700, False),
+    ("M1 two symbols", 1, lambda rng: np.array([[1, 1]], dtype=np.uint32), 50, 300, False),
+    ("peaky masses", 11, _random(11, 4, 40, 0.05), 128, 1000, False),
+    ("model does not fit", 12, _logistic(12, 8), 70, 640, True),
+    ("40 distributions, encode tables in global memory", 9, _random(9, 40, 256, 1.0), 70, 200, False),
+    ("256 distributions", 8, _random(8, 256, 256, 1.0), 64, 100, False),
+    ("4096 pieces of 1000", 12, _logistic(12, 8), 4096, 1000, False),
+    ("M14 random", 14, _random(14, 2, 256, 1.0), 77, 130, False),
+]
+
+
+@pytest.fixture(params=range(len(CASES)), ids=[c[0] for c in CASES], scope="module")
+def case(request):
+    name, m, make, pieces, count, uniform = CASES[request.param]
+    rng = np.random.default_rng(500 + request.param)
+    mass = make(rng)
+    sym, dist = sp.draw_pieces(mass, m, pieces, count, seed=900 + request.param, uniform_sym=uniform, threads=1)
+    print("case", name, "M", m, "D,X", mass.shape, "pieces", pieces, "count", count, flush=True)
+    dp = DevicePieces(m, mass, sym, dist)
+    return dp
+
+
+def test_tables_match_the_reference(case):
+    dp = case
+    got = dp.table_views()
+    ref = ao.build_tables(dp.m, dp.mass_np)
+    for name, g, r in zip(("delta", "phi", "theta", "nbits", "next"), got, ref):
+        assert np.array_equal(g.astype(np.int64), r.astype(np.int64)), name
+
+
+def test_container_is_byte_identical(case):
+    dp = case
+    rc, ref = ao.encode(dp.m, dp.mass_np, dp.sym_np, dp.dist_np)
+    assert rc == ao.OK
+    dp.encode()
+    got = dp.coded_numpy()
+    assert got.size == ref.size and np.array_equal(got, ref), first_difference(got, ref)
+
+
+def test_decode_returns_the_symbols(case):
+    dp = case
+    dp.encode()
+    dp.decode()
+    assert np.array_equal(dp.decoded_numpy(), dp.sym_np)
+    # and a container made by the reference decodes the same way
+    rc, ref = ao.encode(dp.m, dp.mass_np, dp.sym_np, dp.dist_np)
+    buf = torch.zeros(ref.size + 16, dtype=torch.uint8, device="cuda:0")
+    buf[: ref.size] = torch.from_numpy(ref).cuda()
+    dp.decode(coded=buf, nbytes=ref.size)
+    assert np.array_equal(dp.decoded_numpy(), dp.sym_np)
+
+
+# ---------------------------------------------------------------- errors
+@pytest.fixture(scope="module")
+def small():
+    m, mass = 10, sp.logistic_masses(10, 4)
+    sym, dist = sp.draw_pieces(mass, m, 70, 100, seed=3, threads=1)
+    return DevicePieces(m, mass, sym, dist)
+
+
+def test_capacity_and_workspace(small):
+    dp = small
+    _, nbytes = dp.encode()
+    assert dp.max_coded == ao.max_coded_bytes(70, 100, 10)
+    rc, _ = dp.encode(check=False, capacity=((nbytes - 1) // 16) * 16)
+    assert rc == pb.PILC_E_CAPACITY
+    rc, _ = dp.encode(check=False, capacity=64)
+    assert rc == pb.PILC_E_CAPACITY
+    rc, n2 = dp.encode(check=False, capacity=nbytes)
+    assert rc == pb.PILC_OK and n2 == nbytes
+    ws = dp.workspace
+    dp.workspace = ws[: ws.numel() - 256]
+    try:
+        assert dp.encode(check=False)[0] == pb.PILC_E_WORKSPACE
+        assert dp.decode(check=False) == pb.PILC_E_WORKSPACE
+    finally:
+        dp.workspace = ws
+
+
+def test_bad_arguments(small):
+    dp = small
+    dp.encode()
+    good = dp.shape
+    for field, value in (("pieces", 0), ("count", 0), ("prec_bits", 0), ("prec_bits", 16), ("num_dist", 0),
+                         ("num_dist", 257), ("num_sym", 1), ("num_sym", 257)):
+        shape = pb.make_ansai_shape(good.pieces, good.count, good.prec_bits, good.num_dist, good.num_sym)
+        setattr(shape, field, value)
+        dp.shape = shape
+        try:
+            assert dp.encode(check=False)[0] == pb.PILC_E_ARG, field
+            assert dp.decode(check=False) == pb.PILC_E_ARG, field
+        finally:
+            dp.shape = good
+    assert pb.pilc_ansai_table_bytes(3, 1, 256) == 0           # 2^M below the alphabet size
+    # misaligned arrays
+    pad = torch.zeros(dp.sym.numel() + 16, dtype=torch.uint8, device="cuda:0")
+    off1 = pad[1: 1 + dp.sym.numel()].view(dp.sym.shape)
+    assert dp.encode(check=False, sym=off1)[0] == pb.PILC_E_ARG
+    assert dp.decode(check=False, dist=off1) == pb.PILC_E_ARG
+    # a shape the tables were not built for
+    other = pb.make_ansai_shape(good.pieces, good.count, good.prec_bits, good.num_dist - 1, good.num_sym)
+    dp.shape = other
+    try:
+        assert dp.encode(check=False)[0] == pb.PILC_E_ARG
+    finally:
+        dp.shape = good
+    big = pb.make_ansai_shape(1 << 24, 1 << 10, 12, 8, 256)
+    with pytest.raises(pb.PilcError) as e:
+        pb.pilc_ansai_workspace_size(big)
+    assert e.value.code == pb.PILC_E_TOO_LARGE
+
+
+def test_bad_masses_and_indices(small):
+    dp = small
+    mass = dp.mass_np.copy()
+    mass[1, 7] += 1                                            # a row that does not sum to 2^M
+    bad = DevicePieces(dp.m, mass, dp.sym_np, dp.dist_np, build=False)
+    rc = pb.pilc_ansai_build_tables(bad.m, bad.d, bad.x, bad.mass, bad.tables, check=False)
+    assert rc == pb.PILC_E_ARG
+    assert bad.encode(check=False)[0] == pb.PILC_E_ARG         # the blob is marked unusable
+    mass = dp.mass_np.copy()
+    mass[2, 0] += mass[2, 1]
+    mass[2, 1] = 0                                             # an empty symbol
+    bad = DevicePieces(dp.m, mass, dp.sym_np, dp.dist_np, build=False)
+    assert pb.pilc_ansai_build_tables(bad.m, bad.d, bad.x, bad.mass, bad.tables, check=False) == pb.PILC_E_ARG
+    # an index beyond D in the data
+    dist = dp.dist_np.copy()
+    dist[69, 99] = 4
+    assert ao.encode(dp.m, dp.mass_np, dp.sym_np, dist)[0] == ao.E_ARG
+    assert dp.encode(check=False, dist=torch.from_numpy(dist).cuda())[0] == pb.PILC_E_ARG
+    dp.encode()
+    assert dp.decode(check=False, dist=torch.from_numpy(dist).cuda()) in (pb.PILC_E_ARG, pb.PILC_E_CORRUPT)
+    # a symbol beyond X
+    m, mass = 6, sp.random_masses(np.random.default_rng(1), 6, 2, 5)
+    sym, dist = sp.draw_pieces(mass, m, 10, 50, seed=4, threads=1)
+    sym[3, 3] = 5
+    assert ao.encode(m, mass, sym, dist)[0] == ao.E_ARG
+    assert DevicePieces(m, mass, sym, dist).encode(check=False)[0] == pb.PILC_E_ARG
+
+
+def _damaged(dp, coded, edit):
+    c = coded.copy()
+    edit(c)
+    rc_ref, back_ref = ao.decode(dp.m, dp.mass_np, dp.dist_np, c)
+    buf = torch.zeros(c.size + 16, dtype=torch.uint8, device="cuda:0")
+    buf[: c.size] = torch.from_numpy(c).cuda()
+    rc = dp.decode(coded=buf, nbytes=c.size, check=False)
+    return rc_ref, back_ref, rc, dp.decoded_numpy()
+
+
+def test_damaged_containers_agree_with_the_reference(small):
+    dp = small
+    dp.encode()
+    coded = dp.coded_numpy()
+    pieces = dp.shape.pieces
+    offs = np.frombuffer(coded.tobytes(), dtype="<u4", count=pieces + 1, offset=64)
+    body = 64 + 4 * (pieces + 1)
+
+    def put(at, value):
+        def edit(c):
+            c[at:at + 4] = np.frombuffer(struct.pack("<I", value), np.uint8)
+        return edit
+
+    def flip(at, mask):
+        def edit(c):
+            c[at] ^= mask
+        return edit
+
+    edits = {
+        "magic": flip(0, 1),
+        "pieces field": put(8, pieces + 1),
+        "payload size": put(48, int(offs[-1]) + 4),
+        "state below 2^M": put(body + int(offs[1]), 5),
+        "state above 2^(M+1)": put(body + int(offs[65]), 3000),
+        "bit count": flip(body + int(offs[2]) + 4, 0x40),
+        "offset moved": put(64 + 4 * 66, int(offs[66]) + 4),
+        "offset beyond payload": put(64 + 4 * 3, int(offs[-1]) + 8),
+        "payload bit": flip(body + int(offs[3]) + 9, 0x10),
+        "payload bit in last piece": flip(body + int(offs[69]) + 8, 0x01),
+    }
+    for name, edit in edits.items():
+        rc_ref, back_ref, rc, back = _damaged(dp, coded, edit)
+        want = {ao.OK: pb.PILC_OK, ao.E_FORMAT: pb.PILC_E_FORMAT, ao.E_CORRUPT: pb.PILC_E_CORRUPT}[rc_ref]
+        assert rc == want, name
+        if rc == pb.PILC_OK:
+            assert np.array_equal(back, back_ref), name
+    # truncation is a size mismatch
+    assert dp.decode(nbytes=coded.size - 4, check=False) == pb.PILC_E_FORMAT
+    assert dp.decode(nbytes=32, check=False) == pb.PILC_E_FORMAT
+
+
+def test_timing_names(small):
+    dp = small
+    pb.pilc_set_timing(True)
+    try:
+        dp.encode()
+        names = [n for n, _ in pb.pilc_last_timing()]
+        assert names == ["total", "k_ansai_encode", "scan", "k_ansai_pack"]
+        dp.decode()
+        names = [n for n, _ in pb.pilc_last_timing()]
+        assert names == ["total", "k_ansai_check_header", "k_ansai_decode"]
+    finally:
+        pb.pilc_set_timing(False)
