@@ -13,6 +13,10 @@ Besides the contract fields the line carries
                 counter reports for a plain device copy of known size in the same child run;
   cpu_baseline  the CPU oracle timed on the host cores on a bounded prefix of the workload;
   other_workloads  compress / decompress MB/s of the other single-GPU workloads (fewer steps).
+
+--workload ansai times the paper's own table-driven coder (Sec. 3.2 Algs. 3-4) instead, on the
+recipe of its coder measurement (Sec. 4.3: 10^6 pieces of 1000 symbols, 8 distributions); the
+default run reports it among other_workloads.
 """
 from __future__ import annotations
 
@@ -33,6 +37,7 @@ import numpy as np
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 HERE = os.path.dirname(os.path.abspath(__file__))
 METRIC = "compress & decompress MB/s (raw uint8) on 1 MI355X; bits/subpixel"
+METRIC_ANSAI = "coder encode & decode MB/s (uint8 symbols) on 1 MI355X; bits/symbol"
 
 
 def parse_args():
@@ -42,7 +47,10 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=1,
                     help="workload 0..4 of BASELINE.json (default 1: CIFAR-shaped, 50,000 images)")
-    ap.add_argument("--images", type=int, default=None, help="first N images only (debugging)")
+    ap.add_argument("--workload", choices=("pilc", "ansai"), default="pilc",
+                    help="pilc: the image path on --config; ansai: the table-driven coder on pieces")
+    ap.add_argument("--images", type=int, default=None,
+                    help="first N images (pilc) or pieces (ansai) only (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-images", type=int, default=None)
     ap.add_argument("--no-traffic", action="store_true",
@@ -56,14 +64,15 @@ def parse_args():
 # ----------------------------------------------------------------------------------------------
 # HBM traffic from rocprofv3 counters (child processes, started before this process touches HIP)
 # ----------------------------------------------------------------------------------------------
-def _run_pmc(counter: str, config: int, images):
+def _run_pmc(counter: str, config: int, images, workload: str = "pilc"):
     """Returns {kernel name prefix: [values in KiB per dispatch]} for one counter, or None."""
     exe = shutil.which("rocprofv3") or "/opt/rocm/bin/rocprofv3"
     if not os.path.exists(exe):
         return None
     out_dir = tempfile.mkdtemp(prefix="pilc_pmc_", dir="/tmp")
     cmd = [exe, "--pmc", counter, "-d", out_dir, "-o", "pmc", "--output-format", "csv", "--",
-           sys.executable, os.path.join(HERE, "bench.py"), "--pmc-child", "--config", str(config)]
+           sys.executable, os.path.join(HERE, "bench.py"), "--pmc-child", "--config", str(config),
+           "--workload", workload]
     if images is not None:
         cmd += ["--images", str(images)]
     env = dict(os.environ, TMPDIR="/tmp")
@@ -94,12 +103,12 @@ def _run_pmc(counter: str, config: int, images):
         shutil.rmtree(out_dir, ignore_errors=True)
 
 
-def measure_traffic(config: int, images):
+def measure_traffic(config: int, images, workload: str = "pilc"):
     """HBM bytes per launch of every pilc kernel: counter value (KiB) x 1024 x scale, where
     scale = known bytes of a plain device copy / what the counter read for that copy."""
     result = {}
     for counter, key in (("FETCH_SIZE", "read"), ("WRITE_SIZE", "write")):
-        rows = _run_pmc(counter, config, images)
+        rows = _run_pmc(counter, config, images, workload)
         if not rows:
             return None
         copies = rows.get("__amd_rocclr_copyBuffer", [])
@@ -191,6 +200,17 @@ class Run:
         self.out = torch.empty_like(self.img)
         self.name = "cfg%d %s: %d x %dx%dx3 uint8, M=%d, %d lanes" % (
             config, wl.name, wl.n, wl.h, wl.w, wl.prec_bits, pb.pilc_lane_count(self.geom))
+        self.raw = wl.subpixels
+        self.probe_src = self.mu           # plain copy of known size: 2 bytes per subpixel
+        self.probe_bytes = 4.0 * wl.subpixels
+        self.step = "pilc_encode + pilc_decode of the whole batch"
+
+    def algo_bytes(self, nbytes):
+        # either lane kernel: 1 B pixel + 2 B mu + 2 B log-scale per subpixel, plus the container
+        return 5.0 * self.raw + nbytes
+
+    def reference(self):
+        return self.img
 
     def encode(self):
         return self.pb.pilc_encode(self.geom, self.img, self.mu, self.ls, self.coef, self.workspace,
@@ -223,14 +243,108 @@ class Run:
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         pb.pilc_set_timing(False)
-        raw = self.wl.subpixels
+        raw = self.raw
         return {
             "elapsed": elapsed, "nbytes": int(nbytes), "raw": raw,
             "kernel_ms": {k: v / steps for k, v in kernel_ms.items()},
             "compress_MB_s": raw / 1e6 / (enc_ms / steps * 1e-3),
             "decompress_MB_s": raw / 1e6 / (dec_ms / steps * 1e-3),
-            "ok": bool(torch.equal(self.out, self.img)),
+            "ok": bool(torch.equal(self.out, self.reference())),
         }
+
+
+# ----------------------------------------------------------------------------------------------
+# The table-driven coder on pieces
+# ----------------------------------------------------------------------------------------------
+def cpu_baseline_pieces(wl, sample_pieces):
+    from oracle import ansai_oracle as ao
+
+    k = min(sample_pieces, wl.pieces)
+    cores = max(1, min(16, os.cpu_count() or 1))
+    per = -(-k // cores)
+    slabs = [(a, min(a + per, k)) for a in range(0, k, per)]
+    jobs = [(np.ascontiguousarray(wl.sym[a:b]), np.ascontiguousarray(wl.dist[a:b])) for a, b in slabs]
+    ao.lib()
+
+    def enc(job):
+        rc, coded = ao.encode(wl.prec_bits, wl.mass, job[0], job[1])
+        assert rc == ao.OK
+        return coded
+
+    def dec(args):
+        job, coded = args
+        rc, sym = ao.decode(wl.prec_bits, wl.mass, job[1], coded)
+        assert rc == ao.OK and np.array_equal(sym, job[0])
+
+    with ThreadPoolExecutor(max_workers=len(jobs)) as pool:
+        t0 = time.perf_counter()
+        coded = list(pool.map(enc, jobs))
+        t1 = time.perf_counter()
+        list(pool.map(dec, zip(jobs, coded)))
+        t2 = time.perf_counter()
+    raw_mb = k * wl.count / 1e6
+    t3 = time.perf_counter()
+    c0 = enc(jobs[0])
+    t4 = time.perf_counter()
+    dec((jobs[0], c0))
+    t5 = time.perf_counter()
+    mb0 = jobs[0][0].size / 1e6
+    return {
+        "value": raw_mb / (t2 - t0), "unit": "MB/s", "cores": len(jobs), "kind": "oracle",
+        "sample": "first %d pieces of the workload (%.1f MB of symbols), encode+decode with the tables of "
+                  "Algs. 3-4, %d slabs in a thread pool" % (k, raw_mb, len(jobs)),
+        "compress_MB_s": raw_mb / (t1 - t0), "decompress_MB_s": raw_mb / (t2 - t1),
+        "one_core": {"value": mb0 / (t5 - t3), "compress_MB_s": mb0 / (t4 - t3),
+                     "decompress_MB_s": mb0 / (t5 - t4), "sample_MB": mb0},
+    }
+
+
+class PieceRun:
+    """pilc_ansai_encode + pilc_ansai_decode of the whole batch; tables built once, outside."""
+
+    def __init__(self, config, pieces):
+        import torch
+        from paper_2206_05279_amd import binding as pb
+        from paper_2206_05279_amd import synth_pieces
+
+        self.torch, self.pb = torch, pb
+        dev = torch.device("cuda:0")
+        t = time.perf_counter()
+        self.wl = wl = synth_pieces.make_piece_workload(config, pieces, threads=16)
+        self.gen_s = time.perf_counter() - t
+        d, x = wl.mass.shape
+        self.shape = pb.make_ansai_shape(wl.pieces, wl.count, wl.prec_bits, d, x)
+        self.sym = torch.from_numpy(wl.sym).to(dev)
+        self.dist = torch.from_numpy(wl.dist).to(dev)
+        mass = torch.from_numpy(wl.mass).to(dev)
+        self.tables = torch.empty(pb.pilc_ansai_table_bytes(wl.prec_bits, d, x), dtype=torch.uint8, device=dev)
+        pb.pilc_ansai_build_tables(wl.prec_bits, d, x, mass, self.tables)
+        ws_bytes, max_coded = pb.pilc_ansai_workspace_size(self.shape)
+        self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self.coded = torch.empty(max_coded, dtype=torch.uint8, device=dev)
+        self.out = torch.empty_like(self.sym)
+        self.name = "%s, %d symbols, X=%d" % (wl.name, wl.symbols, x)
+        self.raw = wl.symbols
+        self.probe_src = self.sym          # plain copy of known size: 1 byte per symbol
+        self.probe_bytes = 2.0 * wl.symbols
+        self.step = "pilc_ansai_encode + pilc_ansai_decode of the whole batch"
+
+    def algo_bytes(self, nbytes):
+        # either coder kernel: symbols and distribution indices (1 byte each) plus the coded words
+        return 2.0 * self.raw + nbytes
+
+    def encode(self):
+        return self.pb.pilc_ansai_encode(self.shape, self.sym, self.dist, self.tables, self.workspace,
+                                         self.coded)[1]
+
+    def decode(self, nbytes):
+        self.pb.pilc_ansai_decode(self.shape, self.coded, nbytes, self.dist, self.tables, self.workspace,
+                                  self.out)
+
+    def reference(self):
+        return self.sym
+
+    timed = Run.timed
 
 
 def main():
@@ -243,7 +357,7 @@ def main():
     # children first: this process has not initialised HIP yet
     traffic = None
     if not (args.no_traffic or args.pmc_child):
-        traffic = measure_traffic(args.config, args.images)
+        traffic = measure_traffic(args.config, args.images, args.workload)
 
     import torch
     from paper_2206_05279_amd import binding as pb
@@ -253,23 +367,23 @@ def main():
         sys.exit(3)
     pb.lib()
 
-    run = Run(args.config, args.images)
+    ansai = args.workload == "ansai"
+    run = PieceRun(1 if args.config not in (0, 1) else args.config, args.images) if ansai else \
+        Run(args.config, args.images)
     if args.pmc_child:
         run.timed(1, 1)
-        probe = torch.empty_like(run.mu)   # plain device copy of known size: 2 bytes/subpixel
-        probe.copy_(run.mu)
+        probe = torch.empty_like(run.probe_src)   # plain device copy of known size
+        probe.copy_(run.probe_src)
         torch.cuda.synchronize()
         return
     r = run.timed(args.steps, args.warmup)
     raw_bytes, nbytes, kernel_ms = r["raw"], r["nbytes"], r["kernel_ms"]
     dom = max(kernel_ms, key=kernel_ms.get)
-    # algorithmic bytes of one launch of either lane kernel: 1 B pixel + 2 B mu + 2 B log-scale per
-    # subpixel, plus the container (payload + offset table + header)
-    algo_bytes = 5.0 * raw_bytes + nbytes
+    algo_bytes = run.algo_bytes(nbytes)
     achieved = algo_bytes / (kernel_ms[dom] * 1e-3) / 1e9
     traffic_bytes, traffic_detail = None, None
     if traffic:
-        copy_bytes = 2.0 * raw_bytes  # the probe copies the mu tensor
+        copy_bytes = run.probe_bytes / 2.0  # bytes the probe copy reads (and writes)
         detail = {}
         for key in ("read", "write"):
             scale = copy_bytes / (traffic[key + "_copy_kib"] * 1024.0)
@@ -282,7 +396,7 @@ def main():
             traffic_bytes = detail["read_bytes"] + detail["write_bytes"]
             traffic_detail = detail
     result = {
-        "metric": METRIC,
+        "metric": METRIC_ANSAI if ansai else METRIC,
         "value": raw_bytes / 1e6 / (r["elapsed"] / args.steps),
         "unit": "MB/s",
         "n_gpus": 1,
@@ -294,10 +408,10 @@ def main():
         "vs_baseline": None,
         "dtype": "u32",
         "data": "synthetic",
-        "config": {"workload": run.name, "step": "pilc_encode + pilc_decode of the whole batch"},
+        "config": {"workload": run.name, "step": run.step},
         "compress_MB_s": r["compress_MB_s"],
         "decompress_MB_s": r["decompress_MB_s"],
-        "bits_per_subpixel": 8.0 * nbytes / raw_bytes,
+        ("bits_per_symbol" if ansai else "bits_per_subpixel"): 8.0 * nbytes / raw_bytes,
         "coded_bytes": nbytes,
         "round_trip_exact": r["ok"],
         "kernel_ms": kernel_ms,
@@ -306,14 +420,18 @@ def main():
                      "traffic_detail": traffic_detail, "algorithmic_bytes": algo_bytes,
                      "avg_ms": kernel_ms[dom]},
         "paper_context": "PILC reports about 200 MB/s end to end and 675/672 MB/s for its coder "
-                         "phases on one V100 (table-driven coder, different workload)",
+                         "phases on one V100 (table-driven coder; Tab. 5 of the paper, another "
+                         "machine and workload: context, not a baseline)",
         "input_generation_s": run.gen_s,
     }
     ok = r["ok"]
     if not args.no_cpu_baseline:
-        sample = args.cpu_sample_images or {0: 64, 1: 21504, 2: 5376, 3: 10, 4: 336}[args.config]
-        result["cpu_baseline"] = cpu_baseline(run.wl, sample)
-    if not args.no_extra and args.images is None:
+        if ansai:
+            result["cpu_baseline"] = cpu_baseline_pieces(run.wl, args.cpu_sample_images or 131072)
+        else:
+            sample = args.cpu_sample_images or {0: 64, 1: 21504, 2: 5376, 3: 10, 4: 336}[args.config]
+            result["cpu_baseline"] = cpu_baseline(run.wl, sample)
+    if not args.no_extra and args.images is None and not ansai:
         extra = {}
         del run
         torch.cuda.empty_cache()
@@ -333,6 +451,19 @@ def main():
             ok = ok and o["ok"]
             del other
             torch.cuda.empty_cache()
+        other = PieceRun(1, None)   # the paper's own coder variant on its coder-measurement recipe
+        o = other.timed(max(2, args.steps // 3), 1)
+        dk = max(o["kernel_ms"], key=o["kernel_ms"].get)
+        extra["table-driven coder (Sec. 3.2 Algs. 3-4): " + other.name] = {
+            "compress_MB_s": o["compress_MB_s"], "decompress_MB_s": o["decompress_MB_s"],
+            "bits_per_symbol": 8.0 * o["nbytes"] / o["raw"], "round_trip_exact": o["ok"],
+            "kernel_ms": o["kernel_ms"],
+            "dominant_kernel_hbm_frac": other.algo_bytes(o["nbytes"]) / (o["kernel_ms"][dk] * 1e-3) / 1e9
+                                        / HBM_PEAK_GBS,
+        }
+        ok = ok and o["ok"]
+        del other
+        torch.cuda.empty_cache()
         result["other_workloads"] = extra
     print(json.dumps(result))
     if not ok:

@@ -156,7 +156,7 @@ typedef struct {
 } pilc_ansai_shape;
 
 /* Bytes of device memory pilc_ansai_build_tables fills for these M, D, X (0 if invalid):
- * 8*D*X for delta and phi plus 3*D*2^M (5*D*2^M when M > 12) for Theta, B, N, plus padding. */
+ * 8*D*256 for delta and phi plus 3*D*2^M (5*D*2^M when M > 12) for Theta, B, N, plus padding. */
 size_t pilc_ansai_table_bytes(uint32_t prec_bits, uint32_t num_dist, uint32_t num_sym);
 
 /* Builds the tables of Sec. 3.2 on the device from integer masses.

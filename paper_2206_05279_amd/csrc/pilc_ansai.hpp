@@ -29,9 +29,9 @@ constexpr uint32_t kAnsaiTabMagic = 0x42544150u;  // tag of a built table blob
 constexpr int ST_ARG = 1;                         // a symbol / index out of range, or foreign tables
 
 // Device blob written by k_ansai_build: 256-byte header, then
-//   enc   uint2 [D*X]         { delta, phi }                       (Alg. 3)
+//   enc   uint2 [D][256]      { delta, phi }, index d << 8 | x      (Alg. 3)
 //   theta uint8 [D << M]      symbol                               (Alg. 4)
-//   nb    u16 or u32 [D << M] (N - 2^M) << 4 | B; 32-bit entries when M > 12
+//   nb    u16 or u32 [D << M] (N - 2^M) << 4 | (15 - B); 32-bit entries when M > 12
 struct ATabHeader {
     uint32_t magic, M, D, X, ok;
     uint32_t pad[59];
@@ -47,7 +47,7 @@ static inline ATabLayout ansai_tab_layout(uint32_t M, uint32_t D, uint32_t X)
     ATabLayout t;
     t.wide = M > 12;
     t.enc_off = sizeof(ATabHeader);
-    t.theta_off = (t.enc_off + 8 * (size_t)D * X + 255) & ~(size_t)255;
+    t.theta_off = (t.enc_off + 8 * (size_t)D * 256 + 255) & ~(size_t)255;
     t.nb_off = (t.theta_off + ((size_t)D << M) + 255) & ~(size_t)255;
     t.total = (t.nb_off + ((size_t)D << M) * (t.wide ? 4 : 2) + 255) & ~(size_t)255;
     return t;
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(256) void k_ansai_build(uint32_t M, uint32_t X,
     for (uint32_t x = threadIdx.x; x < X; x += blockDim.x) {
         const uint32_t p = cum[x + 1] - cum[x];
         const uint32_t k = M - (31u - __clz(p));
-        enc[d * X + x] = make_uint2(k * top - (p << k), top - p + cum[x]);
+        enc[d * 256u + x] = make_uint2(k * top - (p << k), top - p + cum[x]);
     }
     for (uint32_t s = threadIdx.x; s < top; s += blockDim.x) {
         uint32_t lo = 0, hi = X - 1;  // largest x with cum[x] <= s
@@ -112,25 +112,23 @@ __global__ __launch_bounds__(256) void k_ansai_build(uint32_t M, uint32_t X,
         const uint32_t nrel = (t << b) - top;
         theta[((size_t)d << M) + s] = (uint8_t)lo;
         if (kWide)
-            static_cast<uint32_t *>(nb_raw)[((size_t)d << M) + s] = nrel << 4 | b;
+            static_cast<uint32_t *>(nb_raw)[((size_t)d << M) + s] = nrel << 4 | (b ^ 15u);
         else
-            static_cast<uint16_t *>(nb_raw)[((size_t)d << M) + s] = (uint16_t)(nrel << 4 | b);
+            static_cast<uint16_t *>(nb_raw)[((size_t)d << M) + s] = (uint16_t)(nrel << 4 | (b ^ 15u));
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Staging of a wavefront's 64 rows through LDS
+// Moving a wavefront's 64 rows between the arrays and LDS
 // ---------------------------------------------------------------------------------------------
-// A row is the `count` bytes of one piece in a [pieces, count] array.  It is cut at multiples of
-// kChunk bytes of the array; stage number `st` of a row is its st-th chunk from the front
-// (decode) or from the back (encode).  In LDS a row takes kChunk/4 + 1 dwords: an odd stride,
-// so the 64 threads that each walk their own row hit distinct banks.
-template <int kChunk>
-struct Stage {
-    static constexpr int kVec = kChunk / 16;     // 16-byte vectors per row
-    static constexpr int kRow = kChunk / 4 + 1;  // LDS dwords per row
-    static constexpr int kDwords = 64 * kRow;    // per wavefront and array
-};
+// A row is the `count` bytes of one piece in a [pieces, count] array.  Rows are cut at multiples
+// of 128 bytes of the array ("lines"); line-stage number `ls` of a row is its ls-th line from the
+// front (decode) or from the back (encode).  A wavefront fetches a line-stage of all its rows with
+// 16-byte loads in which eight consecutive threads cover one row's line: thread `lane` holds, for
+// i = 0..7, bytes [16c, 16c+16) of the line of row 8i + lane/8, with c = lane%8.  Every line is
+// thus requested once, whole.  The threads then pass the line through LDS in two halves of 64
+// bytes, where thread r finds the bytes of row r; the registers of the second half simply wait.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // Orders this wavefront's LDS accesses: LDS instructions of one wavefront execute in order, so
 // all that is needed is that the compiler keeps them in order too.
@@ -141,46 +139,62 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-struct RowStage {
-    uint32_t chunk;   // chunk index in the array
-    uint32_t lo, hi;  // the row's bytes inside that chunk: [lo, hi), empty when the row has none
+constexpr uint32_t kLine = 128, kHalf = 64;
+
+struct RowLine {
+    uint32_t line;    // line index in the array
+    uint32_t lo, hi;  // the row's bytes inside that line: [lo, hi), empty when the row has none
 };
 
-template <int kChunk>
-__device__ __forceinline__ RowStage row_stage(uint32_t piece, uint32_t count, uint32_t st,
-                                              bool from_back, bool row_exists)
+__device__ __forceinline__ RowLine row_line(uint32_t piece, uint32_t count, uint32_t ls,
+                                            bool from_back, bool row_exists)
 {
     const uint32_t rb = piece * count, re = rb + count;
-    const uint32_t first = rb / kChunk, last = (re - 1u) / kChunk;
-    RowStage r;
-    r.chunk = from_back ? last - st : first + st;
-    if (!row_exists || st > last - first) {
+    const uint32_t first = rb / kLine, last = (re - 1u) / kLine;
+    RowLine r;
+    r.line = from_back ? last - ls : first + ls;
+    if (!row_exists || ls > last - first) {
         r.lo = r.hi = 0;
         return r;
     }
-    const uint32_t cb = r.chunk * kChunk;
+    const uint32_t cb = r.line * kLine;
     r.lo = rb > cb ? rb - cb : 0u;
-    r.hi = re < cb + kChunk ? re - cb : (uint32_t)kChunk;
+    r.hi = re < cb + kLine ? re - cb : kLine;
     return r;
 }
 
-// Cooperative load of stage `st` of the rows of pieces p0 .. p0+np-1 into `rows`.
-template <int kChunk>
-__device__ __forceinline__ void stage_load(const uint8_t *__restrict__ arr, uint32_t total_bytes,
-                                           uint32_t *rows, uint32_t p0, uint32_t np,
-                                           uint32_t count, uint32_t st, bool from_back)
+// The part of [lo, hi) that falls into half `h` of the line, relative to that half.
+__device__ __forceinline__ void half_range(const RowLine &r, uint32_t h, uint32_t *lo, uint32_t *hi)
 {
-    using S = Stage<kChunk>;
-    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t base = h * kHalf;
+    *lo = min(max(r.lo, base), base + kHalf) - base;
+    *hi = min(max(r.hi, base), base + kHalf) - base;
+}
+
+__device__ __forceinline__ uint32_t line_stage_count(uint32_t count)
+{
+    // a row of `count` bytes starting anywhere touches at most this many lines
+    return (count + 2u * kLine - 2u) / kLine;
+}
+
+// Fetches line-stage `ls` of the rows of pieces p0 .. p0+np-1 (zeros where a row has no such line).
+// The data is used once: the loads are marked non-temporal so that they do not push the lines this
+// kernel writes out of the L2 before they are complete.
+__device__ __forceinline__ void line_load(const uint8_t *__restrict__ arr, uint32_t total_bytes,
+                                          uint32_t p0, uint32_t np, uint32_t count, uint32_t ls,
+                                          bool from_back, uint4 (&v)[8])
+{
+    const uint32_t lane = threadIdx.x & 63u, c = lane & 7u;
 #pragma unroll
-    for (int i = 0; i < S::kVec; ++i) {
-        const uint32_t idx = i * 64 + lane, r = idx / S::kVec, c = idx % S::kVec;
-        const RowStage rs = row_stage<kChunk>(p0 + r, count, st, from_back, r < np);
-        if (rs.hi > rs.lo) {
-            const uint32_t off = rs.chunk * kChunk + c * 16u;
-            uint4 v;
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t r = i * 8 + (lane >> 3);
+        const RowLine rl = row_line(p0 + r, count, ls, from_back, r < np);
+        v[i] = make_uint4(0u, 0u, 0u, 0u);
+        if (rl.hi > rl.lo) {
+            const uint32_t off = rl.line * kLine + c * 16u;
             if (off + 16u <= total_bytes) {
-                v = *reinterpret_cast<const uint4 *>(arr + off);
+                const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(arr + off));
+                v[i] = make_uint4(t.x, t.y, t.z, t.w);
             } else {  // the array ends inside this vector
                 uint32_t w0 = 0u, w1 = 0u, w2 = 0u, w3 = 0u;
 #pragma unroll
@@ -191,78 +205,74 @@ __device__ __forceinline__ void stage_load(const uint8_t *__restrict__ arr, uint
                     if (off + 8u + k < total_bytes) w2 |= (uint32_t)arr[off + 8u + k] << sh8;
                     if (off + 12u + k < total_bytes) w3 |= (uint32_t)arr[off + 12u + k] << sh8;
                 }
-                v = make_uint4(w0, w1, w2, w3);
+                v[i] = make_uint4(w0, w1, w2, w3);
             }
-            uint32_t *dst = rows + r * S::kRow + c * 4u;
-            dst[0] = v.x;
-            dst[1] = v.y;
-            dst[2] = v.z;
-            dst[3] = v.w;
         }
     }
 }
 
-// Cooperative store of stage `st` (front order) from `rows`: only bytes that belong to a row.
-template <int kChunk>
-__device__ __forceinline__ void stage_store(uint8_t *__restrict__ arr, const uint32_t *rows,
-                                            uint32_t p0, uint32_t np, uint32_t count, uint32_t st)
+// True if some byte of w is >= limit (1 <= limit <= 255).  `k7` and `use_or` are derived from the
+// limit once: k7 = ((limit <= 128 ? 128 : 256) - limit) * 0x01010101.
+struct ByteLimit {
+    uint32_t k7;
+    bool use_or, none;  // none: limit 256, nothing to check
+};
+
+__device__ __forceinline__ ByteLimit byte_limit(uint32_t limit)
 {
-    using S = Stage<kChunk>;
-    const uint32_t lane = threadIdx.x & 63u;
+    ByteLimit b;
+    b.none = limit >= 256u;
+    b.use_or = limit <= 128u;
+    b.k7 = ((b.use_or ? 128u : 256u) - (b.none ? 255u : limit)) * 0x01010101u;
+    return b;
+}
+
+__device__ __forceinline__ uint32_t bytes_at_or_above(uint32_t w, const ByteLimit &b)
+{
+    const uint32_t t = (w & 0x7F7F7F7Fu) + b.k7;  // bit 7 of a byte: its low 7 bits reach the bound
+    return (b.use_or ? (t | w) : (t & w)) & 0x80808080u;
+}
+
+// Checks the 8 vectors against a limit; a vector with an offending byte is zeroed (so that no
+// table index leaves its table) and reported.
+__device__ __forceinline__ uint32_t lines_check(uint4 (&v)[8], const ByteLimit &b)
+{
+    uint32_t bad = 0u;
+    if (b.none) return 0u;
 #pragma unroll
-    for (int i = 0; i < S::kVec; ++i) {
-        const uint32_t idx = i * 64 + lane, r = idx / S::kVec, c = idx % S::kVec;
-        const RowStage rs = row_stage<kChunk>(p0 + r, count, st, false, r < np);
-        const uint32_t vb = c * 16u;
-        if (rs.hi > rs.lo && vb < rs.hi && vb + 16u > rs.lo) {
-            const uint32_t *src = rows + r * S::kRow + c * 4u;
-            const uint32_t off = rs.chunk * kChunk + vb;
-            if (rs.lo <= vb && vb + 16u <= rs.hi) {
-                *reinterpret_cast<uint4 *>(arr + off) = make_uint4(src[0], src[1], src[2], src[3]);
-            } else {
-                for (uint32_t k = 0; k < 16u; ++k)
-                    if (vb + k >= rs.lo && vb + k < rs.hi)
-                        arr[off + k] = (uint8_t)(src[k >> 2] >> (8u * (k & 3u)));
-            }
-        }
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t f = bytes_at_or_above(v[i].x, b) | bytes_at_or_above(v[i].y, b) |
+                           bytes_at_or_above(v[i].z, b) | bytes_at_or_above(v[i].w, b);
+        if (f) v[i] = make_uint4(0u, 0u, 0u, 0u);
+        bad |= f;
     }
-}
-
-__device__ __forceinline__ uint32_t ansai_stage_count(uint32_t count, int chunk)
-{
-    // a row of `count` bytes starting anywhere touches at most this many chunks
-    return (count + 2u * (uint32_t)chunk - 2u) / (uint32_t)chunk;
+    return bad;
 }
 
 // ---------------------------------------------------------------------------------------------
 // Encode (Alg. 3), symbols of a piece taken last-first
 // ---------------------------------------------------------------------------------------------
 constexpr int kAnsaiEncWaves = 4;
+constexpr uint32_t kEncRow = 33;  // LDS dwords per row: 64 table indices of 16 bits, one dword pad
 
 struct EncLane {
     uint32_t S;     // state in [2^M, 2^(M+1))
     uint32_t acc;   // bits pushed and not yet written, low bit first
     uint32_t nacc;  // how many of them, < 32
     uint32_t woff;  // scratch index of the next word
-    uint32_t nwords;
-    uint32_t bad;
 };
 
-template <bool kTabLds>
-__device__ __forceinline__ void ansai_push(EncLane &L, uint32_t x, uint32_t d, const AShape &sh,
-                                           const uint2 *tab, uint32_t *__restrict__ scratch)
+// One step of Alg. 3 with the table entry e = {delta, phi} already fetched.
+__device__ __forceinline__ void ansai_push(EncLane &L, const uint2 e, uint32_t M,
+                                           uint32_t *__restrict__ scratch)
 {
-    L.bad |= (uint32_t)(x >= sh.X) | (uint32_t)(d >= sh.D);
-    const uint32_t idx = min(d, sh.D - 1u) * sh.X + min(x, sh.X - 1u);
-    const uint2 e = tab[idx];
-    const uint32_t b = (e.x + L.S) >> sh.M;  // Alg. 3: number of bits to push
+    const uint32_t b = (e.x + L.S) >> M;  // number of bits to push
     const uint32_t low = L.S & ((1u << b) - 1u);
     L.acc |= low << L.nacc;
     uint32_t nn = L.nacc + b;
     if (nn >= 32u) {  // b <= 15, so nacc >= 17 here and the shift below is in 1..15
         scratch[L.woff] = L.acc;
         L.woff += 64u;
-        L.nwords += 1u;
         L.acc = low >> (32u - L.nacc);
         nn -= 32u;
     }
@@ -270,22 +280,41 @@ __device__ __forceinline__ void ansai_push(EncLane &L, uint32_t x, uint32_t d, c
     L.S = (L.S >> b) + e.y;
 }
 
-template <int kChunk, bool kTabLds>
+// Puts half `h` of the fetched lines into LDS as table indices d << 8 | x, 16 bits per symbol.
+__device__ __forceinline__ void enc_put(uint32_t *rows, const uint4 (&sv)[8], const uint4 (&dv)[8],
+                                        uint32_t h)
+{
+    const uint32_t lane = threadIdx.x & 63u, c = lane & 7u;
+    if ((c >> 2) != h) return;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        uint32_t *dst = rows + (i * 8 + (lane >> 3)) * kEncRow + (c & 3u) * 8u;
+        const uint32_t s[4] = {sv[i].x, sv[i].y, sv[i].z, sv[i].w};
+        const uint32_t d[4] = {dv[i].x, dv[i].y, dv[i].z, dv[i].w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            // bytes {s0, d0, s1, d1} and {s2, d2, s3, d3}
+            dst[2 * k] = __builtin_amdgcn_perm(d[k], s[k], 0x05010400u);
+            dst[2 * k + 1] = __builtin_amdgcn_perm(d[k], s[k], 0x07030602u);
+        }
+    }
+}
+
+template <bool kTabLds>
 __global__ __launch_bounds__(64 * kAnsaiEncWaves) void k_ansai_encode(
     AShape sh, const uint8_t *__restrict__ sym, const uint8_t *__restrict__ dist,
     const uint2 *__restrict__ enc_tab, uint32_t *__restrict__ scratch, uint32_t maxw,
     uint32_t *__restrict__ piece_bits, uint32_t *__restrict__ piece_state, int *status)
 {
-    using S = Stage<kChunk>;
     extern __shared__ uint32_t lds[];
     if (*status != ST_OK) return;  // the tables are not the ones this shape needs
     const uint2 *tab = enc_tab;
     uint32_t *stage_base = lds;
     if (kTabLds) {
         uint2 *t = reinterpret_cast<uint2 *>(lds);
-        for (uint32_t i = threadIdx.x; i < sh.D * sh.X; i += blockDim.x) t[i] = enc_tab[i];
+        for (uint32_t i = threadIdx.x; i < sh.D * 256u; i += blockDim.x) t[i] = enc_tab[i];
         tab = t;
-        stage_base = lds + 2u * sh.D * sh.X;
+        stage_base = lds + 2u * sh.D * 256u;
         __syncthreads();
     }
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
@@ -293,52 +322,66 @@ __global__ __launch_bounds__(64 * kAnsaiEncWaves) void k_ansai_encode(
     const uint32_t p0 = gw * 64u;
     if (p0 >= sh.pieces) return;
     const uint32_t np = min(64u, sh.pieces - p0);
-    uint32_t *srow = stage_base + wave * 2u * S::kDwords;
-    uint32_t *drow = srow + S::kDwords;
+    uint32_t *rows = stage_base + wave * 64u * kEncRow;
+    const uint32_t *my = rows + lane * kEncRow;
     const uint32_t total = sh.pieces * sh.count;
     const bool mine = lane < np;
+    const ByteLimit lim_x = byte_limit(sh.X), lim_d = byte_limit(sh.D);
+    const uint32_t M = sh.M;
 
     EncLane L;
-    L.S = 1u << sh.M;
+    L.S = 1u << M;
     L.acc = 0u;
     L.nacc = 0u;
     L.woff = gw * maxw * 64u + lane;
-    L.nwords = 0u;
-    L.bad = 0u;
+    const uint32_t woff0 = L.woff;
+    uint32_t bad = 0u;
 
-    const uint32_t stages = ansai_stage_count(sh.count, kChunk);
-    for (uint32_t st = 0; st < stages; ++st) {
-        wave_lds_sync();
-        stage_load<kChunk>(sym, total, srow, p0, np, sh.count, st, true);
-        stage_load<kChunk>(dist, total, drow, p0, np, sh.count, st, true);
-        wave_lds_sync();
-        const RowStage rs = row_stage<kChunk>(p0 + lane, sh.count, st, true, mine);
-        const uint32_t *ms = srow + lane * S::kRow, *md = drow + lane * S::kRow;
-        if (__all(rs.lo == 0u && rs.hi == (uint32_t)kChunk)) {
+    uint4 sv[8], dv[8];
+    const uint32_t lines = line_stage_count(sh.count);
+    line_load(sym, total, p0, np, sh.count, 0u, true, sv);
+    line_load(dist, total, p0, np, sh.count, 0u, true, dv);
+    for (uint32_t ls = 0; ls < lines; ++ls) {
+        const RowLine rl = row_line(p0 + lane, sh.count, ls, true, mine);
+        bad |= lines_check(sv, lim_x) | lines_check(dv, lim_d);
 #pragma unroll 1
-            for (int dw = kChunk / 4 - 1; dw >= 0; --dw) {
-                const uint32_t s4 = ms[dw], d4 = md[dw];
-#pragma unroll
-                for (int k = 3; k >= 0; --k)
-                    ansai_push<kTabLds>(L, (s4 >> (8 * k)) & 255u, (d4 >> (8 * k)) & 255u, sh, tab, scratch);
+        for (int h = 1; h >= 0; --h) {
+            wave_lds_sync();
+            enc_put(rows, sv, dv, (uint32_t)h);
+            wave_lds_sync();
+            if (h == 0 && ls + 1u < lines) {  // the registers are free: fetch the next lines now
+                line_load(sym, total, p0, np, sh.count, ls + 1u, true, sv);
+                line_load(dist, total, p0, np, sh.count, ls + 1u, true, dv);
             }
-        } else {
+            uint32_t lo, hi;
+            half_range(rl, (uint32_t)h, &lo, &hi);
+            if (__all(lo == 0u && hi == kHalf)) {
 #pragma unroll 1
-            for (int dw = kChunk / 4 - 1; dw >= 0; --dw) {
-                const uint32_t s4 = ms[dw], d4 = md[dw];
-#pragma unroll
-                for (int k = 3; k >= 0; --k)
-                    if ((uint32_t)(dw * 4 + k) - rs.lo < rs.hi - rs.lo)
-                        ansai_push<kTabLds>(L, (s4 >> (8 * k)) & 255u, (d4 >> (8 * k)) & 255u, sh, tab, scratch);
+                for (int j = 15; j >= 0; --j) {  // four symbols a turn, last first
+                    const uint32_t w0 = my[2 * j], w1 = my[2 * j + 1];
+                    const uint2 e3 = tab[w1 >> 16], e2 = tab[w1 & 0xFFFFu];
+                    const uint2 e1 = tab[w0 >> 16], e0 = tab[w0 & 0xFFFFu];
+                    ansai_push(L, e3, M, scratch);
+                    ansai_push(L, e2, M, scratch);
+                    ansai_push(L, e1, M, scratch);
+                    ansai_push(L, e0, M, scratch);
+                }
+            } else {
+#pragma unroll 1
+                for (int j = 31; j >= 0; --j) {  // two symbols a turn
+                    const uint32_t w = my[j];
+                    if ((uint32_t)(2 * j + 1) - lo < hi - lo) ansai_push(L, tab[w >> 16], M, scratch);
+                    if ((uint32_t)(2 * j) - lo < hi - lo) ansai_push(L, tab[w & 0xFFFFu], M, scratch);
+                }
             }
         }
     }
     if (mine) {
         if (L.nacc) scratch[L.woff] = L.acc;
-        piece_bits[p0 + lane] = L.nwords * 32u + L.nacc;
+        piece_bits[p0 + lane] = ((L.woff - woff0) >> 6) * 32u + L.nacc;
         piece_state[p0 + lane] = L.S;
-        if (L.bad) *status = ST_ARG;
     }
+    if (bad) *status = ST_ARG;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -419,65 +462,148 @@ __global__ void k_ansai_check_header(AShape sh, const uint8_t *__restrict__ code
     status->payload_bytes = payload;
 }
 
+// A thread's view of its piece's stream.  The words still to be taken sit in the payload below
+// `widx`; the next ones are kept ahead of use in a small per-thread ring in LDS, which is topped
+// up with aligned 16-byte loads issued a group of symbols before their data is needed, so no
+// step of the decoding chain ever waits for global memory.
+constexpr uint32_t kRingWords = 16;   // per thread; ring slot of a word = its dword index mod 16
+constexpr uint32_t kRingStride = 17;  // odd: threads reading their own rings hit distinct banks
+constexpr int kGroupSyms = 8;         // symbols between top-ups; they take at most 4 words (M <= 15)
+constexpr uint32_t kDecRow = 17;      // LDS dwords per row: 64 index / symbol bytes, one dword pad
+
 struct DecLane {
-    uint32_t s;          // state minus 2^M
-    unsigned long long win;  // the top n bits of the stream, right-aligned; win < 2^n
-    uint32_t n;          // < 64
-    uint32_t widx;       // payload dword index one past the next word to take
-    uint32_t wleft;      // words not yet taken
-    uint32_t bad, corrupt;
+    uint32_t s;              // state minus 2^M
+    unsigned long long win;  // the next n bits of the stream from bit 62 downwards; bit 63 is 0
+    int n;                   // <= 63; negative once a corrupt stream has run dry
+    uint32_t widx;           // dword index (from the container's start) one past the next word
+    uint32_t wleft;          // words not yet taken
+    uint32_t lp;             // the ring holds the words [lp, widx); a multiple of 4
+    uint32_t first;          // dword index of the piece's first word
+    uint32_t cand;           // word widx-1, read ahead from the ring
 };
 
-__device__ __forceinline__ void ansai_refill(DecLane &L, const uint32_t *__restrict__ payload)
+__device__ __forceinline__ uint4 ansai_quad_load(const uint32_t *__restrict__ cw, uint32_t total_dw,
+                                                 uint32_t q)
 {
-    if (L.n < 32u && L.wleft > 0u) {
+    if (q + 4u <= total_dw) return *reinterpret_cast<const uint4 *>(cw + q);
+    uint4 v;  // the container ends inside this quad
+    v.x = q < total_dw ? cw[q] : 0u;
+    v.y = q + 1u < total_dw ? cw[q + 1u] : 0u;
+    v.z = q + 2u < total_dw ? cw[q + 2u] : 0u;
+    v.w = q + 3u < total_dw ? cw[q + 3u] : 0u;
+    return v;
+}
+
+__device__ __forceinline__ void ansai_ring_put(uint32_t *ring, uint32_t q, const uint4 &v)
+{
+    ring[q & 15u] = v.x;  // q is a multiple of 4: the four slots do not wrap
+    ring[(q & 15u) + 1u] = v.y;
+    ring[(q & 15u) + 2u] = v.z;
+    ring[(q & 15u) + 3u] = v.w;
+}
+
+// Takes the next word into the window when fewer than 32 bits are left in it.
+__device__ __forceinline__ void ansai_refill(DecLane &L)
+{
+    if (L.n < 32 && L.wleft > 0u) {
+        L.win |= (unsigned long long)L.cand << (31 - L.n);
+        L.n += 32;
         L.widx -= 1u;
         L.wleft -= 1u;
-        L.win = (L.win << 32) | payload[L.widx];
-        L.n += 32u;
     }
 }
 
-template <bool kWide>
-__device__ __forceinline__ uint32_t ansai_pop(DecLane &L, uint32_t d, const AShape &sh,
-                                              const uint8_t *theta, const void *nb_raw)
+__device__ __forceinline__ void ansai_peek(DecLane &L, const uint32_t *ring)
 {
-    L.bad |= (uint32_t)(d >= sh.D);
-    const uint32_t ti = (min(d, sh.D - 1u) << sh.M) + L.s;
+    L.cand = ring[(L.widx - 1u) & 15u];
+}
+
+// One step of Alg. 4.  `dm` = d << M.  The table entry holds N[d,S] - 2^M above its low four
+// bits and 15 - B[d,S] in them, so that 31 - B, the shift that leaves the B popped bits (kept in
+// the order they were pushed) at the bottom of the window's upper word, is one and-or away.
+// A stream that has run dry yields zeros here; the count n then ends below zero and the piece
+// fails its final check.
+template <bool kWide>
+__device__ __forceinline__ uint32_t ansai_pop(DecLane &L, uint32_t dm, const uint8_t *theta,
+                                              const void *nb_raw)
+{
+    const uint32_t ti = dm + L.s;
     const uint32_t e = kWide ? static_cast<const uint32_t *>(nb_raw)[ti]
                              : (uint32_t) static_cast<const uint16_t *>(nb_raw)[ti];
     const uint32_t x = theta[ti];
-    const uint32_t b = e & 15u;
-    L.corrupt |= (uint32_t)(b > L.n);  // the stream ran dry
-    L.n = max(L.n, b) - b;
-    const uint32_t v = (uint32_t)(L.win >> L.n);  // the last b bits, in the order they were pushed
-    L.win -= (unsigned long long)v << L.n;
-    L.s = (e >> 4) + v;  // Alg. 4: S <- N[d,S] + popped bits
+    const uint32_t sh = (e & 15u) | 16u;  // 31 - B
+    const uint32_t v = (uint32_t)(L.win >> 32) >> sh;
+    L.s = (e >> 4) + v;  // S <- N[d,S] + popped bits
+    const uint32_t b = 31u - sh;
+    L.win = (L.win << b) & 0x7FFFFFFFFFFFFFFFull;
+    L.n -= (int)b;
     return x;
 }
 
-template <int kChunk, bool kWide, bool kTabLds>
-__global__ __launch_bounds__(1024) void k_ansai_decode(
-    AShape sh, const uint8_t *__restrict__ coded, const uint8_t *__restrict__ dist,
-    const uint8_t *__restrict__ theta_g, const void *__restrict__ nb_g, uint8_t *__restrict__ out,
-    uint32_t maxw, Status *status)
+// Puts half `h` of the fetched index lines into LDS, 64 bytes per row.
+__device__ __forceinline__ void dec_put(uint32_t *rows, const uint4 (&dv)[8], uint32_t h)
 {
-    using S = Stage<kChunk>;
+    const uint32_t lane = threadIdx.x & 63u, c = lane & 7u;
+    if ((c >> 2) != h) return;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        uint32_t *dst = rows + (i * 8 + (lane >> 3)) * kDecRow + (c & 3u) * 4u;
+        dst[0] = dv[i].x;
+        dst[1] = dv[i].y;
+        dst[2] = dv[i].z;
+        dst[3] = dv[i].w;
+    }
+}
+
+// Writes the decoded symbols of half `h` of line-stage `ls` from LDS to the output rows: only
+// bytes that belong to a row.  Four threads cover a row's 64 bytes.
+__device__ __forceinline__ void dec_store(uint8_t *__restrict__ out, const uint32_t *rows, uint32_t p0,
+                                          uint32_t np, uint32_t count, uint32_t ls, uint32_t h)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t r = i * 16 + (lane >> 2), c = lane & 3u;
+        const RowLine rl = row_line(p0 + r, count, ls, false, r < np);
+        uint32_t lo, hi;
+        half_range(rl, h, &lo, &hi);
+        const uint32_t vb = c * 16u;
+        if (hi > lo && vb < hi && vb + 16u > lo) {
+            const uint32_t *src = rows + r * kDecRow + c * 4u;
+            const uint32_t off = rl.line * kLine + h * kHalf + vb;
+            if (lo <= vb && vb + 16u <= hi) {
+                *reinterpret_cast<uint4 *>(out + off) = make_uint4(src[0], src[1], src[2], src[3]);
+            } else {
+                for (uint32_t k = 0; k < 16u; ++k)
+                    if (vb + k >= lo && vb + k < hi) out[off + k] = (uint8_t)(src[k >> 2] >> (8u * (k & 3u)));
+            }
+        }
+    }
+}
+
+constexpr int kAnsaiDecMaxWaves = 8;
+
+template <bool kWide, bool kTabLds>
+__global__ __launch_bounds__(64 * kAnsaiDecMaxWaves) void k_ansai_decode(
+    AShape sh, const uint8_t *__restrict__ coded, uint32_t total_dw,
+    const uint8_t *__restrict__ dist, const uint8_t *__restrict__ theta_g,
+    const void *__restrict__ nb_g, uint8_t *__restrict__ out, uint32_t maxw, Status *status)
+{
     extern __shared__ uint32_t lds[];
     if (status->code != ST_OK) return;
     const uint8_t *theta = theta_g;
     const void *nb = nb_g;
     uint32_t *stage_base = lds;
-    if (kTabLds) {
-        const uint32_t entries = sh.D << sh.M;  // a multiple of 4 whenever M >= 2; padded otherwise
+    if (kTabLds) {  // the chain's table first, so that its LDS address is the index times its size
+        const uint32_t entries = sh.D << sh.M;
         const uint32_t th_dw = (entries + 3u) >> 2, nb_dw = kWide ? entries : (entries + 1u) >> 1;
         const uint32_t *tg = reinterpret_cast<const uint32_t *>(theta_g);
         const uint32_t *ng = reinterpret_cast<const uint32_t *>(nb_g);
-        for (uint32_t i = threadIdx.x; i < th_dw; i += blockDim.x) lds[i] = tg[i];
-        for (uint32_t i = threadIdx.x; i < nb_dw; i += blockDim.x) lds[th_dw + i] = ng[i];
-        theta = reinterpret_cast<const uint8_t *>(lds);
-        nb = lds + th_dw;
-        stage_base = lds + th_dw + nb_dw;
+        for (uint32_t i = threadIdx.x; i < nb_dw; i += blockDim.x) lds[i] = ng[i];
+        for (uint32_t i = threadIdx.x; i < th_dw; i += blockDim.x) lds[nb_dw + i] = tg[i];
+        nb = lds;
+        theta = reinterpret_cast<const uint8_t *>(lds + nb_dw);
+        stage_base = lds + nb_dw + th_dw;
         __syncthreads();
     }
     const uint32_t waves = blockDim.x >> 6;
@@ -486,91 +612,118 @@ __global__ __launch_bounds__(1024) void k_ansai_decode(
     const uint32_t p0 = gw * 64u;
     if (p0 >= sh.pieces) return;
     const uint32_t np = min(64u, sh.pieces - p0);
-    uint32_t *rows = stage_base + wave * S::kDwords;
+    uint32_t *rows = stage_base + wave * 64u * (kDecRow + kRingStride);
+    uint32_t *ring = rows + 64u * kDecRow + lane * kRingStride;
+    uint32_t *my = rows + lane * kDecRow;
     const uint32_t total = sh.pieces * sh.count;
-    const uint32_t top = 1u << sh.M;
-    const uint32_t *offsets = reinterpret_cast<const uint32_t *>(coded + kHeaderBytes);
-    const uint32_t *payload = offsets + sh.pieces + 1u;
+    const uint32_t top = 1u << sh.M, M = sh.M;
+    const uint32_t *cw = reinterpret_cast<const uint32_t *>(coded);
+    const uint32_t off_dw = kHeaderBytes / 4u, pay_dw = off_dw + sh.pieces + 1u;
     const uint32_t payload_bytes = (uint32_t)status->payload_bytes;
+    const ByteLimit lim_d = byte_limit(sh.D);
 
     bool mine = lane < np;
+    uint32_t corrupt = 0u, bad = 0u;
     DecLane L;
     L.s = 0u;
     L.win = 0ull;
-    L.n = 0u;
-    L.widx = 0u;
+    L.n = 0;
+    L.widx = pay_dw + 4u;
     L.wleft = 0u;
-    L.bad = 0u;
-    L.corrupt = 0u;
+    L.lp = L.widx & ~3u;
+    L.first = L.widx;
+    L.cand = 0u;
     if (mine) {
-        const uint32_t begin = offsets[p0 + lane], end = offsets[p0 + lane + 1u];
+        const uint32_t begin = cw[off_dw + p0 + lane], end = cw[off_dw + p0 + lane + 1u];
         bool ok = end >= begin && end - begin >= 8u && end <= payload_bytes && ((begin | end) & 3u) == 0u;
         if (ok) {
-            const uint32_t state = payload[begin >> 2], bits = payload[(begin >> 2) + 1u];
+            const uint32_t rec = pay_dw + (begin >> 2);
+            const uint32_t state = cw[rec], bits = cw[rec + 1u];
             const uint32_t nw = (end - begin - 8u) >> 2;
             // no piece of `count` symbols holds more than maxw words
             ok = nw <= maxw && state >= top && state < 2u * top && bits <= 32u * nw && bits + 31u >= 32u * nw;
             if (ok) {
                 L.s = state - top;
-                L.widx = (begin >> 2) + 2u + nw;
+                L.first = rec + 2u;
+                L.widx = L.first + nw;
                 L.wleft = nw;
                 if (nw > 0u) {  // the last word holds the top 1..32 bits
                     const uint32_t r = bits - 32u * (nw - 1u);
                     L.widx -= 1u;
                     L.wleft -= 1u;
-                    L.win = payload[L.widx] & (0xFFFFFFFFu >> (32u - r));
-                    L.n = r;
+                    L.win = (unsigned long long)(cw[L.widx] & (0xFFFFFFFFu >> (32u - r))) << (63u - r);
+                    L.n = (int)r;
+                }
+                // fill the ring with the 16 words that end at the aligned quad holding word widx-1
+                L.lp = (L.widx + 3u) & ~3u;
+                if (L.wleft > 0u) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        L.lp -= 4u;
+                        ansai_ring_put(ring, L.lp, ansai_quad_load(cw, total_dw, L.lp));
+                    }
                 }
             }
         }
         if (!ok) {
-            L.corrupt = 1u;
+            corrupt = 1u;
             mine = false;
         }
     }
 
-    const uint32_t stages = ansai_stage_count(sh.count, kChunk);
-    for (uint32_t st = 0; st < stages; ++st) {
-        wave_lds_sync();
-        stage_load<kChunk>(dist, total, rows, p0, np, sh.count, st, false);
-        wave_lds_sync();
-        const RowStage rs = row_stage<kChunk>(p0 + lane, sh.count, st, false, mine);
-        uint32_t *my = rows + lane * S::kRow;
-        if (__all(rs.lo == 0u && rs.hi == (uint32_t)kChunk)) {
+    uint4 dv[8];
+    const uint32_t lines = line_stage_count(sh.count);
+    line_load(dist, total, p0, np, sh.count, 0u, false, dv);
+    for (uint32_t ls = 0; ls < lines; ++ls) {
+        const RowLine rl = row_line(p0 + lane, sh.count, ls, false, mine);
+        bad |= lines_check(dv, lim_d);
 #pragma unroll 1
-            for (int dw = 0; dw < kChunk / 4; ++dw) {
-                const uint32_t d4 = my[dw];
-                uint32_t x4 = 0u;
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    if ((k & 1) == 0) ansai_refill(L, payload);
-                    x4 |= ansai_pop<kWide>(L, (d4 >> (8 * k)) & 255u, sh, theta, nb) << (8 * k);
-                }
-                my[dw] = x4;
-            }
-        } else {
+        for (uint32_t h = 0; h < 2u; ++h) {
+            wave_lds_sync();
+            dec_put(rows, dv, h);
+            wave_lds_sync();
+            if (h == 1u && ls + 1u < lines) line_load(dist, total, p0, np, sh.count, ls + 1u, false, dv);
+            uint32_t lo, hi;
+            half_range(rl, h, &lo, &hi);
+            const bool all_full = __all(lo == 0u && hi == kHalf);
 #pragma unroll 1
-            for (int dw = 0; dw < kChunk / 4; ++dw) {
-                const uint32_t d4 = my[dw];
-                uint32_t x4 = 0u;
+            for (int g = 0; g < (int)kHalf / kGroupSyms; ++g) {
+                // top-up: ask now for the quad below the ring, store it after this group
+                const uint32_t qb = L.lp - 4u;
+                const bool want = L.wleft > 0u && L.widx - L.lp <= kRingWords - 4u && L.lp > L.first;
+                uint4 q = make_uint4(0u, 0u, 0u, 0u);
+                if (want) q = ansai_quad_load(cw, total_dw, qb);
+                ansai_peek(L, ring);
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    // a check per symbol here: which symbols of a pair run depends on the row
-                    if ((uint32_t)(dw * 4 + k) - rs.lo < rs.hi - rs.lo) {
-                        ansai_refill(L, payload);
-                        x4 |= ansai_pop<kWide>(L, (d4 >> (8 * k)) & 255u, sh, theta, nb) << (8 * k);
+                for (int hh = 0; hh < kGroupSyms / 4; ++hh) {
+                    const int dw = g * (kGroupSyms / 4) + hh;
+                    const uint32_t d4 = my[dw];
+                    uint32_t x4 = 0u;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        if ((k & 1) == 0) {
+                            ansai_refill(L);
+                            ansai_peek(L, ring);
+                        }
+                        const uint32_t dm = ((d4 >> (8 * k)) & 255u) << M;
+                        if (all_full || (uint32_t)(dw * 4 + k) - lo < hi - lo)
+                            x4 |= ansai_pop<kWide>(L, dm, theta, nb) << (8 * k);
                     }
+                    my[dw] = x4;
                 }
-                my[dw] = x4;
+                if (want) {
+                    ansai_ring_put(ring, qb, q);
+                    L.lp = qb;
+                }
             }
+            wave_lds_sync();
+            dec_store(out, rows, p0, np, sh.count, ls, h);
         }
-        wave_lds_sync();
-        stage_store<kChunk>(out, rows, p0, np, sh.count, st);
     }
-    if (mine && (L.s != 0u || L.n != 0u || L.wleft != 0u)) L.corrupt = 1u;
-    if (L.corrupt)
+    if (mine && (L.s != 0u || L.n != 0 || L.wleft != 0u)) corrupt = 1u;
+    if (corrupt)
         status->code = ST_CORRUPT;
-    else if (L.bad)
+    else if (bad)
         status->code = ST_ARG;
 }
 
@@ -624,7 +777,6 @@ static AWorkspace ansai_layout(const AShape &sh)
 
 static int ansai_status_to_error(int st) { return st == ST_ARG ? PILC_E_ARG : status_to_error(st); }
 
-constexpr int kAnsaiChunk = 64;
 
 // LDS one workgroup may use on gfx950: the whole 160 KB of a compute unit.
 constexpr size_t kLdsBytes = 160 * 1024;
@@ -722,13 +874,13 @@ int pilc_ansai_encode(const pilc_ansai_shape *shape, const uint8_t *sym_dev, con
     Timer timer(stream);
     k_ansai_begin<<<1, 1, 0, stream>>>(sh, reinterpret_cast<const ATabHeader *>(tb), status);
     const uint32_t blocks = (uint32_t)ceil_div64(ws.waves, kAnsaiEncWaves);
-    const size_t stage_lds = (size_t)kAnsaiEncWaves * 2 * Stage<kAnsaiChunk>::kDwords * 4;
-    const size_t tab_lds = 8 * (size_t)sh.D * sh.X;
+    const size_t stage_lds = (size_t)kAnsaiEncWaves * 64 * kEncRow * 4;
+    const size_t tab_lds = 8 * (size_t)sh.D * 256;
     if (tab_lds <= 24576)
-        k_ansai_encode<kAnsaiChunk, true><<<blocks, 64 * kAnsaiEncWaves, stage_lds + tab_lds, stream>>>(
+        k_ansai_encode<true><<<blocks, 64 * kAnsaiEncWaves, stage_lds + tab_lds, stream>>>(
             sh, sym_dev, dist_dev, enc_tab, scratch, ws.maxw, piece_bits, piece_state, &status->code);
     else
-        k_ansai_encode<kAnsaiChunk, false><<<blocks, 64 * kAnsaiEncWaves, stage_lds, stream>>>(
+        k_ansai_encode<false><<<blocks, 64 * kAnsaiEncWaves, stage_lds, stream>>>(
             sh, sym_dev, dist_dev, enc_tab, scratch, ws.maxw, piece_bits, piece_state, &status->code);
     timer.mark("k_ansai_encode");
     const ItemBytes piece_bytes = {8u, 4u, 31u, 5u};  // state, bit count, 32-bit words
@@ -775,20 +927,20 @@ int pilc_ansai_decode(const pilc_ansai_shape *shape, const uint8_t *coded_dev, s
     const uint8_t *tb = static_cast<const uint8_t *>(tables_dev);
 
     // Workgroup shape: the decode tables in LDS when they leave room for at least four
-    // wavefronts' staging rows; as many wavefronts (<= 16) as then fit.
+    // wavefronts' staging rows; as many wavefronts (<= 8) as then fit.
     const size_t entries = (size_t)sh.D << sh.M;
     const size_t tab_lds = ((entries + 3) / 4 + (t.wide ? entries : (entries + 1) / 2)) * 4;
-    const size_t row_lds = (size_t)Stage<kAnsaiChunk>::kDwords * 4;
+    const size_t row_lds = (size_t)64 * (kDecRow + kRingStride) * 4;
     bool tab_in_lds = tab_lds + 4 * row_lds <= lds_max;
     uint32_t waves = 4;
     if (tab_in_lds) {
         // small tables: several workgroups per compute unit; large ones: one big workgroup
         size_t fit = (lds_max - tab_lds) / row_lds;
-        waves = tab_lds <= 16384 ? 4u : (uint32_t)(fit > 16 ? 16 : fit);
+        waves = tab_lds <= 16384 ? 4u : (uint32_t)(fit > kAnsaiDecMaxWaves ? kAnsaiDecMaxWaves : fit);
     }
     if (const char *e = getenv("PILC_ANSAI_WAVES")) {  // TEMPORARY tuning knob
         int v = atoi(e);
-        if (v >= 1 && v <= 16 && (!tab_in_lds || tab_lds + v * row_lds <= lds_max)) waves = (uint32_t)v;
+        if (v >= 1 && v <= kAnsaiDecMaxWaves && (!tab_in_lds || tab_lds + v * row_lds <= lds_max)) waves = (uint32_t)v;
     }
     if (getenv("PILC_ANSAI_NOLDS")) tab_in_lds = false;
     Timer timer(stream);
@@ -801,7 +953,7 @@ int pilc_ansai_decode(const pilc_ansai_shape *shape, const uint8_t *coded_dev, s
     // written compiles without private memory, so this does not trigger.
 #define PILC_ANSAI_DECODE(WIDE, LDS)                                                                  \
     do {                                                                                              \
-        auto kern = k_ansai_decode<kAnsaiChunk, WIDE, LDS>;                                           \
+        auto kern = k_ansai_decode<WIDE, LDS>;                                           \
         hipFuncAttributes fa;                                                                         \
         HIP_TRY(hipFuncGetAttributes(&fa, reinterpret_cast<const void *>(kern)));                     \
         if (fa.localSizeBytes != 0 && waves > 4) waves = 4;                                           \
@@ -809,7 +961,8 @@ int pilc_ansai_decode(const pilc_ansai_shape *shape, const uint8_t *coded_dev, s
         const uint32_t blocks = (uint32_t)ceil_div64(ws.waves, waves);                                \
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                             \
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));    \
-        kern<<<blocks, 64 * waves, lds_bytes, stream>>>(sh, coded_dev, dist_dev, tb + t.theta_off,    \
+        kern<<<blocks, 64 * waves, lds_bytes, stream>>>(sh, coded_dev, (uint32_t)(coded_bytes >> 2),   \
+                                                        dist_dev, tb + t.theta_off,                   \
                                                         tb + t.nb_off, sym_out_dev, ws.maxw, status); \
     } while (0)
     if (t.wide) {

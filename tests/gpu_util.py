@@ -105,15 +105,17 @@ class DevicePieces:
 
     def table_views(self):
         """delta, phi, theta, nbits, next as numpy arrays read back from the device blob: a
-        256-byte header, {delta, phi} pairs, then the symbol table and the (next << 4 | nbits)
-        table (16-bit entries up to M = 12, 32-bit above), each part 256-byte aligned."""
+        256-byte header, {delta, phi} pairs in rows of 256 per distribution, then the symbol table
+        and the (next << 4 | 15 - nbits) table (16-bit entries up to M = 12, 32-bit above), each
+        part 256-byte aligned."""
         blob = self.tables.cpu().numpy()
         up = lambda v: (v + 255) & ~255
         entries = self.d << self.m
-        enc = np.frombuffer(blob, dtype="<u4", count=2 * self.d * self.x, offset=256).reshape(self.d, self.x, 2)
-        th_off = up(256 + 8 * self.d * self.x)
+        enc = np.frombuffer(blob, dtype="<u4", count=2 * self.d * 256, offset=256).reshape(self.d, 256, 2)
+        enc = enc[:, : self.x]
+        th_off = up(256 + 8 * self.d * 256)
         theta = np.frombuffer(blob, dtype=np.uint8, count=entries, offset=th_off).reshape(self.d, -1)
         nb_off = up(th_off + entries)
         nb = np.frombuffer(blob, dtype="<u4" if self.m > 12 else "<u2", count=entries, offset=nb_off)
         nb = nb.astype(np.uint32).reshape(self.d, -1)
-        return enc[:, :, 0].astype(np.int32), enc[:, :, 1], theta, (nb & 15).astype(np.uint8), nb >> 4
+        return enc[:, :, 0].astype(np.int32), enc[:, :, 1], theta, (15 - (nb & 15)).astype(np.uint8), nb >> 4

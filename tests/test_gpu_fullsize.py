@@ -76,3 +76,45 @@ def test_full_size_sampled_parity(name, make, samples):
     assert d.decode() == pb.PILC_OK
     assert torch.equal(d.out, d.img)
     print("bits/subpixel %.4f" % (8.0 * nbytes / wl.subpixels), flush=True)
+
+
+def test_table_coder_full_size_sampled_parity():
+    """The table-driven coder (Sec. 3.2 Algs. 3-4) on the 10^6 x 1000 recipe of Sec. 4.3, in the
+    launch configuration bench.py times: pieces are independent, so sampled pieces are encoded by
+    the reference one by one and compared with their records; offsets must be the exclusive scan
+    of the record sizes; decode must return the symbols."""
+    import struct
+
+    from oracle import ansai_oracle as ao
+    from paper_2206_05279_amd import synth_pieces as sp
+
+    from gpu_util import DevicePieces
+
+    print("generating pieces1", flush=True)
+    wl = sp.make_piece_workload(1, threads=16)
+    dp = DevicePieces(wl.prec_bits, wl.mass, wl.sym, wl.dist)
+    print("encoding", flush=True)
+    _, nbytes = dp.encode()
+    coded = dp.coded_numpy()
+    pieces = wl.pieces
+    assert coded[:4].tobytes() == b"PANS"
+    assert struct.unpack_from("<6I", coded, 4) == (1, pieces, wl.count, wl.prec_bits, 8, 256)
+    payload = struct.unpack_from("<Q", coded, 48)[0]
+    offs = np.frombuffer(coded, dtype="<u4", count=pieces + 1, offset=64)
+    body = coded[64 + 4 * (pieces + 1):]
+    assert nbytes == 64 + 4 * (pieces + 1) + payload and offs[0] == 0 and offs[-1] == payload
+    # every record's size follows from its own bit count, and the offsets are their running sum
+    bits = np.frombuffer(body, dtype="<u4")[(offs[:-1] // 4 + 1).astype(np.int64)]
+    sizes = 8 + 4 * ((bits.astype(np.int64) + 31) // 32)
+    assert np.array_equal(np.diff(offs.astype(np.int64)), sizes)
+    rng = np.random.default_rng(11)
+    sample = np.unique(np.concatenate([[0, 63, 64, pieces - 65, pieces - 1], rng.integers(0, pieces, 200)]))
+    rc, ref = ao.encode(wl.prec_bits, wl.mass, wl.sym[sample], wl.dist[sample])
+    assert rc == ao.OK
+    roffs = np.frombuffer(ref, dtype="<u4", count=sample.size + 1, offset=64)
+    rbody = ref[64 + 4 * (sample.size + 1):]
+    for i, p in enumerate(sample):
+        assert np.array_equal(body[offs[p]:offs[p + 1]], rbody[roffs[i]:roffs[i + 1]]), "piece %d" % p
+    print("decoding", flush=True)
+    dp.decode()
+    assert torch.equal(dp.out, dp.sym)
