@@ -177,35 +177,39 @@ __device__ __forceinline__ uint32_t line_stage_count(uint32_t count)
     return (count + 2u * kLine - 2u) / kLine;
 }
 
-// Fetches line-stage `ls` of the rows of pieces p0 .. p0+np-1 (zeros where a row has no such line).
-// The data is used once: the loads are marked non-temporal so that they do not push the lines this
+// Bytes [a, b) of a dword, the others cleared (a, b may lie outside 0..4).
+__device__ __forceinline__ uint32_t keep_bytes(uint32_t w, int a, int b)
+{
+    const uint32_t below_b = b >= 4 ? 0xFFFFFFFFu : (b <= 0 ? 0u : (1u << (8 * b)) - 1u);
+    const uint32_t below_a = a >= 4 ? 0xFFFFFFFFu : (a <= 0 ? 0u : (1u << (8 * a)) - 1u);
+    return w & below_b & ~below_a;
+}
+
+// Fetches line-stage `ls` of the rows of pieces p0 .. p0+np-1: for every row the 16-byte vectors
+// of its line that hold at least one of its bytes (they may also hold bytes of its neighbours);
+// zeros elsewhere.  A vector is aligned and holds a byte of the array, so it lies inside the
+// array's last page even where it reaches past the array's end; such bytes are cleared.  The
+// data is used once: the loads are marked non-temporal so that they do not push the lines this
 // kernel writes out of the L2 before they are complete.
 __device__ __forceinline__ void line_load(const uint8_t *__restrict__ arr, uint32_t total_bytes,
                                           uint32_t p0, uint32_t np, uint32_t count, uint32_t ls,
                                           bool from_back, uint4 (&v)[8])
 {
-    const uint32_t lane = threadIdx.x & 63u, c = lane & 7u;
+    const uint32_t lane = threadIdx.x & 63u, vb = (lane & 7u) * 16u;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const uint32_t r = i * 8 + (lane >> 3);
         const RowLine rl = row_line(p0 + r, count, ls, from_back, r < np);
         v[i] = make_uint4(0u, 0u, 0u, 0u);
-        if (rl.hi > rl.lo) {
-            const uint32_t off = rl.line * kLine + c * 16u;
-            if (off + 16u <= total_bytes) {
-                const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(arr + off));
-                v[i] = make_uint4(t.x, t.y, t.z, t.w);
-            } else {  // the array ends inside this vector
-                uint32_t w0 = 0u, w1 = 0u, w2 = 0u, w3 = 0u;
-#pragma unroll
-                for (uint32_t k = 0; k < 4u; ++k) {
-                    const uint32_t sh8 = 8u * k;
-                    if (off + k < total_bytes) w0 |= (uint32_t)arr[off + k] << sh8;
-                    if (off + 4u + k < total_bytes) w1 |= (uint32_t)arr[off + 4u + k] << sh8;
-                    if (off + 8u + k < total_bytes) w2 |= (uint32_t)arr[off + 8u + k] << sh8;
-                    if (off + 12u + k < total_bytes) w3 |= (uint32_t)arr[off + 12u + k] << sh8;
-                }
-                v[i] = make_uint4(w0, w1, w2, w3);
+        if (vb < rl.hi && vb + 16u > rl.lo) {
+            const uint32_t off = rl.line * kLine + vb;
+            const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(arr + off));
+            v[i] = make_uint4(t.x, t.y, t.z, t.w);
+            if (off + 16u > total_bytes) {  // at most one vector of the whole grid
+                asm volatile("" ::: "memory");  // keep this a branch, not a chain of selects
+                const int b = (int)(total_bytes - off);
+                v[i] = make_uint4(keep_bytes(t.x, 0, b), keep_bytes(t.y, 0, b - 4), keep_bytes(t.z, 0, b - 8),
+                                  keep_bytes(t.w, 0, b - 12));
             }
         }
     }
@@ -323,8 +327,8 @@ __global__ __launch_bounds__(64 * kAnsaiEncWaves) void k_ansai_encode(
     if (p0 >= sh.pieces) return;
     const uint32_t np = min(64u, sh.pieces - p0);
     uint32_t *rows = stage_base + wave * 64u * kEncRow;
-    const uint32_t *my = rows + lane * kEncRow;
     const uint32_t total = sh.pieces * sh.count;
+    const uint32_t *my = rows + lane * kEncRow;
     const bool mine = lane < np;
     const ByteLimit lim_x = byte_limit(sh.X), lim_d = byte_limit(sh.D);
     const uint32_t M = sh.M;
@@ -342,6 +346,7 @@ __global__ __launch_bounds__(64 * kAnsaiEncWaves) void k_ansai_encode(
     line_load(sym, total, p0, np, sh.count, 0u, true, sv);
     line_load(dist, total, p0, np, sh.count, 0u, true, dv);
     for (uint32_t ls = 0; ls < lines; ++ls) {
+        asm volatile("" : "+s"(sh.count));  // recompute the row geometry per line-stage (registers)
         const RowLine rl = row_line(p0 + lane, sh.count, ls, true, mine);
         bad |= lines_check(sv, lim_x) | lines_check(dv, lim_d);
 #pragma unroll 1
@@ -466,111 +471,120 @@ __global__ void k_ansai_check_header(AShape sh, const uint8_t *__restrict__ code
 // `widx`; the next ones are kept ahead of use in a small per-thread ring in LDS, which is topped
 // up with aligned 16-byte loads issued a group of symbols before their data is needed, so no
 // step of the decoding chain ever waits for global memory.
-constexpr uint32_t kRingWords = 16;   // per thread; ring slot of a word = its dword index mod 16
-constexpr uint32_t kRingStride = 17;  // odd: threads reading their own rings hit distinct banks
+// LDS is what limits how many pieces a compute unit decodes at once (the tables take most of
+// it), so both per-thread areas are kept small: a ring of three quads and a row of 32 bytes.
+constexpr uint32_t kRingWords = 12;   // per thread: three aligned quads
+constexpr uint32_t kRingStride = 13;  // odd: threads reading their own rings hit distinct banks
 constexpr int kGroupSyms = 8;         // symbols between top-ups; they take at most 4 words (M <= 15)
-constexpr uint32_t kDecRow = 17;      // LDS dwords per row: 64 index / symbol bytes, one dword pad
+constexpr uint32_t kPart = 32;        // bytes of a row passed through LDS at a time: a quarter line
+constexpr uint32_t kDecRow = 10;      // LDS dwords per row: 32 bytes and a pad that keeps rows 8-byte aligned
 
 struct DecLane {
     uint32_t s;              // state minus 2^M
     unsigned long long win;  // the next n bits of the stream from bit 62 downwards; bit 63 is 0
     int n;                   // <= 63; negative once a corrupt stream has run dry
     uint32_t widx;           // dword index (from the container's start) one past the next word
-    uint32_t wleft;          // words not yet taken
     uint32_t lp;             // the ring holds the words [lp, widx); a multiple of 4
-    uint32_t first;          // dword index of the piece's first word
+    uint32_t first;          // dword index of the piece's first word; widx - first words are left
+    uint32_t rs;             // ring slot of word widx-1; slots fall with the word index, 0 wraps to 11
+    uint32_t ws;             // ring slot of word lp: 0, 4 or 8
     uint32_t cand;           // word widx-1, read ahead from the ring
 };
 
-__device__ __forceinline__ uint4 ansai_quad_load(const uint32_t *__restrict__ cw, uint32_t total_dw,
-                                                 uint32_t q)
+// An aligned quad that holds at least one word of the container: it lies inside the container's
+// last page even where it reaches past the container's end.
+__device__ __forceinline__ uint4 ansai_quad_load(const uint32_t *__restrict__ cw, uint32_t q)
 {
-    if (q + 4u <= total_dw) return *reinterpret_cast<const uint4 *>(cw + q);
-    uint4 v;  // the container ends inside this quad
-    v.x = q < total_dw ? cw[q] : 0u;
-    v.y = q + 1u < total_dw ? cw[q + 1u] : 0u;
-    v.z = q + 2u < total_dw ? cw[q + 2u] : 0u;
-    v.w = q + 3u < total_dw ? cw[q + 3u] : 0u;
-    return v;
+    return *reinterpret_cast<const uint4 *>(cw + q);
 }
 
-__device__ __forceinline__ void ansai_ring_put(uint32_t *ring, uint32_t q, const uint4 &v)
+__device__ __forceinline__ void ansai_ring_put(uint32_t *ring, uint32_t slot, const uint4 &v)
 {
-    ring[q & 15u] = v.x;  // q is a multiple of 4: the four slots do not wrap
-    ring[(q & 15u) + 1u] = v.y;
-    ring[(q & 15u) + 2u] = v.z;
-    ring[(q & 15u) + 3u] = v.w;
+    ring[slot] = v.x;
+    ring[slot + 1u] = v.y;
+    ring[slot + 2u] = v.z;
+    ring[slot + 3u] = v.w;
 }
 
-// Takes the next word into the window when fewer than 32 bits are left in it.
+// Takes the next word into the window when fewer than 32 bits are left in it.  Written without
+// a branch: in a wavefront of 64 streams some thread needs a word at almost every call.
 __device__ __forceinline__ void ansai_refill(DecLane &L)
 {
-    if (L.n < 32 && L.wleft > 0u) {
-        L.win |= (unsigned long long)L.cand << (31 - L.n);
-        L.n += 32;
-        L.widx -= 1u;
-        L.wleft -= 1u;
-    }
+    const bool need = L.n < 32 && L.widx > L.first;
+    const uint32_t c = need ? L.cand : 0u;
+    L.win |= (unsigned long long)c << ((31 - L.n) & 63);  // need implies 0 <= n <= 31
+    const uint32_t t = need ? 1u : 0u;
+    L.n += (int)(t << 5);
+    L.widx -= t;
+    const uint32_t below = L.rs == 0u ? kRingWords - 1u : L.rs - 1u;
+    L.rs = need ? below : L.rs;
 }
 
 __device__ __forceinline__ void ansai_peek(DecLane &L, const uint32_t *ring)
 {
-    L.cand = ring[(L.widx - 1u) & 15u];
+    L.cand = ring[L.rs];
 }
 
 // One step of Alg. 4.  `dm` = d << M.  The table entry holds N[d,S] - 2^M above its low four
 // bits and 15 - B[d,S] in them, so that 31 - B, the shift that leaves the B popped bits (kept in
-// the order they were pushed) at the bottom of the window's upper word, is one and-or away.
-// A stream that has run dry yields zeros here; the count n then ends below zero and the piece
-// fails its final check.
-template <bool kWide>
-__device__ __forceinline__ uint32_t ansai_pop(DecLane &L, uint32_t dm, const uint8_t *theta,
+// the order they were pushed) at the bottom of the window's upper word, is the low five bits of
+// (entry | 16).  A stream that has run dry yields zeros here; the count n then ends below zero and
+// the piece fails its final check.  With `active` false the step is the identity (no symbol of
+// this thread's row at this position).
+template <bool kWide, bool kMasked>
+__device__ __forceinline__ uint32_t ansai_pop(DecLane &L, uint32_t dm, bool active, const uint8_t *theta,
                                               const void *nb_raw)
 {
     const uint32_t ti = dm + L.s;
-    const uint32_t e = kWide ? static_cast<const uint32_t *>(nb_raw)[ti]
-                             : (uint32_t) static_cast<const uint16_t *>(nb_raw)[ti];
+    uint32_t e = kWide ? static_cast<const uint32_t *>(nb_raw)[ti]
+                       : (uint32_t) static_cast<const uint16_t *>(nb_raw)[ti];
     const uint32_t x = theta[ti];
-    const uint32_t sh = (e & 15u) | 16u;  // 31 - B
-    const uint32_t v = (uint32_t)(L.win >> 32) >> sh;
+    if (kMasked) e = active ? e : (L.s << 4 | 15u);  // pops nothing, keeps the state
+    const uint32_t v = (uint32_t)(L.win >> 32) >> ((e | 16u) & 31u);
     L.s = (e >> 4) + v;  // S <- N[d,S] + popped bits
-    const uint32_t b = 31u - sh;
+    const uint32_t b = ~e & 15u;
     L.win = (L.win << b) & 0x7FFFFFFFFFFFFFFFull;
     L.n -= (int)b;
     return x;
 }
 
-// Puts half `h` of the fetched index lines into LDS, 64 bytes per row.
-__device__ __forceinline__ void dec_put(uint32_t *rows, const uint4 (&dv)[8], uint32_t h)
+// The part of [lo, hi) that falls into quarter `ph` of the line, relative to that quarter.
+__device__ __forceinline__ void part_range(const RowLine &r, uint32_t ph, uint32_t *lo, uint32_t *hi)
+{
+    const uint32_t base = ph * kPart;
+    *lo = min(max(r.lo, base), base + kPart) - base;
+    *hi = min(max(r.hi, base), base + kPart) - base;
+}
+
+// Puts quarter `ph` of the fetched index lines into LDS, 32 bytes per row.
+__device__ __forceinline__ void dec_put(uint32_t *rows, const uint4 (&dv)[8], uint32_t ph)
 {
     const uint32_t lane = threadIdx.x & 63u, c = lane & 7u;
-    if ((c >> 2) != h) return;
+    if ((c >> 1) != ph) return;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        uint32_t *dst = rows + (i * 8 + (lane >> 3)) * kDecRow + (c & 3u) * 4u;
-        dst[0] = dv[i].x;
-        dst[1] = dv[i].y;
-        dst[2] = dv[i].z;
-        dst[3] = dv[i].w;
+        uint2 *dst = reinterpret_cast<uint2 *>(rows + (i * 8 + (lane >> 3)) * kDecRow + (c & 1u) * 4u);
+        dst[0] = make_uint2(dv[i].x, dv[i].y);
+        dst[1] = make_uint2(dv[i].z, dv[i].w);
     }
 }
 
-// Writes the decoded symbols of half `h` of line-stage `ls` from LDS to the output rows: only
-// bytes that belong to a row.  Four threads cover a row's 64 bytes.
+// Writes the decoded symbols of quarter `ph` of line-stage `ls` from LDS to the output rows:
+// only bytes that belong to a row.  Two threads cover a row's 32 bytes.
 __device__ __forceinline__ void dec_store(uint8_t *__restrict__ out, const uint32_t *rows, uint32_t p0,
-                                          uint32_t np, uint32_t count, uint32_t ls, uint32_t h)
+                                          uint32_t np, uint32_t count, uint32_t ls, uint32_t ph)
 {
     const uint32_t lane = threadIdx.x & 63u;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const uint32_t r = i * 16 + (lane >> 2), c = lane & 3u;
+    for (int i = 0; i < 2; ++i) {
+        const uint32_t r = i * 32 + (lane >> 1), c = lane & 1u;
         const RowLine rl = row_line(p0 + r, count, ls, false, r < np);
         uint32_t lo, hi;
-        half_range(rl, h, &lo, &hi);
+        part_range(rl, ph, &lo, &hi);
         const uint32_t vb = c * 16u;
         if (hi > lo && vb < hi && vb + 16u > lo) {
             const uint32_t *src = rows + r * kDecRow + c * 4u;
-            const uint32_t off = rl.line * kLine + h * kHalf + vb;
+            const uint32_t off = rl.line * kLine + ph * kPart + vb;
             if (lo <= vb && vb + 16u <= hi) {
                 *reinterpret_cast<uint4 *>(out + off) = make_uint4(src[0], src[1], src[2], src[3]);
             } else {
@@ -581,12 +595,55 @@ __device__ __forceinline__ void dec_store(uint8_t *__restrict__ out, const uint3
     }
 }
 
-constexpr int kAnsaiDecMaxWaves = 8;
+// The 32 symbols of one quarter line of this thread's row, in groups of eight.  Before a group
+// the quad below the ring is requested when there is room for it (it lies below the quads fetched
+// at the start, hence inside the container) and after the group it is stored, so its latency
+// hides behind eight symbols of every wavefront on the SIMD.  A group takes at most four words
+// and starts with at least four in the ring: with room for a quad (at most 8 words held) the quad
+// arrives by the end of the group, without room at least 9 - 4 are left.
+// kMasked: positions outside [lo, hi) are skipped by identity steps.
+template <bool kWide, bool kMasked>
+__device__ __forceinline__ void dec_part(DecLane &L, uint32_t *my, uint32_t *ring,
+                                         const uint32_t *__restrict__ cw, uint32_t M, uint32_t lo,
+                                         uint32_t hi, const uint8_t *theta, const void *nb)
+{
+#pragma unroll 1
+    for (int g = 0; g < (int)kPart / kGroupSyms; ++g) {
+        const uint32_t qb = L.lp - 4u;
+        const bool want = L.widx - L.lp <= kRingWords - 4u && L.lp > L.first;
+        uint4 q;
+        if (want) q = ansai_quad_load(cw, qb);
+        ansai_peek(L, ring);
+#pragma unroll 1
+        for (int hh = 0; hh < kGroupSyms / 4; ++hh) {
+            const int dw = g * (kGroupSyms / 4) + hh;
+            const uint32_t d4 = my[dw];
+            uint32_t x4 = 0u;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if ((k & 1) == 0) {
+                    ansai_refill(L);
+                    ansai_peek(L, ring);
+                }
+                const uint32_t dm = ((d4 >> (8 * k)) & 255u) << M;
+                const bool active = !kMasked || (uint32_t)(dw * 4 + k) - lo < hi - lo;
+                x4 |= ansai_pop<kWide, kMasked>(L, dm, active, theta, nb) << (8 * k);
+            }
+            my[dw] = x4;
+        }
+        if (want) {
+            L.ws = L.ws == 0u ? kRingWords - 4u : L.ws - 4u;
+            ansai_ring_put(ring, L.ws, q);
+            L.lp = qb;
+        }
+    }
+}
+
+constexpr int kAnsaiDecMaxWaves = 12;
 
 template <bool kWide, bool kTabLds>
 __global__ __launch_bounds__(64 * kAnsaiDecMaxWaves) void k_ansai_decode(
-    AShape sh, const uint8_t *__restrict__ coded, uint32_t total_dw,
-    const uint8_t *__restrict__ dist, const uint8_t *__restrict__ theta_g,
+    AShape sh, const uint8_t *__restrict__ coded, const uint8_t *__restrict__ dist, const uint8_t *__restrict__ theta_g,
     const void *__restrict__ nb_g, uint8_t *__restrict__ out, uint32_t maxw, Status *status)
 {
     extern __shared__ uint32_t lds[];
@@ -629,9 +686,10 @@ __global__ __launch_bounds__(64 * kAnsaiDecMaxWaves) void k_ansai_decode(
     L.win = 0ull;
     L.n = 0;
     L.widx = pay_dw + 4u;
-    L.wleft = 0u;
     L.lp = L.widx & ~3u;
     L.first = L.widx;
+    L.rs = 0u;
+    L.ws = 0u;
     L.cand = 0u;
     if (mine) {
         const uint32_t begin = cw[off_dw + p0 + lane], end = cw[off_dw + p0 + lane + 1u];
@@ -646,21 +704,20 @@ __global__ __launch_bounds__(64 * kAnsaiDecMaxWaves) void k_ansai_decode(
                 L.s = state - top;
                 L.first = rec + 2u;
                 L.widx = L.first + nw;
-                L.wleft = nw;
                 if (nw > 0u) {  // the last word holds the top 1..32 bits
                     const uint32_t r = bits - 32u * (nw - 1u);
                     L.widx -= 1u;
-                    L.wleft -= 1u;
                     L.win = (unsigned long long)(cw[L.widx] & (0xFFFFFFFFu >> (32u - r))) << (63u - r);
                     L.n = (int)r;
                 }
-                // fill the ring with the 16 words that end at the aligned quad holding word widx-1
+                // fill the ring with the 12 words that end at the aligned quad holding word widx-1
                 L.lp = (L.widx + 3u) & ~3u;
-                if (L.wleft > 0u) {
+                if (L.widx > L.first) {
+                    L.rs = 8u + ((L.widx - 1u) & 3u);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
+                    for (int i = 2; i >= 0; --i) {
                         L.lp -= 4u;
-                        ansai_ring_put(ring, L.lp, ansai_quad_load(cw, total_dw, L.lp));
+                        ansai_ring_put(ring, 4u * i, ansai_quad_load(cw, L.lp));
                     }
                 }
             }
@@ -675,52 +732,29 @@ __global__ __launch_bounds__(64 * kAnsaiDecMaxWaves) void k_ansai_decode(
     const uint32_t lines = line_stage_count(sh.count);
     line_load(dist, total, p0, np, sh.count, 0u, false, dv);
     for (uint32_t ls = 0; ls < lines; ++ls) {
+        // the row geometry is recomputed per line-stage instead of being kept in registers for
+        // all the rows a thread helps to move: that keeps the kernel free of register spills
+        asm volatile("" : "+s"(sh.count));
         const RowLine rl = row_line(p0 + lane, sh.count, ls, false, mine);
         bad |= lines_check(dv, lim_d);
 #pragma unroll 1
-        for (uint32_t h = 0; h < 2u; ++h) {
+        for (uint32_t h = 0; h < kLine / kPart; ++h) {
             wave_lds_sync();
             dec_put(rows, dv, h);
             wave_lds_sync();
-            if (h == 1u && ls + 1u < lines) line_load(dist, total, p0, np, sh.count, ls + 1u, false, dv);
+            if (h == kLine / kPart - 1u && ls + 1u < lines)
+                line_load(dist, total, p0, np, sh.count, ls + 1u, false, dv);
             uint32_t lo, hi;
-            half_range(rl, h, &lo, &hi);
-            const bool all_full = __all(lo == 0u && hi == kHalf);
-#pragma unroll 1
-            for (int g = 0; g < (int)kHalf / kGroupSyms; ++g) {
-                // top-up: ask now for the quad below the ring, store it after this group
-                const uint32_t qb = L.lp - 4u;
-                const bool want = L.wleft > 0u && L.widx - L.lp <= kRingWords - 4u && L.lp > L.first;
-                uint4 q = make_uint4(0u, 0u, 0u, 0u);
-                if (want) q = ansai_quad_load(cw, total_dw, qb);
-                ansai_peek(L, ring);
-#pragma unroll
-                for (int hh = 0; hh < kGroupSyms / 4; ++hh) {
-                    const int dw = g * (kGroupSyms / 4) + hh;
-                    const uint32_t d4 = my[dw];
-                    uint32_t x4 = 0u;
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        if ((k & 1) == 0) {
-                            ansai_refill(L);
-                            ansai_peek(L, ring);
-                        }
-                        const uint32_t dm = ((d4 >> (8 * k)) & 255u) << M;
-                        if (all_full || (uint32_t)(dw * 4 + k) - lo < hi - lo)
-                            x4 |= ansai_pop<kWide>(L, dm, theta, nb) << (8 * k);
-                    }
-                    my[dw] = x4;
-                }
-                if (want) {
-                    ansai_ring_put(ring, qb, q);
-                    L.lp = qb;
-                }
-            }
+            part_range(rl, h, &lo, &hi);
+            if (__all(lo == 0u && hi == kPart))
+                dec_part<kWide, false>(L, my, ring, cw, M, lo, hi, theta, nb);
+            else
+                dec_part<kWide, true>(L, my, ring, cw, M, lo, hi, theta, nb);
             wave_lds_sync();
             dec_store(out, rows, p0, np, sh.count, ls, h);
         }
     }
-    if (mine && (L.s != 0u || L.n != 0 || L.wleft != 0u)) corrupt = 1u;
+    if (mine && (L.s != 0u || L.n != 0 || L.widx != L.first)) corrupt = 1u;
     if (corrupt)
         status->code = ST_CORRUPT;
     else if (bad)
@@ -961,8 +995,7 @@ int pilc_ansai_decode(const pilc_ansai_shape *shape, const uint8_t *coded_dev, s
         const uint32_t blocks = (uint32_t)ceil_div64(ws.waves, waves);                                \
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                             \
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));    \
-        kern<<<blocks, 64 * waves, lds_bytes, stream>>>(sh, coded_dev, (uint32_t)(coded_bytes >> 2),   \
-                                                        dist_dev, tb + t.theta_off,                   \
+        kern<<<blocks, 64 * waves, lds_bytes, stream>>>(sh, coded_dev, dist_dev, tb + t.theta_off,    \
                                                         tb + t.nb_off, sym_out_dev, ws.maxw, status); \
     } while (0)
     if (t.wide) {
