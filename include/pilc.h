@@ -151,12 +151,12 @@ int pilc_set_kernel_policy(int policy);
 typedef struct {
     uint32_t pieces, count; /* independent pieces, symbols per piece; rounded-up pieces*count < 2^32 */
     uint32_t prec_bits;     /* M, 1..15, 2^M >= num_sym */
-    uint32_t num_dist;      /* D, 1..256 */
+    uint32_t num_dist;      /* D, 1..255 */
     uint32_t num_sym;       /* X, 2..256 */
 } pilc_ansai_shape;
 
 /* Bytes of device memory pilc_ansai_build_tables fills for these M, D, X (0 if invalid):
- * 8*D*256 for delta and phi plus 3*D*2^M (5*D*2^M when M > 12) for Theta, B, N, plus padding. */
+ * 8*(D*256+1) for delta and phi plus 3*D*2^M (5*D*2^M when M > 12) for Theta, B, N, plus padding. */
 size_t pilc_ansai_table_bytes(uint32_t prec_bits, uint32_t num_dist, uint32_t num_sym);
 
 /* Builds the tables of Sec. 3.2 on the device from integer masses.

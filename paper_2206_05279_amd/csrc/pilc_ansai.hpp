@@ -29,7 +29,8 @@ constexpr uint32_t kAnsaiTabMagic = 0x42544150u;  // tag of a built table blob
 constexpr int ST_ARG = 1;                         // a symbol / index out of range, or foreign tables
 
 // Device blob written by k_ansai_build: 256-byte header, then
-//   enc   uint2 [D][256]      { delta, phi }, index d << 8 | x      (Alg. 3)
+//   enc   uint2 [D][256] + 1  { delta, phi }, index d << 8 | x; the last entry, index D << 8,
+//                             is the identity step {-2^M, 0}: no bits pushed, state kept (Alg. 3)
 //   theta uint8 [D << M]      symbol                               (Alg. 4)
 //   nb    u16 or u32 [D << M] (N - 2^M) << 4 | (15 - B); 32-bit entries when M > 12
 struct ATabHeader {
@@ -47,7 +48,7 @@ static inline ATabLayout ansai_tab_layout(uint32_t M, uint32_t D, uint32_t X)
     ATabLayout t;
     t.wide = M > 12;
     t.enc_off = sizeof(ATabHeader);
-    t.theta_off = (t.enc_off + 8 * (size_t)D * 256 + 255) & ~(size_t)255;
+    t.theta_off = (t.enc_off + 8 * ((size_t)D * 256 + 1) + 255) & ~(size_t)255;
     t.nb_off = (t.theta_off + ((size_t)D << M) + 255) & ~(size_t)255;
     t.total = (t.nb_off + ((size_t)D << M) * (t.wide ? 4 : 2) + 255) & ~(size_t)255;
     return t;
@@ -92,6 +93,7 @@ __global__ __launch_bounds__(256) void k_ansai_build(uint32_t M, uint32_t X,
     }
     __syncthreads();
     if (bad) return;
+    if (d == 0 && threadIdx.x == 0) enc[gridDim.x * 256u] = make_uint2(0u - top, 0u);
     for (uint32_t x = threadIdx.x; x < X; x += blockDim.x) {
         const uint32_t p = cum[x + 1] - cum[x];
         const uint32_t k = M - (31u - __clz(p));
@@ -139,7 +141,7 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-constexpr uint32_t kLine = 128, kHalf = 64;
+constexpr uint32_t kLine = 128;
 
 struct RowLine {
     uint32_t line;    // line index in the array
@@ -161,14 +163,6 @@ __device__ __forceinline__ RowLine row_line(uint32_t piece, uint32_t count, uint
     r.lo = rb > cb ? rb - cb : 0u;
     r.hi = re < cb + kLine ? re - cb : kLine;
     return r;
-}
-
-// The part of [lo, hi) that falls into half `h` of the line, relative to that half.
-__device__ __forceinline__ void half_range(const RowLine &r, uint32_t h, uint32_t *lo, uint32_t *hi)
-{
-    const uint32_t base = h * kHalf;
-    *lo = min(max(r.lo, base), base + kHalf) - base;
-    *hi = min(max(r.hi, base), base + kHalf) - base;
 }
 
 __device__ __forceinline__ uint32_t line_stage_count(uint32_t count)
@@ -260,47 +254,69 @@ constexpr int kAnsaiEncWaves = 4;
 constexpr uint32_t kEncRow = 33;  // LDS dwords per row: 64 table indices of 16 bits, one dword pad
 
 struct EncLane {
-    uint32_t S;     // state in [2^M, 2^(M+1))
-    uint32_t acc;   // bits pushed and not yet written, low bit first
-    uint32_t nacc;  // how many of them, < 32
-    uint32_t woff;  // scratch index of the next word
+    uint32_t S;              // state in [2^M, 2^(M+1))
+    unsigned long long acc;  // bits pushed and not yet written, low bit first
+    uint32_t nacc;           // how many of them, < 32 between pairs of symbols
+    uint32_t woff;           // scratch index of the next word
 };
 
 // One step of Alg. 3 with the table entry e = {delta, phi} already fetched.
-__device__ __forceinline__ void ansai_push(EncLane &L, const uint2 e, uint32_t M,
-                                           uint32_t *__restrict__ scratch)
+__device__ __forceinline__ void ansai_push(EncLane &L, const uint2 e, uint32_t M)
 {
-    const uint32_t b = (e.x + L.S) >> M;  // number of bits to push
+    const uint32_t b = (e.x + L.S) >> M;  // number of bits to push, <= 15
     const uint32_t low = L.S & ((1u << b) - 1u);
-    L.acc |= low << L.nacc;
-    uint32_t nn = L.nacc + b;
-    if (nn >= 32u) {  // b <= 15, so nacc >= 17 here and the shift below is in 1..15
-        scratch[L.woff] = L.acc;
-        L.woff += 64u;
-        L.acc = low >> (32u - L.nacc);
-        nn -= 32u;
-    }
-    L.nacc = nn;
+    L.acc |= (unsigned long long)low << L.nacc;
+    L.nacc += b;
     L.S = (L.S >> b) + e.y;
 }
 
-// Puts half `h` of the fetched lines into LDS as table indices d << 8 | x, 16 bits per symbol.
+// Writes a word once 32 bits are there.  Called after every second symbol: two symbols add at
+// most 30 bits to fewer than 32, so the accumulator never overflows.
+__device__ __forceinline__ void ansai_emit(EncLane &L, uint32_t *__restrict__ scratch)
+{
+    if (L.nacc >= 32u) {
+        scratch[L.woff] = (uint32_t)L.acc;
+        L.woff += 64u;
+        L.acc >>= 32;
+        L.nacc -= 32u;
+    }
+}
+
+// Puts half `h` of the fetched lines into LDS as table indices d << 8 | x, 16 bits per symbol;
+// positions that are not part of a row get the index of the identity step, so that every thread
+// can run all 64 positions of the half without asking which are its own.
 __device__ __forceinline__ void enc_put(uint32_t *rows, const uint4 (&sv)[8], const uint4 (&dv)[8],
-                                        uint32_t h)
+                                        uint32_t h, uint32_t p0, uint32_t np, uint32_t count,
+                                        uint32_t ls, uint32_t ident)
 {
     const uint32_t lane = threadIdx.x & 63u, c = lane & 7u;
     if ((c >> 2) != h) return;
+    const uint32_t vb = c * 16u;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        uint32_t *dst = rows + (i * 8 + (lane >> 3)) * kEncRow + (c & 3u) * 8u;
+        const uint32_t r = i * 8 + (lane >> 3);
+        uint32_t *dst = rows + r * kEncRow + (c & 3u) * 8u;
+        const RowLine rl = row_line(p0 + r, count, ls, true, r < np);
         const uint32_t s[4] = {sv[i].x, sv[i].y, sv[i].z, sv[i].w};
         const uint32_t d[4] = {dv[i].x, dv[i].y, dv[i].z, dv[i].w};
+        uint32_t w[8];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             // bytes {s0, d0, s1, d1} and {s2, d2, s3, d3}
-            dst[2 * k] = __builtin_amdgcn_perm(d[k], s[k], 0x05010400u);
-            dst[2 * k + 1] = __builtin_amdgcn_perm(d[k], s[k], 0x07030602u);
+            w[2 * k] = __builtin_amdgcn_perm(d[k], s[k], 0x05010400u);
+            w[2 * k + 1] = __builtin_amdgcn_perm(d[k], s[k], 0x07030602u);
         }
+        if (vb < rl.lo || vb + 16u > rl.hi) {  // not wholly inside the row
+            asm volatile("" ::: "memory");      // keep this a branch, not a chain of selects
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const uint32_t pos = vb + 2u * k;
+                const bool in0 = pos - rl.lo < rl.hi - rl.lo, in1 = pos + 1u - rl.lo < rl.hi - rl.lo;
+                w[k] = (in0 ? (w[k] & 0xFFFFu) : ident) | (in1 ? (w[k] & 0xFFFF0000u) : ident << 16);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) dst[k] = w[k];
     }
 }
 
@@ -316,9 +332,9 @@ __global__ __launch_bounds__(64 * kAnsaiEncWaves) void k_ansai_encode(
     uint32_t *stage_base = lds;
     if (kTabLds) {
         uint2 *t = reinterpret_cast<uint2 *>(lds);
-        for (uint32_t i = threadIdx.x; i < sh.D * 256u; i += blockDim.x) t[i] = enc_tab[i];
+        for (uint32_t i = threadIdx.x; i < sh.D * 256u + 1u; i += blockDim.x) t[i] = enc_tab[i];
         tab = t;
-        stage_base = lds + 2u * sh.D * 256u;
+        stage_base = lds + 2u * (sh.D * 256u + 1u);
         __syncthreads();
     }
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
@@ -335,7 +351,7 @@ __global__ __launch_bounds__(64 * kAnsaiEncWaves) void k_ansai_encode(
 
     EncLane L;
     L.S = 1u << M;
-    L.acc = 0u;
+    L.acc = 0ull;
     L.nacc = 0u;
     L.woff = gw * maxw * 64u + lane;
     const uint32_t woff0 = L.woff;
@@ -347,42 +363,32 @@ __global__ __launch_bounds__(64 * kAnsaiEncWaves) void k_ansai_encode(
     line_load(dist, total, p0, np, sh.count, 0u, true, dv);
     for (uint32_t ls = 0; ls < lines; ++ls) {
         asm volatile("" : "+s"(sh.count));  // recompute the row geometry per line-stage (registers)
-        const RowLine rl = row_line(p0 + lane, sh.count, ls, true, mine);
         bad |= lines_check(sv, lim_x) | lines_check(dv, lim_d);
 #pragma unroll 1
         for (int h = 1; h >= 0; --h) {
             wave_lds_sync();
-            enc_put(rows, sv, dv, (uint32_t)h);
+            enc_put(rows, sv, dv, (uint32_t)h, p0, np, sh.count, ls, sh.D << 8);
             wave_lds_sync();
             if (h == 0 && ls + 1u < lines) {  // the registers are free: fetch the next lines now
                 line_load(sym, total, p0, np, sh.count, ls + 1u, true, sv);
                 line_load(dist, total, p0, np, sh.count, ls + 1u, true, dv);
             }
-            uint32_t lo, hi;
-            half_range(rl, (uint32_t)h, &lo, &hi);
-            if (__all(lo == 0u && hi == kHalf)) {
 #pragma unroll 1
-                for (int j = 15; j >= 0; --j) {  // four symbols a turn, last first
-                    const uint32_t w0 = my[2 * j], w1 = my[2 * j + 1];
-                    const uint2 e3 = tab[w1 >> 16], e2 = tab[w1 & 0xFFFFu];
-                    const uint2 e1 = tab[w0 >> 16], e0 = tab[w0 & 0xFFFFu];
-                    ansai_push(L, e3, M, scratch);
-                    ansai_push(L, e2, M, scratch);
-                    ansai_push(L, e1, M, scratch);
-                    ansai_push(L, e0, M, scratch);
-                }
-            } else {
-#pragma unroll 1
-                for (int j = 31; j >= 0; --j) {  // two symbols a turn
-                    const uint32_t w = my[j];
-                    if ((uint32_t)(2 * j + 1) - lo < hi - lo) ansai_push(L, tab[w >> 16], M, scratch);
-                    if ((uint32_t)(2 * j) - lo < hi - lo) ansai_push(L, tab[w & 0xFFFFu], M, scratch);
-                }
+            for (int j = 15; j >= 0; --j) {  // four symbols a turn, last first
+                const uint32_t w0 = my[2 * j], w1 = my[2 * j + 1];
+                const uint2 e3 = tab[w1 >> 16], e2 = tab[w1 & 0xFFFFu];
+                const uint2 e1 = tab[w0 >> 16], e0 = tab[w0 & 0xFFFFu];
+                ansai_push(L, e3, M);
+                ansai_push(L, e2, M);
+                ansai_emit(L, scratch);
+                ansai_push(L, e1, M);
+                ansai_push(L, e0, M);
+                ansai_emit(L, scratch);
             }
         }
     }
     if (mine) {
-        if (L.nacc) scratch[L.woff] = L.acc;
+        if (L.nacc) scratch[L.woff] = (uint32_t)L.acc;
         piece_bits[p0 + lane] = ((L.woff - woff0) >> 6) * 32u + L.nacc;
         piece_state[p0 + lane] = L.S;
     }
@@ -767,7 +773,7 @@ __global__ __launch_bounds__(64 * kAnsaiDecMaxWaves) void k_ansai_decode(
 static int make_ashape(const pilc_ansai_shape *in, AShape *sh)
 {
     if (!in || in->pieces == 0 || in->count == 0) return PILC_E_ARG;
-    if (in->prec_bits < 1 || in->prec_bits > 15 || in->num_dist < 1 || in->num_dist > 256 ||
+    if (in->prec_bits < 1 || in->prec_bits > 15 || in->num_dist < 1 || in->num_dist > 255 ||
         in->num_sym < 2 || in->num_sym > 256 || (1u << in->prec_bits) < in->num_sym)
         return PILC_E_ARG;
     // 32-bit byte offsets into the [pieces, count] arrays and 32-bit scratch word indices
@@ -909,8 +915,8 @@ int pilc_ansai_encode(const pilc_ansai_shape *shape, const uint8_t *sym_dev, con
     k_ansai_begin<<<1, 1, 0, stream>>>(sh, reinterpret_cast<const ATabHeader *>(tb), status);
     const uint32_t blocks = (uint32_t)ceil_div64(ws.waves, kAnsaiEncWaves);
     const size_t stage_lds = (size_t)kAnsaiEncWaves * 64 * kEncRow * 4;
-    const size_t tab_lds = 8 * (size_t)sh.D * 256;
-    if (tab_lds <= 24576)
+    const size_t tab_lds = 8 * ((size_t)sh.D * 256 + 1);
+    if (tab_lds <= 24576 + 8)
         k_ansai_encode<true><<<blocks, 64 * kAnsaiEncWaves, stage_lds + tab_lds, stream>>>(
             sh, sym_dev, dist_dev, enc_tab, scratch, ws.maxw, piece_bits, piece_state, &status->code);
     else
@@ -972,11 +978,6 @@ int pilc_ansai_decode(const pilc_ansai_shape *shape, const uint8_t *coded_dev, s
         size_t fit = (lds_max - tab_lds) / row_lds;
         waves = tab_lds <= 16384 ? 4u : (uint32_t)(fit > kAnsaiDecMaxWaves ? kAnsaiDecMaxWaves : fit);
     }
-    if (const char *e = getenv("PILC_ANSAI_WAVES")) {  // TEMPORARY tuning knob
-        int v = atoi(e);
-        if (v >= 1 && v <= kAnsaiDecMaxWaves && (!tab_in_lds || tab_lds + v * row_lds <= lds_max)) waves = (uint32_t)v;
-    }
-    if (getenv("PILC_ANSAI_NOLDS")) tab_in_lds = false;
     Timer timer(stream);
     k_ansai_begin<<<1, 1, 0, stream>>>(sh, reinterpret_cast<const ATabHeader *>(tb), status);
     k_ansai_check_header<<<1, 1, 0, stream>>>(sh, coded_dev, (unsigned long long)coded_bytes, status);

@@ -105,7 +105,8 @@ class DevicePieces:
 
     def table_views(self):
         """delta, phi, theta, nbits, next as numpy arrays read back from the device blob: a
-        256-byte header, {delta, phi} pairs in rows of 256 per distribution, then the symbol table
+        256-byte header, {delta, phi} pairs in rows of 256 per distribution (one more pair closes
+        them), then the symbol table
         and the (next << 4 | 15 - nbits) table (16-bit entries up to M = 12, 32-bit above), each
         part 256-byte aligned."""
         blob = self.tables.cpu().numpy()
@@ -113,7 +114,7 @@ class DevicePieces:
         entries = self.d << self.m
         enc = np.frombuffer(blob, dtype="<u4", count=2 * self.d * 256, offset=256).reshape(self.d, 256, 2)
         enc = enc[:, : self.x]
-        th_off = up(256 + 8 * self.d * 256)
+        th_off = up(256 + 8 * (self.d * 256 + 1))
         theta = np.frombuffer(blob, dtype=np.uint8, count=entries, offset=th_off).reshape(self.d, -1)
         nb_off = up(th_off + entries)
         nb = np.frombuffer(blob, dtype="<u4" if self.m > 12 else "<u2", count=entries, offset=nb_off)

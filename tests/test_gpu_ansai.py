@@ -40,7 +40,7 @@ CASES = [
     ("peaky masses", 11, _random(11, 4, 40, 0.05), 128, 1000, False),
     ("model does not fit", 12, _logistic(12, 8), 70, 640, True),
     ("40 distributions, encode tables in global memory", 9, _random(9, 40, 256, 1.0), 70, 200, False),
-    ("256 distributions", 8, _random(8, 256, 256, 1.0), 64, 100, False),
+    ("255 distributions", 8, _random(8, 255, 256, 1.0), 64, 100, False),
     ("4096 pieces of 1000", 12, _logistic(12, 8), 4096, 1000, False),
     ("M14 random", 14, _random(14, 2, 256, 1.0), 77, 130, False),
 ]
@@ -119,7 +119,7 @@ def test_bad_arguments(small):
     dp.encode()
     good = dp.shape
     for field, value in (("pieces", 0), ("count", 0), ("prec_bits", 0), ("prec_bits", 16), ("num_dist", 0),
-                         ("num_dist", 257), ("num_sym", 1), ("num_sym", 257)):
+                         ("num_dist", 256), ("num_sym", 1), ("num_sym", 257)):
         shape = pb.make_ansai_shape(good.pieces, good.count, good.prec_bits, good.num_dist, good.num_sym)
         setattr(shape, field, value)
         dp.shape = shape
