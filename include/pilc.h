@@ -169,6 +169,15 @@ int pilc_ansai_build_tables(uint32_t prec_bits, uint32_t num_dist, uint32_t num_
                             const uint32_t *mass_dev, void *tables_dev, size_t tables_bytes,
                             void *hip_stream);
 
+/* Re-centring of Sec. 3.3: the residual r ~ L(mu, s, 0, 255) is coded as (r - mu + 128) mod 256
+ * ~ L(128, s, 0, 255), so that the distribution index only has to tell the scale.  mu is the
+ * predicted location rounded to an integer.  inverse = 0: out = (in - mu + 128) mod 256 (before
+ * pilc_ansai_encode); inverse != 0: out = (in + mu - 128) mod 256 (after pilc_ansai_decode).
+ * in_dev, mu_dev, out_dev: device uint8 [count], 16-byte aligned; out_dev may be in_dev.
+ * Errors: PILC_E_ARG, PILC_E_HIP. */
+int pilc_ansai_center(const uint8_t *in_dev, const uint8_t *mu_dev, uint64_t count, int inverse,
+                      uint8_t *out_dev, void *hip_stream);
+
 /* Device workspace needed by pilc_ansai_encode / pilc_ansai_decode and an upper bound of the
  * container size (header + offsets + per piece 8 bytes and ceil(count*M/32) words).
  * Errors: PILC_E_ARG, PILC_E_TOO_LARGE. */

@@ -243,3 +243,12 @@ int ansai_oracle_decode(const ansai_model *md, uint32_t pieces, uint32_t count, 
     tables_free(&tb);
     return rc;
 }
+
+void ansai_oracle_center(const uint8_t *in, const uint8_t *mu, uint64_t n, int inverse, uint8_t *out)
+{
+    uint64_t i;
+    for (i = 0; i < n; ++i) {
+        int v = inverse ? (int)in[i] + (int)mu[i] - 128 : (int)in[i] - (int)mu[i] + 128;
+        out[i] = (uint8_t)(((v % 256) + 256) % 256);
+    }
+}

@@ -66,6 +66,12 @@ int ansai_oracle_encode(const ansai_model *model, uint32_t pieces, uint32_t coun
 int ansai_oracle_decode(const ansai_model *model, uint32_t pieces, uint32_t count,
                         const uint8_t *dist, const uint8_t *coded, uint64_t coded_bytes,
                         uint8_t *sym_out);
+
+/* Sec. 3.3: the residual r ~ L(mu, s, 0, 255) is coded as (r - mu + 128) mod 256 ~ L(128, s, 0, 255),
+ * so that the distribution index only has to tell the scale.  mu is the predicted location rounded
+ * to an integer (a reading: the paper predicts "within uint8 space").  inverse = 0: out = (r - mu +
+ * 128) mod 256; inverse != 0: out = (c + mu - 128) mod 256. */
+void ansai_oracle_center(const uint8_t *in, const uint8_t *mu, uint64_t n, int inverse, uint8_t *out);
 #ifdef __cplusplus
 }
 #endif

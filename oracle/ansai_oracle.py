@@ -51,6 +51,8 @@ def lib():
                                           C.POINTER(C.c_uint64)]
         L.ansai_oracle_decode.restype = C.c_int
         L.ansai_oracle_decode.argtypes = [mp, C.c_uint32, C.c_uint32, u8p, u8p, C.c_uint64, u8p]
+        L.ansai_oracle_center.restype = None
+        L.ansai_oracle_center.argtypes = [u8p, u8p, C.c_uint64, C.c_int, u8p]
         _lib = L
     return _lib
 
@@ -144,3 +146,15 @@ def decode(prec_bits: int, mass, dist, coded):
     rc = lib().ansai_oracle_decode(md.ref, pieces, count, _ptr(dist, C.c_uint8), _ptr(cbuf, C.c_uint8),
                                    coded.size, _ptr(out, C.c_uint8))
     return rc, out
+
+
+def center(values, mu, inverse: bool = False):
+    """(r - mu + 128) mod 256, or its inverse (Sec. 3.3)."""
+    a = np.ascontiguousarray(values, dtype=np.uint8)
+    m = np.ascontiguousarray(mu, dtype=np.uint8)
+    assert a.shape == m.shape
+    out = np.zeros(max(a.size, 1), dtype=np.uint8)
+    if a.size:
+        lib().ansai_oracle_center(_ptr(a.reshape(-1), C.c_uint8), _ptr(m.reshape(-1), C.c_uint8), a.size,
+                                  1 if inverse else 0, _ptr(out, C.c_uint8))
+    return out[: a.size].reshape(a.shape)

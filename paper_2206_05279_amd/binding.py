@@ -29,7 +29,7 @@ EXPORTS = [
     "pilc_set_timing", "pilc_set_kernel_policy", "pilc_last_timing", "pilc_timing_name", "pilc_strerror",
     "pilc_last_hip_error", "pilc_version",
     "pilc_ansai_table_bytes", "pilc_ansai_build_tables", "pilc_ansai_workspace_size", "pilc_ansai_encode",
-    "pilc_ansai_decode",
+    "pilc_ansai_decode", "pilc_ansai_center",
 ]
 
 
@@ -103,6 +103,8 @@ def lib():
         L.pilc_ansai_encode.restype = C.c_int
         L.pilc_ansai_encode.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                                         C.c_void_p, C.c_size_t, C.POINTER(C.c_uint64), C.c_void_p]
+        L.pilc_ansai_center.restype = C.c_int
+        L.pilc_ansai_center.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int, C.c_void_p, C.c_void_p]
         L.pilc_ansai_decode.restype = C.c_int
         L.pilc_ansai_decode.argtypes = [sp, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_size_t, C.c_void_p, C.c_void_p]
@@ -256,4 +258,15 @@ def pilc_ansai_decode(shape: pilc_ansai_shape, coded, coded_bytes: int, dist, ta
                                  _dev_ptr(sym_out, torch.uint8, "sym_out"), _stream_handle(stream))
     if check and rc != PILC_OK:
         raise PilcError(rc, "pilc_ansai_decode")
+    return rc
+
+
+def pilc_ansai_center(values, mu, out, inverse: bool = False,
+                      stream: Optional[torch.cuda.Stream] = None, check: bool = True) -> int:
+    """out = (values - mu + 128) mod 256, or with inverse (values + mu - 128) mod 256; uint8 tensors."""
+    rc = lib().pilc_ansai_center(_dev_ptr(values, torch.uint8, "values"), _dev_ptr(mu, torch.uint8, "mu"),
+                                 values.numel(), 1 if inverse else 0, _dev_ptr(out, torch.uint8, "out"),
+                                 _stream_handle(stream))
+    if check and rc != PILC_OK:
+        raise PilcError(rc, "pilc_ansai_center")
     return rc

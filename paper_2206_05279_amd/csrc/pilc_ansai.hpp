@@ -768,6 +768,44 @@ __global__ __launch_bounds__(64 * kAnsaiDecMaxWaves) void k_ansai_decode(
 }
 
 // ---------------------------------------------------------------------------------------------
+// Re-centring (Sec. 3.3): code (r - mu + 128) mod 256 so that the distribution index only has to
+// tell the scale.  Four bytes per 32-bit lane operation: byte-wise subtraction / addition without
+// carries between bytes, and + 128 mod 256 is a flip of every byte's top bit.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t bytes_sub(uint32_t a, uint32_t b)
+{
+    return ((a | 0x80808080u) - (b & 0x7F7F7F7Fu)) ^ ((a ^ ~b) & 0x80808080u);
+}
+
+__device__ __forceinline__ uint32_t bytes_add(uint32_t a, uint32_t b)
+{
+    return ((a & 0x7F7F7F7Fu) + (b & 0x7F7F7F7Fu)) ^ ((a ^ b) & 0x80808080u);
+}
+
+template <bool kInverse>
+__global__ __launch_bounds__(256) void k_ansai_center(const uint8_t *in, const uint8_t *__restrict__ mu,
+                                                      unsigned long long n, uint8_t *out)  // out may be in
+{
+    const unsigned long long vecs = n / 16ull, stride = (unsigned long long)gridDim.x * blockDim.x;
+    for (unsigned long long i = (unsigned long long)blockIdx.x * blockDim.x + threadIdx.x; i < vecs; i += stride) {
+        const uint4 a = reinterpret_cast<const uint4 *>(in)[i], m = reinterpret_cast<const uint4 *>(mu)[i];
+        uint4 r;
+        if (kInverse) {
+            r = make_uint4(bytes_add(a.x ^ 0x80808080u, m.x), bytes_add(a.y ^ 0x80808080u, m.y),
+                           bytes_add(a.z ^ 0x80808080u, m.z), bytes_add(a.w ^ 0x80808080u, m.w));
+        } else {
+            r = make_uint4(bytes_sub(a.x, m.x) ^ 0x80808080u, bytes_sub(a.y, m.y) ^ 0x80808080u,
+                           bytes_sub(a.z, m.z) ^ 0x80808080u, bytes_sub(a.w, m.w) ^ 0x80808080u);
+        }
+        reinterpret_cast<uint4 *>(out)[i] = r;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 15ull)) {  // the last, partial vector
+        const unsigned long long i = vecs * 16ull + threadIdx.x;
+        out[i] = kInverse ? (uint8_t)(in[i] + mu[i] - 128u) : (uint8_t)(in[i] - mu[i] + 128u);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------------------
 static int make_ashape(const pilc_ansai_shape *in, AShape *sh)
@@ -864,6 +902,24 @@ int pilc_ansai_build_tables(uint32_t prec_bits, uint32_t num_dist, uint32_t num_
     HIP_TRY(hipMemcpyAsync(&host, head, sizeof(host), hipMemcpyDeviceToHost, stream));
     HIP_TRY(hipStreamSynchronize(stream));
     return host.ok == 1u ? PILC_OK : PILC_E_ARG;
+}
+
+int pilc_ansai_center(const uint8_t *in_dev, const uint8_t *mu_dev, uint64_t count, int inverse,
+                      uint8_t *out_dev, void *hip_stream)
+{
+    if (!in_dev || !mu_dev || !out_dev || count == 0) return PILC_E_ARG;
+    if (((uintptr_t)in_dev & 15) || ((uintptr_t)mu_dev & 15) || ((uintptr_t)out_dev & 15)) return PILC_E_ARG;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const uint64_t vecs = count / 16;
+    uint32_t blocks = (uint32_t)(vecs / 256 > 16384 ? 16384 : (vecs + 255) / 256);
+    if (blocks == 0) blocks = 1;
+    if (inverse)
+        k_ansai_center<true><<<blocks, 256, 0, stream>>>(in_dev, mu_dev, count, out_dev);
+    else
+        k_ansai_center<false><<<blocks, 256, 0, stream>>>(in_dev, mu_dev, count, out_dev);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(stream));
+    return PILC_OK;
 }
 
 int pilc_ansai_workspace_size(const pilc_ansai_shape *shape, size_t *workspace_bytes_host,

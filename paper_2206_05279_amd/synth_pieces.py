@@ -77,6 +77,21 @@ def random_masses(rng: np.random.Generator, prec_bits: int, num_dist: int, num_s
     return out
 
 
+def index_stream_masses(prec_bits: int, num_sym: int = 256, exponent: float = 1.0, seed: int = 7) -> np.ndarray:
+    """One static law over num_sym codebook indices, for the stream of vector indices (Sec. 3.1:
+    the indices go through the same coder; the paper does not give their distribution): Zipf-like
+    shares over a seeded permutation of the indices, one count per index plus a share of the rest."""
+    top = 1 << prec_bits
+    assert top >= 2 * num_sym
+    rng = np.random.Generator(np.random.PCG64(seed))
+    share = 1.0 / (1.0 + np.arange(num_sym)) ** exponent
+    share = share[rng.permutation(num_sym)]
+    cut = np.rint(np.concatenate([[0.0], np.cumsum(share / share.sum())]) * (top - num_sym)).astype(np.int64)
+    out = (1 + np.diff(cut)).astype(np.uint32)[None, :]
+    assert out.sum() == top and out.min() >= 1
+    return out
+
+
 def _inverse_table(mass: np.ndarray) -> np.ndarray:
     """[D, 2^M] symbol whose count interval holds u (inverse-CDF sampling)."""
     return np.stack([np.repeat(np.arange(mass.shape[1], dtype=np.uint8), row) for row in mass])

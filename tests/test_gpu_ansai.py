@@ -43,6 +43,8 @@ CASES = [
     ("255 distributions", 8, _random(8, 255, 256, 1.0), 64, 100, False),
     ("4096 pieces of 1000", 12, _logistic(12, 8), 4096, 1000, False),
     ("M14 random", 14, _random(14, 2, 256, 1.0), 77, 130, False),
+    # the stream of vector indices (Sec. 3.1): one static law, 16x16 indices per 32x32 image, K = 256
+    ("vector-index stream", 12, lambda rng: sp.index_stream_masses(12), 3000, 256, False),
 ]
 
 
@@ -238,3 +240,21 @@ def test_timing_names(small):
         assert names == ["total", "k_ansai_check_header", "k_ansai_decode"]
     finally:
         pb.pilc_set_timing(False)
+
+
+def test_centering_matches_the_reference():
+    rng = np.random.default_rng(5)
+    for n in (1, 15, 16, 17, 4097, 1 << 20):
+        r = rng.integers(0, 256, n, dtype=np.uint8)
+        mu = rng.integers(0, 256, n, dtype=np.uint8)
+        dr, dmu = torch.from_numpy(r).cuda(), torch.from_numpy(mu).cuda()
+        out = torch.full_like(dr, 0x5A)
+        pb.pilc_ansai_center(dr, dmu, out)
+        assert np.array_equal(out.cpu().numpy(), ao.center(r, mu)), n
+        back = torch.empty_like(dr)
+        pb.pilc_ansai_center(out, dmu, back, inverse=True)
+        assert np.array_equal(back.cpu().numpy(), r), n
+        pb.pilc_ansai_center(out, dmu, out, inverse=True)                  # in place
+        assert np.array_equal(out.cpu().numpy(), r), n
+    pad = torch.zeros(64, dtype=torch.uint8, device="cuda:0")
+    assert pb.pilc_ansai_center(pad[1:33], pad[:32], pad[32:], check=False) == pb.PILC_E_ARG

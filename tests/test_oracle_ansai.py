@@ -86,6 +86,7 @@ MODELS = [
     ("random M6 X5", lambda rng: (6, sp.random_masses(rng, 6, 3, 5))),
     ("random M1 X2", lambda rng: (1, np.array([[1, 1]], dtype=np.uint32))),
     ("random M14 X256", lambda rng: (14, sp.random_masses(rng, 14, 2, 256, 1.0))),
+    ("index stream M12 D1", lambda rng: (12, sp.index_stream_masses(12))),
 ]
 
 
@@ -288,3 +289,31 @@ def test_capacity_format_and_corruption():
     flipped = dist.copy(); flipped[0, 0] ^= 1                        # wrong model for one symbol
     rc, back = ao.decode(m, mass, flipped, coded)
     assert rc == ao.E_CORRUPT or not np.array_equal(back, sym)
+
+
+# ---------------------------------------------------------------- re-centring (Sec. 3.3)
+def test_centering_all_pairs_and_round_trip():
+    r, mu = np.meshgrid(np.arange(256, dtype=np.uint8), np.arange(256, dtype=np.uint8), indexing="ij")
+    c = ao.center(r, mu)
+    assert np.array_equal(c.astype(np.int64), (r.astype(np.int64) - mu.astype(np.int64) + 128) % 256)
+    assert np.array_equal(ao.center(c, mu, inverse=True), r)
+    assert np.array_equal(ao.center(r, np.full_like(r, 128)), r)        # mu = 128 changes nothing
+    assert (ao.center(mu, mu) == 128).all()                             # a hit lands on the centre
+
+
+def test_centred_law_is_close_to_the_true_one_near_128():
+    """Sec. 3.3, Fig. 4: coding (r - mu + 128) mod 256 with L(128, s, 0, 255) costs almost nothing
+    while mu stays within [96, 160], and more the further mu moves away."""
+    def law(mu, s):
+        edges = np.arange(257) - 0.5
+        cdf = 1.0 / (1.0 + np.exp(-(edges - mu) / s))
+        p = np.diff(cdf)
+        return p / p.sum()                                              # truncated to 0..255
+    for s in (6.0, 12.0):  # wide enough for every mass to be a normal float64
+        kl = []
+        for mu in (128, 144, 160, 200, 240):
+            p = law(mu, s)                                              # true law of r
+            q = np.roll(law(128, s), mu - 128)                          # what the shifted coder assumes for r
+            kl.append(float((p * np.log2(p / q)).sum()))
+        assert kl[0] < 1e-12 and kl[1] < 0.01 and kl[2] < 0.01
+        assert kl[2] <= kl[3] <= kl[4] and kl[4] > 10 * max(kl[2], 1e-6)
