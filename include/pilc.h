@@ -203,6 +203,31 @@ int pilc_ansai_decode(const pilc_ansai_shape *shape, const uint8_t *coded_dev, s
                       const uint8_t *dist_dev, const void *tables_dev, void *workspace_dev,
                       size_t workspace_bytes, uint8_t *sym_out_dev, void *hip_stream);
 
+/* ------------------------------------------------------------------------------------------
+ * The Three-Way Auto-regressive residual transform (Sec. 3.1, eqs. (2)-(4)): every subpixel is
+ * predicted from three known values -- R(u,v) from R(u-1,v-1), R(u-1,v), R(u,v-1); G(u,v) from
+ * G(u,v-1), R(u,v-1), R(u,v); B(u,v) from B(u,v-1), G(u,v-1), G(u,v); u the row, v the column --
+ * with three weights and a bias per channel (12 parameters), and the residual goes to the coder.
+ * Readings the paper leaves open: zero padding above and to the left; fixed-point weights,
+ * x^ = clamp((w . ctx + bias + 2^13) >> 14, 0, 255) with an arithmetic shift; residual
+ * r = (x - x^) mod 256, so that x = (r + x^) mod 256.
+ * Images: device uint8 [n, h, w, 3], channel-interleaved; input and output must not overlap.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+    int16_t w[3][3]; /* [channel][context value in the order above], Q2.14 */
+    int32_t bias[3]; /* Q8.14, |bias| <= 2^30 */
+} pilc_twar_params;
+
+/* res = image minus prediction.  Errors: PILC_E_ARG, PILC_E_TOO_LARGE, PILC_E_HIP. */
+int pilc_twar_forward(uint32_t n, uint32_t h, uint32_t w, const uint8_t *img_dev,
+                      const pilc_twar_params *params_host, uint8_t *res_dev, void *hip_stream);
+
+/* The image back from the residual (Sec. 3.1: the anti-diagonal / column schedule of the paper's
+ * decoding figure, here one walk along the anti-diagonals of 64 rows per wavefront).
+ * Errors: PILC_E_ARG, PILC_E_TOO_LARGE, PILC_E_HIP. */
+int pilc_twar_inverse(uint32_t n, uint32_t h, uint32_t w, const uint8_t *res_dev,
+                      const pilc_twar_params *params_host, uint8_t *img_dev, void *hip_stream);
+
 const char *pilc_strerror(int code);
 const char *pilc_last_hip_error(void); /* text of the last HIP failure on this thread */
 uint32_t pilc_version(void);

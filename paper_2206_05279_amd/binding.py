@@ -29,7 +29,7 @@ EXPORTS = [
     "pilc_set_timing", "pilc_set_kernel_policy", "pilc_last_timing", "pilc_timing_name", "pilc_strerror",
     "pilc_last_hip_error", "pilc_version",
     "pilc_ansai_table_bytes", "pilc_ansai_build_tables", "pilc_ansai_workspace_size", "pilc_ansai_encode",
-    "pilc_ansai_decode", "pilc_ansai_center",
+    "pilc_ansai_decode", "pilc_ansai_center", "pilc_twar_forward", "pilc_twar_inverse",
 ]
 
 
@@ -45,6 +45,10 @@ class pilc_params(C.Structure):
 class pilc_ansai_shape(C.Structure):
     _fields_ = [("pieces", C.c_uint32), ("count", C.c_uint32), ("prec_bits", C.c_uint32),
                 ("num_dist", C.c_uint32), ("num_sym", C.c_uint32)]
+
+
+class pilc_twar_params(C.Structure):
+    _fields_ = [("w", (C.c_int16 * 3) * 3), ("bias", C.c_int32 * 3)]
 
 
 class PilcError(RuntimeError):
@@ -103,6 +107,10 @@ def lib():
         L.pilc_ansai_encode.restype = C.c_int
         L.pilc_ansai_encode.argtypes = [sp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                                         C.c_void_p, C.c_size_t, C.POINTER(C.c_uint64), C.c_void_p]
+        tp = C.POINTER(pilc_twar_params)
+        for f in (L.pilc_twar_forward, L.pilc_twar_inverse):
+            f.restype = C.c_int
+            f.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p, tp, C.c_void_p, C.c_void_p]
         L.pilc_ansai_center.restype = C.c_int
         L.pilc_ansai_center.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int, C.c_void_p, C.c_void_p]
         L.pilc_ansai_decode.restype = C.c_int
@@ -270,3 +278,34 @@ def pilc_ansai_center(values, mu, out, inverse: bool = False,
     if check and rc != PILC_OK:
         raise PilcError(rc, "pilc_ansai_center")
     return rc
+
+
+# ---------------------------------------------------------------- Three-Way AR residual transform
+def make_twar_params(weights, bias) -> pilc_twar_params:
+    """weights: 3x3 integers (Q2.14), bias: 3 integers (Q8.14)."""
+    p = pilc_twar_params()
+    for c in range(3):
+        for k in range(3):
+            p.w[c][k] = int(weights[c][k])
+        p.bias[c] = int(bias[c])
+    return p
+
+
+def _twar(fn, name, params, src, dst, stream, check):
+    n, h, w, ch = src.shape
+    assert ch == 3 and dst.shape == src.shape
+    rc = fn(n, h, w, _dev_ptr(src, torch.uint8, "src"), C.byref(params), _dev_ptr(dst, torch.uint8, "dst"),
+            _stream_handle(stream))
+    if check and rc != PILC_OK:
+        raise PilcError(rc, name)
+    return rc
+
+
+def pilc_twar_forward(params: pilc_twar_params, img, res, stream: Optional[torch.cuda.Stream] = None,
+                      check: bool = True) -> int:
+    return _twar(lib().pilc_twar_forward, "pilc_twar_forward", params, img, res, stream, check)
+
+
+def pilc_twar_inverse(params: pilc_twar_params, res, img, stream: Optional[torch.cuda.Stream] = None,
+                      check: bool = True) -> int:
+    return _twar(lib().pilc_twar_inverse, "pilc_twar_inverse", params, res, img, stream, check)

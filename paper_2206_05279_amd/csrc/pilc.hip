@@ -707,3 +707,4 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
 }  // extern "C"
 
 #include "pilc_ansai.hpp"
+#include "pilc_twar.hpp"

@@ -1,0 +1,250 @@
+// The Three-Way Auto-regressive residual transform of Sec. 3.1 (eqs. (2)-(4)) for gfx950.
+//
+//   R(u,v) is predicted from R(u-1,v-1), R(u-1,v), R(u,v-1)   (up-left, up, left)
+//   G(u,v)                from G(u,v-1),   R(u,v-1), R(u,v)     (left G, left R, this pixel's R)
+//   B(u,v)                from B(u,v-1),   G(u,v-1), G(u,v)     (left B, left G, this pixel's G)
+// with three weights and a bias each, zero padding above and to the left, and the residual
+// r = (x - x^) mod 256.  Forward, every pixel is independent (k_twar_forward).  Inverse, a pixel
+// needs its left, upper and upper-left neighbours: the paper's schedule runs the red channel along
+// anti-diagonals and then green and blue column by column; here a wavefront takes 64 rows, one
+// per thread, and walks the anti-diagonals once, recovering R, G and B of a pixel in the same
+// step (G and B only need values of the same row, which the thread already holds), with the two
+// values a row needs from the row above passed down by a cross-lane shift (k_twar_inverse).
+//
+// Included at the end of pilc.hip.
+#pragma once
+
+namespace pilc {
+
+struct TwarK {
+    int w[3][3];  // Q2.14
+    int bias[3];  // Q8.14
+};
+
+__device__ __forceinline__ int twar_predict(const TwarK &p, int ch, int a, int b, int c)
+{
+    const int acc = p.w[ch][0] * a + p.w[ch][1] * b + p.w[ch][2] * c + p.bias[ch] + 8192;
+    return min(max(acc >> 14, 0), 255);  // arithmetic shift: floor
+}
+
+// One thread per pixel.  A workgroup takes 256 / w whole rows (or one row, in steps of 256
+// pixels, when w > 256); neighbouring threads read neighbouring bytes and the row above comes from
+// the caches.
+__global__ __launch_bounds__(256) void k_twar_forward(TwarK p, uint32_t rows, uint32_t h, uint32_t w,
+                                                      uint32_t rows_per_block,
+                                                      const uint8_t *__restrict__ img,
+                                                      uint8_t *__restrict__ res)
+{
+    const uint32_t local = threadIdx.x / w, v0 = threadIdx.x % w;
+    const uint32_t row = blockIdx.x * rows_per_block + local;
+    if (local >= rows_per_block || row >= rows) return;
+    const uint32_t u = row % h;
+    const size_t row_off = (size_t)row * w * 3u;
+    for (uint32_t v = v0; v < w; v += 256u) {  // one turn unless w > 256
+        const uint8_t *x = img + row_off + 3u * v;
+        const int r0 = x[0], g0 = x[1], b0 = x[2];
+        int rl = 0, gl = 0, bl = 0, ru = 0, rul = 0;
+        if (v > 0) {
+            rl = x[-3];
+            gl = x[-2];
+            bl = x[-1];
+        }
+        if (u > 0) {
+            ru = x[-3ll * (long long)w];
+            if (v > 0) rul = x[-3ll * (long long)w - 3];
+        }
+        uint8_t *o = res + row_off + 3u * v;
+        o[0] = (uint8_t)(r0 - twar_predict(p, 0, rul, ru, rl));
+        o[1] = (uint8_t)(g0 - twar_predict(p, 1, gl, rl, r0));
+        o[2] = (uint8_t)(b0 - twar_predict(p, 2, bl, gl, g0));
+    }
+}
+
+// A wavefront per group of up to 64 rows: whole images when h <= 64 (64 / h of them side by side),
+// else the bands of 64 rows of one image one after the other, the last row's red values of a band
+// kept in LDS for the first row of the next.  kTile: the group's residuals are copied to LDS
+// first and the pixels copied back at the end (rows of w * 3 bytes at a stride with an odd number
+// of dwords), so that global memory only sees whole, coalesced rows; without it every thread reads
+// and writes its row in place in global memory.
+constexpr int kTwarWaves = 4;
+
+template <bool kTile>
+__global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint32_t n, uint32_t h,
+                                                                  uint32_t w, uint32_t row_stride,
+                                                                  const uint8_t *__restrict__ res,
+                                                                  uint8_t *__restrict__ img)
+{
+    extern __shared__ uint8_t twar_lds[];
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    const uint32_t per = h <= 64u ? 64u / h : 1u;          // images side by side in a wavefront
+    const uint32_t groups = (n + per - 1u) / per;
+    const uint32_t g = blockIdx.x * kTwarWaves + wave;
+    if (g >= groups) return;
+    const uint32_t bands = h <= 64u ? 1u : (h + 63u) / 64u;
+    // LDS of this wavefront: [w bytes: red values of the row above a band][tile]
+    const uint32_t last_bytes = (w + 3u) & ~3u;
+    uint8_t *lastrow = twar_lds + (size_t)wave * (last_bytes + (kTile ? 64u * row_stride : 0u));
+    uint8_t *tile = lastrow + last_bytes;
+    const size_t row_bytes = (size_t)w * 3u;
+
+    for (uint32_t band = 0; band < bands; ++band) {
+        // this thread's row
+        uint32_t image, u;
+        bool have;
+        if (h <= 64u) {
+            image = g * per + lane / h;
+            u = lane % h;
+            have = lane < per * h && image < n;
+        } else {
+            image = g;
+            u = band * 64u + lane;
+            have = u < h;
+        }
+        const size_t row_off = ((size_t)image * h + u) * row_bytes;
+        const uint32_t rows_here = h <= 64u ? min(per, n - g * per) * h : min(64u, h - band * 64u);
+        if (kTile) {  // the group's rows are contiguous in memory: copy them row by row
+            const size_t first = h <= 64u ? (size_t)g * per * h * row_bytes : ((size_t)g * h + band * 64u) * row_bytes;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            for (uint32_t r = 0; r < rows_here; ++r)
+                for (uint32_t c = lane; c < row_bytes; c += 64u) tile[r * row_stride + c] = res[first + r * row_bytes + c];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        const bool top = u == 0u;                // the row above is padding
+        const bool from_lds = lane == 0u && !top;  // the row above belongs to the previous band
+        int rl = 0, rll = 0, gl = 0, bl = 0;
+        const uint32_t steps = w + 63u;
+        for (uint32_t d = 0; d < steps; ++d) {
+            int up = __shfl_up(rl, 1, 64), upleft = __shfl_up(rll, 1, 64);
+            const int v = (int)d - (int)lane;
+            const bool on = have && v >= 0 && v < (int)w;
+            if (top) {
+                up = 0;
+                upleft = 0;
+            }
+            if (from_lds && on) {
+                up = lastrow[v];
+                upleft = v > 0 ? lastrow[v - 1] : 0;
+            }
+            if (on) {
+                int r0, r1, r2;
+                if (kTile) {
+                    const uint8_t *s = tile + lane * row_stride + 3u * v;
+                    r0 = s[0];
+                    r1 = s[1];
+                    r2 = s[2];
+                } else {
+                    const uint8_t *s = res + row_off + 3u * v;
+                    r0 = s[0];
+                    r1 = s[1];
+                    r2 = s[2];
+                }
+                const int xr = (r0 + twar_predict(p, 0, upleft, up, rl)) & 255;
+                const int xg = (r1 + twar_predict(p, 1, gl, rl, xr)) & 255;
+                const int xb = (r2 + twar_predict(p, 2, bl, gl, xg)) & 255;
+                if (kTile) {
+                    uint8_t *o = tile + lane * row_stride + 3u * v;
+                    o[0] = (uint8_t)xr;
+                    o[1] = (uint8_t)xg;
+                    o[2] = (uint8_t)xb;
+                } else {
+                    uint8_t *o = img + row_off + 3u * v;
+                    o[0] = (uint8_t)xr;
+                    o[1] = (uint8_t)xg;
+                    o[2] = (uint8_t)xb;
+                }
+                // the last row of a band leaves its red values for the next band; it runs 63
+                // positions behind the first row's reads of the same buffer
+                if (bands > 1u && lane == 63u) lastrow[v] = (uint8_t)xr;
+                rll = rl;
+                rl = xr;
+                gl = xg;
+                bl = xb;
+            }
+        }
+        if (kTile) {
+            const size_t first = h <= 64u ? (size_t)g * per * h * row_bytes : ((size_t)g * h + band * 64u) * row_bytes;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            for (uint32_t r = 0; r < rows_here; ++r)
+                for (uint32_t c = lane; c < row_bytes; c += 64u) img[first + r * row_bytes + c] = tile[r * row_stride + c];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+}
+
+static int make_twar(const pilc_twar_params *in, uint32_t n, uint32_t h, uint32_t w, TwarK *k)
+{
+    if (!in || n == 0 || h == 0 || w == 0) return PILC_E_ARG;
+    if ((uint64_t)n * h * w * 3 + 4096 >= (1ull << 40)) return PILC_E_TOO_LARGE;
+    if (w > 65535u) return PILC_E_TOO_LARGE;
+    for (int c = 0; c < 3; ++c) {
+        for (int j = 0; j < 3; ++j) k->w[c][j] = in->w[c][j];
+        // the sum of three products and the bias must stay inside 32 bits: |w| <= 2^15, values <= 255
+        if (in->bias[c] > (1 << 30) || in->bias[c] < -(1 << 30)) return PILC_E_ARG;
+        k->bias[c] = in->bias[c];
+    }
+    return PILC_OK;
+}
+
+}  // namespace pilc
+
+extern "C" {
+
+int pilc_twar_forward(uint32_t n, uint32_t h, uint32_t w, const uint8_t *img_dev,
+                      const pilc_twar_params *params_host, uint8_t *res_dev, void *hip_stream)
+{
+    TwarK k;
+    int rc = make_twar(params_host, n, h, w, &k);
+    if (rc != PILC_OK) return rc;
+    if (!img_dev || !res_dev || img_dev == res_dev) return PILC_E_ARG;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const uint64_t rows = (uint64_t)n * h;
+    if (rows >= (1ull << 31)) return PILC_E_TOO_LARGE;
+    const uint32_t rpb = w >= 256 ? 1u : 256u / w;
+    const uint32_t blocks = (uint32_t)((rows + rpb - 1) / rpb);
+    Timer timer(stream);
+    k_twar_forward<<<blocks, 256, 0, stream>>>(k, (uint32_t)rows, h, w, rpb, img_dev, res_dev);
+    timer.mark("k_twar_forward");
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(stream));
+    timer.finish();
+    return PILC_OK;
+}
+
+int pilc_twar_inverse(uint32_t n, uint32_t h, uint32_t w, const uint8_t *res_dev,
+                      const pilc_twar_params *params_host, uint8_t *img_dev, void *hip_stream)
+{
+    TwarK k;
+    int rc = make_twar(params_host, n, h, w, &k);
+    if (rc != PILC_OK) return rc;
+    if (!img_dev || !res_dev || img_dev == res_dev) return PILC_E_ARG;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const uint32_t per = h <= 64 ? 64 / h : 1;
+    const uint32_t groups = (n + per - 1) / per;
+    const uint32_t blocks = (groups + kTwarWaves - 1) / kTwarWaves;
+    const uint32_t last_bytes = (w + 3u) & ~3u;
+    // a row stride with an odd number of dwords keeps the 64 rows on distinct LDS banks
+    uint32_t row_stride = (w * 3u + 3u) & ~3u;
+    if (((row_stride >> 2) & 1u) == 0u) row_stride += 4u;
+    const size_t tile_lds = (size_t)kTwarWaves * (last_bytes + 64u * (size_t)row_stride);
+    Timer timer(stream);
+    if (tile_lds <= 64 * 1024) {
+        k_twar_inverse<true><<<blocks, 64 * kTwarWaves, tile_lds, stream>>>(k, n, h, w, row_stride, res_dev, img_dev);
+    } else {
+        k_twar_inverse<false><<<blocks, 64 * kTwarWaves, (size_t)kTwarWaves * last_bytes, stream>>>(
+            k, n, h, w, row_stride, res_dev, img_dev);
+    }
+    timer.mark("k_twar_inverse");
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(stream));
+    timer.finish();
+    return PILC_OK;
+}
+
+}  // extern "C"

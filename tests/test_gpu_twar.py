@@ -1,0 +1,58 @@
+"""GPU parity of the Three-Way AR residual transform (Sec. 3.1 eqs. (2)-(4)) against the CPU
+reference, through the C ABI: residuals and recovered images byte for byte, on shapes that
+cover several images per wavefront, bands of 64 rows, and both the LDS-tile and the in-place path."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import twar_oracle as to
+from paper_2206_05279_amd import binding as pb
+
+pytestmark = pytest.mark.gpu
+
+ONE = 1 << 14
+SHAPES = [(1, 1, 1), (3, 32, 32), (5, 7, 9), (2, 64, 64), (7, 16, 16), (2, 33, 5), (1, 100, 37),
+          (1, 130, 300), (2, 3, 700), (513, 32, 32), (1, 200, 64)]
+
+
+def models(rng):
+    yield "plane", [[-ONE, ONE, ONE], [ONE // 2, -ONE // 2, ONE], [ONE // 2, -ONE // 2, ONE]], [0, 0, 0]
+    yield "random", rng.integers(-ONE, ONE + 1, (3, 3)).tolist(), rng.integers(-64 * ONE, 64 * ONE, 3).tolist()
+    yield "extreme", [[32767] * 3, [-32768] * 3, [32767, -32768, 1]], [1 << 30, -(1 << 30), 12345]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=["x".join(map(str, s)) for s in SHAPES])
+def test_forward_and_inverse_match_the_reference(shape):
+    rng = np.random.default_rng(sum(shape))
+    img = rng.integers(0, 256, shape + (3,), dtype=np.uint8)
+    if shape[1] >= 16:  # some structure, so that predictions matter
+        img = (img // 8 + np.linspace(0, 200, shape[2]).astype(np.uint8)[None, None, :, None]).astype(np.uint8)
+    d_img = torch.from_numpy(img).cuda()
+    for name, wq, bq in models(rng):
+        print("shape", shape, "model", name, flush=True)
+        ref = to.forward(to.make_params(wq, bq), img)
+        p = pb.make_twar_params(wq, bq)
+        d_res = torch.full_like(d_img, 0x5A)
+        pb.pilc_twar_forward(p, d_img, d_res)
+        assert np.array_equal(d_res.cpu().numpy(), ref), name
+        d_back = torch.full_like(d_img, 0xA5)
+        pb.pilc_twar_inverse(p, d_res, d_back)
+        assert np.array_equal(d_back.cpu().numpy(), img), name
+        # and the reference's own inverse agrees on a residual that is not a forward image
+        noise = rng.integers(0, 256, img.shape, dtype=np.uint8)
+        d_noise = torch.from_numpy(noise).cuda()
+        pb.pilc_twar_inverse(p, d_noise, d_back)
+        assert np.array_equal(d_back.cpu().numpy(), to.inverse(to.make_params(wq, bq), noise)), name
+
+
+def test_bad_arguments():
+    img = torch.zeros((2, 4, 4, 3), dtype=torch.uint8, device="cuda:0")
+    out = torch.zeros_like(img)
+    p = pb.make_twar_params([[0] * 3] * 3, [0] * 3)
+    assert pb.pilc_twar_forward(p, img, img, check=False) == pb.PILC_E_ARG      # in place is not allowed
+    assert pb.pilc_twar_inverse(p, img, img, check=False) == pb.PILC_E_ARG
+    bad = pb.make_twar_params([[0] * 3] * 3, [(1 << 30) + 1, 0, 0])
+    assert pb.pilc_twar_forward(bad, img, out, check=False) == pb.PILC_E_ARG
+    empty = torch.zeros((0, 4, 4, 3), dtype=torch.uint8, device="cuda:0")
+    assert pb.lib().pilc_twar_forward(0, 4, 4, img.data_ptr(), None, out.data_ptr(), None) == pb.PILC_E_ARG
+    del empty
