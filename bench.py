@@ -38,6 +38,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 HERE = os.path.dirname(os.path.abspath(__file__))
 METRIC = "compress & decompress MB/s (raw uint8) on 1 MI355X; bits/subpixel"
 METRIC_ANSAI = "coder encode & decode MB/s (uint8 symbols) on 1 MI355X; bits/symbol"
+METRIC_TWAR = "residual transform forward & inverse MB/s (raw uint8) on 1 MI355X"
+TWAR_WEIGHTS = ([[-16384, 16384, 16384], [8192, -8192, 16384], [8192, -8192, 16384]], [0, 0, 0])
 
 
 def parse_args():
@@ -47,8 +49,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=1,
                     help="workload 0..4 of BASELINE.json (default 1: CIFAR-shaped, 50,000 images)")
-    ap.add_argument("--workload", choices=("pilc", "ansai"), default="pilc",
-                    help="pilc: the image path on --config; ansai: the table-driven coder on pieces")
+    ap.add_argument("--workload", choices=("pilc", "ansai", "twar"), default="pilc",
+                    help="pilc: the image path on --config; ansai: the table-driven coder on pieces; "
+                         "twar: the Three-Way AR residual transform on the images of --config")
     ap.add_argument("--images", type=int, default=None,
                     help="first N images (pilc) or pieces (ansai) only (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -347,6 +350,72 @@ class PieceRun:
     timed = Run.timed
 
 
+def cpu_baseline_twar(img, sample_images):
+    from oracle import twar_oracle as to
+
+    k = min(sample_images, img.shape[0])
+    cores = max(1, min(16, os.cpu_count() or 1))
+    per = -(-k // cores)
+    jobs = [np.ascontiguousarray(img[a:min(a + per, k)]) for a in range(0, k, per)]
+    p = to.make_params(*TWAR_WEIGHTS)
+    to.lib()
+
+    def both(x):
+        r = to.forward(p, x)
+        assert np.array_equal(to.inverse(p, r), x)
+
+    with ThreadPoolExecutor(max_workers=len(jobs)) as pool:
+        t0 = time.perf_counter()
+        list(pool.map(both, jobs))
+        t1 = time.perf_counter()
+    raw_mb = img[:k].size / 1e6
+    t2 = time.perf_counter()
+    both(jobs[0])
+    t3 = time.perf_counter()
+    return {"value": raw_mb / (t1 - t0), "unit": "MB/s", "cores": len(jobs), "kind": "oracle",
+            "sample": "first %d images (%.1f MB), forward + inverse, %d slabs in a thread pool" % (k, raw_mb, len(jobs)),
+            "one_core": {"value": jobs[0].size / 1e6 / (t3 - t2), "sample_MB": jobs[0].size / 1e6}}
+
+
+class TwarRun:
+    """pilc_twar_forward + pilc_twar_inverse over the images of a workload (Sec. 3.1 eqs. (2)-(4))."""
+
+    def __init__(self, config, images):
+        import torch
+        from paper_2206_05279_amd import binding as pb
+        from paper_2206_05279_amd import synth
+
+        self.torch, self.pb = torch, pb
+        t = time.perf_counter()
+        wl = synth.make_workload(config, images)
+        self.gen_s = time.perf_counter() - t
+        self.img_np = wl.img
+        self.img = torch.from_numpy(wl.img).to("cuda:0")
+        self.res = torch.empty_like(self.img)
+        self.out = torch.empty_like(self.img)
+        self.params = pb.make_twar_params(*TWAR_WEIGHTS)
+        self.name = "cfg%d %s images: %d x %dx%dx3 uint8" % (config, wl.name, wl.n, wl.h, wl.w)
+        self.raw = wl.subpixels
+        self.probe_src = self.img
+        self.probe_bytes = 2.0 * wl.subpixels
+        self.step = "pilc_twar_forward + pilc_twar_inverse of the whole batch"
+
+    def algo_bytes(self, nbytes):
+        return 2.0 * self.raw  # either kernel reads and writes every subpixel once
+
+    def encode(self):
+        self.pb.pilc_twar_forward(self.params, self.img, self.res)
+        return self.raw
+
+    def decode(self, nbytes):
+        self.pb.pilc_twar_inverse(self.params, self.res, self.out)
+
+    def reference(self):
+        return self.img
+
+    timed = Run.timed
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -367,9 +436,13 @@ def main():
         sys.exit(3)
     pb.lib()
 
-    ansai = args.workload == "ansai"
-    run = PieceRun(1 if args.config not in (0, 1) else args.config, args.images) if ansai else \
-        Run(args.config, args.images)
+    ansai, twar = args.workload == "ansai", args.workload == "twar"
+    if ansai:
+        run = PieceRun(1 if args.config not in (0, 1) else args.config, args.images)
+    elif twar:
+        run = TwarRun(args.config, args.images)
+    else:
+        run = Run(args.config, args.images)
     if args.pmc_child:
         run.timed(1, 1)
         probe = torch.empty_like(run.probe_src)   # plain device copy of known size
@@ -396,7 +469,7 @@ def main():
             traffic_bytes = detail["read_bytes"] + detail["write_bytes"]
             traffic_detail = detail
     result = {
-        "metric": METRIC_ANSAI if ansai else METRIC,
+        "metric": METRIC_ANSAI if ansai else (METRIC_TWAR if twar else METRIC),
         "value": raw_bytes / 1e6 / (r["elapsed"] / args.steps),
         "unit": "MB/s",
         "n_gpus": 1,
@@ -411,7 +484,7 @@ def main():
         "config": {"workload": run.name, "step": run.step},
         "compress_MB_s": r["compress_MB_s"],
         "decompress_MB_s": r["decompress_MB_s"],
-        ("bits_per_symbol" if ansai else "bits_per_subpixel"): 8.0 * nbytes / raw_bytes,
+        ("bits_per_symbol" if ansai else "bits_per_subpixel"): None if twar else 8.0 * nbytes / raw_bytes,
         "coded_bytes": nbytes,
         "round_trip_exact": r["ok"],
         "kernel_ms": kernel_ms,
@@ -428,10 +501,12 @@ def main():
     if not args.no_cpu_baseline:
         if ansai:
             result["cpu_baseline"] = cpu_baseline_pieces(run.wl, args.cpu_sample_images or 131072)
+        elif twar:
+            result["cpu_baseline"] = cpu_baseline_twar(run.img_np, args.cpu_sample_images or 20000)
         else:
             sample = args.cpu_sample_images or {0: 64, 1: 21504, 2: 5376, 3: 10, 4: 336}[args.config]
             result["cpu_baseline"] = cpu_baseline(run.wl, sample)
-    if not args.no_extra and args.images is None and not ansai:
+    if not args.no_extra and args.images is None and not ansai and not twar:
         extra = {}
         del run
         torch.cuda.empty_cache()
@@ -460,6 +535,17 @@ def main():
             "kernel_ms": o["kernel_ms"],
             "dominant_kernel_hbm_frac": other.algo_bytes(o["nbytes"]) / (o["kernel_ms"][dk] * 1e-3) / 1e9
                                         / HBM_PEAK_GBS,
+        }
+        ok = ok and o["ok"]
+        del other
+        torch.cuda.empty_cache()
+        other = TwarRun(args.config, None)   # the residual transform either side of the coder
+        o = other.timed(max(2, args.steps // 3), 1)
+        dk = max(o["kernel_ms"], key=o["kernel_ms"].get)
+        extra["Three-Way AR transform (Sec. 3.1 eqs. 2-4): " + other.name] = {
+            "forward_MB_s": o["compress_MB_s"], "inverse_MB_s": o["decompress_MB_s"],
+            "round_trip_exact": o["ok"], "kernel_ms": o["kernel_ms"],
+            "dominant_kernel_hbm_frac": other.algo_bytes(0) / (o["kernel_ms"][dk] * 1e-3) / 1e9 / HBM_PEAK_GBS,
         }
         ok = ok and o["ok"]
         del other

@@ -60,6 +60,62 @@ __global__ __launch_bounds__(256) void k_twar_forward(TwarK p, uint32_t rows, ui
     }
 }
 
+// Byte b (-4 <= b < 12) of the 16 bytes {prev, c0, c1, c2}, b = 0 being the first byte of c0.
+template <int B>
+__device__ __forceinline__ int byte_at(uint32_t prev, uint32_t c0, uint32_t c1, uint32_t c2)
+{
+    constexpr int i = B + 4;
+    const uint32_t word = i < 4 ? prev : (i < 8 ? c0 : (i < 12 ? c1 : c2));
+    return (int)((word >> (8 * (i & 3))) & 255u);
+}
+
+// Four pixels (12 bytes, three dwords) per thread, for rows that are a whole number of such
+// groups in 4-byte aligned arrays: dword loads and stores only.
+__global__ __launch_bounds__(256) void k_twar_forward4(TwarK p, uint32_t groups, uint32_t h,
+                                                       uint32_t groups_per_row,
+                                                       const uint32_t *__restrict__ img,
+                                                       uint32_t *__restrict__ res)
+{
+    const uint32_t gi = blockIdx.x * blockDim.x + threadIdx.x;
+    if (gi >= groups) return;
+    const uint32_t row = gi / groups_per_row, k = gi % groups_per_row, u = row % h;
+    const uint32_t *x = img + (size_t)gi * 3u;
+    const uint32_t c0 = x[0], c1 = x[1], c2 = x[2];
+    const uint32_t prev = k > 0 ? x[-1] : 0u;  // the pixel to the left of the group (its last 3 bytes)
+    uint32_t u0 = 0u, u1 = 0u, u2 = 0u, uprev = 0u;
+    if (u > 0) {
+        const uint32_t *y = x - (size_t)groups_per_row * 3u;
+        u0 = y[0];
+        u1 = y[1];
+        u2 = y[2];
+        uprev = k > 0 ? y[-1] : 0u;
+    }
+    uint32_t out[3] = {0u, 0u, 0u};
+#define PILC_TWAR_PIXEL(J)                                                                         \
+    {                                                                                              \
+        const int r0 = byte_at<3 * J>(prev, c0, c1, c2), g0 = byte_at<3 * J + 1>(prev, c0, c1, c2); \
+        const int b0 = byte_at<3 * J + 2>(prev, c0, c1, c2);                                       \
+        const int rl = byte_at<3 * J - 3>(prev, c0, c1, c2), gl = byte_at<3 * J - 2>(prev, c0, c1, c2); \
+        const int bl = byte_at<3 * J - 1>(prev, c0, c1, c2);                                       \
+        const int ru = byte_at<3 * J>(uprev, u0, u1, u2), rul = byte_at<3 * J - 3>(uprev, u0, u1, u2); \
+        const uint32_t e0 = (uint32_t)(r0 - twar_predict(p, 0, rul, ru, rl)) & 255u;               \
+        const uint32_t e1 = (uint32_t)(g0 - twar_predict(p, 1, gl, rl, r0)) & 255u;                \
+        const uint32_t e2 = (uint32_t)(b0 - twar_predict(p, 2, bl, gl, g0)) & 255u;                \
+        out[(3 * J) >> 2] |= e0 << (8 * ((3 * J) & 3));                                            \
+        out[(3 * J + 1) >> 2] |= e1 << (8 * ((3 * J + 1) & 3));                                    \
+        out[(3 * J + 2) >> 2] |= e2 << (8 * ((3 * J + 2) & 3));                                    \
+    }
+    PILC_TWAR_PIXEL(0)
+    PILC_TWAR_PIXEL(1)
+    PILC_TWAR_PIXEL(2)
+    PILC_TWAR_PIXEL(3)
+#undef PILC_TWAR_PIXEL
+    uint32_t *o = res + (size_t)gi * 3u;
+    o[0] = out[0];
+    o[1] = out[1];
+    o[2] = out[2];
+}
+
 // A wavefront per group of up to 64 rows: whole images when h <= 64 (64 / h of them side by side),
 // else the bands of 64 rows of one image one after the other, the last row's red values of a band
 // kept in LDS for the first row of the next.  kTile: the group's residuals are copied to LDS
@@ -86,6 +142,8 @@ __global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint3
     uint8_t *lastrow = twar_lds + (size_t)wave * (last_bytes + (kTile ? 64u * row_stride : 0u));
     uint8_t *tile = lastrow + last_bytes;
     const size_t row_bytes = (size_t)w * 3u;
+    // rows of whole dwords in 4-byte aligned arrays are copied a dword at a time
+    const bool dwords = (row_bytes & 3u) == 0u && (((uintptr_t)res | (uintptr_t)img) & 3u) == 0u;
 
     for (uint32_t band = 0; band < bands; ++band) {
         // this thread's row
@@ -106,8 +164,21 @@ __global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint3
             const size_t first = h <= 64u ? (size_t)g * per * h * row_bytes : ((size_t)g * h + band * 64u) * row_bytes;
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
-            for (uint32_t r = 0; r < rows_here; ++r)
-                for (uint32_t c = lane; c < row_bytes; c += 64u) tile[r * row_stride + c] = res[first + r * row_bytes + c];
+            if (dwords) {
+                const uint32_t rd = (uint32_t)row_bytes >> 2, total = rows_here * rd;
+                const uint32_t *src = reinterpret_cast<const uint32_t *>(res + first);
+                uint32_t r = lane / rd, c = lane % rd;  // row and dword of element `lane`, then + 64 a turn
+                for (uint32_t o = lane; o < total; o += 64u) {
+                    reinterpret_cast<uint32_t *>(tile + r * row_stride)[c] = src[o];
+                    c += 64u % rd;
+                    r += 64u / rd + (c >= rd ? 1u : 0u);
+                    c -= c >= rd ? rd : 0u;
+                }
+            } else {
+                for (uint32_t r = 0; r < rows_here; ++r)
+                    for (uint32_t c = lane; c < row_bytes; c += 64u)
+                        tile[r * row_stride + c] = res[first + r * row_bytes + c];
+            }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -115,10 +186,12 @@ __global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint3
         const bool top = u == 0u;                // the row above is padding
         const bool from_lds = lane == 0u && !top;  // the row above belongs to the previous band
         int rl = 0, rll = 0, gl = 0, bl = 0;
-        const uint32_t steps = w + 63u;
+        // row k of an image (or band) runs k positions behind row 0: w + rows - 1 steps in all
+        const uint32_t skew = h <= 64u ? lane % h : lane;
+        const uint32_t steps = w + min(h, 64u) - 1u;
         for (uint32_t d = 0; d < steps; ++d) {
             int up = __shfl_up(rl, 1, 64), upleft = __shfl_up(rll, 1, 64);
-            const int v = (int)d - (int)lane;
+            const int v = (int)d - (int)skew;
             const bool on = have && v >= 0 && v < (int)w;
             if (top) {
                 up = 0;
@@ -169,8 +242,21 @@ __global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint3
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            for (uint32_t r = 0; r < rows_here; ++r)
-                for (uint32_t c = lane; c < row_bytes; c += 64u) img[first + r * row_bytes + c] = tile[r * row_stride + c];
+            if (dwords) {
+                const uint32_t rd = (uint32_t)row_bytes >> 2, total = rows_here * rd;
+                uint32_t *dst = reinterpret_cast<uint32_t *>(img + first);
+                uint32_t r = lane / rd, c = lane % rd;
+                for (uint32_t o = lane; o < total; o += 64u) {
+                    dst[o] = reinterpret_cast<const uint32_t *>(tile + r * row_stride)[c];
+                    c += 64u % rd;
+                    r += 64u / rd + (c >= rd ? 1u : 0u);
+                    c -= c >= rd ? rd : 0u;
+                }
+            } else {
+                for (uint32_t r = 0; r < rows_here; ++r)
+                    for (uint32_t c = lane; c < row_bytes; c += 64u)
+                        img[first + r * row_bytes + c] = tile[r * row_stride + c];
+            }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -209,7 +295,13 @@ int pilc_twar_forward(uint32_t n, uint32_t h, uint32_t w, const uint8_t *img_dev
     const uint32_t rpb = w >= 256 ? 1u : 256u / w;
     const uint32_t blocks = (uint32_t)((rows + rpb - 1) / rpb);
     Timer timer(stream);
-    k_twar_forward<<<blocks, 256, 0, stream>>>(k, (uint32_t)rows, h, w, rpb, img_dev, res_dev);
+    const uint64_t groups = rows * (w / 4);
+    if (w % 4 == 0 && ((((uintptr_t)img_dev) | ((uintptr_t)res_dev)) & 3) == 0 && groups < (1ull << 32))
+        k_twar_forward4<<<(uint32_t)((groups + 255) / 256), 256, 0, stream>>>(
+            k, (uint32_t)groups, h, w / 4, reinterpret_cast<const uint32_t *>(img_dev),
+            reinterpret_cast<uint32_t *>(res_dev));
+    else
+        k_twar_forward<<<blocks, 256, 0, stream>>>(k, (uint32_t)rows, h, w, rpb, img_dev, res_dev);
     timer.mark("k_twar_forward");
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipStreamSynchronize(stream));
