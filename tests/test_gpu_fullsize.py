@@ -118,3 +118,21 @@ def test_table_coder_full_size_sampled_parity():
     print("decoding", flush=True)
     dp.decode()
     assert torch.equal(dp.out, dp.sym)
+
+
+def test_twar_full_size_parity():
+    """The Three-Way AR transform on all 50,000 images of the CIFAR-shaped workload: the whole
+    residual against the reference, and the inverse back to the images."""
+    from oracle import twar_oracle as to
+
+    wl = synth.make_workload(1)
+    weights, bias = [[-16384, 16384, 16384], [8192, -8192, 16384], [8192, -8192, 16384]], [0, 0, 0]
+    print("reference forward", flush=True)
+    ref = to.forward(to.make_params(weights, bias), wl.img)
+    img = torch.from_numpy(wl.img).cuda()
+    res, back = torch.empty_like(img), torch.empty_like(img)
+    p = pb.make_twar_params(weights, bias)
+    pb.pilc_twar_forward(p, img, res)
+    assert np.array_equal(res.cpu().numpy(), ref)
+    pb.pilc_twar_inverse(p, res, back)
+    assert torch.equal(back, img)
