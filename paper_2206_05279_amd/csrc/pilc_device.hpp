@@ -92,25 +92,32 @@ __device__ __forceinline__ uint32_t inv_scale(int ls, const LdsTables &t)
 }
 
 // F(k) in 24 bits at the edge k - 1/2:  d = 256*k - 128 - mu'  (Q8.8), inv_s Q6.25 < 2^31.
-// z = clamp(floor(d * inv_s / 2^17), -2^20, 2^20 - 1) is taken from the 64-bit product as its bits
-// 17..48; it saturates exactly when the product's high word leaves [-32, 31].
+// z = clamp(floor(d * inv_s / 2^17), -2^20, 2^20 - 1) and w = z + 2^20 is bits 17..48 of the
+// 64-bit value d * inv_s + 2^37; z saturates exactly when the high word of that sum leaves 0..63.
 __device__ __forceinline__ uint32_t edge_cdf(int d, uint32_t inv_s, const LdsTables &t)
 {
-    const long long p = (long long)d * (long long)(int)inv_s;  // Q.33
+    long long p = (long long)d * (long long)(int)inv_s + (1ll << 37);  // Q.33
+    asm("" : "+v"(p));  // keep the range tests below on the high word alone
     const int hi = (int)(p >> 32);
-    int w = (int)__builtin_amdgcn_alignbit((uint32_t)hi, (uint32_t)p, 17) + (1 << 20);
-    w = hi >= 32 ? (1 << 21) - 1 : w;
-    w = hi < -32 ? 0 : w;
-    const uint2 cell = t.sig[(uint32_t)w >> 10];
-    return cell.x + (__umul24(cell.y, (uint32_t)w & 1023u) >> 10);
+    uint32_t w = __builtin_amdgcn_alignbit((uint32_t)hi, (uint32_t)p, 17);
+    const uint32_t sat = hi < 0 ? 0u : (1u << 21) - 1u;
+    w = (uint32_t)hi < 64u ? w : sat;
+    const uint2 cell = t.sig[w >> 10];
+    return cell.x + (__umul24(cell.y, w & 1023u) >> 10);
+}
+
+// floor(f * (2^M - 256) / 2^24) for a 24-bit f:  2^M - 256 = 256 * (spread >> 8) and the product
+// f * (spread >> 8) stays below 2^32 for M <= 16.
+__device__ __forceinline__ uint32_t scale_mass(uint32_t f, uint32_t spread)
+{
+    return (uint32_t)__umul24(f, spread >> 8) >> 16;  // the builtin's result type is int
 }
 
 // C(k), 1 <= k <= 255:  k + floor(F(k) * (2^M - 256) / 2^24).
 __device__ __forceinline__ uint32_t cum_inner(int k, int mu_eff, uint32_t inv_s, uint32_t spread,
                                               const LdsTables &t)
 {
-    uint32_t f = edge_cdf(256 * k - 128 - mu_eff, inv_s, t);
-    return (uint32_t)k + __umulhi(f << 8, spread);
+    return (uint32_t)k + scale_mass(edge_cdf(256 * k + (-128 - mu_eff), inv_s, t), spread);
 }
 
 // C(k) for any k in 0..256.

@@ -125,7 +125,7 @@ __global__ __launch_bounds__(64 * kGroupWavesPerBlock) void k_decode_group(
             const uint2 cell = (tab.sig + 1024)[z >> 10];
             spec[c] = next((uint32_t)base + j + (uint32_t)(G * c));
             const uint32_t f24 = cell.x + (__umul24(cell.y, (uint32_t)z & 1023u) >> 10);
-            cv[c] = (uint32_t)base + j + (uint32_t)(G * c) + __umulhi(f24 << 8, spread);
+            cv[c] = (uint32_t)base + j + (uint32_t)(G * c) + scale_mass(f24, spread);
         }
 #pragma unroll
         for (int c = 0; c < C; ++c) cnt += group_count(cv[c] <= slot_eff);

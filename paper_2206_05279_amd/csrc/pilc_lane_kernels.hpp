@@ -239,16 +239,15 @@ __global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
                              rsh14(a_bg * (x[1] * 256 - ck.m[i][1]));
                     const uint32_t inv_s = inv_scale(ck.l[i][ch], tab);
                     const uint32_t slot = S & mask;
-                    int lo = 0, hi = 256;
+                    // the symbol is in lo .. lo + 2 * step - 1, and c_hi = C(lo + 2 * step)
+                    int lo = 0;
                     uint32_t c_lo = 0u, c_hi = 1u << m_bits;
 #pragma unroll
-                    for (int it = 0; it < 8; ++it) {
-                        const int mid = (lo + hi) >> 1;
-                        const uint32_t cm = cum_inner(mid, me, inv_s, spread, tab);
+                    for (int step = 128; step >= 1; step >>= 1) {
+                        const uint32_t cm = cum_inner(lo + step, me, inv_s, spread, tab);
                         const bool ge = cm <= slot;
-                        lo = ge ? mid : lo;
+                        lo = ge ? lo + step : lo;
                         c_lo = ge ? cm : c_lo;
-                        hi = ge ? hi : mid;
                         c_hi = ge ? c_hi : cm;
                     }
                     x[ch] = lo;

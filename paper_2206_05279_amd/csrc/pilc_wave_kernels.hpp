@@ -151,7 +151,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_decode_wave(
         w = min(max(w, 0), (1 << 21) - 1);
         const uint2 cell = tab.sig[w >> 10];
         const uint32_t f24 = cell.x + (__umul24(cell.y, (uint32_t)w & 1023u) >> 10);
-        const uint32_t cv = (uint32_t)base + lane_id + __umulhi(f24 << 8, spread);
+        const uint32_t cv = (uint32_t)base + lane_id + scale_mass(f24, spread);
         const uint32_t cnt = (uint32_t)__popcll(__ballot(cv <= slot));
         uint32_t x, c_lo, c_hi;
         if (__builtin_expect((win & 0x100u) != 0u && cnt - 1u < 63u, 1)) {
