@@ -230,6 +230,70 @@ __global__ __launch_bounds__(256) void k_pack(Geo g, uint32_t lanes_per_block,
     }
 }
 
+// The packer for the thread-per-lane encoder, whose scratch is [word number][thread] per 64
+// lanes with room for lane_cap words each, the words of a lane in the reverse of the stream
+// order.  A workgroup owns 64 lanes: it reads 64 word numbers at a time as whole 128-byte rows
+// into an LDS tile and writes every lane's piece of the stream from there, 64 consecutive words
+// per wavefront instruction.
+constexpr int kPackTile = 64;
+constexpr int kPackTileStride = 66;  // 16-bit elements: 33 dwords, odd, so a column read spreads over the banks
+
+__global__ __launch_bounds__(256) void k_pack_by_thread(uint32_t lanes, uint32_t lane_cap,
+                                                        const uint16_t *__restrict__ scratch,
+                                                        const uint32_t *__restrict__ lane_state,
+                                                        const uint32_t *__restrict__ offsets,
+                                                        uint16_t *__restrict__ payload,
+                                                        const Status *__restrict__ status)
+{
+    if (status->code != ST_OK) return;
+    __shared__ uint32_t s_first[64];  // payload word index of the lane's state
+    __shared__ uint32_t s_nw[64];     // words after the state
+    __shared__ uint32_t s_max;
+    __shared__ __align__(4) uint16_t tile[kPackTile * kPackTileStride];
+    const uint32_t t = threadIdx.x;
+    const uint32_t l0 = blockIdx.x * 64u;
+    if (t == 0) s_max = 0u;
+    __syncthreads();
+    if (t < 64u) {
+        uint32_t nw = 0u, first = 0u;
+        if (l0 + t < lanes) {
+            const uint32_t begin = offsets[l0 + t], end = offsets[l0 + t + 1];
+            const uint32_t st = lane_state[l0 + t];
+            first = begin >> 1;
+            nw = (end - begin - 4u) >> 1;
+            payload[first] = (uint16_t)st;
+            payload[first + 1u] = (uint16_t)(st >> 16);
+            atomicMax(&s_max, nw);
+        }
+        s_first[t] = first;
+        s_nw[t] = nw;
+    }
+    __syncthreads();
+    const uint32_t max_nw = s_max;
+    const uint16_t *rows = scratch + (size_t)l0 * lane_cap;
+    for (uint32_t k0 = 0; k0 < max_nw; k0 += kPackTile) {
+        // rows k0 .. k0 + 63 of the block, two lanes (one dword) per thread and 8 rows apart
+#pragma unroll
+        for (int j = 0; j < kPackTile / 8; ++j) {
+            const uint32_t r = (t >> 5) + 8u * j, c2 = t & 31u;
+            if (k0 + r < max_nw) {
+                const uint32_t v =
+                    *reinterpret_cast<const uint32_t *>(rows + (size_t)(k0 + r) * 64u + 2u * c2);
+                *reinterpret_cast<uint32_t *>(&tile[r * kPackTileStride + 2u * c2]) = v;
+            }
+        }
+        __syncthreads();
+        // wavefront w writes lanes 16 w .. 16 w + 15; its thread u has word number k0 + u
+#pragma unroll 4
+        for (int j = 0; j < 16; ++j) {
+            const uint32_t i = (t >> 6) * 16u + j, k = k0 + (t & 63u);
+            const uint32_t nw = s_nw[i];
+            if (k < nw) payload[s_first[i] + 2u + (nw - 1u - k)] = tile[(t & 63u) * kPackTileStride + i];
+        }
+        __syncthreads();
+    }
+}
+
 // --------------------------------------------------------------------------------------------
 // Decode.
 // --------------------------------------------------------------------------------------------
@@ -386,6 +450,15 @@ static int make_geo(const pilc_geom *in, Geo *g)
 
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
+// Symbols of the longest lane.
+static uint32_t max_lane_symbols(const Geo &g)
+{
+    const uint64_t px = g.lane_mode == 0 ? (uint64_t)(g.lane_a < g.total_px ? g.lane_a : g.total_px)
+                                         : (uint64_t)(g.lane_a < g.h ? g.lane_a : g.h) *
+                                               (g.lane_b < g.w ? g.lane_b : g.w);
+    return (uint32_t)(3u * px);
+}
+
 struct Workspace {
     size_t status_off, words_off, state_off, sums_off, scratch_off, total;
     uint32_t scan_blocks;
@@ -405,8 +478,11 @@ static Workspace layout(const Geo &g)
     w.sums_off = off;
     off = align256(off + 8 * (size_t)w.scan_blocks);
     w.scratch_off = off;
-    // one 16-bit word per symbol, plus one dump word per lane for the branch-free encoder
-    off = align256(off + 2 * ((size_t)g.total_px * 3 + g.lanes + 64));
+    // one 16-bit word per symbol, plus one dump word per lane for the branch-free encoder; the
+    // thread-per-lane encoder gives every lane of a block of 64 the room of the longest lane
+    const size_t linear = (size_t)g.total_px * 3 + g.lanes + 64;
+    const size_t by_thread = (((size_t)g.lanes + 63) & ~(size_t)63) * max_lane_symbols(g);
+    off = align256(off + 2 * (linear > by_thread ? linear : by_thread));
     w.total = off;
     return w;
 }
@@ -593,6 +669,7 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
     Timer timer(stream);
     k_init_status<<<1, 1, 0, stream>>>(status);
     const bool few_lanes = use_wave_kernels(g);
+    const uint32_t lane_cap = few_lanes ? 0u : max_lane_symbols(g);  // selects the scratch layout
     if (few_lanes) {
         k_encode_block<<<(uint32_t)ceil_div64(g.lanes, kEncLanes), kEncThreads, 0, stream>>>(
             g, img_dev, params->mu, params->log_scale, params->chan_coef, scratch, g.total_px * 3u,
@@ -602,10 +679,12 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
         const uint32_t nb = (uint32_t)ceil_div64(g.lanes, bt);
         if (chunks_aligned(g, img_dev, params))
             k_encode_lanes<true><<<nb, bt, 0, stream>>>(g, img_dev, params->mu, params->log_scale,
-                                                        params->chan_coef, scratch, lane_words, lane_state);
+                                                        params->chan_coef, scratch, lane_cap, lane_words,
+                                                        lane_state);
         else
             k_encode_lanes<false><<<nb, bt, 0, stream>>>(g, img_dev, params->mu, params->log_scale,
-                                                         params->chan_coef, scratch, lane_words, lane_state);
+                                                         params->chan_coef, scratch, lane_cap, lane_words,
+                                                         lane_state);
     }
     timer.mark(few_lanes ? "k_encode_block" : "k_encode_lanes");
     const ItemBytes lane_bytes = {4u, 2u, 0u, 0u};  // a 32-bit state and 16-bit words
@@ -618,13 +697,15 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
                                                               offsets);
     timer.mark("scan");
     // a run of lanes per workgroup: about 16K symbols' worth, at most 256 lanes
-    const uint64_t lane_sym =
-        3ull * (g.lane_mode == 0 ? (uint64_t)(g.lane_a < g.total_px ? g.lane_a : g.total_px)
-                                 : (uint64_t)g.lane_a * g.lane_b);
-    uint32_t pack_lanes = (uint32_t)(16384 / (lane_sym ? lane_sym : 1));
+    const uint32_t lane_sym = max_lane_symbols(g);
+    uint32_t pack_lanes = 16384u / (lane_sym ? lane_sym : 1u);
     pack_lanes = pack_lanes < 1 ? 1 : (pack_lanes > (uint32_t)kPackMaxLanes ? kPackMaxLanes : pack_lanes);
-    k_pack<<<(uint32_t)ceil_div64(g.lanes, pack_lanes), 256, 0, stream>>>(
-        g, pack_lanes, scratch, lane_state, offsets, payload, status);
+    if (lane_cap != 0u)
+        k_pack_by_thread<<<(uint32_t)ceil_div64(g.lanes, 64), 256, 0, stream>>>(
+            g.lanes, lane_cap, scratch, lane_state, offsets, payload, status);
+    else
+        k_pack<<<(uint32_t)ceil_div64(g.lanes, pack_lanes), 256, 0, stream>>>(
+            g, pack_lanes, scratch, lane_state, offsets, payload, status);
     timer.mark("k_pack");
     HIP_TRY(hipGetLastError());
     Status host_status;

@@ -102,14 +102,24 @@ __device__ __forceinline__ ChunkPos chunk_pos(const Geo &g, const LaneShape &sh,
 }
 
 // --------------------------------------------------------------------------------------------
-// Encode.  Symbols are pushed last-first (App. A eq. (11)); the 16-bit words go to the lane's
-// scratch slot from its end downwards, so that they finish in the order the decoder reads them.
+// Encode.  Symbols are pushed last-first (App. A eq. (11)), so the 16-bit words come out in the
+// reverse of the order the decoder reads them.  Scratch is laid out per wavefront as
+// [word number][thread]: the k-th word of the 64 lanes of a wavefront share a 128-byte line, and
+// since neighbouring lanes emit at nearly the same pace a line is complete soon after it is first
+// touched.  `lane_cap` is the room every lane has (words); the packer reads a lane's words back
+// from the highest number down.
 // --------------------------------------------------------------------------------------------
+__device__ __forceinline__ size_t lane_scratch_base(uint32_t lane, uint32_t lane_cap)
+{
+    return (size_t)(lane & ~63u) * lane_cap + (lane & 63u);
+}
+
 template <bool kVec>
 __global__ void k_encode_lanes(Geo g, const uint8_t *__restrict__ img,
                                const uint16_t *__restrict__ mu, const int16_t *__restrict__ ls,
                                const int16_t *__restrict__ coef, uint16_t *__restrict__ scratch,
-                               uint32_t *__restrict__ lane_words, uint32_t *__restrict__ lane_state)
+                               uint32_t lane_cap, uint32_t *__restrict__ lane_words,
+                               uint32_t *__restrict__ lane_state)
 {
     __shared__ LdsTables tab;
     load_tables(tab);
@@ -121,8 +131,8 @@ __global__ void k_encode_lanes(Geo g, const uint8_t *__restrict__ img,
     const uint32_t per_row = (sh.tw + kChunk - 1) / kChunk;
     const uint32_t chunks = per_row * (sh.npx / sh.tw);
 
-    const uint32_t slot_end = sh.sym_base + 3u * sh.npx;
-    uint32_t wpos = slot_end;
+    uint16_t *wout = scratch + lane_scratch_base(lane, lane_cap);  // the lane's next word
+    uint32_t nwords = 0;
     uint32_t S = 1u << 16;
 
     for (uint32_t c = chunks; c-- > 0u;) {
@@ -164,7 +174,9 @@ __global__ void k_encode_lanes(Geo g, const uint8_t *__restrict__ img,
             if ((uint32_t)k < 3u * cp.len) {
                 const uint32_t f = cf[k] >> 16, lo = cf[k] & 0xFFFFu;
                 if (S >= (f << (32u - m_bits))) {
-                    scratch[--wpos] = (uint16_t)(S & 0xFFFFu);
+                    *wout = (uint16_t)(S & 0xFFFFu);
+                    wout += 64;
+                    ++nwords;
                     S >>= 16;
                 }
                 uint32_t rem;
@@ -173,13 +185,69 @@ __global__ void k_encode_lanes(Geo g, const uint8_t *__restrict__ img,
             }
         }
     }
-    lane_words[lane] = slot_end - wpos;
+    lane_words[lane] = nwords;
     lane_state[lane] = S;
 }
 
 // --------------------------------------------------------------------------------------------
 // Decode.  The symbol is found by an 8-step bisection on C(k) (App. A: "binary search").
 // --------------------------------------------------------------------------------------------
+
+// A lane's 16-bit words, fetched 16 aligned bytes at a time and one load ahead of their use, so
+// that a refill of the state (App. A eq. (12)) never waits for memory and every byte of the
+// stream crosses the memory bus once.  A load is issued only if it starts below `lim`, the end of
+// the container: it then holds at least one byte of it and cannot leave the container's last page.
+// Words beyond the lane's own end are whatever follows; a lane that takes them fails its final
+// check of the number of words taken.
+struct WordStream {
+    uint32_t w0, w1, w2, w3;  // the words not yet taken from the current 16 bytes, lowest first
+    uint4 ahead;              // the 16 bytes after them
+    uint32_t next;            // word offset from `base` of the 16 bytes after `ahead`
+    uint32_t count;           // words skipped and taken so far: a multiple of 8 ends 16 bytes
+
+    // the 8 words at word offset `off` of the 16-byte aligned `base`, if they start below `lim`
+    __device__ __forceinline__ static uint4 fetch(const uint16_t *base, uint32_t off, uint32_t lim)
+    {
+        return off < lim ? *reinterpret_cast<const uint4 *>(base + off) : make_uint4(0u, 0u, 0u, 0u);
+    }
+    // the lane's first word is at word offset `first` < lim
+    __device__ __forceinline__ void open(const uint16_t *base, uint32_t first, uint32_t lim)
+    {
+        const uint32_t q = first & ~7u;
+        const uint4 c = fetch(base, q, lim);
+        ahead = fetch(base, q + 8u, lim);
+        next = q + 16u;
+        const uint32_t skip = first & 7u;  // words of the first 16 bytes before `first`
+        unsigned long long lo = (unsigned long long)c.x | ((unsigned long long)c.y << 32);
+        unsigned long long hi = (unsigned long long)c.z | ((unsigned long long)c.w << 32);
+        if (skip >= 4u) {
+            lo = hi >> (16u * (skip - 4u));
+            hi = 0ull;
+        } else if (skip != 0u) {
+            lo = (lo >> (16u * skip)) | (hi << (64u - 16u * skip));
+            hi >>= 16u * skip;
+        }
+        w0 = (uint32_t)lo; w1 = (uint32_t)(lo >> 32); w2 = (uint32_t)hi; w3 = (uint32_t)(hi >> 32);
+        count = skip;
+    }
+    __device__ __forceinline__ uint32_t take(const uint16_t *base, uint32_t lim)
+    {
+        const uint32_t wd = w0 & 0xFFFFu;
+        w0 = __builtin_amdgcn_alignbit(w1, w0, 16);
+        w1 = __builtin_amdgcn_alignbit(w2, w1, 16);
+        w2 = __builtin_amdgcn_alignbit(w3, w2, 16);
+        w3 >>= 16;
+        if ((++count & 7u) == 0u) {
+            w0 = ahead.x; w1 = ahead.y; w2 = ahead.z; w3 = ahead.w;
+            ahead = fetch(base, next, lim);
+            next += 8u;
+        }
+        return wd;
+    }
+    // words taken by a stream opened at word offset `first`
+    __device__ __forceinline__ uint32_t taken(uint32_t first) const { return count - (first & 7u); }
+};
+
 template <bool kVec>
 __global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
                                const uint16_t *__restrict__ mu, const int16_t *__restrict__ ls,
@@ -207,10 +275,15 @@ __global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
         atomicMax(status_code, 6);
         return;
     }
-    uint32_t pos = begin >> 1;
-    const uint32_t stop = end >> 1;  // in 16-bit words
-    uint32_t S = (uint32_t)payload[pos] | ((uint32_t)payload[pos + 1] << 16);
-    pos += 2;
+    // word offsets from the last 16-byte boundary at or below the payload (the payload is < 4 GiB)
+    const uint32_t adj = (uint32_t)(reinterpret_cast<uintptr_t>(payload) & 15u);
+    const uint16_t *base = reinterpret_cast<const uint16_t *>(reinterpret_cast<const uint8_t *>(payload) - adj);
+    const uint32_t first = (adj + begin) >> 1;
+    const uint32_t lim = (uint32_t)(((unsigned long long)adj + payload_bytes + 1ull) >> 1);
+    WordStream words;
+    words.open(base, first, lim);
+    uint32_t S = words.take(base, lim);
+    S |= words.take(base, lim) << 16;
 
     for (uint32_t c = 0; c < chunks; ++c) {
         const ChunkPos cp = chunk_pos(g, sh, per_row, c);
@@ -253,12 +326,7 @@ __global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
                     x[ch] = lo;
                     // App. A eq. (12)
                     S = (c_hi - c_lo) * (S >> m_bits) + slot - c_lo;
-                    if (S < (1u << 16)) {
-                        // a lane that runs past its end reads zeros and fails the final check
-                        const uint32_t wd = pos < stop ? (uint32_t)payload[pos] : 0u;
-                        S = (S << 16) | wd;
-                        ++pos;
-                    }
+                    if (S < (1u << 16)) S = (S << 16) | words.take(base, lim);
                     const int b = 3 * i + ch;
                     wout[b >> 2] |= (uint32_t)lo << (8 * (b & 3));
                 }
@@ -276,7 +344,7 @@ __global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
                 if ((uint32_t)b < 3u * cp.len) out[s + b] = (uint8_t)(wout[b >> 2] >> (8 * (b & 3)));
         }
     }
-    if (S != (1u << 16) || pos != stop) atomicMax(status_code, 6);
+    if (S != (1u << 16) || words.taken(first) != (end - begin) >> 1) atomicMax(status_code, 6);
 }
 
 }  // namespace pilc
