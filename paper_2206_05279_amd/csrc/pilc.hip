@@ -706,7 +706,7 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
     else
         k_pack<<<(uint32_t)ceil_div64(g.lanes, pack_lanes), 256, 0, stream>>>(
             g, pack_lanes, scratch, lane_state, offsets, payload, status);
-    timer.mark("k_pack");
+    timer.mark(lane_cap != 0u ? "k_pack_by_thread" : "k_pack");
     HIP_TRY(hipGetLastError());
     Status host_status;
     HIP_TRY(hipMemcpyAsync(&host_status, status, sizeof(Status), hipMemcpyDeviceToHost, stream));
