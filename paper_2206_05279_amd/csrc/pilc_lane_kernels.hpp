@@ -193,19 +193,21 @@ __global__ void k_encode_lanes(Geo g, const uint8_t *__restrict__ img,
 // Decode.  The symbol is found by an 8-step bisection on C(k) (App. A: "binary search").
 // --------------------------------------------------------------------------------------------
 
-// A lane's 16-bit words, fetched 16 aligned bytes at a time and one load ahead of their use, so
-// that a refill of the state (App. A eq. (12)) never waits for memory and every byte of the
-// stream crosses the memory bus once.  A load is issued only if it starts below `lim`, the end of
-// the container: it then holds at least one byte of it and cannot leave the container's last page.
-// Words beyond the lane's own end are whatever follows; a lane that takes them fails its final
-// check of the number of words taken.
+// A lane's 16-bit words, fetched as aligned 32-byte pairs of 16-byte pieces, a piece ahead of
+// their use: a refill of the state (App. A eq. (12)) never waits for memory, and a 128-byte line
+// of the stream is asked for four times instead of once per word.  A piece is loaded only if it
+// starts below `lim`, the end of the container: it then holds at least one byte of it and cannot
+// leave the container's last page.  Words beyond the lane's own end are whatever follows; a lane
+// that takes them fails its final check of the number of words taken.
 struct WordStream {
-    uint32_t w0, w1, w2, w3;  // the words not yet taken from the current 16 bytes, lowest first
-    uint4 ahead;              // the 16 bytes after them
-    uint32_t next;            // word offset from `base` of the 16 bytes after `ahead`
-    uint32_t count;           // words skipped and taken so far: a multiple of 8 ends 16 bytes
+    uint32_t w0, w1, w2, w3;  // the words not yet taken from the current piece, lowest first
+    uint4 x, y;               // the piece after the current one; the piece after that when the
+                              // current one is the second of its pair
+    uint32_t next;            // word offset from `base` of the next pair to load
+    uint32_t count;           // words of the current pair skipped or taken, plus 16 per pair done:
+                              // bits 0..2 count within a piece, bit 3 tells the piece of the pair
 
-    // the 8 words at word offset `off` of the 16-byte aligned `base`, if they start below `lim`
+    // the 8 words at word offset `off` of the 32-byte aligned `base`, if they start below `lim`
     __device__ __forceinline__ static uint4 fetch(const uint16_t *base, uint32_t off, uint32_t lim)
     {
         return off < lim ? *reinterpret_cast<const uint4 *>(base + off) : make_uint4(0u, 0u, 0u, 0u);
@@ -215,9 +217,11 @@ struct WordStream {
     {
         const uint32_t q = first & ~7u;
         const uint4 c = fetch(base, q, lim);
-        ahead = fetch(base, q + 8u, lim);
-        next = q + 16u;
-        const uint32_t skip = first & 7u;  // words of the first 16 bytes before `first`
+        x = fetch(base, q + 8u, lim);
+        y = make_uint4(0u, 0u, 0u, 0u);
+        if ((first & 8u) != 0u) y = fetch(base, q + 16u, lim);  // second piece: x, y are the next pair
+        next = (first & ~15u) + 16u + (first & 8u) * 2u;
+        const uint32_t skip = first & 7u;  // words of the first piece before `first`
         unsigned long long lo = (unsigned long long)c.x | ((unsigned long long)c.y << 32);
         unsigned long long hi = (unsigned long long)c.z | ((unsigned long long)c.w << 32);
         if (skip >= 4u) {
@@ -228,7 +232,7 @@ struct WordStream {
             hi >>= 16u * skip;
         }
         w0 = (uint32_t)lo; w1 = (uint32_t)(lo >> 32); w2 = (uint32_t)hi; w3 = (uint32_t)(hi >> 32);
-        count = skip;
+        count = first & 15u;
     }
     __device__ __forceinline__ uint32_t take(const uint16_t *base, uint32_t lim)
     {
@@ -238,14 +242,19 @@ struct WordStream {
         w2 = __builtin_amdgcn_alignbit(w3, w2, 16);
         w3 >>= 16;
         if ((++count & 7u) == 0u) {
-            w0 = ahead.x; w1 = ahead.y; w2 = ahead.z; w3 = ahead.w;
-            ahead = fetch(base, next, lim);
-            next += 8u;
+            w0 = x.x; w1 = x.y; w2 = x.z; w3 = x.w;
+            if ((count & 8u) != 0u) {  // now in the second piece of a pair: fetch the next pair
+                x = fetch(base, next, lim);
+                y = fetch(base, next + 8u, lim);
+                next += 16u;
+            } else {
+                x = y;
+            }
         }
         return wd;
     }
     // words taken by a stream opened at word offset `first`
-    __device__ __forceinline__ uint32_t taken(uint32_t first) const { return count - (first & 7u); }
+    __device__ __forceinline__ uint32_t taken(uint32_t first) const { return count - (first & 15u); }
 };
 
 template <bool kVec>
@@ -275,8 +284,8 @@ __global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
         atomicMax(status_code, 6);
         return;
     }
-    // word offsets from the last 16-byte boundary at or below the payload (the payload is < 4 GiB)
-    const uint32_t adj = (uint32_t)(reinterpret_cast<uintptr_t>(payload) & 15u);
+    // word offsets from the last 32-byte boundary at or below the payload (the payload is < 4 GiB)
+    const uint32_t adj = (uint32_t)(reinterpret_cast<uintptr_t>(payload) & 31u);
     const uint16_t *base = reinterpret_cast<const uint16_t *>(reinterpret_cast<const uint8_t *>(payload) - adj);
     const uint32_t first = (adj + begin) >> 1;
     const uint32_t lim = (uint32_t)(((unsigned long long)adj + payload_bytes + 1ull) >> 1);
