@@ -115,6 +115,36 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
 int pilc_symbol_tables(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params *params,
                        uint32_t *cum_out_dev, uint32_t *freq_out_dev, void *hip_stream);
 
+/* ---- mixture of K logistic laws per subpixel ------------------------------------------
+ * The workload Sec. 2 ("Entropy Coder", and the "Data transfer" item before it) names as the
+ * slow case of earlier learned codecs: a dynamic rANS coder (App. A eqs. (11)-(12)) whose
+ * distribution per symbol is "mixed by 10 logistic ones".  The paper gives no formula; this
+ * library takes: a pixel carries K weights w_j in Q0.15 that sum to 2^15 exactly (shared by its
+ * three subpixels), a subpixel K means and K log-scales (formats of pilc_params); the mixed
+ * 24-bit edge CDF is F(k) = floor(sum_j w_j F_j(k) / 2^15), F_j the single-law edge CDF, and
+ * C(k) = k + floor(F(k) (2^M - 256) / 2^24), so K = 1 is the single law of pilc_encode; G and B
+ * are conditioned as in pilc_params, every component's mean shifted with that component's own
+ * innovations. */
+typedef struct {
+    const uint16_t *mu;        /* device [n,h,w,3,K] Q8.8                                  */
+    const int16_t *log_scale;  /* device [n,h,w,3,K] Q4.12                                 */
+    const uint16_t *weight;    /* device [n,h,w,K]   Q0.15, sum over K = 32768 per pixel   */
+    const int16_t *chan_coef;  /* device [n,3]       Q2.14: a_GR, a_BR, a_BG               */
+    uint32_t num_comp;         /* K, 1..16                                                 */
+} pilc_mix_params;
+
+/* As pilc_encode / pilc_decode (same geometry, workspace size from pilc_workspace_size,
+ * alignment, ownership and container), with the magic "PMIX" and K in header word 11 (bytes
+ * 44..47).  Runs one thread per lane whatever the number of lanes.
+ * Errors: those of pilc_encode / pilc_decode; PILC_E_ARG also for K outside 1..16 and, found on
+ * the device, for a pixel whose weights do not sum to 32768 (outputs then undefined). */
+int pilc_mix_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_mix_params *params,
+                    void *workspace_dev, size_t workspace_bytes, uint8_t *coded_dev,
+                    size_t coded_capacity, uint64_t *coded_bytes_host, void *hip_stream);
+int pilc_mix_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_bytes,
+                    const pilc_mix_params *params, void *workspace_dev, size_t workspace_bytes,
+                    uint8_t *img_out_dev, void *hip_stream);
+
 /* Per-kernel timing, off by default.  When enabled, pilc_encode / pilc_decode bracket each
  * kernel with HIP events on the stream the kernel is launched on.  pilc_last_timing returns
  * the durations in milliseconds of the most recent call on the calling thread: index 0 is

@@ -30,6 +30,7 @@ EXPORTS = [
     "pilc_last_hip_error", "pilc_version",
     "pilc_ansai_table_bytes", "pilc_ansai_build_tables", "pilc_ansai_workspace_size", "pilc_ansai_encode",
     "pilc_ansai_decode", "pilc_ansai_center", "pilc_twar_forward", "pilc_twar_inverse",
+    "pilc_mix_encode", "pilc_mix_decode",
 ]
 
 
@@ -40,6 +41,11 @@ class pilc_geom(C.Structure):
 
 class pilc_params(C.Structure):
     _fields_ = [("mu", C.c_void_p), ("log_scale", C.c_void_p), ("chan_coef", C.c_void_p)]
+
+
+class pilc_mix_params(C.Structure):
+    _fields_ = [("mu", C.c_void_p), ("log_scale", C.c_void_p), ("weight", C.c_void_p),
+                ("chan_coef", C.c_void_p), ("num_comp", C.c_uint32)]
 
 
 class pilc_ansai_shape(C.Structure):
@@ -116,6 +122,13 @@ def lib():
         L.pilc_ansai_decode.restype = C.c_int
         L.pilc_ansai_decode.argtypes = [sp, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_size_t, C.c_void_p, C.c_void_p]
+        mp = C.POINTER(pilc_mix_params)
+        L.pilc_mix_encode.restype = C.c_int
+        L.pilc_mix_encode.argtypes = [gp, C.c_void_p, mp, C.c_void_p, C.c_size_t, C.c_void_p,
+                                      C.c_size_t, C.POINTER(C.c_uint64), C.c_void_p]
+        L.pilc_mix_decode.restype = C.c_int
+        L.pilc_mix_decode.argtypes = [gp, C.c_void_p, C.c_size_t, mp, C.c_void_p, C.c_size_t,
+                                      C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -309,3 +322,37 @@ def pilc_twar_forward(params: pilc_twar_params, img, res, stream: Optional[torch
 def pilc_twar_inverse(params: pilc_twar_params, res, img, stream: Optional[torch.cuda.Stream] = None,
                       check: bool = True) -> int:
     return _twar(lib().pilc_twar_inverse, "pilc_twar_inverse", params, res, img, stream, check)
+
+
+# ---- mixture of K logistic laws per subpixel ------------------------------------------------
+def _mix_params(num_comp, mu, log_scale, weight, chan_coef) -> pilc_mix_params:
+    return pilc_mix_params(_dev_ptr(mu, torch.uint16, "mu"), _dev_ptr(log_scale, torch.int16, "log_scale"),
+                           _dev_ptr(weight, torch.uint16, "weight"),
+                           _dev_ptr(chan_coef, torch.int16, "chan_coef"), int(num_comp))
+
+
+def pilc_mix_encode(geom: pilc_geom, num_comp: int, img, mu, log_scale, weight, chan_coef, workspace,
+                    coded, stream: Optional[torch.cuda.Stream] = None, check: bool = True) -> Tuple[int, int]:
+    """Runs pilc_mix_encode; returns (rc, coded_bytes)."""
+    nbytes = C.c_uint64(0)
+    par = _mix_params(num_comp, mu, log_scale, weight, chan_coef)
+    rc = lib().pilc_mix_encode(C.byref(geom), _dev_ptr(img, torch.uint8, "img"), C.byref(par),
+                               _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+                               _dev_ptr(coded, torch.uint8, "coded"), coded.numel(), C.byref(nbytes),
+                               _stream_handle(stream))
+    if check and rc != PILC_OK:
+        raise PilcError(rc, "pilc_mix_encode")
+    return rc, int(nbytes.value)
+
+
+def pilc_mix_decode(geom: pilc_geom, num_comp: int, coded, coded_bytes: int, mu, log_scale, weight,
+                    chan_coef, workspace, img_out, stream: Optional[torch.cuda.Stream] = None,
+                    check: bool = True) -> int:
+    par = _mix_params(num_comp, mu, log_scale, weight, chan_coef)
+    rc = lib().pilc_mix_decode(C.byref(geom), _dev_ptr(coded, torch.uint8, "coded"), int(coded_bytes),
+                               C.byref(par), _dev_ptr(workspace, torch.uint8, "workspace"),
+                               workspace.numel(), _dev_ptr(img_out, torch.uint8, "img_out"),
+                               _stream_handle(stream))
+    if check and rc != PILC_OK:
+        raise PilcError(rc, "pilc_mix_decode")
+    return rc

@@ -27,7 +27,9 @@ __device__ uint32_t g_exp_lo[kExpLoEntries];
 constexpr uint32_t kHeaderBytes = 64;
 
 // status word kinds (device side), mapped to PILC_E_* on the host
-enum : int { ST_OK = 0, ST_TOO_LARGE = 4, ST_FORMAT = 5, ST_CORRUPT = 6, ST_CAPACITY = 3 };
+constexpr uint32_t kMagicPilc = 0x434C4950u;  // "PILC"
+constexpr uint32_t kMagicMix = 0x58494D50u;   // "PMIX"
+enum : int { ST_OK = 0, ST_TOO_LARGE = 4, ST_FORMAT = 5, ST_CORRUPT = 6, ST_CAPACITY = 3, ST_PARAMS = 7 };
 
 struct Status {
     int code;
@@ -304,13 +306,17 @@ __global__ void k_init_status(Status *status)
     status->payload_bytes = 0;
 }
 
-__global__ void k_check_header(Geo g, const uint8_t *__restrict__ coded,
-                               unsigned long long coded_bytes, Status *__restrict__ status)
+// `word11` is header word 11 for containers that use it (the number of mixture components);
+// containers that leave it reserved pass 0 and it is not looked at.
+__global__ void k_check_header(Geo g, uint32_t magic, uint32_t word11,
+                               const uint8_t *__restrict__ coded, unsigned long long coded_bytes,
+                               Status *__restrict__ status)
 {
     const uint32_t *h = reinterpret_cast<const uint32_t *>(coded);
     int st = ST_OK;
     unsigned long long payload = (unsigned long long)h[12] | ((unsigned long long)h[13] << 32);
-    if (h[0] != 0x434C4950u || h[1] != PILC_VERSION) st = ST_FORMAT;
+    if (h[0] != magic || h[1] != PILC_VERSION) st = ST_FORMAT;
+    if (word11 != 0u && h[11] != word11) st = ST_FORMAT;
     if (h[2] != g.n || h[3] != g.h || h[4] != g.w || h[5] != 3u || h[6] != g.prec_bits ||
         h[7] != g.lane_mode || h[8] != g.lane_a || h[9] != g.lane_b || h[10] != g.lanes)
         st = ST_FORMAT;
@@ -331,6 +337,7 @@ __global__ void k_check_header(Geo g, const uint8_t *__restrict__ coded,
 #include "pilc_wave_kernels.hpp"
 #include "pilc_block_encode.hpp"
 #include "pilc_group_decode.hpp"
+#include "pilc_mix.hpp"
 
 namespace pilc {
 
@@ -494,6 +501,7 @@ static int status_to_error(int st)
     case ST_CAPACITY: return PILC_E_CAPACITY;
     case ST_TOO_LARGE: return PILC_E_TOO_LARGE;
     case ST_FORMAT: return PILC_E_FORMAT;
+    case ST_PARAMS: return PILC_E_ARG;
     default: return PILC_E_CORRUPT;
     }
 }
@@ -688,7 +696,7 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
     }
     timer.mark(few_lanes ? "k_encode_block" : "k_encode_lanes");
     const ItemBytes lane_bytes = {4u, 2u, 0u, 0u};  // a 32-bit state and 16-bit words
-    const HeaderWords head = {{0x434C4950u /* "PILC" */, PILC_VERSION, g.n, g.h, g.w, 3u, g.prec_bits,
+    const HeaderWords head = {{kMagicPilc, PILC_VERSION, g.n, g.h, g.w, 3u, g.prec_bits,
                                g.lane_mode, g.lane_a, g.lane_b, g.lanes, 0u}};
     k_scan_partials<<<ws.scan_blocks, kScanThreads, 0, stream>>>(g.lanes, lane_bytes, lane_words, sums);
     k_scan_spine<<<1, kScanThreads, 0, stream>>>(head, g.lanes, ws.scan_blocks, sums, coded_dev,
@@ -736,7 +744,7 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
     Status *status = reinterpret_cast<Status *>(static_cast<uint8_t *>(workspace_dev) + ws.status_off);
 
     Timer timer(stream);
-    k_check_header<<<1, 1, 0, stream>>>(g, coded_dev, (unsigned long long)coded_bytes, status);
+    k_check_header<<<1, 1, 0, stream>>>(g, kMagicPilc, 0u, coded_dev, (unsigned long long)coded_bytes, status);
     timer.mark("k_check_header");
     const bool few_lanes = use_wave_kernels(g);
     if (few_lanes) {
@@ -777,6 +785,118 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
                                                          &status->payload_bytes);
     }
     timer.mark(few_lanes ? (g_kernel_policy == 6 ? "k_decode_wave" : "k_decode_group") : "k_decode_lanes");
+    HIP_TRY(hipGetLastError());
+    Status host_status;
+    HIP_TRY(hipMemcpyAsync(&host_status, status, sizeof(Status), hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    timer.finish();
+    return status_to_error(host_status.code);
+}
+
+// --------------------------------------------------------------------------------------------
+// Mixture of K logistic laws per subpixel
+// --------------------------------------------------------------------------------------------
+static bool mix_params_ok(const pilc_mix_params *p)
+{
+    return p && p->mu && p->log_scale && p->weight && p->chan_coef && p->num_comp >= 1u &&
+           p->num_comp <= (uint32_t)kMixMaxComp && ((uintptr_t)p->mu & 1) == 0 &&
+           ((uintptr_t)p->log_scale & 1) == 0 && ((uintptr_t)p->weight & 1) == 0 &&
+           ((uintptr_t)p->chan_coef & 1) == 0;
+}
+
+static int mix_set_lds(const void *kernel, size_t bytes)
+{
+    HIP_TRY(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    return PILC_OK;
+}
+
+int pilc_mix_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_mix_params *params,
+                    void *workspace_dev, size_t workspace_bytes, uint8_t *coded_dev,
+                    size_t coded_capacity, uint64_t *coded_bytes_host, void *hip_stream)
+{
+    Geo g;
+    int rc = make_geo(geom, &g);
+    if (rc != PILC_OK) return rc;
+    if (!img_dev || !mix_params_ok(params) || !workspace_dev || !coded_dev || !coded_bytes_host)
+        return PILC_E_ARG;
+    if (((uintptr_t)workspace_dev & 255) || ((uintptr_t)coded_dev & 15)) return PILC_E_ARG;
+    const Workspace ws = layout(g);
+    if (workspace_bytes < ws.total) return PILC_E_WORKSPACE;
+    const size_t table_end = kHeaderBytes + 4 * ((size_t)g.lanes + 1);
+    if (coded_capacity < table_end) return PILC_E_CAPACITY;
+    if ((rc = ensure_tables()) != PILC_OK) return rc;
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+    uint8_t *base = static_cast<uint8_t *>(workspace_dev);
+    Status *status = reinterpret_cast<Status *>(base + ws.status_off);
+    uint32_t *lane_words = reinterpret_cast<uint32_t *>(base + ws.words_off);
+    uint32_t *lane_state = reinterpret_cast<uint32_t *>(base + ws.state_off);
+    unsigned long long *sums = reinterpret_cast<unsigned long long *>(base + ws.sums_off);
+    uint16_t *scratch = reinterpret_cast<uint16_t *>(base + ws.scratch_off);
+    uint32_t *offsets = reinterpret_cast<uint32_t *>(coded_dev + kHeaderBytes);
+    uint16_t *payload = reinterpret_cast<uint16_t *>(coded_dev + table_end);
+    const MixArgs args = {params->mu, params->log_scale, params->weight, params->chan_coef,
+                          params->num_comp};
+    const size_t lds = mix_lds_bytes(params->num_comp);
+    if ((rc = mix_set_lds(reinterpret_cast<const void *>(k_mix_encode), lds)) != PILC_OK) return rc;
+
+    Timer timer(stream);
+    k_init_status<<<1, 1, 0, stream>>>(status);
+    const uint32_t lane_cap = max_lane_symbols(g);
+    k_mix_encode<<<(uint32_t)ceil_div64(g.lanes, kMixThreads), kMixThreads, lds, stream>>>(
+        g, img_dev, args, scratch, lane_cap, lane_words, lane_state, &status->code);
+    timer.mark("k_mix_encode");
+    const ItemBytes lane_bytes = {4u, 2u, 0u, 0u};
+    const HeaderWords head = {{kMagicMix, PILC_VERSION, g.n, g.h, g.w, 3u, g.prec_bits, g.lane_mode,
+                               g.lane_a, g.lane_b, g.lanes, params->num_comp}};
+    k_scan_partials<<<ws.scan_blocks, kScanThreads, 0, stream>>>(g.lanes, lane_bytes, lane_words, sums);
+    k_scan_spine<<<1, kScanThreads, 0, stream>>>(head, g.lanes, ws.scan_blocks, sums, coded_dev,
+                                                 (unsigned long long)coded_capacity, status);
+    k_scan_apply<<<ws.scan_blocks, kScanThreads, 0, stream>>>(g.lanes, lane_bytes, lane_words, sums,
+                                                              offsets);
+    timer.mark("scan");
+    k_pack_by_thread<<<(uint32_t)ceil_div64(g.lanes, 64), 256, 0, stream>>>(
+        g.lanes, lane_cap, scratch, lane_state, offsets, payload, status);
+    timer.mark("k_pack_by_thread");
+    HIP_TRY(hipGetLastError());
+    Status host_status;
+    HIP_TRY(hipMemcpyAsync(&host_status, status, sizeof(Status), hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    timer.finish();
+    if (host_status.code != ST_OK) return status_to_error(host_status.code);
+    *coded_bytes_host = table_end + host_status.payload_bytes;
+    return PILC_OK;
+}
+
+int pilc_mix_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_bytes,
+                    const pilc_mix_params *params, void *workspace_dev, size_t workspace_bytes,
+                    uint8_t *img_out_dev, void *hip_stream)
+{
+    Geo g;
+    int rc = make_geo(geom, &g);
+    if (rc != PILC_OK) return rc;
+    if (!coded_dev || !mix_params_ok(params) || !workspace_dev || !img_out_dev) return PILC_E_ARG;
+    if (((uintptr_t)workspace_dev & 255) || ((uintptr_t)coded_dev & 15)) return PILC_E_ARG;
+    const Workspace ws = layout(g);
+    if (workspace_bytes < ws.total) return PILC_E_WORKSPACE;
+    const size_t table_end = kHeaderBytes + 4 * ((size_t)g.lanes + 1);
+    if (coded_bytes < table_end) return PILC_E_FORMAT;
+    if ((rc = ensure_tables()) != PILC_OK) return rc;
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+    Status *status = reinterpret_cast<Status *>(static_cast<uint8_t *>(workspace_dev) + ws.status_off);
+    const MixArgs args = {params->mu, params->log_scale, params->weight, params->chan_coef,
+                          params->num_comp};
+    const size_t lds = mix_lds_bytes(params->num_comp);
+    if ((rc = mix_set_lds(reinterpret_cast<const void *>(k_mix_decode), lds)) != PILC_OK) return rc;
+
+    Timer timer(stream);
+    k_check_header<<<1, 1, 0, stream>>>(g, kMagicMix, params->num_comp, coded_dev,
+                                        (unsigned long long)coded_bytes, status);
+    timer.mark("k_check_header");
+    k_mix_decode<<<(uint32_t)ceil_div64(g.lanes, kMixThreads), kMixThreads, lds, stream>>>(
+        g, coded_dev, args, img_out_dev, &status->code, &status->payload_bytes);
+    timer.mark("k_mix_decode");
     HIP_TRY(hipGetLastError());
     Status host_status;
     HIP_TRY(hipMemcpyAsync(&host_status, status, sizeof(Status), hipMemcpyDeviceToHost, stream));

@@ -120,3 +120,44 @@ class DevicePieces:
         nb = np.frombuffer(blob, dtype="<u4" if self.m > 12 else "<u2", count=entries, offset=nb_off)
         nb = nb.astype(np.uint32).reshape(self.d, -1)
         return enc[:, :, 0].astype(np.int32), enc[:, :, 1], theta, (15 - (nb & 15)).astype(np.uint8), nb >> 4
+
+
+class DeviceMix:
+    """A mixture workload (synth_mix.MixWorkload) on the device."""
+
+    def __init__(self, wl):
+        self.wl = wl
+        self.k = wl.num_comp
+        self.geom = pb.make_geom(*wl.geom)
+        dev = torch.device("cuda:0")
+        self.img = torch.from_numpy(wl.img).to(dev)
+        self.mu = torch.from_numpy(wl.mu).to(dev)
+        self.log_scale = torch.from_numpy(wl.log_scale).to(dev)
+        self.weight = torch.from_numpy(wl.weight).to(dev)
+        self.chan_coef = torch.from_numpy(wl.chan_coef).to(dev)
+        ws_bytes, self.max_coded = pb.pilc_workspace_size(self.geom)
+        self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self.coded = torch.zeros(self.max_coded + 16, dtype=torch.uint8, device=dev)
+        self.out = torch.zeros_like(self.img)
+        self.nbytes = 0
+
+    def encode(self, check=True, capacity=None, weight=None, k=None):
+        coded = self.coded if capacity is None else self.coded[:capacity]
+        rc, self.nbytes = pb.pilc_mix_encode(self.geom, self.k if k is None else k, self.img, self.mu,
+                                             self.log_scale, self.weight if weight is None else weight,
+                                             self.chan_coef, self.workspace, coded, check=check)
+        return rc, self.nbytes
+
+    def coded_numpy(self):
+        return self.coded[: self.nbytes].cpu().numpy()
+
+    def decode(self, coded=None, nbytes=None, check=True, weight=None, k=None):
+        coded = self.coded if coded is None else coded
+        nbytes = self.nbytes if nbytes is None else nbytes
+        self.out.fill_(0xA5)
+        return pb.pilc_mix_decode(self.geom, self.k if k is None else k, coded, nbytes, self.mu,
+                                  self.log_scale, self.weight if weight is None else weight,
+                                  self.chan_coef, self.workspace, self.out, check=check)
+
+    def decoded_numpy(self):
+        return self.out.cpu().numpy()
