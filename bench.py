@@ -39,6 +39,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 METRIC = "compress & decompress MB/s (raw uint8) on 1 MI355X; bits/subpixel"
 METRIC_ANSAI = "coder encode & decode MB/s (uint8 symbols) on 1 MI355X; bits/symbol"
 METRIC_TWAR = "residual transform forward & inverse MB/s (raw uint8) on 1 MI355X"
+METRIC_MIX = "compress & decompress MB/s (raw uint8) under a logistic mixture on 1 MI355X; bits/subpixel"
+MIX_IMAGES = {0: 64, 2: 2048, 3: 4}   # default number of images per base config
 TWAR_WEIGHTS = ([[-16384, 16384, 16384], [8192, -8192, 16384], [8192, -8192, 16384]], [0, 0, 0])
 
 
@@ -49,9 +51,14 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=1,
                     help="workload 0..4 of BASELINE.json (default 1: CIFAR-shaped, 50,000 images)")
-    ap.add_argument("--workload", choices=("pilc", "ansai", "twar"), default="pilc",
+    ap.add_argument("--components", type=int, default=10,
+                    help="mixture components K of --workload mix (default 10, the count Sec. 2 of the "
+                         "paper names)")
+    ap.add_argument("--workload", choices=("pilc", "ansai", "twar", "mix"), default="pilc",
                     help="pilc: the image path on --config; ansai: the table-driven coder on pieces; "
-                         "twar: the Three-Way AR residual transform on the images of --config")
+                         "twar: the Three-Way AR residual transform on the images of --config; "
+                         "mix: the coder under a mixture of --components logistic laws on the first "
+                         "2048 images of config 2 (or --config 0/3, --images)")
     ap.add_argument("--images", type=int, default=None,
                     help="first N images (pilc) or pieces (ansai) only (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -67,7 +74,7 @@ def parse_args():
 # ----------------------------------------------------------------------------------------------
 # HBM traffic from rocprofv3 counters (child processes, started before this process touches HIP)
 # ----------------------------------------------------------------------------------------------
-def _run_pmc(counter: str, config: int, images, workload: str = "pilc"):
+def _run_pmc(counter: str, config: int, images, workload: str = "pilc", components: int = 10):
     """Returns {kernel name prefix: [values in KiB per dispatch]} for one counter, or None."""
     exe = shutil.which("rocprofv3") or "/opt/rocm/bin/rocprofv3"
     if not os.path.exists(exe):
@@ -75,7 +82,7 @@ def _run_pmc(counter: str, config: int, images, workload: str = "pilc"):
     out_dir = tempfile.mkdtemp(prefix="pilc_pmc_", dir="/tmp")
     cmd = [exe, "--pmc", counter, "-d", out_dir, "-o", "pmc", "--output-format", "csv", "--",
            sys.executable, os.path.join(HERE, "bench.py"), "--pmc-child", "--config", str(config),
-           "--workload", workload]
+           "--workload", workload, "--components", str(components)]
     if images is not None:
         cmd += ["--images", str(images)]
     env = dict(os.environ, TMPDIR="/tmp")
@@ -106,12 +113,12 @@ def _run_pmc(counter: str, config: int, images, workload: str = "pilc"):
         shutil.rmtree(out_dir, ignore_errors=True)
 
 
-def measure_traffic(config: int, images, workload: str = "pilc"):
+def measure_traffic(config: int, images, workload: str = "pilc", components: int = 10):
     """HBM bytes per launch of every pilc kernel: counter value (KiB) x 1024 x scale, where
     scale = known bytes of a plain device copy / what the counter read for that copy."""
     result = {}
     for counter, key in (("FETCH_SIZE", "read"), ("WRITE_SIZE", "write")):
-        rows = _run_pmc(counter, config, images, workload)
+        rows = _run_pmc(counter, config, images, workload, components)
         if not rows:
             return None
         copies = rows.get("__amd_rocclr_copyBuffer", [])
@@ -416,6 +423,108 @@ class TwarRun:
     timed = Run.timed
 
 
+def cpu_baseline_mix(wl, sample_images):
+    from oracle import mix_oracle as mx
+    from oracle import pilc_oracle as orc
+
+    n, h, w, m, mode, la, lb = wl.geom
+    k = max(1, min(sample_images, n))
+    cores = max(1, min(16, os.cpu_count() or 1))
+    per = -(-k // cores)
+    slabs = [(a, min(a + per, k)) for a in range(0, k, per)]   # lanes never span images here
+
+    def prep(a, b):
+        sl = slice(a, b)
+        return (orc.make_geom(b - a, h, w, m, mode, la, lb), wl.img[sl].copy(), wl.mu[sl].copy(),
+                wl.log_scale[sl].copy(), wl.weight[sl].copy(), wl.chan_coef[sl].copy())
+
+    jobs = [prep(a, b) for a, b in slabs]
+    mx.lib()
+
+    def enc(job):
+        rc, coded = mx.encode(job[0], wl.num_comp, *job[1:])
+        assert rc == mx.OK
+        return coded
+
+    def dec(args):
+        job, coded = args
+        rc, img = mx.decode(job[0], wl.num_comp, coded, *job[2:])
+        assert rc == mx.OK and np.array_equal(img, job[1])
+
+    with ThreadPoolExecutor(max_workers=len(jobs)) as pool:
+        t0 = time.perf_counter()
+        coded = list(pool.map(enc, jobs))
+        t1 = time.perf_counter()
+        list(pool.map(dec, zip(jobs, coded)))
+        t2 = time.perf_counter()
+    raw_mb = k * h * w * 3 / 1e6
+    t3 = time.perf_counter()
+    c0 = enc(jobs[0])
+    t4 = time.perf_counter()
+    dec((jobs[0], c0))
+    t5 = time.perf_counter()
+    mb0 = jobs[0][1].size / 1e6
+    return {
+        "value": raw_mb / (t2 - t0), "unit": "MB/s", "cores": len(jobs), "kind": "oracle",
+        "sample": "first %d images of the workload (%.2f MB raw), encode+decode, %d slabs in a thread pool"
+                  % (k, raw_mb, len(jobs)),
+        "compress_MB_s": raw_mb / (t1 - t0), "decompress_MB_s": raw_mb / (t2 - t1),
+        "one_core": {"value": mb0 / (t5 - t3), "compress_MB_s": mb0 / (t4 - t3),
+                     "decompress_MB_s": mb0 / (t5 - t4), "sample_MB": mb0},
+    }
+
+
+class MixRun:
+    """pilc_mix_encode + pilc_mix_decode: the lanes of a base config under K logistic laws per subpixel."""
+
+    def __init__(self, config, images, components):
+        import torch
+        from paper_2206_05279_amd import binding as pb
+        from paper_2206_05279_amd import synth_mix
+
+        self.torch, self.pb = torch, pb
+        dev = torch.device("cuda:0")
+        config = config if config in MIX_IMAGES else 2
+        t = time.perf_counter()
+        self.wl = wl = synth_mix.make_mix_workload(config, images or MIX_IMAGES[config], components)
+        self.gen_s = time.perf_counter() - t
+        self.k = wl.num_comp
+        self.geom = pb.make_geom(*wl.geom)
+        self.img = torch.from_numpy(wl.img).to(dev)
+        self.mu = torch.from_numpy(wl.mu).to(dev)
+        self.ls = torch.from_numpy(wl.log_scale).to(dev)
+        self.weight = torch.from_numpy(wl.weight).to(dev)
+        self.coef = torch.from_numpy(wl.chan_coef).to(dev)
+        ws_bytes, max_coded = pb.pilc_workspace_size(self.geom)
+        self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self.coded = torch.empty(max_coded, dtype=torch.uint8, device=dev)
+        self.out = torch.empty_like(self.img)
+        self.name = "cfg%d %s: %d x %dx%dx3 uint8, K=%d, M=%d, %d lanes" % (
+            config, wl.name, wl.n, wl.h, wl.w, self.k, wl.prec_bits, pb.pilc_lane_count(self.geom))
+        self.raw = wl.subpixels
+        self.probe_src = self.img
+        self.probe_bytes = 2.0 * wl.subpixels
+        self.step = "pilc_mix_encode + pilc_mix_decode of the whole batch"
+
+    def algo_bytes(self, nbytes):
+        # either lane kernel: per subpixel 1 B pixel, 2 K B means, 2 K B log-scales and a third of the
+        # pixel's 2 K B of weights, plus the container
+        return (1.0 + 4.0 * self.k + 2.0 * self.k / 3.0) * self.raw + nbytes
+
+    def reference(self):
+        return self.img
+
+    def encode(self):
+        return self.pb.pilc_mix_encode(self.geom, self.k, self.img, self.mu, self.ls, self.weight, self.coef,
+                                       self.workspace, self.coded)[1]
+
+    def decode(self, nbytes):
+        self.pb.pilc_mix_decode(self.geom, self.k, self.coded, nbytes, self.mu, self.ls, self.weight,
+                                self.coef, self.workspace, self.out)
+
+    timed = Run.timed
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -426,7 +535,7 @@ def main():
     # children first: this process has not initialised HIP yet
     traffic = None
     if not (args.no_traffic or args.pmc_child):
-        traffic = measure_traffic(args.config, args.images, args.workload)
+        traffic = measure_traffic(args.config, args.images, args.workload, args.components)
 
     import torch
     from paper_2206_05279_amd import binding as pb
@@ -436,8 +545,10 @@ def main():
         sys.exit(3)
     pb.lib()
 
-    ansai, twar = args.workload == "ansai", args.workload == "twar"
-    if ansai:
+    ansai, twar, mix = args.workload == "ansai", args.workload == "twar", args.workload == "mix"
+    if mix:
+        run = MixRun(args.config, args.images, args.components)
+    elif ansai:
         run = PieceRun(1 if args.config not in (0, 1) else args.config, args.images)
     elif twar:
         run = TwarRun(args.config, args.images)
@@ -469,7 +580,7 @@ def main():
             traffic_bytes = detail["read_bytes"] + detail["write_bytes"]
             traffic_detail = detail
     result = {
-        "metric": METRIC_ANSAI if ansai else (METRIC_TWAR if twar else METRIC),
+        "metric": METRIC_ANSAI if ansai else (METRIC_TWAR if twar else (METRIC_MIX if mix else METRIC)),
         "value": raw_bytes / 1e6 / (r["elapsed"] / args.steps),
         "unit": "MB/s",
         "n_gpus": 1,
@@ -499,14 +610,16 @@ def main():
     }
     ok = r["ok"]
     if not args.no_cpu_baseline:
-        if ansai:
+        if mix:
+            result["cpu_baseline"] = cpu_baseline_mix(run.wl, args.cpu_sample_images or 1024)
+        elif ansai:
             result["cpu_baseline"] = cpu_baseline_pieces(run.wl, args.cpu_sample_images or 131072)
         elif twar:
             result["cpu_baseline"] = cpu_baseline_twar(run.img_np, args.cpu_sample_images or 20000)
         else:
             sample = args.cpu_sample_images or {0: 64, 1: 21504, 2: 5376, 3: 10, 4: 336}[args.config]
             result["cpu_baseline"] = cpu_baseline(run.wl, sample)
-    if not args.no_extra and args.images is None and not ansai and not twar:
+    if not args.no_extra and args.images is None and not ansai and not twar and not mix:
         extra = {}
         del run
         torch.cuda.empty_cache()
@@ -546,6 +659,19 @@ def main():
             "forward_MB_s": o["compress_MB_s"], "inverse_MB_s": o["decompress_MB_s"],
             "round_trip_exact": o["ok"], "kernel_ms": o["kernel_ms"],
             "dominant_kernel_hbm_frac": other.algo_bytes(0) / (o["kernel_ms"][dk] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        }
+        ok = ok and o["ok"]
+        del other
+        torch.cuda.empty_cache()
+        other = MixRun(2, None, 10)   # the dynamic-coder workload Sec. 2 names as the slow case
+        o = other.timed(2, 1)
+        dk = max(o["kernel_ms"], key=o["kernel_ms"].get)
+        extra["mixture of 10 logistic laws (Sec. 2): " + other.name] = {
+            "compress_MB_s": o["compress_MB_s"], "decompress_MB_s": o["decompress_MB_s"],
+            "bits_per_subpixel": 8.0 * o["nbytes"] / o["raw"], "round_trip_exact": o["ok"],
+            "kernel_ms": o["kernel_ms"],
+            "dominant_kernel_hbm_frac": other.algo_bytes(o["nbytes"]) / (o["kernel_ms"][dk] * 1e-3) / 1e9
+                                        / HBM_PEAK_GBS,
         }
         ok = ok and o["ok"]
         del other

@@ -53,26 +53,59 @@ def quantise_weights(p: np.ndarray) -> np.ndarray:
     q = np.floor(p * 32768.0).astype(np.int64)
     rest = 32768 - q.sum(axis=-1)
     top = np.argmax(q, axis=-1)
-    np.add.at(q, (*np.indices(top.shape), top), rest)
+    flat = q.reshape(-1, q.shape[-1])
+    flat[np.arange(flat.shape[0]), top.reshape(-1)] += rest.reshape(-1)
     assert q.min() >= 0 and q.max() <= 32768 and np.all(q.sum(axis=-1) == 32768)
     return q.astype(np.uint16)
 
 
-def mixture_params(rng: np.random.Generator, base: synth.Workload, num_comp: int):
+def _params_block(rng: np.random.Generator, img, base_mu, base_ls, k: int, mu, ls, weight) -> None:
+    shape = img.shape
+    mu[..., 0] = base_mu
+    ls[..., 0] = base_ls
+    if k > 1:
+        # float32 draws: the values only have to be seeded and plausible
+        m = rng.standard_normal(size=shape + (k - 1,), dtype=np.float32)
+        m *= np.float32(24.0)
+        m += img.astype(np.float32)[..., None]
+        np.clip(m, 0.0, 255.996, out=m)
+        m *= np.float32(256.0)
+        mu[..., 1:] = np.rint(m).astype(np.uint16)
+        u = rng.random(size=shape + (k - 1,), dtype=np.float32)
+        u *= np.float32(3.0 * 4096.0)
+        ls[..., 1:] = np.rint(u).astype(np.int16)
+    g = rng.standard_exponential(size=shape[:3] + (k,), dtype=np.float32).astype(np.float64)
+    g[..., 0] += 1.0
+    weight[...] = quantise_weights(g / g.sum(axis=-1, keepdims=True))
+
+
+_BLOCK = 64  # images per independently seeded block
+
+
+def mixture_params(seed_seq: np.random.SeedSequence, base: synth.Workload, num_comp: int,
+                   threads: int = 8):
+    """Blocks of 64 images, each from its own child seed, drawn in a thread pool: the result does
+    not depend on the number of threads."""
     k = int(num_comp)
     shape = base.img.shape
     mu = np.empty(shape + (k,), dtype=np.uint16)
     ls = np.empty(shape + (k,), dtype=np.int16)
-    mu[..., 0] = base.mu
-    ls[..., 0] = base.log_scale
-    if k > 1:
-        x = base.img.astype(np.float64)[..., None]
-        m = np.clip(x + rng.normal(0.0, 24.0, size=shape + (k - 1,)), 0.0, 255.996)
-        mu[..., 1:] = np.round(m * 256.0).astype(np.uint16)
-        ls[..., 1:] = np.round(rng.uniform(0.0, 3.0, size=shape + (k - 1,)) * 4096.0).astype(np.int16)
-    g = rng.gamma(1.0, 1.0, size=shape[:3] + (k,))
-    g[..., 0] += 1.0
-    weight = quantise_weights(g / g.sum(axis=-1, keepdims=True))
+    weight = np.empty(shape[:3] + (k,), dtype=np.uint16)
+    starts = list(range(0, shape[0], _BLOCK))
+    children = seed_seq.spawn(len(starts))
+
+    def work(i):
+        sl = slice(starts[i], min(starts[i] + _BLOCK, shape[0]))
+        rng = np.random.Generator(np.random.PCG64(children[i]))
+        _params_block(rng, base.img[sl], base.mu[sl], base.log_scale[sl], k, mu[sl], ls[sl], weight[sl])
+
+    if threads > 1 and len(starts) > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=threads) as pool:
+            list(pool.map(work, range(len(starts))))
+    else:
+        for i in range(len(starts)):
+            work(i)
     return mu, ls, weight
 
 
@@ -82,9 +115,8 @@ def make_mix_workload(cfg: int, n: int, num_comp: int, *, seed: Optional[int] = 
     """Base workload `cfg` of `synth.make_workload` (first n images) with K-component parameters."""
     base = synth.make_workload(cfg, n, seed=seed, h=h, w=w, prec_bits=prec_bits,
                                lanes_per_image=lanes_per_image)
-    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence(
-        [20220605 if seed is None else seed, 77, cfg, n, num_comp])))
-    mu, ls, weight = mixture_params(rng, base, num_comp)
+    mu, ls, weight = mixture_params(
+        np.random.SeedSequence([20220605 if seed is None else seed, 77, cfg, num_comp]), base, num_comp)
     return MixWorkload(base.name + "-mix%d" % num_comp, base.n, base.h, base.w, base.prec_bits,
                        base.lane_mode, base.lane_a, base.lane_b, int(num_comp), base.img, mu, ls,
                        weight, base.chan_coef)
@@ -92,8 +124,7 @@ def make_mix_workload(cfg: int, n: int, num_comp: int, *, seed: Optional[int] = 
 
 def from_base(base: synth.Workload, num_comp: int, seed: int) -> MixWorkload:
     """Mixture parameters around any base workload (edge-case shapes of the tests)."""
-    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 78, num_comp])))
-    mu, ls, weight = mixture_params(rng, base, num_comp)
+    mu, ls, weight = mixture_params(np.random.SeedSequence([seed, 78, num_comp]), base, num_comp)
     return MixWorkload(base.name + "-mix%d" % num_comp, base.n, base.h, base.w, base.prec_bits,
                        base.lane_mode, base.lane_a, base.lane_b, int(num_comp), base.img, mu, ls,
                        weight, base.chan_coef)
