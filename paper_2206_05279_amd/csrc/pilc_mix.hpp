@@ -90,6 +90,58 @@ __device__ __forceinline__ bool mix_load_pixel(const MixArgs &a, uint32_t p, con
     return sum == (1u << 15);
 }
 
+// Even K with dword-aligned arrays: a pixel's raw parameters are 3 K / 2 + 3 K / 2 + K / 2 whole
+// dwords, and the kernels keep the NEXT pixel's dwords in registers while they work on the
+// current one, so that the loads have a pixel's worth of arithmetic to arrive in.
+constexpr int kMixPreMu = 3 * kMixMaxComp / 2, kMixPreW = kMixMaxComp / 2;
+struct MixAhead {
+    uint32_t m[kMixPreMu], l[kMixPreMu], w[kMixPreW];
+};
+
+__device__ __forceinline__ bool mix_can_run_ahead(const MixArgs &a)
+{
+    return (a.k & 1u) == 0u && ((reinterpret_cast<uintptr_t>(a.mu) | reinterpret_cast<uintptr_t>(a.ls) |
+                                 reinterpret_cast<uintptr_t>(a.weight)) & 3u) == 0u;
+}
+
+__device__ __forceinline__ void mix_fetch_ahead(const MixArgs &a, uint32_t p, MixAhead &r)
+{
+    const size_t px = (size_t)p * 3u * a.k;
+    const uint32_t *gm = reinterpret_cast<const uint32_t *>(a.mu + px);
+    const uint32_t *gl = reinterpret_cast<const uint32_t *>(a.ls + px);
+    const uint32_t *gw = reinterpret_cast<const uint32_t *>(a.weight + (size_t)p * a.k);
+    const uint32_t n3 = 3u * a.k / 2u, n1 = a.k / 2u;
+#pragma unroll
+    for (int i = 0; i < kMixPreMu; ++i)
+        if ((uint32_t)i < n3) r.m[i] = gm[i];
+#pragma unroll
+    for (int i = 0; i < kMixPreMu; ++i)
+        if ((uint32_t)i < n3) r.l[i] = gl[i];
+#pragma unroll
+    for (int i = 0; i < kMixPreW; ++i)
+        if ((uint32_t)i < n1) r.w[i] = gw[i];
+}
+
+// The fetched pixel into the slots; false if its weights do not sum to 2^15.
+__device__ __forceinline__ bool mix_store_ahead(const MixAhead &r, const MixSlots &s)
+{
+    const uint32_t n3 = 3u * s.k / 2u, n1 = s.k / 2u;
+    uint32_t sum = 0;
+#pragma unroll
+    for (int i = 0; i < kMixPreMu; ++i)
+        if ((uint32_t)i < n3) s.dword(s.raw_mu + i) = r.m[i];
+#pragma unroll
+    for (int i = 0; i < kMixPreMu; ++i)
+        if ((uint32_t)i < n3) s.dword(s.raw_ls + i) = r.l[i];
+#pragma unroll
+    for (int i = 0; i < kMixPreW; ++i)
+        if ((uint32_t)i < n1) {
+            s.dword(s.raw_w + i) = r.w[i];
+            sum += (r.w[i] & 0xFFFFu) + (r.w[i] >> 16);
+        }
+    return sum == (1u << 15);
+}
+
 // {shifted mean, 1/scale} of every component of channel `ch` of the loaded pixel into the pair
 // slots; x_r and x_g are the pixel's red and green values (used for ch >= 1 and ch == 2).
 __device__ __forceinline__ void mix_load_channel(const MixSlots &s, int ch, int x_r, int x_g, int a_gr,
@@ -149,12 +201,40 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_encode(
     uint32_t nwords = 0, S = 1u << 16;
     bool ok = true;
     // pixels last-first, and B, G, R inside a pixel (App. A eq. (11) runs against the decoder)
+    const bool ahead = mix_can_run_ahead(a);
+    MixAhead pre;
+    uint32_t pre_x = 0, im_now = 0xFFFFFFFFu;
+    int a_gr = 0, a_br = 0, a_bg = 0;
+    auto fetch_pixel_bytes = [&](uint32_t q) -> uint32_t {
+        const uint8_t *b = img + 3 * (size_t)q;
+        return (uint32_t)b[0] | ((uint32_t)b[1] << 8) | ((uint32_t)b[2] << 16);
+    };
+    if (ahead && sh.npx != 0u) {
+        const uint32_t q = lane_pixel(g, sh, sh.npx - 1u);
+        mix_fetch_ahead(a, q, pre);
+        pre_x = fetch_pixel_bytes(q);
+    }
     for (uint32_t t = sh.npx; t-- > 0u;) {
         const uint32_t p = lane_pixel(g, sh, t);
         const uint32_t im = p / g.hw;
-        const int a_gr = a.coef[3 * im], a_br = a.coef[3 * im + 1], a_bg = a.coef[3 * im + 2];
-        const int x[3] = {img[3 * (size_t)p], img[3 * (size_t)p + 1], img[3 * (size_t)p + 2]};
-        ok = mix_load_pixel(a, p, slots) && ok;
+        if (im != im_now) {
+            im_now = im;
+            a_gr = a.coef[3 * im]; a_br = a.coef[3 * im + 1]; a_bg = a.coef[3 * im + 2];
+        }
+        uint32_t xb;
+        if (ahead) {
+            ok = mix_store_ahead(pre, slots) && ok;
+            xb = pre_x;
+            if (t != 0u) {
+                const uint32_t q = lane_pixel(g, sh, t - 1u);
+                mix_fetch_ahead(a, q, pre);
+                pre_x = fetch_pixel_bytes(q);
+            }
+        } else {
+            ok = mix_load_pixel(a, p, slots) && ok;
+            xb = fetch_pixel_bytes(p);
+        }
+        const int x[3] = {(int)(xb & 0xFFu), (int)((xb >> 8) & 0xFFu), (int)(xb >> 16)};
 #pragma unroll 1
         for (int ch = 2; ch >= 0; --ch) {
             mix_load_channel(slots, ch, x[0], x[1], a_gr, a_br, a_bg, tab);
@@ -248,6 +328,11 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_decode(
     ByteRun run;
     run.begin(0);
     uint32_t p_next = 0xFFFFFFFFu;  // the pixel that would continue the current run of bytes
+    const bool ahead = mix_can_run_ahead(a);
+    MixAhead pre;
+    uint32_t im_now = 0xFFFFFFFFu;
+    int a_gr = 0, a_br = 0, a_bg = 0;
+    if (ahead && sh.npx != 0u) mix_fetch_ahead(a, lane_pixel(g, sh, 0u), pre);
     for (uint32_t t = 0; t < sh.npx; ++t) {
         const uint32_t p = lane_pixel(g, sh, t);
         if (p != p_next) {  // a new row of the lane
@@ -256,8 +341,16 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_decode(
         }
         p_next = p + 1u;
         const uint32_t im = p / g.hw;
-        const int a_gr = a.coef[3 * im], a_br = a.coef[3 * im + 1], a_bg = a.coef[3 * im + 2];
-        ok = mix_load_pixel(a, p, slots) && ok;
+        if (im != im_now) {
+            im_now = im;
+            a_gr = a.coef[3 * im]; a_br = a.coef[3 * im + 1]; a_bg = a.coef[3 * im + 2];
+        }
+        if (ahead) {
+            ok = mix_store_ahead(pre, slots) && ok;
+            if (t + 1u < sh.npx) mix_fetch_ahead(a, lane_pixel(g, sh, t + 1u), pre);
+        } else {
+            ok = mix_load_pixel(a, p, slots) && ok;
+        }
         int x_r = 0, x_g = 0, x_b = 0;
 #pragma unroll 1
         for (int ch = 0; ch < 3; ++ch) {

@@ -136,3 +136,43 @@ def test_twar_full_size_parity():
     assert np.array_equal(res.cpu().numpy(), ref)
     pb.pilc_twar_inverse(p, res, back)
     assert torch.equal(back, img)
+
+
+def test_mixture_full_size_sampled_parity():
+    """The mixture workload bench.py times (2048 images of cfg 2, K = 10, one lane per row):
+    sampled images are encoded by the mixture oracle on their own and their 64 lanes compared byte
+    for byte with the GPU container; offsets are the scan of lane sizes; the GPU decode returns
+    the images."""
+    from oracle import mix_oracle as mx
+    from paper_2206_05279_amd import synth_mix
+    from gpu_util import DeviceMix
+
+    print("generating mixture workload", flush=True)
+    wl = synth_mix.make_mix_workload(2, 2048, 10)
+    d = DeviceMix(wl)
+    print("encoding", wl.geom, flush=True)
+    _, nbytes = d.encode()
+    coded = d.coded_numpy()
+    assert coded[:4].tobytes() == b"PMIX" and int(np.frombuffer(coded.tobytes(), "<u4", 1, 44)[0]) == 10
+    lanes = pb.pilc_lane_count(d.geom)
+    offs = np.frombuffer(coded.tobytes(), dtype="<u4", count=lanes + 1, offset=64)
+    body = coded[64 + 4 * (lanes + 1):]
+    sizes = np.diff(offs.astype(np.int64))
+    assert offs[0] == 0 and offs[-1] == body.size and sizes.min() >= 4 and not np.any(sizes & 1)
+    n, h, w, m, mode, la, lb = wl.geom
+    per = h * w // la
+    rng = np.random.default_rng(98)
+    for i in sorted(set([0, n - 1] + [int(v) for v in rng.integers(0, n, size=6)])):
+        sl = slice(i, i + 1)
+        g = orc.make_geom(1, h, w, m, mode, la, lb)
+        rc, one = mx.encode(g, 10, wl.img[sl], wl.mu[sl], wl.log_scale[sl], wl.weight[sl], wl.chan_coef[sl])
+        assert rc == mx.OK
+        want = one[64 + 4 * (per + 1):]
+        got = body[offs[i * per]:offs[(i + 1) * per]]
+        assert np.array_equal(got, want), "image %d differs" % i
+        o1 = np.frombuffer(one.tobytes(), dtype="<u4", count=per + 1, offset=64)
+        assert np.array_equal(np.diff(o1.astype(np.int64)), sizes[i * per:(i + 1) * per])
+    print("decoding", flush=True)
+    assert d.decode() == pb.PILC_OK
+    assert torch.equal(d.out, d.img)
+    print("bits/subpixel %.4f" % (8.0 * nbytes / wl.subpixels), flush=True)
