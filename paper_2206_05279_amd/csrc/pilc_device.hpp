@@ -94,14 +94,15 @@ __device__ __forceinline__ uint32_t inv_scale(int ls, const LdsTables &t)
 // F(k) in 24 bits at the edge k - 1/2:  d = 256*k - 128 - mu'  (Q8.8), inv_s Q6.25 < 2^31.
 // z = clamp(floor(d * inv_s / 2^17), -2^20, 2^20 - 1) and w = z + 2^20 is bits 17..48 of the
 // 64-bit value d * inv_s + 2^37; z saturates exactly when the high word of that sum leaves 0..63.
+// Clamping the high word to -1..64 first keeps the saturated cases on their side of 0..2^21 - 1
+// after the shift (all ones above bit 14, or bit 21 set), so one more clamp finishes the job.
 __device__ __forceinline__ uint32_t edge_cdf(int d, uint32_t inv_s, const LdsTables &t)
 {
     long long p = (long long)d * (long long)(int)inv_s + (1ll << 37);  // Q.33
-    asm("" : "+v"(p));  // keep the range tests below on the high word alone
-    const int hi = (int)(p >> 32);
-    uint32_t w = __builtin_amdgcn_alignbit((uint32_t)hi, (uint32_t)p, 17);
-    const uint32_t sat = hi < 0 ? 0u : (1u << 21) - 1u;
-    w = (uint32_t)hi < 64u ? w : sat;
+    asm("" : "+v"(p));  // keep the clamps below on 32-bit words
+    const int hi = min(max((int)(p >> 32), -1), 64);
+    const int v = (int)__builtin_amdgcn_alignbit((uint32_t)hi, (uint32_t)p, 17);
+    const uint32_t w = (uint32_t)min(max(v, 0), (1 << 21) - 1);
     const uint2 cell = t.sig[w >> 10];
     return cell.x + (__umul24(cell.y, w & 1023u) >> 10);
 }

@@ -257,6 +257,66 @@ struct WordStream {
     __device__ __forceinline__ uint32_t taken(uint32_t first) const { return count - (first & 15u); }
 };
 
+// The same stream for a decoder that works in chunks of at most kRingChunk symbols: the words wait
+// in a ring of 32 per thread in LDS ([16-byte piece][thread]), which is filled to the brim with
+// aligned 16-byte loads before every chunk, together with the chunk's parameter loads, so that
+// no refill inside the chunk ever touches memory or branches on the fill level: a symbol takes at
+// most one word and a full ring holds at least 25.  The word after the current one is read from
+// the ring ahead of time.
+constexpr int kRingChunk = 24;
+constexpr int kRingMaxThreads = 256;  // the lane kernels run in workgroups of 64 or 256
+static_assert(3 * kChunk <= kRingChunk, "a chunk must not take more words than a full ring guarantees");
+
+struct WordRing {
+    uint4 *slot;        // this thread's column of the ring: piece q is slot[q * stride]
+    uint32_t stride;
+    uint32_t pos;       // word offset (from the 16-byte aligned `base`) of the next word
+    uint32_t filled;    // word offset up to which the ring holds the stream: a multiple of 8
+    uint32_t nextw;     // the word at `pos`
+
+    __device__ __forceinline__ static uint4 fetch(const uint16_t *base, uint32_t off, uint32_t lim)
+    {
+        return off < lim ? *reinterpret_cast<const uint4 *>(base + off) : make_uint4(0u, 0u, 0u, 0u);
+    }
+    __device__ __forceinline__ uint32_t peek() const
+    {
+        // read as the dwords the pieces are made of, so that the access is of the stored type
+        const uint32_t *d = reinterpret_cast<const uint32_t *>(&slot[((pos >> 3) & 3u) * stride]);
+        return (d[(pos & 7u) >> 1] >> (16u * (pos & 1u))) & 0xFFFFu;
+    }
+    // Brings `filled` to (pos rounded down to 8) + 32: at most 3 pieces before a chunk, 4 at the start.
+    __device__ __forceinline__ void fill(const uint16_t *base, uint32_t lim)
+    {
+        const uint32_t want = (pos & ~7u) + 32u;
+        const uint32_t n = (want - filled) >> 3;
+        uint4 piece[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if ((uint32_t)i < n) piece[i] = fetch(base, filled + 8u * i, lim);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if ((uint32_t)i < n) slot[(((filled >> 3) + i) & 3u) * stride] = piece[i];
+        filled = want;
+        nextw = peek();
+    }
+    // the lane's first word is at word offset `first` < lim
+    __device__ __forceinline__ void open(uint4 *ring, const uint16_t *base, uint32_t first, uint32_t lim)
+    {
+        slot = ring + threadIdx.x;
+        stride = blockDim.x;
+        pos = first;
+        filled = first & ~7u;
+        fill(base, lim);
+    }
+    __device__ __forceinline__ uint32_t take()
+    {
+        const uint32_t wd = nextw;
+        ++pos;
+        nextw = peek();  // at most kRingChunk takes between fills: pos stays below `filled`
+        return wd;
+    }
+};
+
 template <bool kVec>
 __global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
                                const uint16_t *__restrict__ mu, const int16_t *__restrict__ ls,
@@ -265,6 +325,7 @@ __global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
                                const unsigned long long *__restrict__ status_payload)
 {
     __shared__ LdsTables tab;
+    __shared__ uint4 ring[4 * kRingMaxThreads];  // [piece][thread]
     load_tables(tab);
     if (*status_code != 0) return;  // uniform: written by an earlier kernel
     const uint32_t lane = blockIdx.x * blockDim.x + threadIdx.x;
@@ -284,20 +345,21 @@ __global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
         atomicMax(status_code, 6);
         return;
     }
-    // word offsets from the last 32-byte boundary at or below the payload (the payload is < 4 GiB)
-    const uint32_t adj = (uint32_t)(reinterpret_cast<uintptr_t>(payload) & 31u);
+    // word offsets from the last 16-byte boundary at or below the payload (the payload is < 4 GiB)
+    const uint32_t adj = (uint32_t)(reinterpret_cast<uintptr_t>(payload) & 15u);
     const uint16_t *base = reinterpret_cast<const uint16_t *>(reinterpret_cast<const uint8_t *>(payload) - adj);
     const uint32_t first = (adj + begin) >> 1;
     const uint32_t lim = (uint32_t)(((unsigned long long)adj + payload_bytes + 1ull) >> 1);
-    WordStream words;
-    words.open(base, first, lim);
-    uint32_t S = words.take(base, lim);
-    S |= words.take(base, lim) << 16;
+    WordRing words;
+    words.open(ring, base, first, lim);
+    uint32_t S = words.take();
+    S |= words.take() << 16;
 
     for (uint32_t c = 0; c < chunks; ++c) {
         const ChunkPos cp = chunk_pos(g, sh, per_row, c);
         Chunk ck;
         load_chunk<kVec, false>(ck, cp.p, cp.len, nullptr, mu, ls);
+        words.fill(base, lim);  // its loads travel with the chunk's
         uint32_t im = cp.p / g.hw;
         int a_gr = coef[3 * im], a_br = coef[3 * im + 1], a_bg = coef[3 * im + 2];
         uint32_t wout[6] = {0, 0, 0, 0, 0, 0};  // the chunk's 24 decoded bytes
@@ -335,7 +397,7 @@ __global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
                     x[ch] = lo;
                     // App. A eq. (12)
                     S = (c_hi - c_lo) * (S >> m_bits) + slot - c_lo;
-                    if (S < (1u << 16)) S = (S << 16) | words.take(base, lim);
+                    if (S < (1u << 16)) S = (S << 16) | words.take();
                     const int b = 3 * i + ch;
                     wout[b >> 2] |= (uint32_t)lo << (8 * (b & 3));
                 }
@@ -353,7 +415,7 @@ __global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
                 if ((uint32_t)b < 3u * cp.len) out[s + b] = (uint8_t)(wout[b >> 2] >> (8 * (b & 3)));
         }
     }
-    if (S != (1u << 16) || words.taken(first) != (end - begin) >> 1) atomicMax(status_code, 6);
+    if (S != (1u << 16) || words.pos - first != (end - begin) >> 1) atomicMax(status_code, 6);
 }
 
 }  // namespace pilc
