@@ -556,7 +556,9 @@ static bool chunks_aligned(const Geo &g, const void *img, const pilc_params *p)
            ((uintptr_t)p->log_scale & 15) == 0;
 }
 
-static int lane_block_threads(const Geo &g) { return g.lanes >= (1u << 16) ? 256 : 64; }
+// Workgroup size of the thread-per-lane kernels (at most kRingMaxThreads: the decoder's word ring
+// in LDS is sized for that).
+static int lane_block_threads(const Geo &g) { return g.lanes >= (1u << 16) ? kRingMaxThreads : 64; }
 
 }  // namespace pilc
 

@@ -1,11 +1,14 @@
 // One thread per lane: the kernels for batches with many lanes (gfx950).
 //
 // Every thread walks its own lane (App. A eqs. (11)-(12) of arXiv 2206.05279 are serial per
-// lane), so neighbouring threads read memory a whole lane apart.  To keep the L2->L1 traffic
-// near the useful bytes, a lane is consumed in chunks of 8 pixels held in registers: when the
-// geometry keeps every chunk 8-pixel aligned (kVec) the 24 + 48 + 48 bytes of a chunk arrive as
-// 64- and 128-bit loads, and decoded pixels leave as 64-bit stores; otherwise, and for ragged
-// chunk tails, the same registers are filled element by element.
+// lane), so neighbouring threads read memory a whole lane apart.  A lane is consumed in chunks of
+// 8 pixels held in registers: when the geometry keeps every chunk 8-pixel aligned (kVec) the
+// 24 + 48 + 48 bytes of a chunk arrive as 64- and 128-bit loads, and decoded pixels leave as
+// 64-bit stores; otherwise, and for ragged chunk tails, the same registers are filled element by
+// element.  The coded words, which a thread produces or consumes one at a time, never go to
+// memory one at a time: the encoder writes them to a scratch laid out [word number][thread], so
+// that the 64 lanes of a wavefront fill whole lines, and the decoder reads them through a ring
+// of 32 words per thread in LDS that is refilled with 16-byte loads between chunks.
 #pragma once
 
 #include "pilc_device.hpp"
