@@ -558,6 +558,15 @@ static bool chunks_aligned(const Geo &g, const void *img, const pilc_params *p)
 
 // Workgroup size of the thread-per-lane kernels (at most kRingMaxThreads: the decoder's word ring
 // in LDS is sized for that).
+// On top of chunks_aligned: every row of every lane is a whole number of 16-pixel chunk pairs
+// that start at multiples of 16 pixels, and the pixels allow 16-byte loads.
+static bool chunks_pair_up(const Geo &g, const void *img)
+{
+    const bool geo = g.lane_mode == 0 ? (g.lane_a % 16 == 0 && g.hw % 16 == 0)
+                                      : (g.w % 16 == 0 && g.lane_b % 16 == 0);
+    return geo && ((uintptr_t)img & 15) == 0;
+}
+
 static int lane_block_threads(const Geo &g) { return g.lanes >= (1u << 16) ? kRingMaxThreads : 64; }
 
 }  // namespace pilc
@@ -687,14 +696,18 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
     } else {
         const int bt = lane_block_threads(g);
         const uint32_t nb = (uint32_t)ceil_div64(g.lanes, bt);
-        if (chunks_aligned(g, img_dev, params))
-            k_encode_lanes<true><<<nb, bt, 0, stream>>>(g, img_dev, params->mu, params->log_scale,
-                                                        params->chan_coef, scratch, lane_cap, lane_words,
-                                                        lane_state);
+        if (chunks_aligned(g, img_dev, params) && chunks_pair_up(g, img_dev))
+            k_encode_lanes<true, true><<<nb, bt, 0, stream>>>(g, img_dev, params->mu, params->log_scale,
+                                                              params->chan_coef, scratch, lane_cap,
+                                                              lane_words, lane_state);
+        else if (chunks_aligned(g, img_dev, params))
+            k_encode_lanes<true, false><<<nb, bt, 0, stream>>>(g, img_dev, params->mu, params->log_scale,
+                                                               params->chan_coef, scratch, lane_cap,
+                                                               lane_words, lane_state);
         else
-            k_encode_lanes<false><<<nb, bt, 0, stream>>>(g, img_dev, params->mu, params->log_scale,
-                                                         params->chan_coef, scratch, lane_cap, lane_words,
-                                                         lane_state);
+            k_encode_lanes<false, false><<<nb, bt, 0, stream>>>(g, img_dev, params->mu, params->log_scale,
+                                                                params->chan_coef, scratch, lane_cap,
+                                                                lane_words, lane_state);
     }
     timer.mark(few_lanes ? "k_encode_block" : "k_encode_lanes");
     const ItemBytes lane_bytes = {4u, 2u, 0u, 0u};  // a 32-bit state and 16-bit words
@@ -777,14 +790,19 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
     } else {
         const int bt = lane_block_threads(g);
         const uint32_t nb = (uint32_t)ceil_div64(g.lanes, bt);
-        if (chunks_aligned(g, img_out_dev, params))
-            k_decode_lanes<true><<<nb, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
-                                                        params->chan_coef, img_out_dev, &status->code,
-                                                        &status->payload_bytes);
+        if (chunks_aligned(g, img_out_dev, params) && chunks_pair_up(g, img_out_dev))
+            k_decode_lanes<true, true><<<nb, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
+                                                              params->chan_coef, img_out_dev,
+                                                              &status->code, &status->payload_bytes);
+        else if (chunks_aligned(g, img_out_dev, params))
+            k_decode_lanes<true, false><<<nb, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
+                                                               params->chan_coef, img_out_dev,
+                                                               &status->code, &status->payload_bytes);
         else
-            k_decode_lanes<false><<<nb, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
-                                                         params->chan_coef, img_out_dev, &status->code,
-                                                         &status->payload_bytes);
+            k_decode_lanes<false, false><<<nb, bt, 0, stream>>>(g, coded_dev, params->mu,
+                                                                params->log_scale, params->chan_coef,
+                                                                img_out_dev, &status->code,
+                                                                &status->payload_bytes);
     }
     timer.mark(few_lanes ? (g_kernel_policy == 6 ? "k_decode_wave" : "k_decode_group") : "k_decode_lanes");
     HIP_TRY(hipGetLastError());

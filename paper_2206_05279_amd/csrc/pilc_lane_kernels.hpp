@@ -11,11 +11,14 @@
 // of 32 words per thread in LDS that is refilled with 16-byte loads between chunks.
 #pragma once
 
+#include <type_traits>
+
 #include "pilc_device.hpp"
 
 namespace pilc {
 
 constexpr int kChunk = 8;  // pixels per chunk
+constexpr int kLaneMaxThreads = 256;  // the lane kernels run in workgroups of 64 or 256
 
 struct Chunk {
     int x[kChunk][3];   // pixel values (encode)
@@ -76,6 +79,51 @@ __device__ __forceinline__ void load_chunk(Chunk &c, uint32_t p, uint32_t len,
     }
 }
 
+// The 8 pixels held in the words wx (6 dwords of pixels), wm and wl (12 dwords each) into `c`.
+template <bool kPixels>
+__device__ __forceinline__ void unpack_chunk(Chunk &c, const uint32_t *wx, const uint32_t *wm,
+                                             const uint32_t *wl)
+{
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i)
+#pragma unroll
+        for (int ch = 0; ch < 3; ++ch) {
+            if (kPixels) c.x[i][ch] = byte_of(wx, 3 * i + ch);
+            c.m[i][ch] = half_of(wm, 3 * i + ch);
+            c.l[i][ch] = (int)(short)half_of(wl, 3 * i + ch);
+        }
+}
+
+// Two neighbouring chunks (16 pixels from p, a multiple of 16) as raw words: 96 bytes of each
+// parameter array and 48 of pixels in 16-byte loads.  Taking two chunks at a time halves the
+// number of times a thread comes back to a 128-byte line.
+struct ChunkPair {
+    uint32_t wx[12], wm[24], wl[24];
+};
+template <bool kPixels>
+__device__ __forceinline__ void load_pair(ChunkPair &r, uint32_t p, const uint8_t *__restrict__ img,
+                                          const uint16_t *__restrict__ mu,
+                                          const int16_t *__restrict__ ls)
+{
+    const size_t s = (size_t)p * 3;
+    const uint4 *pm = reinterpret_cast<const uint4 *>(mu + s);
+    const uint4 *pl = reinterpret_cast<const uint4 *>(ls + s);
+#pragma unroll
+    for (int q = 0; q < 6; ++q) {
+        const uint4 a = pm[q], b = pl[q];
+        r.wm[4 * q] = a.x; r.wm[4 * q + 1] = a.y; r.wm[4 * q + 2] = a.z; r.wm[4 * q + 3] = a.w;
+        r.wl[4 * q] = b.x; r.wl[4 * q + 1] = b.y; r.wl[4 * q + 2] = b.z; r.wl[4 * q + 3] = b.w;
+    }
+    if (kPixels) {
+        const uint4 *px = reinterpret_cast<const uint4 *>(img + s);
+#pragma unroll
+        for (int q = 0; q < 3; ++q) {
+            const uint4 a = px[q];
+            r.wx[4 * q] = a.x; r.wx[4 * q + 1] = a.y; r.wx[4 * q + 2] = a.z; r.wx[4 * q + 3] = a.w;
+        }
+    }
+}
+
 // floor(n / f) and the remainder for f < 2^16 and n / f < 2^22 (true after the renormalisation
 // of the encoder), given rf ~ 1/f to float accuracy: the float estimate is within [-2, +1] of the
 // quotient and is fixed up exactly.
@@ -117,8 +165,10 @@ __device__ __forceinline__ size_t lane_scratch_base(uint32_t lane, uint32_t lane
     return (size_t)(lane & ~63u) * lane_cap + (lane & 63u);
 }
 
-template <bool kVec>
-__global__ void k_encode_lanes(Geo g, const uint8_t *__restrict__ img,
+// kPair (with kVec): every row of every lane is a whole number of 16-pixel pairs of chunks that
+// start at multiples of 16 pixels, and the arrays allow 16-byte loads.
+template <bool kVec, bool kPair>
+__global__ __launch_bounds__(kLaneMaxThreads) void k_encode_lanes(Geo g, const uint8_t *__restrict__ img,
                                const uint16_t *__restrict__ mu, const int16_t *__restrict__ ls,
                                const int16_t *__restrict__ coef, uint16_t *__restrict__ scratch,
                                uint32_t lane_cap, uint32_t *__restrict__ lane_words,
@@ -138,10 +188,7 @@ __global__ void k_encode_lanes(Geo g, const uint8_t *__restrict__ img,
     uint32_t nwords = 0;
     uint32_t S = 1u << 16;
 
-    for (uint32_t c = chunks; c-- > 0u;) {
-        const ChunkPos cp = chunk_pos(g, sh, per_row, c);
-        Chunk ck;
-        load_chunk<kVec, true>(ck, cp.p, cp.len, img, mu, ls);
+    auto encode_chunk = [&](const Chunk &ck, const ChunkPos cp) {
         // a chunk never straddles two images when kVec; otherwise take the image per pixel
         uint32_t im = cp.p / g.hw;
         int a_gr = coef[3 * im], a_br = coef[3 * im + 1], a_bg = coef[3 * im + 2];
@@ -186,6 +233,33 @@ __global__ void k_encode_lanes(Geo g, const uint8_t *__restrict__ img,
                 const uint32_t q = div_small(S, f, rf[k], rem);
                 S = (q << m_bits) + rem + lo;
             }
+        }
+    };
+
+    if (kVec && kPair) {
+        // chunks 2i and 2i + 1 of a lane are neighbours in a row; the right one is coded first
+        for (uint32_t c = chunks; c >= 2u; c -= 2u) {
+            const ChunkPos left = chunk_pos(g, sh, per_row, c - 2u);
+            ChunkPair raw;
+            load_pair<true>(raw, left.p, img, mu, ls);
+            auto half = [&](auto h) {  // h: which chunk of the pair, as a compile-time constant
+                constexpr int kH = decltype(h)::value;
+                Chunk ck;
+                unpack_chunk<true>(ck, raw.wx + 6 * kH, raw.wm + 12 * kH, raw.wl + 12 * kH);
+                ChunkPos cp;
+                cp.p = left.p + (uint32_t)(kChunk * kH);
+                cp.len = (uint32_t)kChunk;
+                encode_chunk(ck, cp);
+            };
+            half(std::integral_constant<int, 1>{});
+            half(std::integral_constant<int, 0>{});
+        }
+    } else {
+        for (uint32_t c = chunks; c-- > 0u;) {
+            const ChunkPos cp = chunk_pos(g, sh, per_row, c);
+            Chunk ck;
+            load_chunk<kVec, true>(ck, cp.p, cp.len, img, mu, ls);
+            encode_chunk(ck, cp);
         }
     }
     lane_words[lane] = nwords;
@@ -267,7 +341,7 @@ struct WordStream {
 // most one word and a full ring holds at least 25.  The word after the current one is read from
 // the ring ahead of time.
 constexpr int kRingChunk = 24;
-constexpr int kRingMaxThreads = 256;  // the lane kernels run in workgroups of 64 or 256
+constexpr int kRingMaxThreads = kLaneMaxThreads;
 static_assert(3 * kChunk <= kRingChunk, "a chunk must not take more words than a full ring guarantees");
 
 struct WordRing {
@@ -320,8 +394,8 @@ struct WordRing {
     }
 };
 
-template <bool kVec>
-__global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
+template <bool kVec, bool kPair>
+__global__ __launch_bounds__(kLaneMaxThreads) void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
                                const uint16_t *__restrict__ mu, const int16_t *__restrict__ ls,
                                const int16_t *__restrict__ coef, uint8_t *__restrict__ out,
                                int *__restrict__ status_code,
@@ -358,14 +432,12 @@ __global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
     uint32_t S = words.take();
     S |= words.take() << 16;
 
-    for (uint32_t c = 0; c < chunks; ++c) {
-        const ChunkPos cp = chunk_pos(g, sh, per_row, c);
-        Chunk ck;
-        load_chunk<kVec, false>(ck, cp.p, cp.len, nullptr, mu, ls);
-        words.fill(base, lim);  // its loads travel with the chunk's
+    // decodes the chunk into its 24 bytes (6 dwords)
+    auto decode_chunk = [&](const Chunk &ck, const ChunkPos cp, uint32_t *wout) {
         uint32_t im = cp.p / g.hw;
         int a_gr = coef[3 * im], a_br = coef[3 * im + 1], a_bg = coef[3 * im + 2];
-        uint32_t wout[6] = {0, 0, 0, 0, 0, 0};  // the chunk's 24 decoded bytes
+#pragma unroll
+        for (int b = 0; b < 6; ++b) wout[b] = 0u;
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) {
             if ((uint32_t)i < cp.len) {
@@ -406,16 +478,51 @@ __global__ void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
                 }
             }
         }
-        const size_t s = (size_t)cp.p * 3;
-        if (kVec && cp.len == (uint32_t)kChunk) {
-            uint2 *po = reinterpret_cast<uint2 *>(out + s);
-            po[0] = make_uint2(wout[0], wout[1]);
-            po[1] = make_uint2(wout[2], wout[3]);
-            po[2] = make_uint2(wout[4], wout[5]);
-        } else {
+    };
+
+    if (kVec && kPair) {
+        // two neighbouring chunks per round: 96 bytes of each parameter array in, 48 bytes out
+        for (uint32_t c = 0; c + 2u <= chunks; c += 2u) {
+            const ChunkPos left = chunk_pos(g, sh, per_row, c);
+            ChunkPair raw;
+            load_pair<false>(raw, left.p, nullptr, mu, ls);
+            uint32_t wout[12];
+            auto half = [&](auto h) {  // h: which chunk of the pair, as a compile-time constant
+                constexpr int kH = decltype(h)::value;
+                words.fill(base, lim);
+                Chunk ck;
+                unpack_chunk<false>(ck, nullptr, raw.wm + 12 * kH, raw.wl + 12 * kH);
+                ChunkPos cp;
+                cp.p = left.p + (uint32_t)(kChunk * kH);
+                cp.len = (uint32_t)kChunk;
+                decode_chunk(ck, cp, wout + 6 * kH);
+            };
+            half(std::integral_constant<int, 0>{});
+            half(std::integral_constant<int, 1>{});
+            uint4 *po = reinterpret_cast<uint4 *>(out + (size_t)left.p * 3);
+            po[0] = make_uint4(wout[0], wout[1], wout[2], wout[3]);
+            po[1] = make_uint4(wout[4], wout[5], wout[6], wout[7]);
+            po[2] = make_uint4(wout[8], wout[9], wout[10], wout[11]);
+        }
+    } else {
+        for (uint32_t c = 0; c < chunks; ++c) {
+            const ChunkPos cp = chunk_pos(g, sh, per_row, c);
+            Chunk ck;
+            load_chunk<kVec, false>(ck, cp.p, cp.len, nullptr, mu, ls);
+            words.fill(base, lim);  // its loads travel with the chunk's
+            uint32_t wout[6];
+            decode_chunk(ck, cp, wout);
+            const size_t s = (size_t)cp.p * 3;
+            if (kVec && cp.len == (uint32_t)kChunk) {
+                uint2 *po = reinterpret_cast<uint2 *>(out + s);
+                po[0] = make_uint2(wout[0], wout[1]);
+                po[1] = make_uint2(wout[2], wout[3]);
+                po[2] = make_uint2(wout[4], wout[5]);
+            } else {
 #pragma unroll
-            for (int b = 0; b < 3 * kChunk; ++b)
-                if ((uint32_t)b < 3u * cp.len) out[s + b] = (uint8_t)(wout[b >> 2] >> (8 * (b & 3)));
+                for (int b = 0; b < 3 * kChunk; ++b)
+                    if ((uint32_t)b < 3u * cp.len) out[s + b] = (uint8_t)(wout[b >> 2] >> (8 * (b & 3)));
+            }
         }
     }
     if (S != (1u << 16) || words.pos - first != (end - begin) >> 1) atomicMax(status_code, 6);
