@@ -47,8 +47,8 @@ __device__ __forceinline__ void mean_shift(const int x[3], const int m[3], int a
     int e_r = x[0] * 256 - m[0];
     int e_g = x[1] * 256 - m[1];
     out[0] = m[0];
-    out[1] = m[1] + rsh14(a_gr * e_r);
-    out[2] = m[2] + rsh14(a_br * e_r) + rsh14(a_bg * e_g);
+    out[1] = m[1] + rsh14_mul(a_gr, e_r);
+    out[2] = m[2] + rsh14_mul(a_br, e_r) + rsh14_mul(a_bg, e_g);
 }
 
 // --------------------------------------------------------------------------------------------

@@ -106,8 +106,8 @@ __global__ __launch_bounds__(kEncThreads) void k_encode_block(
     auto produce = [&](const PixelIn &in, uint32_t buf) {
         if (!(my < (uint32_t)kEncLanes)) return;
         const int e_r = in.x[0] * 256 - in.m[0], e_g = in.x[1] * 256 - in.m[1];
-        const int me[3] = {in.m[0], in.m[1] + rsh14(in.a[0] * e_r),
-                           in.m[2] + rsh14(in.a[1] * e_r) + rsh14(in.a[2] * e_g)};
+        const int me[3] = {in.m[0], in.m[1] + rsh14_mul(in.a[0], e_r),
+                           in.m[2] + rsh14_mul(in.a[1], e_r) + rsh14_mul(in.a[2], e_g)};
 #pragma unroll
         for (int c = 0; c < 3; ++c) {
             const uint32_t inv_s = inv_scale(in.ls[c], tab);

@@ -84,6 +84,10 @@ __device__ __forceinline__ LaneShape lane_shape(const Geo &g, uint32_t lane)
 // Rounded Q2.14 * Q8.8 product: floor((v + 2^13) / 2^14).
 __device__ __forceinline__ int rsh14(int v) { return (v + 8192) >> 14; }
 
+// rsh14(a * e) for a Q2.14 coefficient a (16 bits) and an innovation e = 256 x - mu (18 bits): the
+// product is below 2^31 in magnitude, so the 24-bit multiply-add gives it exactly at full rate.
+__device__ __forceinline__ int rsh14_mul(int a, int e) { return (__mul24(a, e) + 8192) >> 14; }
+
 // Q6.25 value of exp(-log_scale); log_scale Q4.12 clamped to [-4, 6).
 __device__ __forceinline__ uint32_t inv_scale(int ls, const LdsTables &t)
 {

@@ -225,11 +225,11 @@ __global__ __launch_bounds__(64 * kGroupWavesPerBlock) void k_decode_group(
                 }
                 uint32_t pk_g, pk_b, unused;
                 const uint32_t x_r = decode_symbol(ragged, act, pk_r, i0, [&](uint32_t x) {
-                    return pack_window(m_g + rsh14(a_gr * ((int)(x << 8) - m_r)));
+                    return pack_window(m_g + rsh14_mul(a_gr, ((int)(x << 8) - m_r)));
                 }, pk_g);
-                const int mb1 = m_b + rsh14(a_br * ((int)(x_r << 8) - m_r));
+                const int mb1 = m_b + rsh14_mul(a_br, ((int)(x_r << 8) - m_r));
                 const uint32_t x_g = decode_symbol(ragged, act, pk_g, i1, [&](uint32_t x) {
-                    return pack_window(mb1 + rsh14(a_bg * ((int)(x << 8) - m_g)));
+                    return pack_window(mb1 + rsh14_mul(a_bg, ((int)(x << 8) - m_g)));
                 }, pk_b);
                 const uint32_t x_b = decode_symbol(ragged, act, pk_b, i2, [](uint32_t) { return 0u; }, unused);
                 v_out = j == i ? (x_r | (x_g << 8) | (x_b << 16)) : v_out;

@@ -206,8 +206,8 @@ __global__ __launch_bounds__(kLaneMaxThreads) void k_encode_lanes(Geo g, const u
                 }
             }
             const int e_r = ck.x[i][0] * 256 - ck.m[i][0], e_g = ck.x[i][1] * 256 - ck.m[i][1];
-            const int me[3] = {ck.m[i][0], ck.m[i][1] + rsh14(a_gr * e_r),
-                               ck.m[i][2] + rsh14(a_br * e_r) + rsh14(a_bg * e_g)};
+            const int me[3] = {ck.m[i][0], ck.m[i][1] + rsh14_mul(a_gr, e_r),
+                               ck.m[i][2] + rsh14_mul(a_br, e_r) + rsh14_mul(a_bg, e_g)};
 #pragma unroll
             for (int ch = 0; ch < 3; ++ch) {
                 const int x = ck.x[i][ch];
@@ -452,10 +452,10 @@ __global__ __launch_bounds__(kLaneMaxThreads) void k_decode_lanes(Geo g, const u
 #pragma unroll
                 for (int ch = 0; ch < 3; ++ch) {
                     int me = ck.m[i][0];
-                    if (ch == 1) me = ck.m[i][1] + rsh14(a_gr * (x[0] * 256 - ck.m[i][0]));
+                    if (ch == 1) me = ck.m[i][1] + rsh14_mul(a_gr, (x[0] * 256 - ck.m[i][0]));
                     if (ch == 2)
-                        me = ck.m[i][2] + rsh14(a_br * (x[0] * 256 - ck.m[i][0])) +
-                             rsh14(a_bg * (x[1] * 256 - ck.m[i][1]));
+                        me = ck.m[i][2] + rsh14_mul(a_br, (x[0] * 256 - ck.m[i][0])) +
+                             rsh14_mul(a_bg, (x[1] * 256 - ck.m[i][1]));
                     const uint32_t inv_s = inv_scale(ck.l[i][ch], tab);
                     const uint32_t slot = S & mask;
                     // the symbol is in lo .. lo + 2 * step - 1, and c_hi = C(lo + 2 * step)

@@ -152,10 +152,10 @@ __device__ __forceinline__ void mix_load_channel(const MixSlots &s, int ch, int 
         if (ch >= 1) {
             const int e_r = x_r * 256 - (int)s.half(s.raw_mu, j);
             if (ch == 1) {
-                me += rsh14(a_gr * e_r);
+                me += rsh14_mul(a_gr, e_r);
             } else {
                 const int e_g = x_g * 256 - (int)s.half(s.raw_mu, s.k + j);
-                me += rsh14(a_br * e_r) + rsh14(a_bg * e_g);
+                me += rsh14_mul(a_br, e_r) + rsh14_mul(a_bg, e_g);
             }
         }
         const int l = (int)(short)s.half(s.raw_ls, (uint32_t)ch * s.k + j);

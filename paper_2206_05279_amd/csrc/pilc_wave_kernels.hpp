@@ -207,10 +207,10 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_decode_wave(
 
             const uint32_t x_r = decode_symbol(m_r, m2w >> 16, i0, i0 >> 16, i0 & 0xFFFFu);
             const int e_r = (int)(x_r << 8) - m_r;
-            const int me_g = m_g + rsh14(a_gr * e_r);
+            const int me_g = m_g + rsh14_mul(a_gr, e_r);
             const uint32_t x_g = decode_symbol(me_g, window_of(me_g), i1, i1 >> 16, i1 & 0xFFFFu);
             const int e_g = (int)(x_g << 8) - m_g;
-            const int me_b = m_b + rsh14(a_br * e_r) + rsh14(a_bg * e_g);
+            const int me_b = m_b + rsh14_mul(a_br, e_r) + rsh14_mul(a_bg, e_g);
             const uint32_t x_b = decode_symbol(me_b, window_of(me_b), i2, i2 >> 16, i2 & 0xFFFFu);
             v_out = write_lane(x_r | (x_g << 8) | (x_b << 16), i, v_out);
         }
@@ -284,8 +284,8 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_encode_wave(
         {
             int e_r = x[0] * 256 - m[0], e_g = x[1] * 256 - m[1];
             me[0] = m[0];
-            me[1] = m[1] + rsh14((int)coef[3 * im] * e_r);
-            me[2] = m[2] + rsh14((int)coef[3 * im + 1] * e_r) + rsh14((int)coef[3 * im + 2] * e_g);
+            me[1] = m[1] + rsh14_mul((int)coef[3 * im], e_r);
+            me[2] = m[2] + rsh14_mul((int)coef[3 * im + 1], e_r) + rsh14_mul((int)coef[3 * im + 2], e_g);
         }
         uint32_t v_cf[3], v_mg[3];
 #pragma unroll
