@@ -171,12 +171,17 @@ __device__ __forceinline__ uint32_t mix_cum_inner(int k, const MixSlots &s, uint
         const uint2 c = s.pairs[j * s.stride];
         return (unsigned long long)s.half(s.raw_w, j) * edge_cdf(256 * k + (-128 - (int)c.x), c.y, tab);
     };
-    // two components per round, so that their table reads are in flight together
+    // four (then two) components per round, so that their table reads are in flight together
     unsigned long long acc = 0ull;
     uint32_t j = 0;
-    for (; j + 1u < s.k; j += 2u) {
+    for (; j + 3u < s.k; j += 4u) {
+        const unsigned long long t0 = term(j), t1 = term(j + 1u), t2 = term(j + 2u), t3 = term(j + 3u);
+        acc += (t0 + t1) + (t2 + t3);
+    }
+    if (j + 1u < s.k) {
         const unsigned long long t0 = term(j), t1 = term(j + 1u);
         acc += t0 + t1;
+        j += 2u;
     }
     if (j < s.k) acc += term(j);
     return (uint32_t)k + scale_mass((uint32_t)(acc >> 15), spread);
