@@ -133,10 +133,26 @@ __global__ __launch_bounds__(64 * kGroupWavesPerBlock) void k_decode_group(
         if (ragged) bad = bad && act;
         if (__builtin_expect(__any(bad), 0)) {
             // general evaluation; windows walk towards the slot: C(0) = 0 <= slot ends a walk
-            // down at base 0, C(256) = 2^M > slot ends a walk up at base 257 - W
+            // down at base 0, C(256) = 2^M > slot ends a walk up at base 257 - W.  With the narrow
+            // 16-candidate window a walk can be long, so there a coarse pass comes first: the lane's
+            // candidates look at every 16th value, the count of those at or below the slot names the
+            // band that holds the symbol (C(0) = 0 always counts), and the walk starts at that band.
+            // (Wider windows keep the plain walk: the extra code slowed their common case.)
+            constexpr bool kCoarse = W == 16;
+            constexpr int kBand = 256 / W;
             const int me = (base << 8) - sc;
             const bool redo = bad;
             int step = (pk & 0x100u) != 0u ? 0 : (cnt == 0u ? -(W - 1) : (W - 1));
+            if (kCoarse) {
+                uint32_t below = 0;
+#pragma unroll
+                for (int c = 0; c < C; ++c)
+                    below += group_count(cum_at(kBand * ((int)j + G * c), me, inv_s, m_bits, tab) <= slot);
+                if (bad) {
+                    base = min(max((int)(below - 1u) * kBand, 0), 257 - W);
+                    step = 0;
+                }
+            }
             do {
                 if (bad) {
                     base = min(max(base + step, 0), 257 - W);
