@@ -349,13 +349,17 @@ namespace pilc {
 // per lane and two candidates per thread
 static int g_kernel_policy = 0;
 
-// A wavefront per lane pays off while there are too few lanes to fill the chip with one thread
-// each (256 CUs x 4 SIMDs x 64 threads = 65,536 threads for a single wave per SIMD).
-static bool use_wave_kernels(const Geo &g)
+// The few-lane kernels pay off while there are too few lanes to fill the chip with one thread
+// each (256 CUs x 4 SIMDs x 64 threads = 65,536 threads for a single wave per SIMD).  Measured
+// on CIFAR-shaped data cut into lanes of different lengths, the block encoder is ahead of the
+// thread-per-lane encoder up to about 28K lanes (1.85 against 2.15 ms at 25,000 lanes, 1.74
+// against 1.13 ms at 50,000) and the group decoder up to about 12K (9.9 against 15.5 ms at 6250
+// lanes, 7.85 against 7.77 ms at 12,500, 6.2 against 4.2 ms at 25,000).
+static bool use_wave_kernels(const Geo &g, bool decode)
 {
     if (g_kernel_policy == 1) return false;
     if (g_kernel_policy >= 2) return true;
-    return g.lanes <= 16384u;
+    return g.lanes <= (decode ? 12288u : 28672u);
 }
 
 // Threads per lane of the few-lane decoder: enough lanes per wavefront that no SIMD has to host
@@ -687,7 +691,7 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
 
     Timer timer(stream);
     k_init_status<<<1, 1, 0, stream>>>(status);
-    const bool few_lanes = use_wave_kernels(g);
+    const bool few_lanes = use_wave_kernels(g, false);
     const uint32_t lane_cap = few_lanes ? 0u : max_lane_symbols(g);  // selects the scratch layout
     if (few_lanes) {
         k_encode_block<<<(uint32_t)ceil_div64(g.lanes, kEncLanes), kEncThreads, 0, stream>>>(
@@ -761,7 +765,7 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
     Timer timer(stream);
     k_check_header<<<1, 1, 0, stream>>>(g, kMagicPilc, 0u, coded_dev, (unsigned long long)coded_bytes, status);
     timer.mark("k_check_header");
-    const bool few_lanes = use_wave_kernels(g);
+    const bool few_lanes = use_wave_kernels(g, true);
     if (few_lanes) {
         const int gs = decode_group_size(g);  // 17: 16 threads per lane with two candidates each
         const uint32_t waves = (uint32_t)ceil_div64(g.lanes, gs == 17 ? 4 : 64 / gs);
