@@ -1,0 +1,71 @@
+"""Seeded random geometries (all valid) through every kernel family: the container must equal the
+oracle's byte for byte and the decode must return the images.  Covers what the fixed cases may
+miss: odd sizes next to the vector paths' alignment rules (rows of 8 and 16 pixels), lane lengths
+around 64 words and 64 lanes, ragged tiles, lanes that span or split images."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mix_oracle as mx
+from oracle import pilc_oracle as orc
+from paper_2206_05279_amd import binding as pb
+from paper_2206_05279_amd import synth, synth_mix
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import DeviceMix, DeviceWorkload, first_difference  # noqa: E402
+
+
+def _random_geometry(seed):
+    rng = np.random.default_rng(1000 + seed)
+    h = int(rng.choice([1, 3, 8, 16, 24, 32, 40, 48]))
+    w = int(rng.choice([1, 5, 8, 16, 24, 32, 48, 64, 80]))
+    n = int(rng.integers(1, 9))
+    m = int(rng.integers(10, 17))
+    hw = h * w
+    if rng.random() < 0.5:  # flat lanes: a divisor of an image, or whole images
+        divisors = [d for d in range(1, hw + 1) if hw % d == 0]
+        if rng.random() < 0.7:
+            la = int(rng.choice(divisors))
+        else:
+            la = hw * int(rng.integers(1, 4))
+        return n, h, w, m, 0, la, 0
+    la = int(rng.choice([1, 2, 4, 8, 16, 17]))
+    lb = int(rng.choice([1, 3, 8, 16, 32, 33]))
+    return n, h, w, m, 1, la, lb
+
+
+@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("policy", [0, 1, 2], ids=["auto", "thread-per-lane", "few-lane"])
+def test_random_geometry_matches_oracle(seed, policy):
+    n, h, w, m, mode, la, lb = _random_geometry(seed)
+    wl = synth.make_random_case(seed, n, h, w, m, mode, la, lb, wild=(seed % 3 == 0))
+    print("geometry", wl.geom, "policy", policy, flush=True)
+    rc, want = orc.encode(orc.make_geom(*wl.geom), wl.img, wl.mu, wl.log_scale, wl.chan_coef)
+    assert rc == orc.OK
+    pb.pilc_set_kernel_policy(policy)
+    try:
+        d = DeviceWorkload(wl)
+        _, nbytes = d.encode()
+        got = d.coded_numpy()
+        assert nbytes == want.size and np.array_equal(got, want), first_difference(got, want)
+        assert d.decode() == pb.PILC_OK
+        assert np.array_equal(d.decoded_numpy(), wl.img)
+    finally:
+        pb.pilc_set_kernel_policy(0)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_geometry_mixture_matches_oracle(seed):
+    n, h, w, m, mode, la, lb = _random_geometry(100 + seed)
+    k = int(np.random.default_rng(seed).integers(1, 17))
+    wl = synth_mix.from_base(synth.make_random_case(seed, n, h, w, m, mode, la, lb, wild=(seed % 4 == 0)), k, seed)
+    print("geometry", wl.geom, "K", k, flush=True)
+    rc, want = mx.encode(orc.make_geom(*wl.geom), k, wl.img, wl.mu, wl.log_scale, wl.weight, wl.chan_coef)
+    assert rc == mx.OK
+    d = DeviceMix(wl)
+    _, nbytes = d.encode()
+    got = d.coded_numpy()
+    assert nbytes == want.size and np.array_equal(got, want), first_difference(got, want)
+    assert d.decode() == pb.PILC_OK
+    assert np.array_equal(d.decoded_numpy(), wl.img)
