@@ -15,8 +15,11 @@ Besides the contract fields the line carries
   other_workloads  compress / decompress MB/s of the other single-GPU workloads (fewer steps).
 
 --workload ansai times the paper's own table-driven coder (Sec. 3.2 Algs. 3-4) instead, on the
-recipe of its coder measurement (Sec. 4.3: 10^6 pieces of 1000 symbols, 8 distributions); the
-default run reports it among other_workloads.
+recipe of its coder measurement (Sec. 4.3: 10^6 pieces of 1000 symbols, 8 distributions);
+--workload twar the Three-Way AR residual transform (Sec. 3.1 eqs. (2)-(4)) on the images of
+--config; --workload mix the coder under a mixture of --components logistic laws per subpixel
+(the workload Sec. 2 names) on ImageNet64-shaped rows.  The default run reports all three among
+other_workloads.
 """
 from __future__ import annotations
 
