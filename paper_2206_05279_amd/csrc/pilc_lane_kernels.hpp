@@ -471,7 +471,8 @@ __global__ __launch_bounds__(kLaneMaxThreads) void k_decode_lanes(Geo g, const u
                     }
                     x[ch] = lo;
                     // App. A eq. (12)
-                    S = (c_hi - c_lo) * (S >> m_bits) + slot - c_lo;
+                    // the mass is at most 2^16 and S >> M below 2^22: a 24-bit multiply is exact
+                    S = (uint32_t)__umul24(c_hi - c_lo, S >> m_bits) + slot - c_lo;
                     if (S < (1u << 16)) S = (S << 16) | words.take();
                     const int b = 3 * i + ch;
                     wout[b >> 2] |= (uint32_t)lo << (8 * (b & 3));

@@ -373,7 +373,8 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_decode(
                 c_hi = ge ? c_hi : cv;
             }
             // App. A eq. (12)
-            S = (c_hi - c_lo) * (S >> m_bits) + slot - c_lo;
+            // the mass is at most 2^16 and S >> M below 2^22: a 24-bit multiply is exact
+            S = (uint32_t)__umul24(c_hi - c_lo, S >> m_bits) + slot - c_lo;
             if (S < (1u << 16)) S = (S << 16) | words.take(base, lim);
             x_b = ch == 2 ? lo : x_b;
             x_g = ch == 1 ? lo : x_g;
