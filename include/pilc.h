@@ -102,6 +102,9 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
 /* Decompress (Sec. 3.1 "Decompress", coder part; App. A eq. (12) per symbol, the symbol
  * being the x with C_x <= S mod 2^M < C_x + P_x).  The geometry and parameters must be the
  * ones used to encode.  img_out_dev uint8 [n,h,w,3]; on error its contents are undefined.
+ * coded_dev is 16-byte aligned; the decoder reads the stream in aligned 16-byte blocks and may
+ * therefore read (never use) up to 15 bytes beyond coded_bytes, inside the block that holds the
+ * container's last byte.
  * Errors: PILC_E_ARG, PILC_E_WORKSPACE, PILC_E_FORMAT, PILC_E_CORRUPT, PILC_E_HIP. */
 int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_bytes,
                 const pilc_params *params, void *workspace_dev, size_t workspace_bytes,
