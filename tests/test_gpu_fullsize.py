@@ -51,6 +51,7 @@ FULL = [
     ("cfg2-full", lambda: synth.make_workload(2), 6),
     ("cfg3-full", lambda: synth.make_workload(3), 2),
     ("cfg4-M12-L64-256img", lambda: synth.make_workload(4, 256, prec_bits=12, lanes_per_image=64), 4),
+    ("cfg4-full-M16-L256", lambda: synth.make_workload(4, prec_bits=16, lanes_per_image=256), 6),
 ]
 
 
