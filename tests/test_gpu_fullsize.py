@@ -50,9 +50,14 @@ FULL = [
     ("cfg1-full", lambda: synth.make_workload(1), 12),
     ("cfg2-full", lambda: synth.make_workload(2), 6),
     ("cfg3-full", lambda: synth.make_workload(3), 2),
-    ("cfg4-M12-L64-256img", lambda: synth.make_workload(4, 256, prec_bits=12, lanes_per_image=64), 4),
-    ("cfg4-full-M16-L256", lambda: synth.make_workload(4, prec_bits=16, lanes_per_image=256), 6),
+    ("cfg4-full-M12-L64", lambda: synth.make_workload(4, prec_bits=12, lanes_per_image=64), 6),
+    ("cfg4-full-M16-L64", lambda: synth.make_workload(4, prec_bits=16, lanes_per_image=64), 6),
 ]
+# the rest of the stress workload's sweep (lanes per image 1..1024, M = 12 and 16) on a subset of
+# 256 of its 256x256 images: 128 of the random half and 128 of the constant half
+FULL += [("cfg4-256img-M%d-L%d" % (m, lpi),
+          (lambda m=m, lpi=lpi: synth.make_workload(4, 256, prec_bits=m, lanes_per_image=lpi)), 3)
+         for m in (12, 16) for lpi in (1, 2, 4, 8, 16, 32, 128, 256, 512, 1024)]
 
 
 @pytest.mark.parametrize("name,make,samples", FULL, ids=[c[0] for c in FULL])
