@@ -11,6 +11,8 @@ Besides the contract fields the line carries
                 the 8 TB/s HBM peak, and `traffic` = HBM bytes of one launch read from two
                 rocprofv3 --pmc child runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same
                 counter reports for a plain device copy of known size in the same child run;
+                `plain_copy_GBs` is a device-to-device copy timed in the same run (read + written
+                bytes per second): the achievable figure beside the published peak;
   cpu_baseline  the CPU oracle timed on the host cores on a bounded prefix of the workload;
   other_workloads  compress / decompress MB/s of the other single-GPU workloads (fewer steps).
 
@@ -528,6 +530,21 @@ class MixRun:
     timed = Run.timed
 
 
+def copy_bandwidth(torch, src, reps=10):
+    """GB/s (bytes read plus bytes written) of a plain device-to-device copy of `src`: what a
+    streaming kernel can reach on this GPU, to set beside the 8 TB/s peak."""
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    return 2.0 * src.numel() * src.element_size() * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -605,7 +622,8 @@ def main():
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_bytes,
                      "traffic_detail": traffic_detail, "algorithmic_bytes": algo_bytes,
-                     "avg_ms": kernel_ms[dom]},
+                     "avg_ms": kernel_ms[dom],
+                     "plain_copy_GBs": copy_bandwidth(torch, run.probe_src)},
         "paper_context": "PILC reports about 200 MB/s end to end and 675/672 MB/s for its coder "
                          "phases on one V100 (table-driven coder; Tab. 5 of the paper, another "
                          "machine and workload: context, not a baseline)",
