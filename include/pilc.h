@@ -119,9 +119,9 @@ int pilc_symbol_tables(const pilc_geom *geom, const uint8_t *img_dev, const pilc
                        uint32_t *cum_out_dev, uint32_t *freq_out_dev, void *hip_stream);
 
 /* ---- mixture of K logistic laws per subpixel ------------------------------------------
- * The workload Sec. 2 ("Entropy Coder", and the "Data transfer" item before it) names as the
+ * The workload Sec. 2 ("Entropy Coder") and the "Data transfer" item of Sec. 1 name as the
  * slow case of earlier learned codecs: a dynamic rANS coder (App. A eqs. (11)-(12)) whose
- * distribution per symbol is "mixed by 10 logistic ones".  The paper gives no formula; this
+ * distribution per symbol is a mixture of ten logistic laws.  The paper gives no formula; this
  * library takes: a pixel carries K weights w_j in Q0.15 that sum to 2^15 exactly (shared by its
  * three subpixels), a subpixel K means and K log-scales (formats of pilc_params); the mixed
  * 24-bit edge CDF is F(k) = floor(sum_j w_j F_j(k) / 2^15), F_j the single-law edge CDF, and

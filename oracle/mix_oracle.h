@@ -11,7 +11,7 @@
  *
  * What it follows (arXiv 2206.05279): Sec. 2 ("Entropy Coder" and the "Data
  * transfer" item of Sec. 1) names the workload -- a dynamic rANS coder driven
- * by "a distribution mixed by 10 logistic ones" per symbol -- as what makes
+ * by a mixture of ten logistic laws per symbol -- as what makes
  * earlier learned codecs slow; the paper gives no formula for it.  The coder
  * is that of App. A eqs. (11)-(12) and Sec. 3.2 (integer masses P_x summing to
  * 2^M, C_x their running sum).  Readings taken here, all integer:

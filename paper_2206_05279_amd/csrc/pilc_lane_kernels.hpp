@@ -267,7 +267,7 @@ __global__ __launch_bounds__(kLaneMaxThreads) void k_encode_lanes(Geo g, const u
 }
 
 // --------------------------------------------------------------------------------------------
-// Decode.  The symbol is found by an 8-step bisection on C(k) (App. A: "binary search").
+// Decode.  The symbol is found by an 8-step bisection on C(k) (App. A names a binary search).
 // --------------------------------------------------------------------------------------------
 
 // A lane's 16-bit words, fetched as aligned 32-byte pairs of 16-byte pieces, a piece ahead of

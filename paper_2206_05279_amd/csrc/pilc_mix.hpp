@@ -1,7 +1,7 @@
 // rANS lanes under a mixture of K logistic laws per subpixel, one thread per lane (gfx950).
 //
-// Sec. 2 of arXiv 2206.05279 names this workload (a dynamic rANS coder fed "a distribution mixed
-// by 10 logistic ones") as what holds earlier learned codecs near 1 MB/s; the coder itself is
+// Sec. 2 of arXiv 2206.05279 names this workload (a dynamic rANS coder fed a mixture of ten
+// logistic laws per symbol) as what holds earlier learned codecs near 1 MB/s; the coder itself is
 // App. A eqs. (11)-(12).  A pixel has K weights (Q0.15, summing to 2^15), a subpixel K means and
 // K log-scales.  The mixed 24-bit edge CDF is F(k) = floor(sum_j w_j F_j(k) / 2^15) with F_j the
 // single-law edge CDF, and C(k) = k + floor(F(k) (2^M - 256) / 2^24); the channel conditioning

@@ -3,7 +3,7 @@
 Serves the oracle, the tests and the benchmark alike and holds none of the method's arithmetic:
 it only draws images and parameter arrays.  The images are those of `synth.make_workload`; the
 mixture parameters stand in for the output of a PixelCNN++-style head, which Sec. 2 of
-arXiv 2206.05279 names ("a distribution mixed by 10 logistic ones") without giving one:
+arXiv 2206.05279 names (a mixture of ten logistic laws per symbol) without giving one:
 
 * component 0 of a subpixel is the single-law parameter set of the base workload (mean near the
   true value);
