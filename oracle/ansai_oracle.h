@@ -69,7 +69,7 @@ int ansai_oracle_decode(const ansai_model *model, uint32_t pieces, uint32_t coun
 
 /* Sec. 3.3: the residual r ~ L(mu, s, 0, 255) is coded as (r - mu + 128) mod 256 ~ L(128, s, 0, 255),
  * so that the distribution index only has to tell the scale.  mu is the predicted location rounded
- * to an integer (a reading: the paper predicts "within uint8 space").  inverse = 0: out = (r - mu +
+ * to an integer (a reading: the paper keeps the prediction in the uint8 range).  inverse = 0: out = (r - mu +
  * 128) mod 256; inverse != 0: out = (c + mu - 128) mod 256. */
 void ansai_oracle_center(const uint8_t *in, const uint8_t *mu, uint64_t n, int inverse, uint8_t *out);
 #ifdef __cplusplus

@@ -8,7 +8,7 @@
 //     thread, and handed to the serial part through v_readlane;
 //   - the state, the stream position and all control flow are wave-uniform, so they live in
 //     scalar registers;
-//   - decode replaces the bisection for the symbol (App. A: "binary search is needed") by one
+//   - decode replaces the bisection for the symbol (App. A searches for it by bisection) by one
 //     64-candidate evaluation of C(k) around the predicted mean plus a ballot.
 #pragma once
 
