@@ -99,6 +99,21 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
                 void *workspace_dev, size_t workspace_bytes, uint8_t *coded_dev,
                 size_t coded_capacity, uint64_t *coded_bytes_host, void *hip_stream);
 
+/* pilc_encode for callers that cannot allocate device memory or carry a workspace: code under
+ * HIP graph capture set-up, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, container, alignment rules and errors as pilc_encode, without the workspace: the
+ * scratch memory is an array of PILC_STATIC_SCRATCH_BYTES inside the library (one copy per GPU,
+ * held until the process ends), and the call allocates and frees nothing (no HIP events either:
+ * pilc_last_timing reports nothing for it).  A geometry whose pilc_workspace_size exceeds
+ * PILC_STATIC_SCRATCH_BYTES is refused with PILC_E_WORKSPACE before anything runs (16 MiB holds
+ * one 1920x1080 frame, or about 2.7 million pixels in all).  All calls on one GPU share that
+ * GPU's array: calls that overlap in time on the same GPU, from any threads or streams, race and
+ * give undefined output; calls one after another are independent (nothing is kept between them). */
+#define PILC_STATIC_SCRATCH_BYTES (16u << 20)
+int pilc_encode_static(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params *params,
+                       uint8_t *coded_dev, size_t coded_capacity, uint64_t *coded_bytes_host,
+                       void *hip_stream);
+
 /* Decompress (Sec. 3.1 "Decompress", coder part; App. A eq. (12) per symbol, the symbol
  * being the x with C_x <= S mod 2^M < C_x + P_x).  The geometry and parameters must be the
  * ones used to encode.  img_out_dev uint8 [n,h,w,3]; on error its contents are undefined.

@@ -25,7 +25,8 @@ PILC_E_CORRUPT = -6
 PILC_E_HIP = -7
 
 EXPORTS = [
-    "pilc_lane_count", "pilc_workspace_size", "pilc_encode", "pilc_decode", "pilc_symbol_tables",
+    "pilc_lane_count", "pilc_workspace_size", "pilc_encode", "pilc_encode_static", "pilc_decode",
+    "pilc_symbol_tables",
     "pilc_set_timing", "pilc_set_kernel_policy", "pilc_last_timing", "pilc_timing_name", "pilc_strerror",
     "pilc_last_hip_error", "pilc_version",
     "pilc_ansai_table_bytes", "pilc_ansai_build_tables", "pilc_ansai_workspace_size", "pilc_ansai_encode",
@@ -85,6 +86,9 @@ def lib():
         L.pilc_encode.restype = C.c_int
         L.pilc_encode.argtypes = [gp, C.c_void_p, pp, C.c_void_p, C.c_size_t, C.c_void_p,
                                   C.c_size_t, C.POINTER(C.c_uint64), C.c_void_p]
+        L.pilc_encode_static.restype = C.c_int
+        L.pilc_encode_static.argtypes = [gp, C.c_void_p, pp, C.c_void_p, C.c_size_t,
+                                         C.POINTER(C.c_uint64), C.c_void_p]
         L.pilc_decode.restype = C.c_int
         L.pilc_decode.argtypes = [gp, C.c_void_p, C.c_size_t, pp, C.c_void_p, C.c_size_t,
                                   C.c_void_p, C.c_void_p]
@@ -179,6 +183,22 @@ def pilc_encode(geom: pilc_geom, img, mu, log_scale, chan_coef, workspace, coded
                            _stream_handle(stream))
     if check and rc != PILC_OK:
         raise PilcError(rc, "pilc_encode")
+    return rc, int(nbytes.value)
+
+
+PILC_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def pilc_encode_static(geom: pilc_geom, img, mu, log_scale, chan_coef, coded,
+                       stream: Optional[torch.cuda.Stream] = None, check: bool = True) -> Tuple[int, int]:
+    """Runs pilc_encode_static (the library's own scratch array instead of a workspace)."""
+    nbytes = C.c_uint64(0)
+    par = _params(mu, log_scale, chan_coef)
+    rc = lib().pilc_encode_static(C.byref(geom), _dev_ptr(img, torch.uint8, "img"), C.byref(par),
+                                  _dev_ptr(coded, torch.uint8, "coded"), coded.numel(), C.byref(nbytes),
+                                  _stream_handle(stream))
+    if check and rc != PILC_OK:
+        raise PilcError(rc, "pilc_encode_static")
     return rc, int(nbytes.value)
 
 

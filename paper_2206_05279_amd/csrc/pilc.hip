@@ -517,7 +517,7 @@ struct Timer {
     const char *name[16];
     int n = 0;
     bool on;
-    explicit Timer(hipStream_t s) : stream(s), on(g_timing_enabled != 0)
+    explicit Timer(hipStream_t s, bool allowed = true) : stream(s), on(allowed && g_timing_enabled != 0)
     {
         t_timing_count = 0;
         if (on) {
@@ -663,23 +663,14 @@ int pilc_symbol_tables(const pilc_geom *geom, const uint8_t *img_dev, const pilc
     return PILC_OK;
 }
 
-int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params *params,
-                void *workspace_dev, size_t workspace_bytes, uint8_t *coded_dev,
-                size_t coded_capacity, uint64_t *coded_bytes_host, void *hip_stream)
+// The body of pilc_encode once the arguments have been checked: `workspace_dev` holds at least
+// layout(g).total bytes.  `timed` is false for callers that must not create HIP events.
+static int encode_checked(const Geo &g, const uint8_t *img_dev, const pilc_params *params,
+                          void *workspace_dev, uint8_t *coded_dev, size_t coded_capacity,
+                          uint64_t *coded_bytes_host, hipStream_t stream, bool timed)
 {
-    Geo g;
-    int rc = make_geo(geom, &g);
-    if (rc != PILC_OK) return rc;
-    if (!img_dev || !params_ok(params) || !workspace_dev || !coded_dev || !coded_bytes_host)
-        return PILC_E_ARG;
-    if (((uintptr_t)workspace_dev & 255) || ((uintptr_t)coded_dev & 15)) return PILC_E_ARG;
     const Workspace ws = layout(g);
-    if (workspace_bytes < ws.total) return PILC_E_WORKSPACE;
     const size_t table_end = kHeaderBytes + 4 * ((size_t)g.lanes + 1);
-    if (coded_capacity < table_end) return PILC_E_CAPACITY;
-    if ((rc = ensure_tables()) != PILC_OK) return rc;
-
-    hipStream_t stream = (hipStream_t)hip_stream;
     uint8_t *base = static_cast<uint8_t *>(workspace_dev);
     Status *status = reinterpret_cast<Status *>(base + ws.status_off);
     uint32_t *lane_words = reinterpret_cast<uint32_t *>(base + ws.words_off);
@@ -689,7 +680,7 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
     uint32_t *offsets = reinterpret_cast<uint32_t *>(coded_dev + kHeaderBytes);
     uint16_t *payload = reinterpret_cast<uint16_t *>(coded_dev + table_end);
 
-    Timer timer(stream);
+    Timer timer(stream, timed);
     k_init_status<<<1, 1, 0, stream>>>(status);
     const bool few_lanes = use_wave_kernels(g, false);
     const uint32_t lane_cap = few_lanes ? 0u : max_lane_symbols(g);  // selects the scratch layout
@@ -742,6 +733,73 @@ int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params
     if (host_status.code != ST_OK) return status_to_error(host_status.code);
     *coded_bytes_host = table_end + host_status.payload_bytes;
     return PILC_OK;
+}
+
+int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params *params,
+                void *workspace_dev, size_t workspace_bytes, uint8_t *coded_dev,
+                size_t coded_capacity, uint64_t *coded_bytes_host, void *hip_stream)
+{
+    Geo g;
+    int rc = make_geo(geom, &g);
+    if (rc != PILC_OK) return rc;
+    if (!img_dev || !params_ok(params) || !workspace_dev || !coded_dev || !coded_bytes_host)
+        return PILC_E_ARG;
+    if (((uintptr_t)workspace_dev & 255) || ((uintptr_t)coded_dev & 15)) return PILC_E_ARG;
+    if (workspace_bytes < layout(g).total) return PILC_E_WORKSPACE;
+    if (coded_capacity < kHeaderBytes + 4 * ((size_t)g.lanes + 1)) return PILC_E_CAPACITY;
+    if ((rc = ensure_tables()) != PILC_OK) return rc;
+    return encode_checked(g, img_dev, params, workspace_dev, coded_dev, coded_capacity,
+                          coded_bytes_host, (hipStream_t)hip_stream, true);
+}
+
+// --------------------------------------------------------------------------------------------
+// pilc_encode for callers that cannot allocate device memory: the workspace is a file-scope
+// device array.  Every GPU holds its own copy at its own address; the address is asked for once
+// per device, with that device current, and host code uses only that pointer (the array's name
+// is not a device address in host code).
+// --------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[PILC_STATIC_SCRATCH_BYTES];
+
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[64] = {nullptr};
+
+static int static_scratch(void **out)
+{
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return PILC_E_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || ((uintptr_t)ptr & 255)) {
+            snprintf(t_hip_error, sizeof(t_hip_error), "hipGetSymbolAddress(scratch) gave %p", ptr);
+            return PILC_E_HIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return PILC_OK;
+}
+
+int pilc_encode_static(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params *params,
+                       uint8_t *coded_dev, size_t coded_capacity, uint64_t *coded_bytes_host,
+                       void *hip_stream)
+{
+    Geo g;
+    int rc = make_geo(geom, &g);
+    if (rc != PILC_OK) return rc;
+    if (!img_dev || !params_ok(params) || !coded_dev || !coded_bytes_host) return PILC_E_ARG;
+    if ((uintptr_t)coded_dev & 15) return PILC_E_ARG;
+    if (layout(g).total > (size_t)PILC_STATIC_SCRATCH_BYTES) return PILC_E_WORKSPACE;
+    if (coded_capacity < kHeaderBytes + 4 * ((size_t)g.lanes + 1)) return PILC_E_CAPACITY;
+    if ((rc = ensure_tables()) != PILC_OK) return rc;
+    void *ws = nullptr;
+    if ((rc = static_scratch(&ws)) != PILC_OK) return rc;
+    // Nothing in the workspace has to start at zero: the status block is set by the first kernel
+    // and every count, state and scratch word that is read has been written by this call.
+    return encode_checked(g, img_dev, params, ws, coded_dev, coded_capacity, coded_bytes_host,
+                          (hipStream_t)hip_stream, false);
 }
 
 int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_bytes,
