@@ -337,6 +337,7 @@ __global__ void k_check_header(Geo g, uint32_t magic, uint32_t word11,
 #include "pilc_wave_kernels.hpp"
 #include "pilc_block_encode.hpp"
 #include "pilc_group_decode.hpp"
+#include "pilc_row_decode.hpp"
 #include "pilc_mix.hpp"
 
 namespace pilc {
@@ -366,6 +367,7 @@ static bool use_wave_kernels(const Geo &g, bool decode)
 // more than two wavefronts (1024 SIMDs), as few as possible otherwise (wider candidate windows).
 static int decode_group_size(const Geo &g)
 {
+    if (g_kernel_policy == 0 || g_kernel_policy == 2 || g_kernel_policy == 8) return 0;  // rows of 16
     if (g_kernel_policy == 3) return 64;
     if (g_kernel_policy == 4) return 32;
     if (g_kernel_policy == 5) return 16;
@@ -602,7 +604,7 @@ void pilc_set_timing(int enabled) { g_timing_enabled = enabled; }
 
 int pilc_set_kernel_policy(int policy)
 {
-    if (policy < 0 || policy > 7) return PILC_E_ARG;
+    if (policy < 0 || policy > 8) return PILC_E_ARG;
     g_kernel_policy = policy;
     return PILC_OK;
 }
@@ -826,10 +828,24 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
     const bool few_lanes = use_wave_kernels(g, true);
     if (few_lanes) {
         const int gs = decode_group_size(g);  // 17: 16 threads per lane with two candidates each
-        const uint32_t waves = (uint32_t)ceil_div64(g.lanes, gs == 17 ? 4 : 64 / gs);
+        const uint32_t waves = (uint32_t)ceil_div64(g.lanes, gs == 17 ? 4 : 64 / (gs ? gs : 64));
         const uint32_t blocks = (uint32_t)ceil_div64(waves, kGroupWavesPerBlock);
         const int bt = 64 * kGroupWavesPerBlock;
-        if (g_kernel_policy == 6)
+        if (gs == 0) {
+            // all lanes alike and made of whole batches of 16 pixels: no per-row activity masks
+            const bool even = g.lane_mode == 0 ? (g.lane_a % kRowBatch == 0 && g.total_px % g.lane_a == 0)
+                                               : (g.h % g.lane_a == 0 && g.w % g.lane_b == 0 &&
+                                                  (g.lane_a * g.lane_b) % kRowBatch == 0);
+            const uint32_t nblk = (uint32_t)ceil_div64(g.lanes, kRowLanes);
+            if (even)
+                k_decode_rows<false><<<nblk, 64 * kRowWaves, 0, stream>>>(
+                    g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev,
+                    &status->code, &status->payload_bytes);
+            else
+                k_decode_rows<true><<<nblk, 64 * kRowWaves, 0, stream>>>(
+                    g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev,
+                    &status->code, &status->payload_bytes);
+        } else if (g_kernel_policy == 6)
             k_decode_wave<<<(uint32_t)ceil_div64(g.lanes, kWavesPerBlock), 64 * kWavesPerBlock, 0, stream>>>(
                 g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev,
                 &status->code, &status->payload_bytes);
@@ -866,7 +882,9 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
                                                                 img_out_dev, &status->code,
                                                                 &status->payload_bytes);
     }
-    timer.mark(few_lanes ? (g_kernel_policy == 6 ? "k_decode_wave" : "k_decode_group") : "k_decode_lanes");
+    timer.mark(few_lanes ? (decode_group_size(g) == 0 ? "k_decode_rows"
+                                                      : (g_kernel_policy == 6 ? "k_decode_wave" : "k_decode_group"))
+                         : "k_decode_lanes");
     HIP_TRY(hipGetLastError());
     Status host_status;
     HIP_TRY(hipMemcpyAsync(&host_status, status, sizeof(Status), hipMemcpyDeviceToHost, stream));

@@ -17,9 +17,9 @@ def _ogeom(wl):
     return orc.make_geom(*wl.geom)
 
 
-@pytest.fixture(params=[1, 3, 4, 5, 6, 7],
+@pytest.fixture(params=[1, 3, 4, 5, 6, 7, 8],
                 ids=["thread-per-lane", "few-lane-64", "few-lane-32", "few-lane-16", "few-lane-scalar",
-                     "few-lane-16x2"])
+                     "few-lane-16x2", "few-lane-rows"])
 def policy(request):
     """Runs a test once with each lane-kernel family forced."""
     pb.pilc_set_kernel_policy(request.param)
