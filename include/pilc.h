@@ -174,12 +174,10 @@ int pilc_last_timing(float *ms_out_host, int capacity);
 const char *pilc_timing_name(int index_in_last_call);
 
 /* Which lane kernels encode and decode use: 0 = chosen from the lane count (default), 1 = one
- * thread per lane, 2 = the kernels for few long lanes (workgroup-cooperative encode, several
- * threads per lane in decode); 3, 4, 5 = as 2 with 64, 32, 16 threads per lane in decode;
- * 6 = as 2 with the scalar-state wavefront-per-lane decoder; 7 = as 2 with 16 threads per lane
- * that each evaluate two candidates.  All choices produce the same
- * bytes; the knob exists for tuning and for testing every kernel on the same input.
- * Process-wide.  Errors: PILC_E_ARG for any other value. */
+ * thread per lane, 2 = the kernels for few long lanes (workgroup-cooperative encode, a row of 16
+ * threads per lane in decode).  All choices produce the same bytes; the knob exists for tuning and
+ * for testing every kernel on the same input.  Process-wide.  Errors: PILC_E_ARG for any other
+ * value. */
 int pilc_set_kernel_policy(int policy);
 
 /* ------------------------------------------------------------------------------------------

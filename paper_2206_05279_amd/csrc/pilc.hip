@@ -6,7 +6,7 @@
 //           -> pack (lane streams copied to their offsets)
 //   decode: header check -> lane kernel (search of the symbol, state update, refill)
 // Lane kernels: pilc_lane_kernels.hpp (thread per lane), pilc_block_encode.hpp and
-// pilc_group_decode.hpp / pilc_wave_kernels.hpp (few long lanes).
+// pilc_row_decode.hpp (few long lanes).
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -334,9 +334,7 @@ __global__ void k_check_header(Geo g, uint32_t magic, uint32_t word11,
 }  // namespace pilc
 
 #include "pilc_lane_kernels.hpp"
-#include "pilc_wave_kernels.hpp"
 #include "pilc_block_encode.hpp"
-#include "pilc_group_decode.hpp"
 #include "pilc_row_decode.hpp"
 #include "pilc_mix.hpp"
 
@@ -345,36 +343,21 @@ namespace pilc {
 // --------------------------------------------------------------------------------------------
 // Host side
 // --------------------------------------------------------------------------------------------
-// 0 auto, 1 thread per lane, 2 few-lane kernels; 3/4/5 few-lane with 64/32/16 threads per lane
-// in decode, 6 few-lane with the scalar-state wave-per-lane decoder, 7 few-lane with 16 threads
-// per lane and two candidates per thread
+// 0 chosen from the lane count, 1 thread per lane, 2 the kernels for few long lanes
 static int g_kernel_policy = 0;
 
 // The few-lane kernels pay off while there are too few lanes to fill the chip with one thread
 // each (256 CUs x 4 SIMDs x 64 threads = 65,536 threads for a single wave per SIMD).  Measured
 // on CIFAR-shaped data cut into lanes of different lengths, the block encoder is ahead of the
 // thread-per-lane encoder up to about 28K lanes (1.85 against 2.15 ms at 25,000 lanes, 1.74
-// against 1.13 ms at 50,000) and the group decoder up to about 12K (9.9 against 15.5 ms at 6250
-// lanes, 7.85 against 7.77 ms at 12,500, 6.2 against 4.2 ms at 25,000).
-static bool use_wave_kernels(const Geo &g, bool decode)
+// against 1.13 ms at 50,000) and the row decoder up to about 13K (7.8 against 15.5 ms at 6250
+// lanes, 7.5 against 7.8 ms at 12,500, 6.4 against 4.2 ms at 25,000; on uniformly random pixels
+// 5.3 against 7.7 ms at 8192 lanes, 4.7 against 3.9 ms at 16,384).
+static bool use_few_lane_kernels(const Geo &g, bool decode)
 {
     if (g_kernel_policy == 1) return false;
-    if (g_kernel_policy >= 2) return true;
+    if (g_kernel_policy == 2) return true;
     return g.lanes <= (decode ? 12288u : 28672u);
-}
-
-// Threads per lane of the few-lane decoder: enough lanes per wavefront that no SIMD has to host
-// more than two wavefronts (1024 SIMDs), as few as possible otherwise (wider candidate windows).
-static int decode_group_size(const Geo &g)
-{
-    if (g_kernel_policy == 0 || g_kernel_policy == 2 || g_kernel_policy == 8) return 0;  // rows of 16
-    if (g_kernel_policy == 3) return 64;
-    if (g_kernel_policy == 4) return 32;
-    if (g_kernel_policy == 5) return 16;
-    if (g_kernel_policy == 7) return 17;
-    if (g.lanes <= 2048u) return 64;
-    if (g.lanes <= 4096u) return 32;
-    return 16;
 }
 
 thread_local char t_hip_error[256] = "";
@@ -604,7 +587,7 @@ void pilc_set_timing(int enabled) { g_timing_enabled = enabled; }
 
 int pilc_set_kernel_policy(int policy)
 {
-    if (policy < 0 || policy > 8) return PILC_E_ARG;
+    if (policy < 0 || policy > 2) return PILC_E_ARG;
     g_kernel_policy = policy;
     return PILC_OK;
 }
@@ -684,7 +667,7 @@ static int encode_checked(const Geo &g, const uint8_t *img_dev, const pilc_param
 
     Timer timer(stream, timed);
     k_init_status<<<1, 1, 0, stream>>>(status);
-    const bool few_lanes = use_wave_kernels(g, false);
+    const bool few_lanes = use_few_lane_kernels(g, false);
     const uint32_t lane_cap = few_lanes ? 0u : max_lane_symbols(g);  // selects the scratch layout
     if (few_lanes) {
         k_encode_block<<<(uint32_t)ceil_div64(g.lanes, kEncLanes), kEncThreads, 0, stream>>>(
@@ -825,46 +808,21 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
     Timer timer(stream);
     k_check_header<<<1, 1, 0, stream>>>(g, kMagicPilc, 0u, coded_dev, (unsigned long long)coded_bytes, status);
     timer.mark("k_check_header");
-    const bool few_lanes = use_wave_kernels(g, true);
+    const bool few_lanes = use_few_lane_kernels(g, true);
     if (few_lanes) {
-        const int gs = decode_group_size(g);  // 17: 16 threads per lane with two candidates each
-        const uint32_t waves = (uint32_t)ceil_div64(g.lanes, gs == 17 ? 4 : 64 / (gs ? gs : 64));
-        const uint32_t blocks = (uint32_t)ceil_div64(waves, kGroupWavesPerBlock);
-        const int bt = 64 * kGroupWavesPerBlock;
-        if (gs == 0) {
-            // all lanes alike and made of whole batches of 16 pixels: no per-row activity masks
-            const bool even = g.lane_mode == 0 ? (g.lane_a % kRowBatch == 0 && g.total_px % g.lane_a == 0)
-                                               : (g.h % g.lane_a == 0 && g.w % g.lane_b == 0 &&
-                                                  (g.lane_a * g.lane_b) % kRowBatch == 0);
-            const uint32_t nblk = (uint32_t)ceil_div64(g.lanes, kRowLanes);
-            if (even)
-                k_decode_rows<false><<<nblk, 64 * kRowWaves, 0, stream>>>(
-                    g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev,
-                    &status->code, &status->payload_bytes);
-            else
-                k_decode_rows<true><<<nblk, 64 * kRowWaves, 0, stream>>>(
-                    g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev,
-                    &status->code, &status->payload_bytes);
-        } else if (g_kernel_policy == 6)
-            k_decode_wave<<<(uint32_t)ceil_div64(g.lanes, kWavesPerBlock), 64 * kWavesPerBlock, 0, stream>>>(
+        // all lanes alike and made of whole batches of 16 pixels: no per-row activity masks
+        const bool even = g.lane_mode == 0 ? (g.lane_a % kRowBatch == 0 && g.total_px % g.lane_a == 0)
+                                           : (g.h % g.lane_a == 0 && g.w % g.lane_b == 0 &&
+                                              (g.lane_a * g.lane_b) % kRowBatch == 0);
+        const uint32_t nblk = (uint32_t)ceil_div64(g.lanes, kRowLanes);
+        if (even)
+            k_decode_rows<false><<<nblk, 64 * kRowWaves, 0, stream>>>(
                 g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev,
                 &status->code, &status->payload_bytes);
-        else if (gs == 64)
-            k_decode_group<64, 1><<<blocks, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
-                                                          params->chan_coef, img_out_dev, &status->code,
-                                                          &status->payload_bytes);
-        else if (gs == 32)
-            k_decode_group<32, 1><<<blocks, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
-                                                          params->chan_coef, img_out_dev, &status->code,
-                                                          &status->payload_bytes);
-        else if (gs == 16)
-            k_decode_group<16, 1><<<blocks, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
-                                                             params->chan_coef, img_out_dev, &status->code,
-                                                             &status->payload_bytes);
         else
-            k_decode_group<16, 2><<<blocks, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
-                                                             params->chan_coef, img_out_dev, &status->code,
-                                                             &status->payload_bytes);
+            k_decode_rows<true><<<nblk, 64 * kRowWaves, 0, stream>>>(
+                g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev,
+                &status->code, &status->payload_bytes);
     } else {
         const int bt = lane_block_threads(g);
         const uint32_t nb = (uint32_t)ceil_div64(g.lanes, bt);
@@ -882,9 +840,7 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
                                                                 img_out_dev, &status->code,
                                                                 &status->payload_bytes);
     }
-    timer.mark(few_lanes ? (decode_group_size(g) == 0 ? "k_decode_rows"
-                                                      : (g_kernel_policy == 6 ? "k_decode_wave" : "k_decode_group"))
-                         : "k_decode_lanes");
+    timer.mark(few_lanes ? "k_decode_rows" : "k_decode_lanes");
     HIP_TRY(hipGetLastError());
     Status host_status;
     HIP_TRY(hipMemcpyAsync(&host_status, status, sizeof(Status), hipMemcpyDeviceToHost, stream));

@@ -81,6 +81,13 @@ __device__ __forceinline__ LaneShape lane_shape(const Geo &g, uint32_t lane)
     return s;
 }
 
+// Flat pixel index of the t-th pixel of a lane (rows of sh.tw pixels, g.w apart).
+__device__ __forceinline__ uint32_t lane_pixel(const Geo &g, const LaneShape &sh, uint32_t t)
+{
+    uint32_t row = t / sh.tw;
+    return sh.first + row * g.w + (t - row * sh.tw);
+}
+
 // Rounded Q2.14 * Q8.8 product: floor((v + 2^13) / 2^14).
 __device__ __forceinline__ int rsh14(int v) { return (v + 8192) >> 14; }
 

@@ -40,6 +40,8 @@ constexpr int kRowWords = 112;                // stream words kept per lane and 
                                               // most 48 and is fetched before the previous one's 48
 constexpr int kRowWindow = 32;                // candidates per symbol
 constexpr int kRowBaseMax = 256 - kRowWindow; // window bases 0..224: candidates stay within 0..255
+constexpr int kRowRedoLimit = 4;              // a batch with this many pixels outside their windows sends
+constexpr int kRowSearchBatches = 7;          // the wavefront's next 7 batches straight to the search
 
 // OR over the 16 threads of a row, result in every thread: rotate right by 1, 2, 4, 8 and OR.
 __device__ __forceinline__ uint32_t row_or(uint32_t v)
@@ -303,6 +305,7 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_decode_rows(
         return (uint32_t)kb + n - 1u;
     };
 
+    uint32_t search_batches = 0;  // wavefront-uniform: batches still to decode by search alone
     // ---- prologue: batch 0 staged, batch 1 in flight ----
     put_stage(fetch_raw(0), 0);
     Raw raw_next = fetch_raw(kRowBatch);
@@ -331,64 +334,88 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_decode_rows(
 
         const RowPixel *px = stage[buf][lrow];
         uint32_t v_out = 0;
-        // One pixel: `cur` holds its parameters (read from LDS a pixel ago), `nxt` receives the
-        // next pixel's, and `cr` enters with this pixel's first-channel candidates and leaves with
-        // the next pixel's.
-        auto pixel = [&](uint32_t i, const RowPixel &cur, RowPixel &nxt, RowCand &cr) {
-            const bool act = i < nb;
-            nxt = px[(i + 1u) & (kRowBatch - 1)];
+        // The three symbols of a pixel by search, on the state (Sr, pr).
+        auto search_pixel = [&](const RowPixel &cur, uint32_t &Sr, uint32_t &pr, uint32_t &y_r, uint32_t &y_g,
+                                uint32_t &y_b) {
             const int m_r = (int)cur.r.x, m_g = (int)cur.a.x, m_b = (int)cur.a.y;
             const int a_gr = (int)cur.a.z, a_br = (int)cur.a.w, a_bg = (int)cur.b.x;
-            const uint32_t S0 = S, pos0 = pos;
-            uint32_t seen = 256u;
-
-            uint32_t x_r = decode_symbol(act, cr, seen);
-            const int e_r = (int)(x_r << 8) - m_r;
-            const int me_g = m_g + rsh14_mad(a_gr, e_r);
-            const RowAim ag = aim(me_g, cur.b.y, cur.b.z);
-            __builtin_amdgcn_sched_barrier(0);
-            // the next pixel's first channel depends on no decoded value: its arithmetic fills the
-            // waits for the table cells of the two channels that do
-            const RowAim an = aim((int)nxt.r.x, nxt.r.y, nxt.r.z);
-            const int mb1 = m_b + rsh14_mad(a_br, e_r);
-            __builtin_amdgcn_sched_barrier(0);
-            const RowCand cg = finish(ag);
-            uint32_t x_g = decode_symbol(act, cg, seen);
-            const int me_b = mb1 + rsh14_mad(a_bg, (int)(x_g << 8) - m_g);
-            const RowAim ab = aim(me_b, cur.b.w, cur.c.x);
-            __builtin_amdgcn_sched_barrier(0);
-            cr = finish(an);
-            __builtin_amdgcn_sched_barrier(0);
-            const RowCand cb = finish(ab);
-            uint32_t x_b = decode_symbol(act, cb, seen);
-
-            bool bad = (seen & 256u) == 0u;
-            if (kRagged) bad = bad && act;
-            if (__builtin_expect(__any(bad), 0)) {
-                // the pixel once more, from the state at its start, for the rows that need it
-                uint32_t Sr = S0, pr = pos0;
-                const uint32_t y_r = search_symbol(m_r, cur.r.w, Sr, pr);
-                const int f_r = (int)(y_r << 8) - m_r;
-                const int ne_g = m_g + rsh14_mul(a_gr, f_r);
-                const uint32_t y_g = search_symbol(ne_g, cur.c.y, Sr, pr);
-                const int ne_b = m_b + rsh14_mul(a_br, f_r) + rsh14_mul(a_bg, (int)(y_g << 8) - m_g);
-                const uint32_t y_b = search_symbol(ne_b, cur.c.z, Sr, pr);
-                if (bad) {
+            y_r = search_symbol(m_r, cur.r.w, Sr, pr);
+            const int f_r = (int)(y_r << 8) - m_r;
+            y_g = search_symbol(m_g + rsh14_mul(a_gr, f_r), cur.c.y, Sr, pr);
+            y_b = search_symbol(m_b + rsh14_mul(a_br, f_r) + rsh14_mul(a_bg, (int)(y_g << 8) - m_g), cur.c.z,
+                                Sr, pr);
+        };
+        if (search_batches != 0) {
+            // data the model does not fit (such as uniformly random pixels): the windows are not tried
+            --search_batches;
+            for (uint32_t i = 0; kRagged ? __any(i < nb) : i < (uint32_t)kRowBatch; ++i) {
+                uint32_t Sr = S, pr = pos, y_r, y_g, y_b;
+                search_pixel(px[i], Sr, pr, y_r, y_g, y_b);
+                if (!kRagged || i < nb) {
                     S = Sr;
                     pos = pr;
-                    x_r = y_r;
-                    x_g = y_g;
-                    x_b = y_b;
                 }
-                wnext = my_words[pos - wbase];
+                v_out = j == i ? (y_r | (y_g << 8) | (y_b << 16)) : v_out;
             }
-            v_out = j == i ? (x_r | (x_g << 8) | (x_b << 16)) : v_out;
-        };
-        RowPixel pe = px[0], po;
-        RowCand cr = candidates((int)pe.r.x, pe.r.y, pe.r.z);
-        for (uint32_t i = 0; kRagged ? __any(i < nb) : i < (uint32_t)kRowBatch; i += 2) {
-            pixel(i, pe, po, cr);
-            pixel(i + 1u, po, pe, cr);
+        } else {
+            uint32_t redone = 0;  // pixels of this batch that had a symbol outside its window
+            // One pixel: `cur` holds its parameters (read from LDS a pixel ago), `nxt` receives the
+            // next pixel's, and `cr` enters with this pixel's first-channel candidates and leaves
+            // with the next pixel's.
+            auto pixel = [&](uint32_t i, const RowPixel &cur, RowPixel &nxt, RowCand &cr) {
+                const bool act = i < nb;
+                nxt = px[(i + 1u) & (kRowBatch - 1)];
+                __builtin_amdgcn_sched_barrier(0);  // asked for here, used a pixel later
+                const int m_r = (int)cur.r.x, m_g = (int)cur.a.x, m_b = (int)cur.a.y;
+                const int a_gr = (int)cur.a.z, a_br = (int)cur.a.w, a_bg = (int)cur.b.x;
+                const uint32_t S0 = S, pos0 = pos;
+                uint32_t seen = 256u;
+
+                uint32_t x_r = decode_symbol(act, cr, seen);
+                const int e_r = (int)(x_r << 8) - m_r;
+                const int me_g = m_g + rsh14_mad(a_gr, e_r);
+                const RowAim ag = aim(me_g, cur.b.y, cur.b.z);
+                __builtin_amdgcn_sched_barrier(0);
+                // the next pixel's first channel depends on no decoded value: its arithmetic fills
+                // the waits for the table cells of the two channels that do
+                const RowAim an = aim((int)nxt.r.x, nxt.r.y, nxt.r.z);
+                const int mb1 = m_b + rsh14_mad(a_br, e_r);
+                __builtin_amdgcn_sched_barrier(0);
+                const RowCand cg = finish(ag);
+                uint32_t x_g = decode_symbol(act, cg, seen);
+                const int me_b = mb1 + rsh14_mad(a_bg, (int)(x_g << 8) - m_g);
+                const RowAim ab = aim(me_b, cur.b.w, cur.c.x);
+                __builtin_amdgcn_sched_barrier(0);
+                cr = finish(an);
+                __builtin_amdgcn_sched_barrier(0);
+                const RowCand cb = finish(ab);
+                uint32_t x_b = decode_symbol(act, cb, seen);
+
+                bool bad = (seen & 256u) == 0u;
+                if (kRagged) bad = bad && act;
+                if (__builtin_expect(__any(bad), 0)) {
+                    // the pixel once more, from the state at its start, for the rows that need it
+                    uint32_t Sr = S0, pr = pos0, y_r, y_g, y_b;
+                    search_pixel(cur, Sr, pr, y_r, y_g, y_b);
+                    if (bad) {
+                        S = Sr;
+                        pos = pr;
+                        x_r = y_r;
+                        x_g = y_g;
+                        x_b = y_b;
+                    }
+                    wnext = my_words[pos - wbase];
+                    ++redone;
+                }
+                v_out = j == i ? (x_r | (x_g << 8) | (x_b << 16)) : v_out;
+            };
+            RowPixel pe = px[0], po;
+            RowCand cr = candidates((int)pe.r.x, pe.r.y, pe.r.z);
+            for (uint32_t i = 0; kRagged ? __any(i < nb) : i < (uint32_t)kRowBatch; i += 2) {
+                pixel(i, pe, po, cr);
+                pixel(i + 1u, po, pe, cr);
+            }
+            if (redone >= (uint32_t)kRowRedoLimit) search_batches = kRowSearchBatches;
         }
         if (j < nb && has_lane) {
             const size_t s = (size_t)lane_pixel(g, sh, t0 + j) * 3;

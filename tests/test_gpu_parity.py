@@ -17,14 +17,23 @@ def _ogeom(wl):
     return orc.make_geom(*wl.geom)
 
 
-@pytest.fixture(params=[1, 3, 4, 5, 6, 7, 8],
-                ids=["thread-per-lane", "few-lane-64", "few-lane-32", "few-lane-16", "few-lane-scalar",
-                     "few-lane-16x2", "few-lane-rows"])
+@pytest.fixture(params=[1, 2], ids=["thread-per-lane", "few-lane"])
 def policy(request):
     """Runs a test once with each lane-kernel family forced."""
     pb.pilc_set_kernel_policy(request.param)
     yield request.param
     pb.pilc_set_kernel_policy(0)
+
+
+def _alternating_fit():
+    """CIFAR-shaped lanes of 16 images in which every other run of 4 images is uniformly random
+    while the parameters still describe the smooth images: the few-lane decoder has to go from
+    its windows to the search and back several times inside a lane."""
+    wl = synth.make_workload(1, 16 * 9)
+    rng = np.random.default_rng(5)
+    for i0 in range(4, wl.n, 8):
+        wl.img[i0:i0 + 4] = rng.integers(0, 256, size=wl.img[i0:i0 + 4].shape, dtype=np.uint8)
+    return wl
 
 
 SMALL_CASES = [
@@ -35,6 +44,8 @@ SMALL_CASES = [
     ("cfg3-clipped-tiles", lambda: synth.make_workload(3, 2, h=88, w=200)),
     ("cfg4-M12-L1", lambda: synth.make_workload(4, 8, h=64, w=64, prec_bits=12, lanes_per_image=1)),
     ("cfg4-M16-L16", lambda: synth.make_workload(4, 8, h=64, w=64, prec_bits=16, lanes_per_image=16)),
+    ("cfg4-M16-L1-mixed-wavefront", lambda: synth.make_workload(4, 6, h=64, w=64, prec_bits=16, lanes_per_image=1)),
+    ("cfg1-fit-and-random-runs", _alternating_fit),
     ("cfg4-M12-L1024", lambda: synth.make_workload(4, 8, h=64, w=64, prec_bits=12, lanes_per_image=1024)),
     ("cfg4-M16-L1024", lambda: synth.make_workload(4, 6, h=64, w=64, prec_bits=16, lanes_per_image=1024)),
     ("wild-flat-M10", lambda: synth.make_random_case(1, 37, 12, 10, 10, 0, 40, wild=True)),
