@@ -4,9 +4,7 @@
 A step is one pass of the whole path over one batch of synthetic input: pilc_encode (mean shift,
 fixed-point CDF -> (cum,freq), rANS lanes, offset scan, pack) followed by pilc_decode of the
 container it produced.  Inputs are resident in HBM before the timed region starts.  Prints one
-JSON line.
-
-Besides the contract fields the line carries
+JSON line: the headline workload (--config, default 1: the CIFAR-shaped batch) with
   roofline      dominant kernel of the step: algorithmic bytes / its HIP-event duration against
                 the 8 TB/s HBM peak, and `traffic` = HBM bytes of one launch read from two
                 rocprofv3 --pmc child runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same
@@ -14,14 +12,16 @@ Besides the contract fields the line carries
                 `plain_copy_GBs` is a device-to-device copy timed in the same run (read + written
                 bytes per second): the achievable figure beside the published peak;
   cpu_baseline  the CPU oracle timed on the host cores on a bounded prefix of the workload;
-  other_workloads  compress / decompress MB/s of the other single-GPU workloads (fewer steps).
+and, under other_workloads, the same three things (rates, roofline with traffic, cpu_baseline) for
+every other single-GPU workload: the tiny, ImageNet64-shaped, 1080p and entropy-extreme batches
+(the last at 12 and 16 bits of precision with 64 lanes per image on all 8192 images, and at 1 and
+1024 lanes per image on its first 512), the paper's own table-driven coder (Sec. 3.2 Algs. 3-4) on
+the recipe of its coder measurement (Sec. 4.3) and on the stream of vector indices (Sec. 3.1), the
+Three-Way AR residual transform (Sec. 3.1 eqs. (2)-(4)) on three image shapes, and the coder under
+a mixture of ten logistic laws (the workload Sec. 2 names).
 
---workload ansai times the paper's own table-driven coder (Sec. 3.2 Algs. 3-4) instead, on the
-recipe of its coder measurement (Sec. 4.3: 10^6 pieces of 1000 symbols, 8 distributions);
---workload twar the Three-Way AR residual transform (Sec. 3.1 eqs. (2)-(4)) on the images of
---config; --workload mix the coder under a mixture of --components logistic laws per subpixel
-(the workload Sec. 2 names) on ImageNet64-shaped rows.  The default run reports all three among
-other_workloads.
+--workload / --config / --prec-bits / --lanes-per-image / --images pick another headline;
+--no-extra leaves the other workloads out.
 """
 from __future__ import annotations
 
@@ -64,6 +64,8 @@ def parse_args():
                          "twar: the Three-Way AR residual transform on the images of --config; "
                          "mix: the coder under a mixture of --components logistic laws on the first "
                          "2048 images of config 2 (or --config 0/3, --images)")
+    ap.add_argument("--prec-bits", type=int, default=None, help="M of --config 4 (12 or 16)")
+    ap.add_argument("--lanes-per-image", type=int, default=None, help="lanes per image of --config 4")
     ap.add_argument("--images", type=int, default=None,
                     help="first N images (pilc) or pieces (ansai) only (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -72,66 +74,98 @@ def parse_args():
                     help="skip the two rocprofv3 --pmc child runs that measure HBM traffic")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     ap.add_argument("--pmc-child", action="store_true",
-                    help="internal: one warm-up and one step plus a device copy, no report extras")
+                    help="internal: one warm-up and one step of every workload of the run, each followed "
+                         "by a plain device copy; prints nothing")
     return ap.parse_args()
 
 
 # ----------------------------------------------------------------------------------------------
 # HBM traffic from rocprofv3 counters (child processes, started before this process touches HIP)
 # ----------------------------------------------------------------------------------------------
-def _run_pmc(counter: str, config: int, images, workload: str = "pilc", components: int = 10):
-    """Returns {kernel name prefix: [values in KiB per dispatch]} for one counter, or None."""
+def _run_pmc(counter: str, argv):
+    """One rocprofv3 --pmc run of `bench.py --pmc-child <argv>`.  Returns the dispatches in launch
+    order as (kernel name, counter value in KiB), or None."""
     exe = shutil.which("rocprofv3") or "/opt/rocm/bin/rocprofv3"
     if not os.path.exists(exe):
         return None
     out_dir = tempfile.mkdtemp(prefix="pilc_pmc_", dir="/tmp")
     cmd = [exe, "--pmc", counter, "-d", out_dir, "-o", "pmc", "--output-format", "csv", "--",
-           sys.executable, os.path.join(HERE, "bench.py"), "--pmc-child", "--config", str(config),
-           "--workload", workload, "--components", str(components)]
-    if images is not None:
-        cmd += ["--images", str(images)]
+           sys.executable, os.path.join(HERE, "bench.py"), "--pmc-child"] + argv
     env = dict(os.environ, TMPDIR="/tmp")
     try:
         proc = subprocess.Popen(cmd, cwd="/tmp", env=env, stdout=subprocess.DEVNULL,
                                 stderr=subprocess.DEVNULL, start_new_session=True)
         try:
-            proc.wait(timeout=240)
+            proc.wait(timeout=420)
         except subprocess.TimeoutExpired:
             os.killpg(proc.pid, signal.SIGKILL)
             proc.wait()
             return None
         if proc.returncode != 0:
             return None
-        rows = {}
+        rows = []
         for root, _, files in os.walk(out_dir):
             for f in files:
                 if f.endswith("counter_collection.csv"):
                     with open(os.path.join(root, f)) as fh:
                         for r in csv.DictReader(fh):
                             if r["Counter_Name"] == counter:
-                                name = r["Kernel_Name"].split("(")[0]
-                                rows.setdefault(name, []).append(float(r["Counter_Value"]))
-        return rows
-    except OSError:
+                                rows.append((int(r["Dispatch_Id"]), r["Kernel_Name"].split("(")[0],
+                                             float(r["Counter_Value"])))
+        rows.sort()
+        return [(name, value) for _, name, value in rows]
+    except (OSError, KeyError, ValueError):
         return None
     finally:
         shutil.rmtree(out_dir, ignore_errors=True)
 
 
-def measure_traffic(config: int, images, workload: str = "pilc", components: int = 10):
-    """HBM bytes per launch of every pilc kernel: counter value (KiB) x 1024 x scale, where
-    scale = known bytes of a plain device copy / what the counter read for that copy."""
-    result = {}
+COPY_KERNEL = "bitwise_not"   # the child's plain read-all-write-all pass between two workloads
+
+
+def measure_traffic(argv, count):
+    """HBM bytes per launch of the kernels of each of the `count` workloads of this run.  The
+    child runs them in order, each followed by a plain copy-like pass over a buffer of known
+    size, so those passes cut the launch sequence into one segment per workload.  Returns a list of
+    {"read": {kernel: KiB of its last launch}, "write": {...}, "read_copy_kib", "write_copy_kib"}
+    or None."""
+    out = [dict() for _ in range(count)]
     for counter, key in (("FETCH_SIZE", "read"), ("WRITE_SIZE", "write")):
-        rows = _run_pmc(counter, config, images, workload, components)
+        rows = _run_pmc(counter, argv)
         if not rows:
             return None
-        copies = rows.get("__amd_rocclr_copyBuffer", [])
-        if not copies:
+        seg, cur = [], {}
+        for name, value in rows:
+            if COPY_KERNEL in name:
+                seg.append((cur, value))
+                cur = {}
+            else:
+                cur[name] = value      # a later launch of the same kernel replaces the warm-up's
+        if len(seg) != count:
             return None
-        result[key] = rows
-        result[key + "_copy_kib"] = max(copies)
-    return result
+        for i, (kernels, copy_kib) in enumerate(seg):
+            out[i][key] = kernels
+            out[i][key + "_copy_kib"] = copy_kib
+    return out
+
+
+def traffic_of(kernel, seg, copy_bytes):
+    """(bytes, detail) of one launch of `kernel` from a segment of measure_traffic: counter value x
+    1024 x scale, scale = known bytes of the plain copy / what the counter read for that copy."""
+    if not seg:
+        return None, None
+    detail = {}
+    for key in ("read", "write"):
+        if not seg.get(key + "_copy_kib"):
+            return None, None
+        scale = copy_bytes / (seg[key + "_copy_kib"] * 1024.0)
+        vals = [v for name, v in seg[key].items()
+                if ("::" + kernel) in name and name.split("::" + kernel)[1][:1] in ("", "<")]
+        if not vals:
+            return None, None
+        detail[key + "_bytes"] = vals[-1] * 1024.0 * scale
+        detail[key + "_scale"] = scale
+    return detail["read_bytes"] + detail["write_bytes"], detail
 
 
 # ----------------------------------------------------------------------------------------------
@@ -194,7 +228,7 @@ def cpu_baseline(wl, sample_images):
 # One workload on the GPU
 # ----------------------------------------------------------------------------------------------
 class Run:
-    def __init__(self, config, images):
+    def __init__(self, config, images, prec_bits=None, lanes_per_image=None, workload=None):
         import torch
         from paper_2206_05279_amd import binding as pb
         from paper_2206_05279_amd import synth
@@ -202,7 +236,14 @@ class Run:
         self.torch, self.pb = torch, pb
         dev = torch.device("cuda:0")
         t = time.perf_counter()
-        self.wl = wl = synth.make_workload(config, images)
+        if workload is not None:
+            wl = workload          # arrays shared with another run of the same data
+        elif config == 4:
+            wl = synth.make_workload(4, images, prec_bits=prec_bits or 12, lanes_per_image=lanes_per_image or 64)
+        else:
+            wl = synth.make_workload(config, images)
+        self.wl = wl
+        self.config = config
         self.gen_s = time.perf_counter() - t
         self.geom = pb.make_geom(*wl.geom)
         self.img = torch.from_numpy(wl.img).to(dev)
@@ -219,6 +260,10 @@ class Run:
         self.probe_src = self.mu           # plain copy of known size: 2 bytes per subpixel
         self.probe_bytes = 4.0 * wl.subpixels
         self.step = "pilc_encode + pilc_decode of the whole batch"
+        self.cpu_sample = {0: 64, 1: 21504, 2: 5376, 3: 10, 4: 336}[config]
+
+    def cpu(self, scale=1.0):
+        return cpu_baseline(self.wl, max(1, int(self.cpu_sample * scale)))
 
     def algo_bytes(self, nbytes):
         # either lane kernel: 1 B pixel + 2 B mu + 2 B log-scale per subpixel, plus the container
@@ -338,11 +383,16 @@ class PieceRun:
         self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
         self.coded = torch.empty(max_coded, dtype=torch.uint8, device=dev)
         self.out = torch.empty_like(self.sym)
-        self.name = "%s, %d symbols, X=%d" % (wl.name, wl.symbols, x)
+        self.name = "table-driven coder (Sec. 3.2 Algs. 3-4): %s, %d symbols, X=%d" % (wl.name, wl.symbols, x)
+        self.bits_key = "bits_per_symbol"
         self.raw = wl.symbols
         self.probe_src = self.sym          # plain copy of known size: 1 byte per symbol
         self.probe_bytes = 2.0 * wl.symbols
         self.step = "pilc_ansai_encode + pilc_ansai_decode of the whole batch"
+        self.cpu_sample = 131072 * 1000 // wl.count
+
+    def cpu(self, scale=1.0):
+        return cpu_baseline_pieces(self.wl, max(64, int(self.cpu_sample * scale)))
 
     def algo_bytes(self, nbytes):
         # either coder kernel: symbols and distribution indices (1 byte each) plus the coded words
@@ -406,11 +456,16 @@ class TwarRun:
         self.res = torch.empty_like(self.img)
         self.out = torch.empty_like(self.img)
         self.params = pb.make_twar_params(*TWAR_WEIGHTS)
-        self.name = "cfg%d %s images: %d x %dx%dx3 uint8" % (config, wl.name, wl.n, wl.h, wl.w)
+        self.name = "Three-Way AR transform (Sec. 3.1 eqs. 2-4): cfg%d %s images: %d x %dx%dx3 uint8" % (
+            config, wl.name, wl.n, wl.h, wl.w)
         self.raw = wl.subpixels
         self.probe_src = self.img
         self.probe_bytes = 2.0 * wl.subpixels
         self.step = "pilc_twar_forward + pilc_twar_inverse of the whole batch"
+        self.cpu_sample = max(1, 61440000 // (wl.h * wl.w * 3))     # about 60 MB of images
+
+    def cpu(self, scale=1.0):
+        return cpu_baseline_twar(self.img_np, max(1, int(self.cpu_sample * scale)))
 
     def algo_bytes(self, nbytes):
         return 2.0 * self.raw  # either kernel reads and writes every subpixel once
@@ -504,12 +559,16 @@ class MixRun:
         self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
         self.coded = torch.empty(max_coded, dtype=torch.uint8, device=dev)
         self.out = torch.empty_like(self.img)
-        self.name = "cfg%d %s: %d x %dx%dx3 uint8, K=%d, M=%d, %d lanes" % (
+        self.name = "mixture of logistic laws (Sec. 2): cfg%d %s: %d x %dx%dx3 uint8, K=%d, M=%d, %d lanes" % (
             config, wl.name, wl.n, wl.h, wl.w, self.k, wl.prec_bits, pb.pilc_lane_count(self.geom))
         self.raw = wl.subpixels
         self.probe_src = self.img
         self.probe_bytes = 2.0 * wl.subpixels
         self.step = "pilc_mix_encode + pilc_mix_decode of the whole batch"
+        self.cpu_sample = 1024
+
+    def cpu(self, scale=1.0):
+        return cpu_baseline_mix(self.wl, max(1, int(self.cpu_sample * scale)))
 
     def algo_bytes(self, nbytes):
         # either lane kernel: per subpixel 1 B pixel, 2 K B means, 2 K B log-scales and a third of the
@@ -555,163 +614,174 @@ def copy_bandwidth(torch, src, reps=10):
     return 2.0 * src.numel() * src.element_size() * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
+def headline_run(args):
+    if args.workload == "mix":
+        return MixRun(args.config, args.images, args.components)
+    if args.workload == "ansai":
+        return PieceRun(args.config if args.config in (0, 1, 2) else 1, args.images)
+    if args.workload == "twar":
+        return TwarRun(args.config, args.images)
+    return Run(args.config, args.images, args.prec_bits, args.lanes_per_image)
+
+
+def other_runs(args):
+    """The other workloads of the default run, as (label, factory) in the order they are run; a
+    factory may return several runs that share their input arrays."""
+    import dataclasses
+
+    def stress():
+        from paper_2206_05279_amd import synth
+        full = synth.make_workload(4, None, prec_bits=12, lanes_per_image=64)
+        px = full.h * full.w
+        yield Run(4, None, workload=full)
+        yield Run(4, None, workload=dataclasses.replace(full, prec_bits=16, name="entropy-extreme-M16-L64"))
+        half = full.n // 2
+        pick = np.r_[0:256, half:half + 256]     # 256 random and 256 constant images
+        sub = dataclasses.replace(full, n=512, img=np.ascontiguousarray(full.img[pick]),
+                                  mu=np.ascontiguousarray(full.mu[pick]),
+                                  log_scale=np.ascontiguousarray(full.log_scale[pick]),
+                                  chan_coef=np.ascontiguousarray(full.chan_coef[pick]))
+        del full
+        yield Run(4, None, workload=dataclasses.replace(sub, lane_a=px, name="entropy-extreme-M12-L1 (512 images)"))
+        yield Run(4, None, workload=dataclasses.replace(sub, lane_a=px // 1024,
+                                                        name="entropy-extreme-M12-L1024 (512 images)"))
+
+    plan = [(lambda c=c: [Run(c, None)]) for c in (0, 2, 3) if not (args.workload == "pilc" and args.config == c)]
+    if not (args.workload == "pilc" and args.config == 1):
+        plan.insert(1, lambda: [Run(1, None)])
+    plan += [stress,
+             lambda: [PieceRun(1, None)],      # the paper's own coder variant on its coder-measurement recipe
+             lambda: [PieceRun(2, None)],      # the stream of vector indices
+             lambda: [TwarRun(1, None)], lambda: [TwarRun(2, None)], lambda: [TwarRun(3, None)],
+             lambda: [MixRun(2, None, 10)]]    # the dynamic-coder workload Sec. 2 names as the slow case
+    return plan
+
+
+def report(run, r, seg, torch, with_copy=False):
+    """The figures of one workload: rates, the dominant kernel against the roofline, traffic."""
+    kernel_ms, nbytes = r["kernel_ms"], r["nbytes"]
+    dom = max(kernel_ms, key=kernel_ms.get)
+    algo = run.algo_bytes(nbytes)
+    achieved = algo / (kernel_ms[dom] * 1e-3) / 1e9
+    traffic, detail = traffic_of(dom, seg, run.probe_bytes / 2.0)
+    twar = isinstance(run, TwarRun)
+    out = {
+        "step": run.step,
+        ("forward_MB_s" if twar else "compress_MB_s"): r["compress_MB_s"],
+        ("inverse_MB_s" if twar else "decompress_MB_s"): r["decompress_MB_s"],
+        "round_trip_exact": r["ok"],
+        "kernel_ms": kernel_ms,
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_detail": detail,
+                     "algorithmic_bytes": algo, "avg_ms": kernel_ms[dom]},
+    }
+    if not twar:
+        out[getattr(run, "bits_key", "bits_per_subpixel")] = 8.0 * nbytes / r["raw"]
+        out["coded_bytes"] = nbytes
+    if with_copy:
+        out["roofline"]["plain_copy_GBs"] = copy_bandwidth(torch, run.probe_src)
+    if isinstance(run, Run) and run.config == 3:
+        out["video_1080p30"] = video_margin(r, run.wl.n)
+    return out
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU runs are not "
               "part of it", file=sys.stderr)
         sys.exit(2)
+    extras = not args.no_extra and args.images is None
 
     # children first: this process has not initialised HIP yet
-    traffic = None
-    if not (args.no_traffic or args.pmc_child):
-        traffic = measure_traffic(args.config, args.images, args.workload, args.components)
+    child_argv = ["--config", str(args.config), "--workload", args.workload, "--components", str(args.components)]
+    for flag, val in (("--images", args.images), ("--prec-bits", args.prec_bits),
+                      ("--lanes-per-image", args.lanes_per_image)):
+        if val is not None:
+            child_argv += [flag, str(val)]
+    if not extras:
+        child_argv.append("--no-extra")
 
     import torch
     from paper_2206_05279_amd import binding as pb
+
+    def all_runs():
+        yield headline_run(args)
+        if extras:
+            for factory in other_runs(args):
+                for run in factory():
+                    yield run
+                torch.cuda.empty_cache()
+
+    if args.pmc_child:
+        if not torch.cuda.is_available():
+            sys.exit(3)
+        pb.lib()
+        for run in all_runs():
+            run.timed(1, 1)
+            # a plain pass over a buffer of known size (every byte read once and written once) under
+            # a kernel name nothing else here uses: it ends the workload's segment and calibrates
+            src = run.probe_src.view(torch.uint8)
+            probe = torch.empty_like(src)
+            torch.bitwise_not(src, out=probe)
+            torch.cuda.synchronize()
+            del probe, src, run
+        return
+
+    traffic = None
+    if not args.no_traffic:
+        # the number of workloads is known without building them: 1 + what other_runs yields
+        count = 1 + ((len(other_runs(args)) - 1 + 4) if extras else 0)
+        traffic = measure_traffic(child_argv, count)
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     pb.lib()
 
-    ansai, twar, mix = args.workload == "ansai", args.workload == "twar", args.workload == "mix"
-    if mix:
-        run = MixRun(args.config, args.images, args.components)
-    elif ansai:
-        run = PieceRun(1 if args.config not in (0, 1) else args.config, args.images)
-    elif twar:
-        run = TwarRun(args.config, args.images)
-    else:
-        run = Run(args.config, args.images)
-    if args.pmc_child:
-        run.timed(1, 1)
-        probe = torch.empty_like(run.probe_src)   # plain device copy of known size
-        probe.copy_(run.probe_src)
-        torch.cuda.synchronize()
-        return
-    r = run.timed(args.steps, args.warmup)
-    raw_bytes, nbytes, kernel_ms = r["raw"], r["nbytes"], r["kernel_ms"]
-    dom = max(kernel_ms, key=kernel_ms.get)
-    algo_bytes = run.algo_bytes(nbytes)
-    achieved = algo_bytes / (kernel_ms[dom] * 1e-3) / 1e9
-    traffic_bytes, traffic_detail = None, None
-    if traffic:
-        copy_bytes = run.probe_bytes / 2.0  # bytes the probe copy reads (and writes)
-        detail = {}
-        for key in ("read", "write"):
-            scale = copy_bytes / (traffic[key + "_copy_kib"] * 1024.0)
-            vals = [v for name, rows in traffic[key].items()
-                    if ("::" + dom) in name and name.split("::" + dom)[1][:1] in ("", "<") for v in rows]
-            if vals:
-                detail[key + "_bytes"] = sum(vals) / len(vals) * 1024.0 * scale
-                detail[key + "_scale"] = scale
-        if "read_bytes" in detail and "write_bytes" in detail:
-            traffic_bytes = detail["read_bytes"] + detail["write_bytes"]
-            traffic_detail = detail
-    result = {
-        "metric": METRIC_ANSAI if ansai else (METRIC_TWAR if twar else (METRIC_MIX if mix else METRIC)),
-        "value": raw_bytes / 1e6 / (r["elapsed"] / args.steps),
-        "unit": "MB/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": 1e3 * r["elapsed"] / args.steps,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "u32",
-        "data": "synthetic",
-        "config": {"workload": run.name, "step": run.step},
-        "compress_MB_s": r["compress_MB_s"],
-        "decompress_MB_s": r["decompress_MB_s"],
-        ("bits_per_symbol" if ansai else "bits_per_subpixel"): None if twar else 8.0 * nbytes / raw_bytes,
-        "coded_bytes": nbytes,
-        "round_trip_exact": r["ok"],
-        "kernel_ms": kernel_ms,
-        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_bytes,
-                     "traffic_detail": traffic_detail, "algorithmic_bytes": algo_bytes,
-                     "avg_ms": kernel_ms[dom],
-                     "plain_copy_GBs": copy_bandwidth(torch, run.probe_src)},
-        "paper_context": "PILC reports about 200 MB/s end to end and 675/672 MB/s for its coder "
-                         "phases on one V100 (table-driven coder; Tab. 5 of the paper, another "
-                         "machine and workload: context, not a baseline)",
-        "input_generation_s": run.gen_s,
-    }
-    ok = r["ok"]
-    if args.workload == "pilc" and args.config == 3:
-        result["video_1080p30"] = video_margin(r, run.wl.n)
-    if not args.no_cpu_baseline:
-        if mix:
-            result["cpu_baseline"] = cpu_baseline_mix(run.wl, args.cpu_sample_images or 1024)
-        elif ansai:
-            result["cpu_baseline"] = cpu_baseline_pieces(run.wl, args.cpu_sample_images or 131072)
-        elif twar:
-            result["cpu_baseline"] = cpu_baseline_twar(run.img_np, args.cpu_sample_images or 20000)
-        else:
-            sample = args.cpu_sample_images or {0: 64, 1: 21504, 2: 5376, 3: 10, 4: 336}[args.config]
-            result["cpu_baseline"] = cpu_baseline(run.wl, sample)
-    if not args.no_extra and args.images is None and not ansai and not twar and not mix:
-        extra = {}
-        del run
-        torch.cuda.empty_cache()
-        for cfg in (2, 3):
-            if cfg == args.config:
-                continue
-            other = Run(cfg, None)
-            o = other.timed(max(2, args.steps // 3), 1)
-            dk = max(o["kernel_ms"], key=o["kernel_ms"].get)
-            ab = 5.0 * o["raw"] + o["nbytes"]
-            extra[other.name] = {
-                "compress_MB_s": o["compress_MB_s"], "decompress_MB_s": o["decompress_MB_s"],
-                "bits_per_subpixel": 8.0 * o["nbytes"] / o["raw"], "round_trip_exact": o["ok"],
-                "kernel_ms": o["kernel_ms"],
-                "dominant_kernel_hbm_frac": ab / (o["kernel_ms"][dk] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+    result, others, ok = None, {}, True
+    for i, run in enumerate(all_runs()):
+        seg = traffic[i] if traffic else None
+        if i == 0:
+            r = run.timed(args.steps, args.warmup)
+            rep = report(run, r, seg, torch, with_copy=True)
+            result = {
+                "metric": {PieceRun: METRIC_ANSAI, TwarRun: METRIC_TWAR, MixRun: METRIC_MIX}.get(type(run), METRIC),
+                "value": r["raw"] / 1e6 / (r["elapsed"] / args.steps),
+                "unit": "MB/s",
+                "n_gpus": 1,
+                "steps": args.steps,
+                "warmup": args.warmup,
+                "ms_per_step": 1e3 * r["elapsed"] / args.steps,
+                "higher_is_better": True,
+                "scaling": "weak",
+                "vs_baseline": None,
+                "dtype": "u32",
+                "data": "synthetic",
+                "config": {"workload": run.name, "step": run.step},
             }
-            if cfg == 3:  # against the 1080p at 30 frames a second that Sec. 1 of the paper asks for
-                extra[other.name]["video_1080p30"] = video_margin(o, other.wl.n)
-            ok = ok and o["ok"]
-            del other
-            torch.cuda.empty_cache()
-        other = PieceRun(1, None)   # the paper's own coder variant on its coder-measurement recipe
-        o = other.timed(max(2, args.steps // 3), 1)
-        dk = max(o["kernel_ms"], key=o["kernel_ms"].get)
-        extra["table-driven coder (Sec. 3.2 Algs. 3-4): " + other.name] = {
-            "compress_MB_s": o["compress_MB_s"], "decompress_MB_s": o["decompress_MB_s"],
-            "bits_per_symbol": 8.0 * o["nbytes"] / o["raw"], "round_trip_exact": o["ok"],
-            "kernel_ms": o["kernel_ms"],
-            "dominant_kernel_hbm_frac": other.algo_bytes(o["nbytes"]) / (o["kernel_ms"][dk] * 1e-3) / 1e9
-                                        / HBM_PEAK_GBS,
-        }
-        ok = ok and o["ok"]
-        del other
-        torch.cuda.empty_cache()
-        other = TwarRun(args.config, None)   # the residual transform either side of the coder
-        o = other.timed(max(2, args.steps // 3), 1)
-        dk = max(o["kernel_ms"], key=o["kernel_ms"].get)
-        extra["Three-Way AR transform (Sec. 3.1 eqs. 2-4): " + other.name] = {
-            "forward_MB_s": o["compress_MB_s"], "inverse_MB_s": o["decompress_MB_s"],
-            "round_trip_exact": o["ok"], "kernel_ms": o["kernel_ms"],
-            "dominant_kernel_hbm_frac": other.algo_bytes(0) / (o["kernel_ms"][dk] * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        }
-        ok = ok and o["ok"]
-        del other
-        torch.cuda.empty_cache()
-        other = MixRun(2, None, 10)   # the dynamic-coder workload Sec. 2 names as the slow case
-        o = other.timed(2, 1)
-        dk = max(o["kernel_ms"], key=o["kernel_ms"].get)
-        extra["mixture of 10 logistic laws (Sec. 2): " + other.name] = {
-            "compress_MB_s": o["compress_MB_s"], "decompress_MB_s": o["decompress_MB_s"],
-            "bits_per_subpixel": 8.0 * o["nbytes"] / o["raw"], "round_trip_exact": o["ok"],
-            "kernel_ms": o["kernel_ms"],
-            "dominant_kernel_hbm_frac": other.algo_bytes(o["nbytes"]) / (o["kernel_ms"][dk] * 1e-3) / 1e9
-                                        / HBM_PEAK_GBS,
-        }
-        ok = ok and o["ok"]
-        del other
-        torch.cuda.empty_cache()
-        result["other_workloads"] = extra
+            rep.pop("step")
+            result.update(rep)
+            result["paper_context"] = ("PILC reports about 200 MB/s end to end and 675/672 MB/s for its coder "
+                                       "phases on one V100 (table-driven coder; Tab. 5 of the paper, another "
+                                       "machine and workload: context, not a baseline)")
+            result["input_generation_s"] = run.gen_s
+            if not args.no_cpu_baseline:
+                if args.cpu_sample_images:
+                    run.cpu_sample = args.cpu_sample_images
+                result["cpu_baseline"] = run.cpu()
+        else:
+            r = run.timed(max(3, args.steps // 3), 1)
+            rep = report(run, r, seg, torch)
+            rep["value"] = r["raw"] / 1e6 / (r["elapsed"] / max(3, args.steps // 3))
+            rep["unit"] = "MB/s"
+            if not args.no_cpu_baseline:
+                rep["cpu_baseline"] = run.cpu(0.35)
+            others[run.name] = rep
+        ok = ok and r["ok"]
+        del run
+    if others:
+        result["other_workloads"] = others
     print(json.dumps(result))
     if not ok:
         sys.exit(4)

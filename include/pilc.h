@@ -16,9 +16,11 @@
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default
  *     stream).  Every call synchronises that stream before it returns, so the status and
  *     all outputs are final on return.
- *   - Return value: 0 on success, a negative PILC_E_* code otherwise.  No exceptions, no
- *     global mutable state besides the constant tables; calls on different streams may run
- *     concurrently if they use different workspaces.
+ *   - Return value: 0 on success, a negative PILC_E_* code otherwise.  No exceptions.  Calls on
+ *     different streams may run concurrently, from any threads, if they use different workspaces.
+ *     The library's only process-wide state: the constant tables (filled once per device under a
+ *     lock), the two tuning knobs pilc_set_timing and pilc_set_kernel_policy (atomic integers, read
+ *     once at the start of a call), and the scratch array of pilc_encode_static.
  *   - Tensors are dense, row-major, channel-interleaved: index ((i*h + y)*w + x)*3 + c.
  */
 #ifndef PILC_H

@@ -8,7 +8,7 @@ static int model_ok(const ansai_model *md)
 {
     int i, x;
     if (!md || !md->mass || md->prec_bits < 1 || md->prec_bits > 15 || md->num_dist < 1 ||
-        md->num_dist > 256 || md->num_sym < 2 || md->num_sym > 256)
+        md->num_dist > 255 || md->num_sym < 2 || md->num_sym > 256)
         return 0;
     for (i = 0; i < md->num_dist; ++i) {
         uint64_t sum = 0;

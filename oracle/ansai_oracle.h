@@ -34,7 +34,7 @@ extern "C" {
 
 typedef struct {
     int prec_bits; /* M, 1..15 */
-    int num_dist;  /* D, 1..256 */
+    int num_dist;  /* D, 1..255 (an interface limit; Sec. 4.3 of the paper uses 8) */
     int num_sym;   /* X, 2..256 */
     const uint32_t *mass; /* [D, X] integer masses P_x >= 1, each row sums to 2^M */
 } ansai_model;

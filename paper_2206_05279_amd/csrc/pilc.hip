@@ -13,7 +13,10 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <atomic>
+#include <map>
 #include <mutex>
+#include <utility>
 
 #include "../../include/pilc.h"
 #include "pilc_device.hpp"
@@ -344,7 +347,7 @@ namespace pilc {
 // Host side
 // --------------------------------------------------------------------------------------------
 // 0 chosen from the lane count, 1 thread per lane, 2 the kernels for few long lanes
-static int g_kernel_policy = 0;
+static std::atomic<int> g_kernel_policy{0};
 
 // The few-lane kernels pay off while there are too few lanes to fill the chip with one thread
 // each (256 CUs x 4 SIMDs x 64 threads = 65,536 threads for a single wave per SIMD).  Measured
@@ -355,8 +358,9 @@ static int g_kernel_policy = 0;
 // 5.3 against 7.7 ms at 8192 lanes, 4.7 against 3.9 ms at 16,384).
 static bool use_few_lane_kernels(const Geo &g, bool decode)
 {
-    if (g_kernel_policy == 1) return false;
-    if (g_kernel_policy == 2) return true;
+    const int policy = g_kernel_policy.load(std::memory_order_relaxed);
+    if (policy == 1) return false;
+    if (policy == 2) return true;
     return g.lanes <= (decode ? 12288u : 28672u);
 }
 
@@ -364,7 +368,7 @@ thread_local char t_hip_error[256] = "";
 thread_local float t_timing_ms[16];
 thread_local const char *t_timing_name[16];
 thread_local int t_timing_count = 0;
-static int g_timing_enabled = 0;
+static std::atomic<int> g_timing_enabled{0};
 
 static int hip_fail(hipError_t e, const char *what)
 {
@@ -495,20 +499,43 @@ static int status_to_error(int st)
     }
 }
 
-// Optional per-kernel event timing on the caller's stream.
+// Optional per-kernel event timing on the caller's stream.  The events are created once per host
+// thread and device and reused by every later call.
+struct EventPool {
+    int dev = -1;
+    hipEvent_t ev[17];
+};
+thread_local EventPool t_events;
+
 struct Timer {
     hipStream_t stream;
-    hipEvent_t ev[17];
+    hipEvent_t *ev = nullptr;
     const char *name[16];
     int n = 0;
     bool on;
-    explicit Timer(hipStream_t s, bool allowed = true) : stream(s), on(allowed && g_timing_enabled != 0)
+    explicit Timer(hipStream_t s, bool allowed = true)
+        : stream(s), on(allowed && g_timing_enabled.load(std::memory_order_relaxed) != 0)
     {
         t_timing_count = 0;
-        if (on) {
-            for (auto &e : ev) (void)hipEventCreate(&e);
-            (void)hipEventRecord(ev[0], stream);
+        if (!on) return;
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess) {
+            on = false;
+            return;
         }
+        if (t_events.dev != dev) {
+            if (t_events.dev >= 0)
+                for (auto &e : t_events.ev) (void)hipEventDestroy(e);
+            t_events.dev = -1;
+            for (auto &e : t_events.ev)
+                if (hipEventCreate(&e) != hipSuccess) {
+                    on = false;
+                    return;
+                }
+            t_events.dev = dev;
+        }
+        ev = t_events.ev;
+        (void)hipEventRecord(ev[0], stream);
     }
     void mark(const char *what)
     {
@@ -528,12 +555,28 @@ struct Timer {
         }
         t_timing_count = n + 1 > 16 ? 16 : n + 1;
     }
-    ~Timer()
-    {
-        if (on)
-            for (auto &e : ev) (void)hipEventDestroy(e);
-    }
 };
+
+// Kernels that take more than 64 KB of dynamic LDS need the limit raised once per device; it is
+// raised to all of a compute unit's 160 KB less the kernel's static part, so that no later call
+// ever has to change it again.
+static std::mutex g_lds_mutex;
+static std::map<std::pair<const void *, int>, bool> g_lds_raised;
+static int allow_large_lds(const void *kernel)
+{
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(g_lds_mutex);
+    bool &done = g_lds_raised[std::make_pair(kernel, dev)];
+    if (!done) {
+        hipFuncAttributes fa;
+        HIP_TRY(hipFuncGetAttributes(&fa, kernel));
+        HIP_TRY(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    160 * 1024 - (int)fa.sharedSizeBytes));
+        done = true;
+    }
+    return PILC_OK;
+}
 
 // True when every 8-pixel chunk of every lane starts at a multiple of 8 pixels, never straddles
 // two images, and the arrays allow 16-byte (parameters) / 8-byte (pixels) vector accesses.
@@ -583,12 +626,12 @@ const char *pilc_strerror(int code)
 
 const char *pilc_last_hip_error(void) { return t_hip_error; }
 
-void pilc_set_timing(int enabled) { g_timing_enabled = enabled; }
+void pilc_set_timing(int enabled) { g_timing_enabled.store(enabled, std::memory_order_relaxed); }
 
 int pilc_set_kernel_policy(int policy)
 {
     if (policy < 0 || policy > 2) return PILC_E_ARG;
-    g_kernel_policy = policy;
+    g_kernel_policy.store(policy, std::memory_order_relaxed);
     return PILC_OK;
 }
 
@@ -860,12 +903,6 @@ static bool mix_params_ok(const pilc_mix_params *p)
            ((uintptr_t)p->chan_coef & 1) == 0;
 }
 
-static int mix_set_lds(const void *kernel, size_t bytes)
-{
-    HIP_TRY(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
-    return PILC_OK;
-}
-
 int pilc_mix_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_mix_params *params,
                     void *workspace_dev, size_t workspace_bytes, uint8_t *coded_dev,
                     size_t coded_capacity, uint64_t *coded_bytes_host, void *hip_stream)
@@ -894,7 +931,7 @@ int pilc_mix_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_mi
     const MixArgs args = {params->mu, params->log_scale, params->weight, params->chan_coef,
                           params->num_comp};
     const size_t lds = mix_lds_bytes(params->num_comp);
-    if ((rc = mix_set_lds(reinterpret_cast<const void *>(k_mix_encode), lds)) != PILC_OK) return rc;
+    if ((rc = allow_large_lds(reinterpret_cast<const void *>(k_mix_encode))) != PILC_OK) return rc;
 
     Timer timer(stream);
     k_init_status<<<1, 1, 0, stream>>>(status);
@@ -944,7 +981,7 @@ int pilc_mix_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t code
     const MixArgs args = {params->mu, params->log_scale, params->weight, params->chan_coef,
                           params->num_comp};
     const size_t lds = mix_lds_bytes(params->num_comp);
-    if ((rc = mix_set_lds(reinterpret_cast<const void *>(k_mix_decode), lds)) != PILC_OK) return rc;
+    if ((rc = allow_large_lds(reinterpret_cast<const void *>(k_mix_decode))) != PILC_OK) return rc;
 
     Timer timer(stream);
     k_check_header<<<1, 1, 0, stream>>>(g, kMagicMix, params->num_comp, coded_dev,

@@ -392,7 +392,7 @@ __global__ __launch_bounds__(64 * kAnsaiEncWaves) void k_ansai_encode(
         piece_bits[p0 + lane] = ((L.woff - woff0) >> 6) * 32u + L.nacc;
         piece_state[p0 + lane] = L.S;
     }
-    if (bad) *status = ST_ARG;
+    if (bad) atomicMax(status, ST_ARG);  // the same value from every thread that found one
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -761,10 +761,11 @@ __global__ __launch_bounds__(64 * kAnsaiDecMaxWaves) void k_ansai_decode(
         }
     }
     if (mine && (L.s != 0u || L.n != 0 || L.widx != L.first)) corrupt = 1u;
+    // many threads may report: the larger code (a damaged container) wins, whatever the order
     if (corrupt)
-        status->code = ST_CORRUPT;
+        atomicMax(&status->code, ST_CORRUPT);
     else if (bad)
-        status->code = ST_ARG;
+        atomicMax(&status->code, ST_ARG);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1038,20 +1039,23 @@ int pilc_ansai_decode(const pilc_ansai_shape *shape, const uint8_t *coded_dev, s
     k_ansai_begin<<<1, 1, 0, stream>>>(sh, reinterpret_cast<const ATabHeader *>(tb), status);
     k_ansai_check_header<<<1, 1, 0, stream>>>(sh, coded_dev, (unsigned long long)coded_bytes, status);
     timer.mark("k_ansai_check_header");
-    // A build of this kernel that needs private memory (register spills) is only ever launched
-    // with four wavefronts per workgroup: with more, the wavefronts beyond the fourth of a
-    // workgroup were seen to read back wrong spilled values on this machine.  The kernel as
-    // written compiles without private memory, so this does not trigger.
+    // A build of this kernel that needed private memory (register spills) once decoded wrongly in
+    // the wavefronts beyond the fourth of a workgroup, and the cause was never found.  The kernel as
+    // written compiles without private memory; a build that does not is refused rather than run.
 #define PILC_ANSAI_DECODE(WIDE, LDS)                                                                  \
     do {                                                                                              \
-        auto kern = k_ansai_decode<WIDE, LDS>;                                           \
+        auto kern = k_ansai_decode<WIDE, LDS>;                                                        \
         hipFuncAttributes fa;                                                                         \
         HIP_TRY(hipFuncGetAttributes(&fa, reinterpret_cast<const void *>(kern)));                     \
-        if (fa.localSizeBytes != 0 && waves > 4) waves = 4;                                           \
+        if (fa.localSizeBytes != 0) {                                                                 \
+            snprintf(t_hip_error, sizeof(t_hip_error),                                                \
+                     "k_ansai_decode was built with %zu bytes of private memory per thread; this "   \
+                     "library only runs a build of it that has none", (size_t)fa.localSizeBytes);     \
+            return PILC_E_HIP;                                                                        \
+        }                                                                                             \
         const size_t lds_bytes = (LDS ? tab_lds : 0) + waves * row_lds;                               \
         const uint32_t blocks = (uint32_t)ceil_div64(ws.waves, waves);                                \
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                             \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));    \
+        if ((rc = allow_large_lds(reinterpret_cast<const void *>(kern))) != PILC_OK) return rc;       \
         kern<<<blocks, 64 * waves, lds_bytes, stream>>>(sh, coded_dev, dist_dev, tb + t.theta_off,    \
                                                         tb + t.nb_off, sym_out_dev, ws.maxw, status); \
     } while (0)

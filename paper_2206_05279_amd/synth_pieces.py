@@ -139,12 +139,16 @@ def draw_pieces(mass: np.ndarray, prec_bits: int, pieces: int, count: int, seed:
 PIECE_CONFIGS = {
     0: dict(name="pieces0: 4096 x 1000, D=8, M=12", pieces=4096, count=1000, num_dist=8, prec_bits=12),
     1: dict(name="pieces1: 1,000,000 x 1000, D=8, M=12", pieces=1000000, count=1000, num_dist=8, prec_bits=12),
+    # The stream of vector indices (Sec. 3.1; the "Coder Decode" phase of the per-phase table): one
+    # piece per 32x32 image = its 16x16 codebook indices, one static law, as many images as that table.
+    2: dict(name="index stream: 1,000,000 x 256 indices, K=256, D=1, M=12", pieces=1000000, count=256,
+            num_dist=1, prec_bits=12),
 }
 
 
 def make_piece_workload(cfg: int, pieces: int | None = None, threads: int = 8) -> PieceWorkload:
     c = PIECE_CONFIGS[cfg]
     n = c["pieces"] if pieces is None else int(pieces)
-    mass = logistic_masses(c["prec_bits"], c["num_dist"])
+    mass = index_stream_masses(c["prec_bits"]) if cfg == 2 else logistic_masses(c["prec_bits"], c["num_dist"])
     sym, dist = draw_pieces(mass, c["prec_bits"], n, c["count"], seed=BASE_SEED + cfg, threads=threads)
     return PieceWorkload(c["name"], c["prec_bits"], mass, sym, dist)
