@@ -23,7 +23,8 @@ struct TwarK {
 
 __device__ __forceinline__ int twar_predict(const TwarK &p, int ch, int a, int b, int c)
 {
-    const int acc = p.w[ch][0] * a + p.w[ch][1] * b + p.w[ch][2] * c + p.bias[ch] + 8192;
+    // 16-bit weights times 8-bit values: 24-bit multiplies are exact and run at full rate
+    const int acc = __mul24(p.w[ch][0], a) + __mul24(p.w[ch][1], b) + __mul24(p.w[ch][2], c) + p.bias[ch] + 8192;
     return min(max(acc >> 14, 0), 255);  // arithmetic shift: floor
 }
 
@@ -264,6 +265,124 @@ __global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint3
     }
 }
 
+// Images taller than 64 rows whose rows are whole 16-pixel chunks in 16-byte aligned arrays: a
+// workgroup per image, a thread per row, every wavefront a band of 64 rows, all bands under way at
+// once.  Thread t of the workgroup runs t + 16 (t / 64) positions behind thread 0, so inside a
+// wavefront a row still gets the two values it needs from the row above by a cross-lane shift, and
+// the first row of a band finds them in LDS, where the last row of the band above left them 17
+// steps earlier; a workgroup barrier every 16 steps separates the two.  Images with more rows than
+// a workgroup has threads go in rounds, the last row's red values of a round kept in LDS for the
+// first row of the next.  A thread reads and writes its row in chunks of 16 pixels (48 bytes,
+// three 16-byte accesses): the chunk it is in and the next wait in a three-chunk ring in LDS, the
+// one after that is on its way from memory in registers, the one it left is written back.
+constexpr int kTallLag = 16;         // steps between barriers = extra lag per wavefront
+constexpr int kTallChunk = 48;       // bytes of a chunk of 16 pixels
+constexpr int kTallRing = 3 * kTallChunk;
+constexpr int kTallStride = kTallRing + 4;  // LDS bytes per thread: 37 dwords, odd
+constexpr int kTallMaxThreads = 768;
+constexpr int kTallLead = 32;        // steps a wavefront runs before its first pixel (two chunk turns)
+
+__global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, uint32_t h, uint32_t w,
+                                                                       uint32_t rounds,
+                                                                       const uint8_t *__restrict__ res,
+                                                                       uint8_t *__restrict__ img)
+{
+    extern __shared__ uint8_t twar_lds[];
+    const uint32_t nt = blockDim.x, waves = nt >> 6;
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    uint8_t *my = twar_lds + (size_t)threadIdx.x * kTallStride;
+    uint8_t *hand = twar_lds + (size_t)nt * kTallStride;  // [wavefront][64]: red of its last row, by column mod 64
+    uint8_t *carry = hand + waves * 64u;                  // [w]: red of the last row of the round before
+    const size_t row_bytes = (size_t)w * 3u;
+    const int chunks = (int)(w >> 4);
+    const uint32_t lag = wave * (64u + kTallLag);
+    // local steps -kTallLead .. w + 63 + 16: the last lane's last chunk is written back by then
+    const uint32_t local_steps = kTallLead + w + 80u;
+    const uint32_t total = local_steps + (waves - 1u) * (64u + kTallLag);
+
+    for (uint32_t round = 0; round < rounds; ++round) {
+        const uint32_t u = round * nt + threadIdx.x;
+        const bool have = u < h;
+        const size_t row_off = ((size_t)blockIdx.x * h + (have ? u : 0u)) * row_bytes;
+        const uint4 *src = reinterpret_cast<const uint4 *>(res + row_off);
+        uint4 *dst = reinterpret_cast<uint4 *>(img + row_off);
+        const bool last_row = have && (u + 1u == h || threadIdx.x + 1u == nt);
+        int rl = 0, rll = 0, gl = 0, bl = 0, first_prev = 0;
+        uint32_t ptr = 0;             // ring offset of the pixel about to be decoded
+        // the chunk index before that of column -kTallLead - lane (the first chunk turn moves on to
+        // it), and that index mod 3
+        int cur = (((int)-kTallLead - (int)lane) >> 4) - 1;
+        int cur3 = ((cur % 3) + 3) % 3;
+        uint4 ahead[3] = {};          // the chunk two after `cur`, on its way
+        for (uint32_t D = 0; D < total; ++D) {
+            if ((D & (kTallLag - 1)) == 0u) __syncthreads();
+            const int d = (int)D - (int)lag - kTallLead;  // this wavefront's step; lane 0 is at column d
+            if (d < -kTallLead || d >= (int)(w + 80u)) continue;
+            if ((d & 15) == 0) {
+                // a chunk turn: every lane moves one chunk on within the next 16 steps
+                cur = (d - (int)lane) >> 4;
+                cur3 = cur3 == 2 ? 0 : cur3 + 1;
+                if (have) {
+                    const int nxt3 = cur3 == 2 ? 0 : cur3 + 1, prv3 = cur3 == 0 ? 2 : cur3 - 1;
+                    if (cur - 1 >= 0 && cur - 1 < chunks) {  // written back: it was left for good
+                        const uint32_t *q = reinterpret_cast<const uint32_t *>(my + prv3 * kTallChunk);
+#pragma unroll
+                        for (int i = 0; i < 3; ++i)
+                            dst[3 * (cur - 1) + i] = make_uint4(q[4 * i], q[4 * i + 1], q[4 * i + 2], q[4 * i + 3]);
+                    }
+                    if (cur + 1 >= 0 && cur + 1 < chunks) {  // arrived: into the ring
+                        uint32_t *q = reinterpret_cast<uint32_t *>(my + nxt3 * kTallChunk);
+#pragma unroll
+                        for (int i = 0; i < 3; ++i) {
+                            q[4 * i] = ahead[i].x;
+                            q[4 * i + 1] = ahead[i].y;
+                            q[4 * i + 2] = ahead[i].z;
+                            q[4 * i + 3] = ahead[i].w;
+                        }
+                    }
+                    if (cur + 2 >= 0 && cur + 2 < chunks) {  // asked for
+#pragma unroll
+                        for (int i = 0; i < 3; ++i) ahead[i] = src[3 * (cur + 2) + i];
+                    }
+                }
+            }
+            const int v = d - (int)lane;
+            const bool on = have && v >= 0 && v < (int)w;
+            if (!__any(on)) continue;
+            int up = __builtin_amdgcn_update_dpp(0, rl, 0x138 /* wave_shr:1 */, 0xF, 0xF, true);
+            int upleft = __builtin_amdgcn_update_dpp(0, rll, 0x138, 0xF, 0xF, true);
+            if (lane == 0u && on) {
+                // the row above belongs to another wavefront, or to the round before, or is padding
+                int above = 0;
+                if (wave != 0u)
+                    above = hand[(wave - 1u) * 64u + ((uint32_t)v & 63u)];
+                else if (round != 0u)
+                    above = carry[v];
+                up = above;
+                upleft = first_prev;
+                first_prev = above;
+            }
+            if (on) {
+                uint8_t *q = my + ptr;
+                const int xr = ((int)q[0] + twar_predict(p, 0, upleft, up, rl)) & 255;
+                const int xg = ((int)q[1] + twar_predict(p, 1, gl, rl, xr)) & 255;
+                const int xb = ((int)q[2] + twar_predict(p, 2, bl, gl, xg)) & 255;
+                q[0] = (uint8_t)xr;
+                q[1] = (uint8_t)xg;
+                q[2] = (uint8_t)xb;
+                ptr = ptr + 3u == (uint32_t)kTallRing ? 0u : ptr + 3u;
+                if (lane == 63u) hand[wave * 64u + ((uint32_t)v & 63u)] = (uint8_t)xr;
+                if (last_row) carry[v] = (uint8_t)xr;
+                rll = rl;
+                rl = xr;
+                gl = xg;
+                bl = xb;
+            }
+        }
+        __syncthreads();
+    }
+}
+
 static int make_twar(const pilc_twar_params *in, uint32_t n, uint32_t h, uint32_t w, TwarK *k)
 {
     if (!in || n == 0 || h == 0 || w == 0) return PILC_E_ARG;
@@ -326,7 +445,17 @@ int pilc_twar_inverse(uint32_t n, uint32_t h, uint32_t w, const uint8_t *res_dev
     if (((row_stride >> 2) & 1u) == 0u) row_stride += 4u;
     const size_t tile_lds = (size_t)kTwarWaves * (last_bytes + 64u * (size_t)row_stride);
     Timer timer(stream);
-    if (tile_lds <= 64 * 1024) {
+    const bool tall = h > 64 && w % 16 == 0 && w <= 16384 && ((((uintptr_t)img_dev) | ((uintptr_t)res_dev)) & 15) == 0;
+    if (tall) {
+        // as few rounds as the workgroup size allows, of equal size (three rounds of 512, 512 and 56
+        // rows of a 1080-row frame took 2.8 ms where two rounds of 540 take 2.2)
+        const uint32_t rounds = (h + kTallMaxThreads - 1) / kTallMaxThreads;
+        const uint32_t per = (h + rounds - 1) / rounds;
+        const uint32_t nt = (per + 63u) & ~63u;
+        const size_t lds = (size_t)nt * kTallStride + (nt / 64) * 64 + w;
+        if ((rc = allow_large_lds(reinterpret_cast<const void *>(k_twar_inverse_tall))) != PILC_OK) return rc;
+        k_twar_inverse_tall<<<n, nt, lds, stream>>>(k, h, w, rounds, res_dev, img_dev);
+    } else if (tile_lds <= 64 * 1024) {
         k_twar_inverse<true><<<blocks, 64 * kTwarWaves, tile_lds, stream>>>(k, n, h, w, row_stride, res_dev, img_dev);
     } else {
         k_twar_inverse<false><<<blocks, 64 * kTwarWaves, (size_t)kTwarWaves * last_bytes, stream>>>(

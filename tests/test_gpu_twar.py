@@ -1,6 +1,7 @@
 """GPU parity of the Three-Way AR residual transform (Sec. 3.1 eqs. (2)-(4)) against the CPU
 reference, through the C ABI: residuals and recovered images byte for byte, on shapes that
-cover several images per wavefront, bands of 64 rows, and both the LDS-tile and the in-place path."""
+cover several images per wavefront, bands of 64 rows, the LDS-tile and the in-place path, and
+the workgroup-per-image path for tall images."""
 import numpy as np
 import pytest
 import torch
@@ -12,7 +13,11 @@ pytestmark = pytest.mark.gpu
 
 ONE = 1 << 14
 SHAPES = [(1, 1, 1), (3, 32, 32), (5, 7, 9), (2, 64, 64), (7, 16, 16), (2, 33, 5), (1, 100, 37),
-          (1, 130, 300), (2, 3, 700), (513, 32, 32), (1, 200, 64)]
+          (1, 130, 300), (2, 3, 700), (513, 32, 32), (1, 200, 64),
+          # taller than a wavefront with rows of whole 16-pixel chunks: a workgroup per image with all
+          # bands under way at once; one band and a bit, a band boundary at the last row, three
+          # rounds of a workgroup, a full-size frame
+          (3, 65, 16), (2, 128, 48), (1, 1600, 32), (2, 1080, 1920)]
 
 
 def models(rng):
