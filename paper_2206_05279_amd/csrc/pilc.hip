@@ -599,6 +599,14 @@ static bool chunks_pair_up(const Geo &g, const void *img)
     return geo && ((uintptr_t)img & 15) == 0;
 }
 
+// On top of chunks_pair_up: flat lanes of whole 64-pixel groups (three 128-byte lines of each
+// parameter array) that start on a line.
+static bool lanes_line_up(const Geo &g, const pilc_params *p)
+{
+    return g.lane_mode == 0 && g.lane_a % 64 == 0 && g.total_px % g.lane_a == 0 &&
+           ((uintptr_t)p->mu & 127) == 0 && ((uintptr_t)p->log_scale & 127) == 0;
+}
+
 static int lane_block_threads(const Geo &g) { return g.lanes >= (1u << 16) ? kRingMaxThreads : 64; }
 
 }  // namespace pilc
@@ -719,7 +727,11 @@ static int encode_checked(const Geo &g, const uint8_t *img_dev, const pilc_param
     } else {
         const int bt = lane_block_threads(g);
         const uint32_t nb = (uint32_t)ceil_div64(g.lanes, bt);
-        if (chunks_aligned(g, img_dev, params) && chunks_pair_up(g, img_dev))
+        if (chunks_aligned(g, img_dev, params) && chunks_pair_up(g, img_dev) && lanes_line_up(g, params))
+            k_encode_lanes<true, true, true><<<nb, bt, 0, stream>>>(g, img_dev, params->mu, params->log_scale,
+                                                                    params->chan_coef, scratch, lane_cap,
+                                                                    lane_words, lane_state);
+        else if (chunks_aligned(g, img_dev, params) && chunks_pair_up(g, img_dev))
             k_encode_lanes<true, true><<<nb, bt, 0, stream>>>(g, img_dev, params->mu, params->log_scale,
                                                               params->chan_coef, scratch, lane_cap,
                                                               lane_words, lane_state);
@@ -869,7 +881,11 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
     } else {
         const int bt = lane_block_threads(g);
         const uint32_t nb = (uint32_t)ceil_div64(g.lanes, bt);
-        if (chunks_aligned(g, img_out_dev, params) && chunks_pair_up(g, img_out_dev))
+        if (chunks_aligned(g, img_out_dev, params) && chunks_pair_up(g, img_out_dev) && lanes_line_up(g, params))
+            k_decode_lanes<true, true, true><<<nb, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
+                                                                    params->chan_coef, img_out_dev,
+                                                                    &status->code, &status->payload_bytes);
+        else if (chunks_aligned(g, img_out_dev, params) && chunks_pair_up(g, img_out_dev))
             k_decode_lanes<true, true><<<nb, bt, 0, stream>>>(g, coded_dev, params->mu, params->log_scale,
                                                               params->chan_coef, img_out_dev,
                                                               &status->code, &status->payload_bytes);

@@ -124,6 +124,119 @@ __device__ __forceinline__ void load_pair(ChunkPair &r, uint32_t p, const uint8_
     }
 }
 
+// Whole-line feeding of ChunkPair for flat lanes made of 64-pixel groups that start on a 128-byte
+// line of the parameter arrays (a group is three lines of each, a line 21 1/3 pixels).  A pair of
+// chunks takes 96 bytes of each array, so three of every four pairs straddle a line; asked for by
+// the pair, every line would be fetched twice, because it has left the caches when the thread
+// comes back to it.  Here a thread asks for whole lines, eight 16-byte pieces at once, when a pair
+// first needs one, and carries the pieces the pair does not use in registers to the pairs that
+// do: every line is fetched once.  The pixels go the same way in halves of a group (96 bytes).
+// `v` is the pair's number within its group (0..3); forward feeds pairs in the order 0,1,2,3,
+// backward in the order 3,2,1,0.
+struct LineCarry {
+    uint4 m[6], l[6], x[3];
+};
+__device__ __forceinline__ void put_piece(uint32_t *w, int i, const uint4 &q)
+{
+    w[4 * i] = q.x; w[4 * i + 1] = q.y; w[4 * i + 2] = q.z; w[4 * i + 3] = q.w;
+}
+// One array's share of a pair: `grp` points at the group's 24 pieces.  Every piece is loaded
+// straight into the place it is used from (the pair's words or the carry), so no more registers
+// are alive than the pair and the carry take.
+__device__ __forceinline__ void load_piece(uint32_t *w, int i, const uint4 *__restrict__ src)
+{
+    put_piece(w, i, *src);
+}
+template <bool kBackward>
+__device__ __forceinline__ void feed_array(uint32_t *w, uint4 *carry, uint32_t v, const uint4 *__restrict__ grp)
+{
+    // forward:  v=0 line A: use A0-5, keep A6,7 | v=1 line B: kept + B0-3, keep B4-7 |
+    //           v=2 line C: kept + C0,1, keep C2-7 | v=3: kept
+    // backward: v=3 line C: use C2-7, keep C0,1 | v=2 line B: B4-7 + kept, keep B0-3 |
+    //           v=1 line A: A6,7 + kept, keep A0-5 | v=0: kept
+    if (!kBackward) {
+        switch (v) {
+        case 0:
+#pragma unroll
+            for (int i = 0; i < 6; ++i) load_piece(w, i, grp + i);
+            carry[0] = grp[6]; carry[1] = grp[7];
+            break;
+        case 1:
+            put_piece(w, 0, carry[0]); put_piece(w, 1, carry[1]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) load_piece(w, 2 + i, grp + 8 + i);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) carry[i] = grp[12 + i];
+            break;
+        case 2:
+#pragma unroll
+            for (int i = 0; i < 4; ++i) put_piece(w, i, carry[i]);
+            load_piece(w, 4, grp + 16); load_piece(w, 5, grp + 17);
+#pragma unroll
+            for (int i = 0; i < 6; ++i) carry[i] = grp[18 + i];
+            break;
+        default:
+#pragma unroll
+            for (int i = 0; i < 6; ++i) put_piece(w, i, carry[i]);
+            break;
+        }
+    } else {
+        switch (v) {
+        case 3:
+#pragma unroll
+            for (int i = 0; i < 6; ++i) load_piece(w, i, grp + 18 + i);
+            carry[0] = grp[16]; carry[1] = grp[17];
+            break;
+        case 2:
+#pragma unroll
+            for (int i = 0; i < 4; ++i) load_piece(w, i, grp + 12 + i);
+            put_piece(w, 4, carry[0]); put_piece(w, 5, carry[1]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) carry[i] = grp[8 + i];
+            break;
+        case 1:
+            load_piece(w, 0, grp + 6); load_piece(w, 1, grp + 7);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) put_piece(w, 2 + i, carry[i]);
+#pragma unroll
+            for (int i = 0; i < 6; ++i) carry[i] = grp[i];
+            break;
+        default:
+#pragma unroll
+            for (int i = 0; i < 6; ++i) put_piece(w, i, carry[i]);
+            break;
+        }
+    }
+}
+// The pair `v` of the group whose first pixel is `pg` (a multiple of 64 pixels from the lane's start).
+template <bool kBackward, bool kPixels>
+__device__ __forceinline__ void feed_pair(ChunkPair &r, LineCarry &c, uint32_t v, uint32_t pg,
+                                          const uint8_t *__restrict__ img, const uint16_t *__restrict__ mu,
+                                          const int16_t *__restrict__ ls)
+{
+    const size_t s = (size_t)pg * 3;
+    feed_array<kBackward>(r.wm, c.m, v, reinterpret_cast<const uint4 *>(mu + s));
+    feed_array<kBackward>(r.wl, c.l, v, reinterpret_cast<const uint4 *>(ls + s));
+    if (kPixels) {
+        const uint4 *px = reinterpret_cast<const uint4 *>(img + s);  // 12 pieces a group, 3 a pair
+        const bool fresh = kBackward ? (v & 1u) != 0u : (v & 1u) == 0u;  // first pair of its half
+        if (fresh) {
+            const uint32_t h = 6u * (v >> 1);
+            uint4 n[6];
+#pragma unroll
+            for (int i = 0; i < 6; ++i) n[i] = px[h + i];
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                put_piece(r.wx, i, kBackward ? n[3 + i] : n[i]);
+                c.x[i] = kBackward ? n[i] : n[3 + i];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 3; ++i) put_piece(r.wx, i, c.x[i]);
+        }
+    }
+}
+
 // floor(n / f) and the remainder for f < 2^16 and n / f < 2^22 (true after the renormalisation
 // of the encoder), given rf ~ 1/f to float accuracy: the float estimate is within [-2, +1] of the
 // quotient and is fixed up exactly.
@@ -167,7 +280,8 @@ __device__ __forceinline__ size_t lane_scratch_base(uint32_t lane, uint32_t lane
 
 // kPair (with kVec): every row of every lane is a whole number of 16-pixel pairs of chunks that
 // start at multiples of 16 pixels, and the arrays allow 16-byte loads.
-template <bool kVec, bool kPair>
+// kLine (with kPair, flat lanes): lanes are whole 64-pixel groups that start on 128-byte lines.
+template <bool kVec, bool kPair, bool kLine = false>
 __global__ __launch_bounds__(kLaneMaxThreads) void k_encode_lanes(Geo g, const uint8_t *__restrict__ img,
                                const uint16_t *__restrict__ mu, const int16_t *__restrict__ ls,
                                const int16_t *__restrict__ coef, uint16_t *__restrict__ scratch,
@@ -192,56 +306,67 @@ __global__ __launch_bounds__(kLaneMaxThreads) void k_encode_lanes(Geo g, const u
         // a chunk never straddles two images when kVec; otherwise take the image per pixel
         uint32_t im = cp.p / g.hw;
         int a_gr = coef[3 * im], a_br = coef[3 * im + 1], a_bg = coef[3 * im + 2];
-        // Phase 1: (cum | freq << 16) and 1/freq of the chunk's 24 symbols.  Nothing here depends on
-        // the state, so the 24 evaluations overlap freely.
-        uint32_t cf[3 * kChunk];
-        float rf[3 * kChunk];
+        // The chunk in two halves of four pixels, the later half first.  Phase 1 of a half:
+        // (cum | freq << 16) of its 12 symbols; nothing there depends on the state, so the
+        // evaluations overlap freely.  Phase 2: the serial chain (App. A eq. (11)), last symbol
+        // first.  (Halves, and 1/freq formed in phase 2, keep the registers of the whole-line
+        // variant at three wavefronts per SIMD.)
+        constexpr int kHalf = kChunk / 2;
 #pragma unroll
-        for (int i = 0; i < kChunk; ++i) {
-            if (!kVec && (uint32_t)i < cp.len) {
-                const uint32_t im_i = (cp.p + i) / g.hw;
-                if (im_i != im) {
-                    im = im_i;
-                    a_gr = coef[3 * im]; a_br = coef[3 * im + 1]; a_bg = coef[3 * im + 2];
+        for (int hb = 1; hb >= 0; --hb) {
+            uint32_t cf[3 * kHalf];
+#pragma unroll
+            for (int ii = 0; ii < kHalf; ++ii) {
+                const int i = kHalf * hb + ii;
+                if (!kVec && (uint32_t)i < cp.len) {
+                    const uint32_t im_i = (cp.p + i) / g.hw;
+                    if (im_i != im) {
+                        im = im_i;
+                        a_gr = coef[3 * im]; a_br = coef[3 * im + 1]; a_bg = coef[3 * im + 2];
+                    }
+                }
+                const int e_r = ck.x[i][0] * 256 - ck.m[i][0], e_g = ck.x[i][1] * 256 - ck.m[i][1];
+                const int me[3] = {ck.m[i][0], ck.m[i][1] + rsh14_mul(a_gr, e_r),
+                                   ck.m[i][2] + rsh14_mul(a_br, e_r) + rsh14_mul(a_bg, e_g)};
+#pragma unroll
+                for (int ch = 0; ch < 3; ++ch) {
+                    const int x = ck.x[i][ch];
+                    const uint32_t inv_s = inv_scale(ck.l[i][ch], tab);
+                    const uint32_t lo = x == 0 ? 0u : cum_inner(x, me[ch], inv_s, spread, tab);
+                    const uint32_t hi = x == 255 ? top : cum_inner(x + 1, me[ch], inv_s, spread, tab);
+                    cf[3 * ii + ch] = lo | ((hi - lo) << 16);  // cum < 2^16, freq <= 2^16 - 255
                 }
             }
-            const int e_r = ck.x[i][0] * 256 - ck.m[i][0], e_g = ck.x[i][1] * 256 - ck.m[i][1];
-            const int me[3] = {ck.m[i][0], ck.m[i][1] + rsh14_mul(a_gr, e_r),
-                               ck.m[i][2] + rsh14_mul(a_br, e_r) + rsh14_mul(a_bg, e_g)};
 #pragma unroll
-            for (int ch = 0; ch < 3; ++ch) {
-                const int x = ck.x[i][ch];
-                const uint32_t inv_s = inv_scale(ck.l[i][ch], tab);
-                const uint32_t lo = x == 0 ? 0u : cum_inner(x, me[ch], inv_s, spread, tab);
-                const uint32_t hi = x == 255 ? top : cum_inner(x + 1, me[ch], inv_s, spread, tab);
-                cf[3 * i + ch] = lo | ((hi - lo) << 16);  // cum < 2^16, freq <= 2^16 - 255
-                rf[3 * i + ch] = __builtin_amdgcn_rcpf((float)(hi - lo));
-            }
-        }
-        // Phase 2: the serial chain (App. A eq. (11)), last symbol first.
-#pragma unroll
-        for (int k = 3 * kChunk - 1; k >= 0; --k) {
-            if ((uint32_t)k < 3u * cp.len) {
-                const uint32_t f = cf[k] >> 16, lo = cf[k] & 0xFFFFu;
-                if (S >= (f << (32u - m_bits))) {
-                    *wout = (uint16_t)(S & 0xFFFFu);
-                    wout += 64;
-                    ++nwords;
-                    S >>= 16;
+            for (int kk = 3 * kHalf - 1; kk >= 0; --kk) {
+                if ((uint32_t)(3 * kHalf * hb + kk) < 3u * cp.len) {
+                    const uint32_t f = cf[kk] >> 16, lo = cf[kk] & 0xFFFFu;
+                    if (S >= (f << (32u - m_bits))) {
+                        *wout = (uint16_t)(S & 0xFFFFu);
+                        wout += 64;
+                        ++nwords;
+                        S >>= 16;
+                    }
+                    uint32_t rem;
+                    const uint32_t q = div_small(S, f, __builtin_amdgcn_rcpf((float)f), rem);
+                    S = (q << m_bits) + rem + lo;
                 }
-                uint32_t rem;
-                const uint32_t q = div_small(S, f, rf[k], rem);
-                S = (q << m_bits) + rem + lo;
             }
         }
     };
 
     if (kVec && kPair) {
         // chunks 2i and 2i + 1 of a lane are neighbours in a row; the right one is coded first
+        LineCarry carry;
         for (uint32_t c = chunks; c >= 2u; c -= 2u) {
             const ChunkPos left = chunk_pos(g, sh, per_row, c - 2u);
             ChunkPair raw;
-            load_pair<true>(raw, left.p, img, mu, ls);
+            if (kLine) {
+                const uint32_t pair = (c - 2u) >> 1;  // pairs of a flat lane are 16 pixels apart
+                feed_pair<true, true>(raw, carry, pair & 3u, sh.first + 16u * (pair & ~3u), img, mu, ls);
+            } else {
+                load_pair<true>(raw, left.p, img, mu, ls);
+            }
             auto half = [&](auto h) {  // h: which chunk of the pair, as a compile-time constant
                 constexpr int kH = decltype(h)::value;
                 Chunk ck;
@@ -335,14 +460,17 @@ struct WordStream {
 };
 
 // The same stream for a decoder that works in chunks of at most kRingChunk symbols: the words wait
-// in a ring of 32 per thread in LDS ([16-byte piece][thread]), which is filled to the brim with
-// aligned 16-byte loads before every chunk, together with the chunk's parameter loads, so that
-// no refill inside the chunk ever touches memory or branches on the fill level: a symbol takes at
-// most one word and a full ring holds at least 25.  The word after the current one is read from
-// the ring ahead of time.
+// in a ring of 64 per thread in LDS ([16-byte piece][thread]).  Before a chunk the ring is looked
+// at: while it still holds 32 words or more nothing happens (a chunk takes at most 24), otherwise
+// it is filled to the brim with aligned 16-byte loads, four to eight at once, together with the
+// chunk's parameter loads.  No refill inside the chunk ever touches memory or branches on the fill
+// level, and a 128-byte line of the stream is asked for by one or two fills, not by eight.  The
+// word after the current one is read from the ring ahead of time.
 constexpr int kRingChunk = 24;
+constexpr int kRingPieces = 8;                      // 16-byte pieces per thread: 64 words
+constexpr int kRingWordsHeld = 8 * kRingPieces;
 constexpr int kRingMaxThreads = kLaneMaxThreads;
-static_assert(3 * kChunk <= kRingChunk, "a chunk must not take more words than a full ring guarantees");
+static_assert(3 * kChunk <= kRingChunk, "a chunk must not take more words than the ring guarantees");
 
 struct WordRing {
     uint4 *slot;        // this thread's column of the ring: piece q is slot[q * stride]
@@ -358,22 +486,25 @@ struct WordRing {
     __device__ __forceinline__ uint32_t peek() const
     {
         // read as the dwords the pieces are made of, so that the access is of the stored type
-        const uint32_t *d = reinterpret_cast<const uint32_t *>(&slot[((pos >> 3) & 3u) * stride]);
+        const uint32_t *d =
+            reinterpret_cast<const uint32_t *>(&slot[((pos >> 3) & (kRingPieces - 1)) * stride]);
         return (d[(pos & 7u) >> 1] >> (16u * (pos & 1u))) & 0xFFFFu;
     }
-    // Brings `filled` to (pos rounded down to 8) + 32: at most 3 pieces before a chunk, 4 at the start.
+    // Brings `filled` to (pos rounded down to 8) + 64 if fewer than 32 words are held.
     __device__ __forceinline__ void fill(const uint16_t *base, uint32_t lim)
     {
-        const uint32_t want = (pos & ~7u) + 32u;
-        const uint32_t n = (want - filled) >> 3;
-        uint4 piece[4];
+        if ((int)(filled - pos) < 32) {  // signed: at the opening `filled` may lie below `pos`
+            const uint32_t want = (pos & ~7u) + kRingWordsHeld;
+            const uint32_t n = (want - filled) >> 3;  // 4..8
+            uint4 piece[kRingPieces];
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if ((uint32_t)i < n) piece[i] = fetch(base, filled + 8u * i, lim);
+            for (int i = 0; i < kRingPieces; ++i)
+                if ((uint32_t)i < n) piece[i] = fetch(base, filled + 8u * i, lim);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if ((uint32_t)i < n) slot[(((filled >> 3) + i) & 3u) * stride] = piece[i];
-        filled = want;
+            for (int i = 0; i < kRingPieces; ++i)
+                if ((uint32_t)i < n) slot[(((filled >> 3) + i) & (kRingPieces - 1)) * stride] = piece[i];
+            filled = want;
+        }
         nextw = peek();
     }
     // the lane's first word is at word offset `first` < lim
@@ -394,7 +525,7 @@ struct WordRing {
     }
 };
 
-template <bool kVec, bool kPair>
+template <bool kVec, bool kPair, bool kLine = false>
 __global__ __launch_bounds__(kLaneMaxThreads) void k_decode_lanes(Geo g, const uint8_t *__restrict__ coded,
                                const uint16_t *__restrict__ mu, const int16_t *__restrict__ ls,
                                const int16_t *__restrict__ coef, uint8_t *__restrict__ out,
@@ -402,7 +533,7 @@ __global__ __launch_bounds__(kLaneMaxThreads) void k_decode_lanes(Geo g, const u
                                const unsigned long long *__restrict__ status_payload)
 {
     __shared__ LdsTables tab;
-    __shared__ uint4 ring[4 * kRingMaxThreads];  // [piece][thread]
+    __shared__ uint4 ring[kRingPieces * kRingMaxThreads];  // [piece][thread]
     load_tables(tab);
     if (*status_code != 0) return;  // uniform: written by an earlier kernel
     const uint32_t lane = blockIdx.x * blockDim.x + threadIdx.x;
@@ -483,10 +614,16 @@ __global__ __launch_bounds__(kLaneMaxThreads) void k_decode_lanes(Geo g, const u
 
     if (kVec && kPair) {
         // two neighbouring chunks per round: 96 bytes of each parameter array in, 48 bytes out
+        LineCarry carry;
         for (uint32_t c = 0; c + 2u <= chunks; c += 2u) {
             const ChunkPos left = chunk_pos(g, sh, per_row, c);
             ChunkPair raw;
-            load_pair<false>(raw, left.p, nullptr, mu, ls);
+            if (kLine) {
+                const uint32_t pair = c >> 1;
+                feed_pair<false, false>(raw, carry, pair & 3u, sh.first + 16u * (pair & ~3u), nullptr, mu, ls);
+            } else {
+                load_pair<false>(raw, left.p, nullptr, mu, ls);
+            }
             uint32_t wout[12];
             auto half = [&](auto h) {  // h: which chunk of the pair, as a compile-time constant
                 constexpr int kH = decltype(h)::value;
