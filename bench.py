@@ -673,7 +673,8 @@ def report(run, r, seg, torch, with_copy=False):
         "kernel_ms": kernel_ms,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_detail": detail,
-                     "algorithmic_bytes": algo, "avg_ms": kernel_ms[dom]},
+                     "algorithmic_bytes": algo, "avg_ms": kernel_ms[dom],
+                     "calibration_copy_bytes": run.probe_bytes / 2.0},
     }
     if not twar:
         out[getattr(run, "bits_key", "bits_per_subpixel")] = 8.0 * nbytes / r["raw"]

@@ -397,7 +397,7 @@ static int ensure_tables()
     static uint32_t eh[kExpHiEntries], el[kExpLoEntries];
     for (int i = 0; i <= kSigEntries; ++i)
         sig[i] = (uint32_t)std::llround(std::ldexp(1.0 / (1.0 + std::exp(-(i - 1024) / 64.0)), 24));
-    for (int i = 0; i < kSigEntries; ++i) cell[i] = make_uint2(sig[i], sig[i + 1] - sig[i]);
+    for (int i = 0; i < kSigEntries; ++i) cell[i] = make_uint2(sig[i], (sig[i + 1] - sig[i]) << 6);
     for (int i = 0; i < kExpHiEntries; ++i)
         eh[i] = (uint32_t)std::llround(std::ldexp(std::exp(4.0 - i / 64.0), 26));
     for (int i = 0; i < kExpLoEntries; ++i)

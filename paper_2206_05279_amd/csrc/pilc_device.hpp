@@ -16,7 +16,9 @@ constexpr int kExpHiEntries = 640;
 constexpr int kExpLoEntries = 64;
 
 // Constant tables in device globals, filled by the host once per device.
-//   g_sig_cell[i] = { T[i], T[i+1]-T[i] },  T[i] = round(2^24 * sigmoid((i-1024)/64))
+//   g_sig_cell[i] = { T[i], (T[i+1]-T[i]) * 64 },  T[i] = round(2^24 * sigmoid((i-1024)/64))
+//     (the slope is below 2^16, so slope * 64 * r for a 10-bit r stays below 2^32 and its upper
+//     half is floor(slope * r / 2^10): the interpolation is one multiply and one add of a half)
 //   g_exp_hi[i]   = round(2^26 * exp(4 - i/64)),  g_exp_lo[j] = round(2^31 * exp(-j/4096))
 extern __device__ uint2 g_sig_cell[kSigEntries];
 extern __device__ uint32_t g_exp_hi[kExpHiEntries];
@@ -115,7 +117,7 @@ __device__ __forceinline__ uint32_t edge_cdf(int d, uint32_t inv_s, const LdsTab
     const int v = (int)__builtin_amdgcn_alignbit((uint32_t)hi, (uint32_t)p, 17);
     const uint32_t w = (uint32_t)min(max(v, 0), (1 << 21) - 1);
     const uint2 cell = t.sig[w >> 10];
-    return cell.x + (__umul24(cell.y, w & 1023u) >> 10);
+    return cell.x + ((uint32_t)__umul24(cell.y, w & 1023u) >> 16);
 }
 
 // floor(f * (2^M - 256) / 2^24) for a 24-bit f:  2^M - 256 = 256 * (spread >> 8) and the product
@@ -130,6 +132,22 @@ __device__ __forceinline__ uint32_t cum_inner(int k, int mu_eff, uint32_t inv_s,
                                               const LdsTables &t)
 {
     return (uint32_t)k + scale_mass(edge_cdf(256 * k + (-128 - mu_eff), inv_s, t), spread);
+}
+
+// -128 - mu' in a register of its own: the edge offset of C(k) is then one shift-and-add per k,
+// instead of being formed again from a packed parameter at every evaluation.
+__device__ __forceinline__ int edge_offset(int mu_eff)
+{
+    int c0 = -128 - mu_eff;
+    asm("" : "+v"(c0));
+    return c0;
+}
+
+// C(k), 1 <= k <= 255, from c0 = edge_offset(mu').
+__device__ __forceinline__ uint32_t cum_inner_at(int k, int c0, uint32_t inv_s, uint32_t spread,
+                                                 const LdsTables &t)
+{
+    return (uint32_t)k + scale_mass(edge_cdf(256 * k + c0, inv_s, t), spread);
 }
 
 // C(k) for any k in 0..256.

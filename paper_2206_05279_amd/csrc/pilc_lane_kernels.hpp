@@ -332,8 +332,9 @@ __global__ __launch_bounds__(kLaneMaxThreads) void k_encode_lanes(Geo g, const u
                 for (int ch = 0; ch < 3; ++ch) {
                     const int x = ck.x[i][ch];
                     const uint32_t inv_s = inv_scale(ck.l[i][ch], tab);
-                    const uint32_t lo = x == 0 ? 0u : cum_inner(x, me[ch], inv_s, spread, tab);
-                    const uint32_t hi = x == 255 ? top : cum_inner(x + 1, me[ch], inv_s, spread, tab);
+                    const int c0 = edge_offset(me[ch]);
+                    const uint32_t lo = x == 0 ? 0u : cum_inner_at(x, c0, inv_s, spread, tab);
+                    const uint32_t hi = x == 255 ? top : cum_inner_at(x + 1, c0, inv_s, spread, tab);
                     cf[3 * ii + ch] = lo | ((hi - lo) << 16);  // cum < 2^16, freq <= 2^16 - 255
                 }
             }
@@ -460,21 +461,23 @@ struct WordStream {
 };
 
 // The same stream for a decoder that works in chunks of at most kRingChunk symbols: the words wait
-// in a ring of 64 per thread in LDS ([16-byte piece][thread]).  Before a chunk the ring is looked
-// at: while it still holds 32 words or more nothing happens (a chunk takes at most 24), otherwise
-// it is filled to the brim with aligned 16-byte loads, four to eight at once, together with the
-// chunk's parameter loads.  No refill inside the chunk ever touches memory or branches on the fill
-// level, and a 128-byte line of the stream is asked for by one or two fills, not by eight.  The
-// word after the current one is read from the ring ahead of time.
+// in a ring of 64 per thread in LDS.  Before a chunk the ring is looked at: while it still holds 32
+// words or more nothing happens (a chunk takes at most 24), otherwise it is filled to the brim with
+// aligned 16-byte loads, four to eight at once, together with the chunk's parameter loads.  No
+// refill inside the chunk ever touches memory or branches on the fill level, and a 128-byte line of
+// the stream is asked for by one or two fills, not by eight.  A thread's 64 words lie side by side
+// (rows of 33 dwords, so that the threads of a wavefront start in different banks): the word at
+// stream position pos is one 16-bit read at (pos mod 64), fetched ahead of its use.
 constexpr int kRingChunk = 24;
 constexpr int kRingPieces = 8;                      // 16-byte pieces per thread: 64 words
 constexpr int kRingWordsHeld = 8 * kRingPieces;
+constexpr int kRingRow = kRingWordsHeld + 2;        // 16-bit elements per thread, padding included
 constexpr int kRingMaxThreads = kLaneMaxThreads;
 static_assert(3 * kChunk <= kRingChunk, "a chunk must not take more words than the ring guarantees");
 
 struct WordRing {
-    uint4 *slot;        // this thread's column of the ring: piece q is slot[q * stride]
-    uint32_t stride;
+    typedef uint32_t __attribute__((may_alias)) word_pair;  // two ring words stored at once
+    uint16_t *row;      // this thread's 64 words
     uint32_t pos;       // word offset (from the 16-byte aligned `base`) of the next word
     uint32_t filled;    // word offset up to which the ring holds the stream: a multiple of 8
     uint32_t nextw;     // the word at `pos`
@@ -483,13 +486,7 @@ struct WordRing {
     {
         return off < lim ? *reinterpret_cast<const uint4 *>(base + off) : make_uint4(0u, 0u, 0u, 0u);
     }
-    __device__ __forceinline__ uint32_t peek() const
-    {
-        // read as the dwords the pieces are made of, so that the access is of the stored type
-        const uint32_t *d =
-            reinterpret_cast<const uint32_t *>(&slot[((pos >> 3) & (kRingPieces - 1)) * stride]);
-        return (d[(pos & 7u) >> 1] >> (16u * (pos & 1u))) & 0xFFFFu;
-    }
+    __device__ __forceinline__ uint32_t peek() const { return row[pos & (kRingWordsHeld - 1)]; }
     // Brings `filled` to (pos rounded down to 8) + 64 if fewer than 32 words are held.
     __device__ __forceinline__ void fill(const uint16_t *base, uint32_t lim)
     {
@@ -502,16 +499,18 @@ struct WordRing {
                 if ((uint32_t)i < n) piece[i] = fetch(base, filled + 8u * i, lim);
 #pragma unroll
             for (int i = 0; i < kRingPieces; ++i)
-                if ((uint32_t)i < n) slot[(((filled >> 3) + i) & (kRingPieces - 1)) * stride] = piece[i];
+                if ((uint32_t)i < n) {
+                    word_pair *d = reinterpret_cast<word_pair *>(row + ((filled + 8u * i) & (kRingWordsHeld - 1)));
+                    d[0] = piece[i].x; d[1] = piece[i].y; d[2] = piece[i].z; d[3] = piece[i].w;
+                }
             filled = want;
         }
         nextw = peek();
     }
     // the lane's first word is at word offset `first` < lim
-    __device__ __forceinline__ void open(uint4 *ring, const uint16_t *base, uint32_t first, uint32_t lim)
+    __device__ __forceinline__ void open(uint16_t *ring, const uint16_t *base, uint32_t first, uint32_t lim)
     {
-        slot = ring + threadIdx.x;
-        stride = blockDim.x;
+        row = ring + threadIdx.x * kRingRow;
         pos = first;
         filled = first & ~7u;
         fill(base, lim);
@@ -533,7 +532,7 @@ __global__ __launch_bounds__(kLaneMaxThreads) void k_decode_lanes(Geo g, const u
                                const unsigned long long *__restrict__ status_payload)
 {
     __shared__ LdsTables tab;
-    __shared__ uint4 ring[kRingPieces * kRingMaxThreads];  // [piece][thread]
+    __shared__ __align__(16) uint16_t ring[kRingRow * kRingMaxThreads];  // [thread][word]
     load_tables(tab);
     if (*status_code != 0) return;  // uniform: written by an earlier kernel
     const uint32_t lane = blockIdx.x * blockDim.x + threadIdx.x;
@@ -589,12 +588,13 @@ __global__ __launch_bounds__(kLaneMaxThreads) void k_decode_lanes(Geo g, const u
                              rsh14_mul(a_bg, (x[1] * 256 - ck.m[i][1]));
                     const uint32_t inv_s = inv_scale(ck.l[i][ch], tab);
                     const uint32_t slot = S & mask;
+                    const int c0 = edge_offset(me);
                     // the symbol is in lo .. lo + 2 * step - 1, and c_hi = C(lo + 2 * step)
                     int lo = 0;
                     uint32_t c_lo = 0u, c_hi = 1u << m_bits;
 #pragma unroll
                     for (int step = 128; step >= 1; step >>= 1) {
-                        const uint32_t cm = cum_inner(lo + step, me, inv_s, spread, tab);
+                        const uint32_t cm = cum_inner_at(lo + step, c0, inv_s, spread, tab);
                         const bool ge = cm <= slot;
                         lo = ge ? lo + step : lo;
                         c_lo = ge ? cm : c_lo;

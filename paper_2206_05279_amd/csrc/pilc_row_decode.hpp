@@ -233,7 +233,7 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_decode_rows(
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
             const uint32_t f24 =
-                am.cell[c].x + ((uint32_t)__umul24(am.cell[c].y, (uint32_t)am.z[c] & 1023u) >> 10);
+                am.cell[c].x + ((uint32_t)__umul24(am.cell[c].y, (uint32_t)am.z[c] & 1023u) >> 16);
             cv[c] = (uint32_t)(am.k0 + c) + ((uint32_t)__umul24(f24, sp8) >> 16);
         }
         cv[0] = am.k0 == 0 ? 0u : cv[0];  // C(0) = 0
