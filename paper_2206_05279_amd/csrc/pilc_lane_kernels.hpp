@@ -237,17 +237,24 @@ __device__ __forceinline__ void feed_pair(ChunkPair &r, LineCarry &c, uint32_t v
     }
 }
 
-// floor(n / f) and the remainder for f < 2^16 and n / f < 2^22 (true after the renormalisation
-// of the encoder), given rf ~ 1/f to float accuracy: the float estimate is within [-2, +1] of the
-// quotient and is fixed up exactly.
-__device__ __forceinline__ uint32_t div_small(uint32_t n, uint32_t f, float rf, uint32_t &rem)
+// floor(n / f) and the remainder for f <= 2^16 and n / f < 2^(32-M) (true after the
+// renormalisation of the encoder), given rf = 1/f to float accuracy.  Conversion, reciprocal and
+// product are each within 2^-24, 2^-23 and 2^-24 of exact, so scaling the estimate by 1 - 2^-21
+// keeps it at or below n / f and within 3.25 * 2^-22 of it: the truncated estimate is the
+// quotient or, for quotients below 2^20 (M >= 12), one less; for M = 10 and 11 up to four less
+// (`more_fixups`, the same for every thread of the launch).
+__device__ __forceinline__ uint32_t div_small(uint32_t n, uint32_t f, float rf, bool more_fixups,
+                                              uint32_t &rem)
 {
-    uint32_t q = (uint32_t)((float)n * rf);
-    int r = (int)(n - __umul24(q, f));
-    if (r < 0) { r += (int)f; q -= 1u; }
-    if (r >= (int)f) { r -= (int)f; q += 1u; }
-    if (r >= (int)f) { r -= (int)f; q += 1u; }
-    rem = (uint32_t)r;
+    uint32_t q = (uint32_t)(((float)n * rf) * 0.999999523162841796875f);
+    uint32_t r = n - (uint32_t)__umul24(q, f);  // q < 2^22 and f < 2^24; q * f <= n
+    if (more_fixups) {
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+            if (r >= f) { r -= f; q += 1u; }
+    }
+    if (r >= f) { r -= f; q += 1u; }
+    rem = r;
     return q;
 }
 
@@ -302,6 +309,8 @@ __global__ __launch_bounds__(kLaneMaxThreads) void k_encode_lanes(Geo g, const u
     uint32_t nwords = 0;
     uint32_t S = 1u << 16;
 
+    const bool more_fixups = m_bits < 12u;
+
     auto encode_chunk = [&](const Chunk &ck, const ChunkPos cp) {
         // a chunk never straddles two images when kVec; otherwise take the image per pixel
         uint32_t im = cp.p / g.hw;
@@ -349,7 +358,7 @@ __global__ __launch_bounds__(kLaneMaxThreads) void k_encode_lanes(Geo g, const u
                         S >>= 16;
                     }
                     uint32_t rem;
-                    const uint32_t q = div_small(S, f, __builtin_amdgcn_rcpf((float)f), rem);
+                    const uint32_t q = div_small(S, f, __builtin_amdgcn_rcpf((float)f), more_fixups, rem);
                     S = (q << m_bits) + rem + lo;
                 }
             }
@@ -563,6 +572,7 @@ __global__ __launch_bounds__(kLaneMaxThreads) void k_decode_lanes(Geo g, const u
     S |= words.take() << 16;
 
     // decodes the chunk into its 24 bytes (6 dwords)
+    // tiles and flat lanes no longer than an image lie in one image: its coefficients are loaded once
     auto decode_chunk = [&](const Chunk &ck, const ChunkPos cp, uint32_t *wout) {
         uint32_t im = cp.p / g.hw;
         int a_gr = coef[3 * im], a_br = coef[3 * im + 1], a_bg = coef[3 * im + 2];

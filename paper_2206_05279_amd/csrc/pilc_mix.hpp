@@ -254,7 +254,7 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_encode(
                 S >>= 16;
             }
             uint32_t rem;
-            const uint32_t q = div_small(S, f, __builtin_amdgcn_rcpf((float)f), rem);
+            const uint32_t q = div_small(S, f, __builtin_amdgcn_rcpf((float)f), m_bits < 12u, rem);
             S = (q << m_bits) + rem + lo;
         }
     }
