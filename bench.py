@@ -121,6 +121,13 @@ def _run_pmc(counter: str, argv):
 
 
 COPY_KERNEL = "bitwise_not"   # the child's plain read-all-write-all pass between two workloads
+PROBE_MAX_BYTES = 1 << 30     # the pass covers at most this much: one launch (torch splits an
+                              # elementwise kernel beyond 2^31 elements), counters far from any limit
+
+
+def probe_copy_bytes(run):
+    """Bytes read (and bytes written) by the child's plain pass after `run`."""
+    return float(min(int(run.probe_bytes // 2), PROBE_MAX_BYTES))
 
 
 def measure_traffic(argv, count):
@@ -159,8 +166,9 @@ def traffic_of(kernel, seg, copy_bytes):
         if not seg.get(key + "_copy_kib"):
             return None, None
         scale = copy_bytes / (seg[key + "_copy_kib"] * 1024.0)
+        # the timing name is the kernel's, or its stem (k_twar_inverse: k_twar_inverse<..>, .._tall)
         vals = [v for name, v in seg[key].items()
-                if ("::" + kernel) in name and name.split("::" + kernel)[1][:1] in ("", "<")]
+                if ("::" + kernel) in name and not name.split("::" + kernel)[1][:1].isalpha()]
         if not vals:
             return None, None
         detail[key + "_bytes"] = vals[-1] * 1024.0 * scale
@@ -663,7 +671,7 @@ def report(run, r, seg, torch, with_copy=False):
     dom = max(kernel_ms, key=kernel_ms.get)
     algo = run.algo_bytes(nbytes)
     achieved = algo / (kernel_ms[dom] * 1e-3) / 1e9
-    traffic, detail = traffic_of(dom, seg, run.probe_bytes / 2.0)
+    traffic, detail = traffic_of(dom, seg, probe_copy_bytes(run))
     twar = isinstance(run, TwarRun)
     out = {
         "step": run.step,
@@ -674,7 +682,7 @@ def report(run, r, seg, torch, with_copy=False):
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_detail": detail,
                      "algorithmic_bytes": algo, "avg_ms": kernel_ms[dom],
-                     "calibration_copy_bytes": run.probe_bytes / 2.0},
+                     "calibration_copy_bytes": probe_copy_bytes(run)},
     }
     if not twar:
         out[getattr(run, "bits_key", "bits_per_subpixel")] = 8.0 * nbytes / r["raw"]
@@ -722,7 +730,7 @@ def main():
             run.timed(1, 1)
             # a plain pass over a buffer of known size (every byte read once and written once) under
             # a kernel name nothing else here uses: it ends the workload's segment and calibrates
-            src = run.probe_src.view(torch.uint8)
+            src = run.probe_src.view(torch.uint8).reshape(-1)[:int(probe_copy_bytes(run))]
             probe = torch.empty_like(src)
             torch.bitwise_not(src, out=probe)
             torch.cuda.synchronize()
