@@ -52,59 +52,75 @@ int ansai_oracle_build_tables(const ansai_model *md, int32_t *delta, uint32_t *p
     return 0;
 }
 
-int64_t ansai_oracle_encode_piece_loops(const ansai_model *md, const uint8_t *sym,
-                                        const uint8_t *dist, int64_t count, uint8_t *bits_out,
-                                        uint32_t *state_out)
+/* Number of significant bits of v (0 for v = 0). */
+static int bit_length(uint32_t v)
 {
-    uint32_t top, s = 0; /* Alg. 1 holds S in [0, 2^M) between symbols */
+    int n = 0;
+    while (v) { ++n; v >>= 1; }
+    return n;
+}
+
+/* The modified rANS of Sec. 3.2 (Algs. 1-2) without tables, a symbol's whole group of bits at
+ * once.  Push of x under masses P, C: the state v in [2^M, 2^(M+1)) gives up its b low bits, b the
+ * smallest count with floor(v / 2^b) < 2 P_x (which leaves the rest in [P_x, 2 P_x)), and becomes
+ * 2^M + (rest - P_x) + C_x.  b follows from the bit lengths of v and of 2 P_x - 1: shifting by
+ * their difference makes the lengths equal, and one more shift is needed exactly if the rest is
+ * still above 2 P_x - 1. */
+int64_t ansai_oracle_encode_piece_direct(const ansai_model *md, const uint8_t *sym,
+                                         const uint8_t *dist, int64_t count, uint8_t *bits_out,
+                                         uint32_t *state_out)
+{
+    uint32_t top, v;
     int64_t n = 0, t;
     if (!model_ok(md)) return -1;
     top = (uint32_t)1 << md->prec_bits;
+    v = top; /* the initial state */
     for (t = count - 1; t >= 0; --t) {
         const uint32_t *row;
         uint32_t p, c = 0;
-        int x;
+        int x, b, i;
         if (dist[t] >= md->num_dist || sym[t] >= md->num_sym) return -1;
         row = md->mass + (size_t)md->num_sym * dist[t];
         p = row[sym[t]];
         for (x = 0; x < sym[t]; ++x) c += row[x];
-        s += top;
-        while (s >= 2 * p) {
-            bits_out[n++] = (uint8_t)(s & 1);
-            s >>= 1;
-        }
-        s = s - p + c;
+        b = bit_length(v) - bit_length(2 * p - 1);
+        if (b < 0) b = 0;
+        if ((v >> b) >= 2 * p) ++b;
+        for (i = 0; i < b; ++i) bits_out[n++] = (uint8_t)((v >> i) & 1); /* bit 0 first */
+        v = top + ((v >> b) - p) + c;
     }
-    *state_out = s + top;
+    *state_out = v;
     return n;
 }
 
-int ansai_oracle_decode_piece_loops(const ansai_model *md, const uint8_t *dist, int64_t count,
-                                    const uint8_t *bits, int64_t nbits, uint32_t state,
-                                    uint8_t *sym_out)
+/* Pop: x is the symbol whose interval [C_x, C_x + P_x) holds v - 2^M; t = v - 2^M - C_x + P_x lies
+ * in [P_x, 2 P_x), and the b = M + 1 - (bit length of t) bits pushed last return below it, the
+ * last pushed one highest, which puts the state back into [2^M, 2^(M+1)). */
+int ansai_oracle_decode_piece_direct(const ansai_model *md, const uint8_t *dist, int64_t count,
+                                     const uint8_t *bits, int64_t nbits, uint32_t state,
+                                     uint8_t *sym_out)
 {
-    uint32_t top, s;
+    uint32_t top, v;
     int64_t t;
     if (!model_ok(md)) return -1;
     top = (uint32_t)1 << md->prec_bits;
     if (state < top || state >= 2 * top) return -6;
-    s = state - top;
+    v = state;
     for (t = 0; t < count; ++t) {
         const uint32_t *row;
-        uint32_t c = 0;
-        int x = 0;
+        uint32_t c = 0, r = v - top, u;
+        int x = 0, b, i;
         if (dist[t] >= md->num_dist) return -1;
         row = md->mass + (size_t)md->num_sym * dist[t];
-        while (c + row[x] <= s) c += row[x++]; /* the x with C_x <= S < C_x + P_x */
+        while (c + row[x] <= r) c += row[x++];
         sym_out[t] = (uint8_t)x;
-        s = s - c + row[x];
-        while (s < top) {
-            if (nbits == 0) return -6;
-            s = 2 * s + bits[--nbits];
-        }
-        s -= top;
+        u = r - c + row[x];
+        b = md->prec_bits + 1 - bit_length(u);
+        if (nbits < b) return -6;
+        for (i = 0; i < b; ++i) u = (u << 1) | bits[--nbits];
+        v = u;
     }
-    return (s == 0 && nbits == 0) ? 0 : -6;
+    return (v == top && nbits == 0) ? 0 : -6;
 }
 
 #define HDR 64

@@ -45,15 +45,17 @@ typedef struct {
 int ansai_oracle_build_tables(const ansai_model *model, int32_t *delta, uint32_t *phi,
                               uint8_t *theta, uint8_t *nbits, uint16_t *next);
 
-/* One piece with the loops of Alg. 1, no tables.  bits_out (capacity count*M): one bit per
- * byte in push order.  Returns the number of bits (-1 on a bad symbol or index); *state_out is
- * the final state as the merged form of Alg. 3 holds it, in [2^M, 2^(M+1)). */
-int64_t ansai_oracle_encode_piece_loops(const ansai_model *model, const uint8_t *sym,
+/* One piece with the modified rANS of Sec. 3.2 computed directly from the masses, no tables: per
+ * symbol the count of bits that leave the state follows from bit lengths (see the .c file).
+ * bits_out (capacity count*M): one bit per byte in push order.  Returns the number of bits (-1 on
+ * a bad symbol or index); *state_out is the final state in [2^M, 2^(M+1)). */
+int64_t ansai_oracle_encode_piece_direct(const ansai_model *model, const uint8_t *sym,
                                         const uint8_t *dist, int64_t count, uint8_t *bits_out,
                                         uint32_t *state_out);
-/* The inverse with the search and the loop of Alg. 2.  0 on success, -6 if the stream runs dry,
- * is not used up, or the state does not return to its start. */
-int ansai_oracle_decode_piece_loops(const ansai_model *model, const uint8_t *dist, int64_t count,
+/* Its inverse: interval search over the running sums, then the bits that restore the state's
+ * range, counted from the bit length.  0 on success, -6 if the stream runs dry, is not used up, or
+ * the state does not return to its start. */
+int ansai_oracle_decode_piece_direct(const ansai_model *model, const uint8_t *dist, int64_t count,
                                     const uint8_t *bits, int64_t nbits, uint32_t state,
                                     uint8_t *sym_out);
 

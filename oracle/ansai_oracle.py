@@ -40,10 +40,10 @@ def lib():
         mp = C.POINTER(Model)
         L.ansai_oracle_build_tables.restype = C.c_int
         L.ansai_oracle_build_tables.argtypes = [mp, i32p, u32p, u8p, u8p, u16p]
-        L.ansai_oracle_encode_piece_loops.restype = C.c_int64
-        L.ansai_oracle_encode_piece_loops.argtypes = [mp, u8p, u8p, C.c_int64, u8p, u32p]
-        L.ansai_oracle_decode_piece_loops.restype = C.c_int
-        L.ansai_oracle_decode_piece_loops.argtypes = [mp, u8p, C.c_int64, u8p, C.c_int64, C.c_uint32, u8p]
+        L.ansai_oracle_encode_piece_direct.restype = C.c_int64
+        L.ansai_oracle_encode_piece_direct.argtypes = [mp, u8p, u8p, C.c_int64, u8p, u32p]
+        L.ansai_oracle_decode_piece_direct.restype = C.c_int
+        L.ansai_oracle_decode_piece_direct.argtypes = [mp, u8p, C.c_int64, u8p, C.c_int64, C.c_uint32, u8p]
         L.ansai_oracle_max_coded_bytes.restype = C.c_uint64
         L.ansai_oracle_max_coded_bytes.argtypes = [C.c_uint32, C.c_uint32, C.c_int]
         L.ansai_oracle_encode.restype = C.c_int
@@ -91,27 +91,27 @@ def build_tables(prec_bits: int, mass):
     return delta, phi, theta, nbits, nxt
 
 
-def encode_piece_loops(prec_bits: int, mass, sym, dist):
+def encode_piece_direct(prec_bits: int, mass, sym, dist):
     md = _Held(prec_bits, mass)
     sym = np.ascontiguousarray(sym, dtype=np.uint8)
     dist = np.ascontiguousarray(dist, dtype=np.uint8)
     assert sym.shape == dist.shape and sym.ndim == 1
     bits = np.zeros(max(sym.size * prec_bits, 1), dtype=np.uint8)
     state = C.c_uint32(0)
-    n = lib().ansai_oracle_encode_piece_loops(md.ref, _ptr(sym, C.c_uint8), _ptr(dist, C.c_uint8), sym.size,
+    n = lib().ansai_oracle_encode_piece_direct(md.ref, _ptr(sym, C.c_uint8), _ptr(dist, C.c_uint8), sym.size,
                                               _ptr(bits, C.c_uint8), C.byref(state))
     if n < 0:
-        raise ValueError("ansai encode_piece_loops rc=%d" % n)
+        raise ValueError("ansai encode_piece_direct rc=%d" % n)
     return bits[:n].copy(), int(state.value)
 
 
-def decode_piece_loops(prec_bits: int, mass, dist, bits, state: int):
+def decode_piece_direct(prec_bits: int, mass, dist, bits, state: int):
     md = _Held(prec_bits, mass)
     dist = np.ascontiguousarray(dist, dtype=np.uint8)
     bits = np.ascontiguousarray(bits, dtype=np.uint8)
     out = np.zeros(max(dist.size, 1), dtype=np.uint8)
     bbuf = bits if bits.size else np.zeros(1, dtype=np.uint8)
-    rc = lib().ansai_oracle_decode_piece_loops(md.ref, _ptr(dist, C.c_uint8), dist.size, _ptr(bbuf, C.c_uint8),
+    rc = lib().ansai_oracle_decode_piece_direct(md.ref, _ptr(dist, C.c_uint8), dist.size, _ptr(bbuf, C.c_uint8),
                                                bits.size, int(state), _ptr(out, C.c_uint8))
     return rc, out[: dist.size].copy()
 

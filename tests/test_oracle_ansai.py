@@ -63,14 +63,14 @@ def test_worked_example_streams():
     mass = np.array([g["mass"]], dtype=np.uint32)
     sym = np.array(g["symbols"], dtype=np.uint8)
     dist = np.zeros_like(sym)
-    bits, state = ao.encode_piece_loops(m, mass, sym, dist)
+    bits, state = ao.encode_piece_direct(m, mass, sym, dist)
     assert bits.tolist() == g["pushed_bits"] and state == g["final_state"][0]
     rc, coded = ao.encode(m, mass, sym[None], dist[None])
     assert rc == ao.OK
     _, fields, payload, offs, recs = parse(coded, 1)
     assert fields == (1, 1, 4, 3, 1, 3) and payload == 12 and offs.tolist() == [0, 12]
     assert recs[0][0] == g["final_state"][0] and recs[0][1] == 5 and recs[0][2].tolist() == g["stream_word"]
-    rc, back = ao.decode_piece_loops(m, mass, dist, bits, state)
+    rc, back = ao.decode_piece_direct(m, mass, dist, bits, state)
     assert rc == 0 and back.tolist() == g["symbols"]
     rc, back = ao.decode(m, mass, dist[None], coded)
     assert rc == 0 and back[0].tolist() == g["symbols"]
@@ -177,13 +177,13 @@ def test_lemma_delta_fits_16_bits():
     assert ao.build_tables(12, mass)[0].min() < 0
 
 
-# ---------------------------------------------------------------- loops == tables, round trips
+# ------------------------------------------------- table-free coder == tables, round trips
 def draw(rng, m, mass, pieces, count, uniform=False):
     return sp.draw_pieces(mass, m, pieces, count, seed=int(rng.integers(1 << 30)), uniform_sym=uniform, threads=1)
 
 
 @pytest.mark.parametrize("uniform", [False, True], ids=["from-law", "uniform"])
-def test_tables_and_loops_produce_the_same_stream(model, uniform):
+def test_tables_and_table_free_coder_produce_the_same_stream(model, uniform):
     """Appendix: ANS-AI and the modified rANS are numerically equivalent."""
     m, mass, rng = model
     pieces, count = 6, 257
@@ -195,13 +195,13 @@ def test_tables_and_loops_produce_the_same_stream(model, uniform):
     assert coded.size == 64 + 4 * (pieces + 1) + payload and offs[0] == 0 and offs[-1] == payload
     assert coded.size <= ao.max_coded_bytes(pieces, count, m)
     for i in range(pieces):
-        bits, state = ao.encode_piece_loops(m, mass, sym[i], dist[i])
+        bits, state = ao.encode_piece_direct(m, mass, sym[i], dist[i])
         assert recs[i][0] == state and recs[i][1] == bits.size
         assert recs[i][2].size == (bits.size + 31) // 32
         assert np.array_equal(bits_of(recs[i][1], recs[i][2]), bits)
         if bits.size % 32:
             assert int(recs[i][2][-1]) >> (bits.size % 32) == 0  # padding bits are zero
-        rc, back = ao.decode_piece_loops(m, mass, dist[i], bits, state)
+        rc, back = ao.decode_piece_direct(m, mass, dist[i], bits, state)
         assert rc == 0 and np.array_equal(back, sym[i])
     rc, back = ao.decode(m, mass, dist, coded)
     assert rc == ao.OK and np.array_equal(back, sym)
