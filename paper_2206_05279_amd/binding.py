@@ -71,12 +71,17 @@ _lib = None
 
 
 def lib():
-    """Loads libpilc.so (building it first only if no built library exists)."""
+    """Loads libpilc.so (building it first only if no built library exists; a library older than
+    its sources is loaded with a warning: `python -m paper_2206_05279_amd.build` rebuilds it)."""
     global _lib
     if _lib is None:
+        from . import build
         if not os.path.exists(LIB_PATH):
-            from . import build
             build.build_lib()
+        elif build.built_digest() != build.source_digest():
+            import warnings
+            warnings.warn("libpilc.so was not built from the current csrc/ and include/pilc.h: "
+                          "run `python -m paper_2206_05279_amd.build`", RuntimeWarning, stacklevel=2)
         L = C.CDLL(LIB_PATH)
         gp, pp = C.POINTER(pilc_geom), C.POINTER(pilc_params)
         L.pilc_lane_count.restype = C.c_uint64

@@ -1,6 +1,8 @@
 """Builds libpilc.so (hipcc, gfx950 only) next to this file."""
 from __future__ import annotations
 
+import glob
+import hashlib
 import os
 import subprocess
 
@@ -17,13 +19,40 @@ FLAGS = [
 ]
 
 
+DIGEST = LIB + ".digest"   # what the library was built from, so that a stale one is noticed
+
+
+def source_digest() -> str:
+    """SHA-256 over the compile flags and every file the library is built from."""
+    h = hashlib.sha256(" ".join(FLAGS).encode())
+    files = sorted(glob.glob(os.path.join(CSRC, "*")))
+    files.append(os.path.join(os.path.dirname(_HERE), "include", "pilc.h"))
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def built_digest() -> str:
+    """The digest recorded by the build that made the library ('' if none)."""
+    try:
+        with open(DIGEST) as fh:
+            return fh.read().strip()
+    except OSError:
+        return ""
+
+
 def build_lib(verbose: bool = False) -> str:
     tmp = LIB + ".tmp%d" % os.getpid()
     cmd = [HIPCC] + FLAGS + ["-o", tmp] + SOURCES
     if verbose:
         print(" ".join(cmd), flush=True)
+    digest = source_digest()
     subprocess.check_call(cmd)
     os.replace(tmp, LIB)
+    with open(DIGEST, "w") as fh:
+        fh.write(digest + "\n")
     return LIB
 
 

@@ -25,6 +25,14 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, name), name
 
 
+def test_library_was_built_from_the_current_sources():
+    """The build records a digest of csrc/ and include/pilc.h beside the library; a library that
+    was not rebuilt after a source change would be tested in place of the sources."""
+    from paper_2206_05279_amd import build
+    pb.lib()
+    assert build.built_digest() == build.source_digest(), "run python -m paper_2206_05279_amd.build"
+
+
 def test_version_and_messages():
     assert pb.pilc_version() == 1
     for code in range(-7, 1):
