@@ -19,8 +19,8 @@
  *   - Return value: 0 on success, a negative PILC_E_* code otherwise.  No exceptions.  Calls on
  *     different streams may run concurrently, from any threads, if they use different workspaces.
  *     The library's only process-wide state: the constant tables (filled once per device under a
- *     lock), the two tuning knobs pilc_set_timing and pilc_set_kernel_policy (atomic integers, read
- *     once at the start of a call), and the scratch array of pilc_encode_static.
+ *     lock), the knobs pilc_set_timing, pilc_set_kernel_policy and pilc_set_one_pass_wait (atomic
+ *     integers, read once at the start of a call), and the scratch array of pilc_encode_static.
  *   - Tensors are dense, row-major, channel-interleaved: index ((i*h + y)*w + x)*3 + c.
  */
 #ifndef PILC_H
@@ -44,7 +44,9 @@ enum {
     PILC_E_FORMAT = -5,    /* decode: bad magic / version / geometry mismatch / size        */
     PILC_E_CORRUPT = -6,   /* decode: offsets not monotone or out of bounds, a lane runs
                               past its end, or does not return to its initial state         */
-    PILC_E_HIP = -7        /* HIP runtime failure (see pilc_last_hip_error)                 */
+    PILC_E_HIP = -7,       /* HIP runtime failure (see pilc_last_hip_error)                 */
+    PILC_E_TIMEOUT = -8    /* encode: a bounded wait between workgroups ran out (see
+                              pilc_set_one_pass_wait); coded_dev contents undefined         */
 };
 
 /* Geometry of a batch.  M = prec_bits is the constant of Sec. 3.2 for which every
@@ -96,7 +98,7 @@ int pilc_workspace_size(const pilc_geom *geom, size_t *workspace_bytes_host,
  * prefix sum of lane byte counts, relative to the payload); payload = for each lane its
  * final 32-bit state followed by its 16-bit words in the order the decoder reads them.
  * Errors: PILC_E_ARG, PILC_E_WORKSPACE, PILC_E_CAPACITY (coded_dev contents undefined),
- * PILC_E_TOO_LARGE, PILC_E_HIP. */
+ * PILC_E_TOO_LARGE, PILC_E_HIP, PILC_E_TIMEOUT. */
 int pilc_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_params *params,
                 void *workspace_dev, size_t workspace_bytes, uint8_t *coded_dev,
                 size_t coded_capacity, uint64_t *coded_bytes_host, void *hip_stream);
@@ -177,10 +179,21 @@ const char *pilc_timing_name(int index_in_last_call);
 
 /* Which lane kernels encode and decode use: 0 = chosen from the lane count (default), 1 = one
  * thread per lane, 2 = the kernels for few long lanes (workgroup-cooperative encode, a row of 16
- * threads per lane in decode).  All choices produce the same bytes; the knob exists for tuning and
- * for testing every kernel on the same input.  Process-wide.  Errors: PILC_E_ARG for any other
- * value. */
+ * threads per lane in decode), 3 = one thread per lane with the one-pass encoder (the lane kernel
+ * also computes the offsets and places its lanes in the container, instead of leaving that to the
+ * scan and pack kernels; measured slower, kept for comparison).  All choices produce the same
+ * bytes; the knob exists for tuning and for testing every kernel on the same input.  Process-wide.
+ * Errors: PILC_E_ARG for any other value. */
 int pilc_set_kernel_policy(int policy);
+
+/* The one-pass encoder's (policy 3) workgroups learn where their lanes go from the workgroups
+ * before them (the scan of Sec. 4.1's container offsets, fused into the lane kernel); a workgroup
+ * waits for an earlier one at most `ticks` ticks of the GPU's constant-rate clock (0 = the
+ * default, two seconds) and then gives up: the call returns PILC_E_TIMEOUT and every kernel still
+ * ends.
+ * `withhold_first` != 0 makes the first workgroup publish nothing, which forces that path: for
+ * tests of the give-up path only.  Process-wide. */
+void pilc_set_one_pass_wait(uint64_t ticks, int withhold_first);
 
 /* ------------------------------------------------------------------------------------------
  * The paper's own coder variant: ANS-AI (Sec. 3.2, Alg. 3 "Encode x", Alg. 4 "Decode one

@@ -32,11 +32,11 @@ constexpr uint32_t kHeaderBytes = 64;
 // status word kinds (device side), mapped to PILC_E_* on the host
 constexpr uint32_t kMagicPilc = 0x434C4950u;  // "PILC"
 constexpr uint32_t kMagicMix = 0x58494D50u;   // "PMIX"
-enum : int { ST_OK = 0, ST_TOO_LARGE = 4, ST_FORMAT = 5, ST_CORRUPT = 6, ST_CAPACITY = 3, ST_PARAMS = 7 };
+enum : int { ST_OK = 0, ST_TOO_LARGE = 4, ST_FORMAT = 5, ST_CORRUPT = 6, ST_CAPACITY = 3, ST_PARAMS = 7, ST_TIMEOUT = 8 };
 
 struct Status {
     int code;
-    int pad;
+    uint32_t ticket;  // the one-pass encoder's workgroups number themselves from it
     unsigned long long payload_bytes;
 };
 
@@ -305,8 +305,20 @@ __global__ __launch_bounds__(256) void k_pack_by_thread(uint32_t lanes, uint32_t
 __global__ void k_init_status(Status *status)
 {
     status->code = ST_OK;
-    status->pad = 0;
+    status->ticket = 0;
     status->payload_bytes = 0;
+}
+
+// The same, and the look-back descriptors of the one-pass encoder cleared.
+__global__ void k_init_one_pass(Status *status, unsigned long long *desc, uint32_t n)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0u) {
+        status->code = ST_OK;
+        status->ticket = 0;
+        status->payload_bytes = 0;
+    }
+    if (i < n) desc[i] = 0ull;
 }
 
 // `word11` is header word 11 for containers that use it (the number of mixture components);
@@ -346,8 +358,13 @@ namespace pilc {
 // --------------------------------------------------------------------------------------------
 // Host side
 // --------------------------------------------------------------------------------------------
-// 0 chosen from the lane count, 1 thread per lane, 2 the kernels for few long lanes
+// 0 chosen from the lane count, 1 thread per lane, 2 the kernels for few long lanes, 3 thread per
+// lane with the one-pass encoder (the lane kernel also scans and packs)
 static std::atomic<int> g_kernel_policy{0};
+// Bound of a look-back wait of the one-pass encoder in ticks of the constant-rate clock (0: two
+// seconds), and the switch that makes its first workgroup publish nothing (tests only).
+static std::atomic<unsigned long long> g_one_pass_wait{0};
+static std::atomic<int> g_one_pass_withhold{0};
 
 // The few-lane kernels pay off while there are too few lanes to fill the chip with one thread
 // each (256 CUs x 4 SIMDs x 64 threads = 65,536 threads for a single wave per SIMD).  Measured
@@ -359,7 +376,7 @@ static std::atomic<int> g_kernel_policy{0};
 static bool use_few_lane_kernels(const Geo &g, bool decode)
 {
     const int policy = g_kernel_policy.load(std::memory_order_relaxed);
-    if (policy == 1) return false;
+    if (policy == 1 || policy == 3) return false;
     if (policy == 2) return true;
     return g.lanes <= (decode ? 12288u : 28672u);
 }
@@ -460,7 +477,7 @@ static uint32_t max_lane_symbols(const Geo &g)
 }
 
 struct Workspace {
-    size_t status_off, words_off, state_off, sums_off, scratch_off, total;
+    size_t status_off, words_off, state_off, sums_off, desc_off, scratch_off, total;
     uint32_t scan_blocks;
 };
 
@@ -477,6 +494,8 @@ static Workspace layout(const Geo &g)
     off = align256(off + 4 * (size_t)g.lanes);
     w.sums_off = off;
     off = align256(off + 8 * (size_t)w.scan_blocks);
+    w.desc_off = off;  // one look-back descriptor per workgroup of the one-pass encoder (>= 64 lanes each)
+    off = align256(off + 8 * (size_t)ceil_div64(g.lanes, 64));
     w.scratch_off = off;
     // one 16-bit word per symbol, plus one dump word per lane for the branch-free encoder; the
     // thread-per-lane encoder gives every lane of a block of 64 the room of the longest lane
@@ -495,6 +514,7 @@ static int status_to_error(int st)
     case ST_TOO_LARGE: return PILC_E_TOO_LARGE;
     case ST_FORMAT: return PILC_E_FORMAT;
     case ST_PARAMS: return PILC_E_ARG;
+    case ST_TIMEOUT: return PILC_E_TIMEOUT;
     default: return PILC_E_CORRUPT;
     }
 }
@@ -628,6 +648,7 @@ const char *pilc_strerror(int code)
     case PILC_E_FORMAT: return "container header does not match (magic, version, geometry or size)";
     case PILC_E_CORRUPT: return "container is corrupt (offsets, lane overrun or final state)";
     case PILC_E_HIP: return "HIP runtime failure";
+    case PILC_E_TIMEOUT: return "a bounded wait between workgroups ran out";
     default: return "unknown error code";
     }
 }
@@ -638,9 +659,15 @@ void pilc_set_timing(int enabled) { g_timing_enabled.store(enabled, std::memory_
 
 int pilc_set_kernel_policy(int policy)
 {
-    if (policy < 0 || policy > 2) return PILC_E_ARG;
+    if (policy < 0 || policy > 3) return PILC_E_ARG;
     g_kernel_policy.store(policy, std::memory_order_relaxed);
     return PILC_OK;
+}
+
+void pilc_set_one_pass_wait(uint64_t ticks, int withhold_first)
+{
+    g_one_pass_wait.store(ticks, std::memory_order_relaxed);
+    g_one_pass_withhold.store(withhold_first != 0, std::memory_order_relaxed);
 }
 
 int pilc_last_timing(float *ms_out_host, int capacity)
@@ -717,54 +744,94 @@ static int encode_checked(const Geo &g, const uint8_t *img_dev, const pilc_param
     uint16_t *payload = reinterpret_cast<uint16_t *>(coded_dev + table_end);
 
     Timer timer(stream, timed);
-    k_init_status<<<1, 1, 0, stream>>>(status);
     const bool few_lanes = use_few_lane_kernels(g, false);
     const uint32_t lane_cap = few_lanes ? 0u : max_lane_symbols(g);  // selects the scratch layout
+    const HeaderWords head = {{kMagicPilc, PILC_VERSION, g.n, g.h, g.w, 3u, g.prec_bits,
+                               g.lane_mode, g.lane_a, g.lane_b, g.lanes, 0u}};
+    // Policy 3: the lane kernel also scans and packs (one pass).  Not the default: measured 5 %
+    // (64 x 64 images, one lane per row) to 10 % (16 x 16 tiles of video frames) slower than the
+    // lane kernel followed by the scan and pack kernels.
+    const bool one_pass = !few_lanes && g_kernel_policy.load(std::memory_order_relaxed) == 3;
+    OnePass op = {};
+    if (one_pass) {
+        const int bt = lane_block_threads(g);
+        const uint32_t nb = (uint32_t)ceil_div64(g.lanes, bt);
+        int dev = 0, khz = 0;
+        HIP_TRY(hipGetDevice(&dev));
+        if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0)
+            khz = 100000;
+        const unsigned long long wait = g_one_pass_wait.load(std::memory_order_relaxed);
+        op.desc = reinterpret_cast<unsigned long long *>(base + ws.desc_off);
+        op.ticket = &status->ticket;
+        op.status = status;
+        op.coded = coded_dev;
+        op.payload_capacity = coded_capacity - table_end;
+        op.wait_ticks = wait ? wait : 2000ull * (unsigned long long)khz;
+        op.groups = nb;
+        op.withhold_first = (uint32_t)g_one_pass_withhold.load(std::memory_order_relaxed);
+        op.head = head;
+        k_init_one_pass<<<(nb + 255u) / 256u, 256, 0, stream>>>(status, op.desc, nb);
+    } else {
+        k_init_status<<<1, 1, 0, stream>>>(status);
+    }
     if (few_lanes) {
         k_encode_block<<<(uint32_t)ceil_div64(g.lanes, kEncLanes), kEncThreads, 0, stream>>>(
             g, img_dev, params->mu, params->log_scale, params->chan_coef, scratch, g.total_px * 3u,
             lane_words, lane_state);
     } else {
         const int bt = lane_block_threads(g);
-        const uint32_t nb = (uint32_t)ceil_div64(g.lanes, bt);
-        if (chunks_aligned(g, img_dev, params) && chunks_pair_up(g, img_dev) && lanes_line_up(g, params))
-            k_encode_lanes<true, true, true><<<nb, bt, 0, stream>>>(g, img_dev, params->mu, params->log_scale,
-                                                                    params->chan_coef, scratch, lane_cap,
-                                                                    lane_words, lane_state);
-        else if (chunks_aligned(g, img_dev, params) && chunks_pair_up(g, img_dev))
-            k_encode_lanes<true, true><<<nb, bt, 0, stream>>>(g, img_dev, params->mu, params->log_scale,
-                                                              params->chan_coef, scratch, lane_cap,
-                                                              lane_words, lane_state);
-        else if (chunks_aligned(g, img_dev, params))
-            k_encode_lanes<true, false><<<nb, bt, 0, stream>>>(g, img_dev, params->mu, params->log_scale,
-                                                               params->chan_coef, scratch, lane_cap,
-                                                               lane_words, lane_state);
-        else
-            k_encode_lanes<false, false><<<nb, bt, 0, stream>>>(g, img_dev, params->mu, params->log_scale,
-                                                                params->chan_coef, scratch, lane_cap,
-                                                                lane_words, lane_state);
+        uint32_t nb = (uint32_t)ceil_div64(g.lanes, bt);
+        if (one_pass) {
+            // workgroups take groups of lanes from a counter until none is left: no more of them
+            // than the chip holds at once (a workgroup that starts late finds nothing to do)
+            int dev = 0, cus = 0;
+            HIP_TRY(hipGetDevice(&dev));
+            if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+                cus = 256;
+            const uint32_t resident = (uint32_t)cus * (uint32_t)(1024 / bt);
+            if (nb > resident) nb = resident;
+        }
+        const bool vec = chunks_aligned(g, img_dev, params);
+        const bool pair = vec && chunks_pair_up(g, img_dev);
+        const bool line = pair && lanes_line_up(g, params);
+#define PILC_LAUNCH_ENCODE(ONE, VEC, PAIR, LINE)                                                      \
+    k_encode_lanes<ONE, VEC, PAIR, LINE><<<nb, bt, 0, stream>>>(g, img_dev, params->mu, params->log_scale, \
+                                                               params->chan_coef, scratch, lane_cap,  \
+                                                               lane_words, lane_state, op)
+        if (one_pass) {
+            if (line) PILC_LAUNCH_ENCODE(true, true, true, true);
+            else if (pair) PILC_LAUNCH_ENCODE(true, true, true, false);
+            else if (vec) PILC_LAUNCH_ENCODE(true, true, false, false);
+            else PILC_LAUNCH_ENCODE(true, false, false, false);
+        } else {
+            if (line) PILC_LAUNCH_ENCODE(false, true, true, true);
+            else if (pair) PILC_LAUNCH_ENCODE(false, true, true, false);
+            else if (vec) PILC_LAUNCH_ENCODE(false, true, false, false);
+            else PILC_LAUNCH_ENCODE(false, false, false, false);
+        }
+#undef PILC_LAUNCH_ENCODE
     }
     timer.mark(few_lanes ? "k_encode_block" : "k_encode_lanes");
-    const ItemBytes lane_bytes = {4u, 2u, 0u, 0u};  // a 32-bit state and 16-bit words
-    const HeaderWords head = {{kMagicPilc, PILC_VERSION, g.n, g.h, g.w, 3u, g.prec_bits,
-                               g.lane_mode, g.lane_a, g.lane_b, g.lanes, 0u}};
-    k_scan_partials<<<ws.scan_blocks, kScanThreads, 0, stream>>>(g.lanes, lane_bytes, lane_words, sums);
-    k_scan_spine<<<1, kScanThreads, 0, stream>>>(head, g.lanes, ws.scan_blocks, sums, coded_dev,
-                                                 (unsigned long long)coded_capacity, status);
-    k_scan_apply<<<ws.scan_blocks, kScanThreads, 0, stream>>>(g.lanes, lane_bytes, lane_words, sums,
-                                                              offsets);
-    timer.mark("scan");
-    // a run of lanes per workgroup: about 16K symbols' worth, at most 256 lanes
-    const uint32_t lane_sym = max_lane_symbols(g);
-    uint32_t pack_lanes = 16384u / (lane_sym ? lane_sym : 1u);
-    pack_lanes = pack_lanes < 1 ? 1 : (pack_lanes > (uint32_t)kPackMaxLanes ? kPackMaxLanes : pack_lanes);
-    if (lane_cap != 0u)
-        k_pack_by_thread<<<(uint32_t)ceil_div64(g.lanes, 64), 256, 0, stream>>>(
-            g.lanes, lane_cap, scratch, lane_state, offsets, payload, status);
-    else
-        k_pack<<<(uint32_t)ceil_div64(g.lanes, pack_lanes), 256, 0, stream>>>(
-            g, pack_lanes, scratch, lane_state, offsets, payload, status);
-    timer.mark(lane_cap != 0u ? "k_pack_by_thread" : "k_pack");
+    if (!one_pass) {
+        const ItemBytes lane_bytes = {4u, 2u, 0u, 0u};  // a 32-bit state and 16-bit words
+        k_scan_partials<<<ws.scan_blocks, kScanThreads, 0, stream>>>(g.lanes, lane_bytes, lane_words, sums);
+        k_scan_spine<<<1, kScanThreads, 0, stream>>>(head, g.lanes, ws.scan_blocks, sums, coded_dev,
+                                                     (unsigned long long)coded_capacity, status);
+        k_scan_apply<<<ws.scan_blocks, kScanThreads, 0, stream>>>(g.lanes, lane_bytes, lane_words, sums,
+                                                                  offsets);
+        timer.mark("scan");
+        // a run of lanes per workgroup: about 16K symbols' worth, at most 256 lanes
+        const uint32_t lane_sym = max_lane_symbols(g);
+        uint32_t pack_lanes = 16384u / (lane_sym ? lane_sym : 1u);
+        pack_lanes = pack_lanes < 1 ? 1 : (pack_lanes > (uint32_t)kPackMaxLanes ? kPackMaxLanes : pack_lanes);
+        if (lane_cap != 0u)
+            k_pack_by_thread<<<(uint32_t)ceil_div64(g.lanes, 64), 256, 0, stream>>>(
+                g.lanes, lane_cap, scratch, lane_state, offsets, payload, status);
+        else
+            k_pack<<<(uint32_t)ceil_div64(g.lanes, pack_lanes), 256, 0, stream>>>(
+                g, pack_lanes, scratch, lane_state, offsets, payload, status);
+        timer.mark(lane_cap != 0u ? "k_pack_by_thread" : "k_pack");
+    }
     HIP_TRY(hipGetLastError());
     Status host_status;
     HIP_TRY(hipMemcpyAsync(&host_status, status, sizeof(Status), hipMemcpyDeviceToHost, stream));

@@ -132,15 +132,6 @@ __global__ __launch_bounds__(256) void k_ansai_build(uint32_t M, uint32_t X,
 // bytes, where thread r finds the bytes of row r; the registers of the second half simply wait.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// Orders this wavefront's LDS accesses: LDS instructions of one wavefront execute in order, so
-// all that is needed is that the compiler keeps them in order too.
-__device__ __forceinline__ void wave_lds_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 constexpr uint32_t kLine = 128;
 
 struct RowLine {
@@ -452,7 +443,7 @@ __global__ void k_ansai_begin(AShape sh, const ATabHeader *__restrict__ tab, Sta
                     tab->X == sh.X)
                        ? ST_OK
                        : ST_ARG;
-    status->pad = 0;
+    status->ticket = 0;
     status->payload_bytes = 0;
 }
 

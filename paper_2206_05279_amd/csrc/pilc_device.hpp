@@ -39,6 +39,15 @@ __device__ __forceinline__ void load_tables(LdsTables &t)
     __syncthreads();
 }
 
+// Orders this wavefront's LDS accesses: LDS instructions of one wavefront execute in order, so
+// all that is needed is that the compiler keeps them in order too.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // Batch geometry as the kernels see it (derived on the host from pilc_geom).
 struct Geo {
     uint32_t n, h, w, hw;

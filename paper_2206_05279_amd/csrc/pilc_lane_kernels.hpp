@@ -288,17 +288,16 @@ __device__ __forceinline__ size_t lane_scratch_base(uint32_t lane, uint32_t lane
 // kPair (with kVec): every row of every lane is a whole number of 16-pixel pairs of chunks that
 // start at multiples of 16 pixels, and the arrays allow 16-byte loads.
 // kLine (with kPair, flat lanes): lanes are whole 64-pixel groups that start on 128-byte lines.
-template <bool kVec, bool kPair, bool kLine = false>
-__global__ __launch_bounds__(kLaneMaxThreads) void k_encode_lanes(Geo g, const uint8_t *__restrict__ img,
-                               const uint16_t *__restrict__ mu, const int16_t *__restrict__ ls,
-                               const int16_t *__restrict__ coef, uint16_t *__restrict__ scratch,
-                               uint32_t lane_cap, uint32_t *__restrict__ lane_words,
-                               uint32_t *__restrict__ lane_state)
+// Encodes lane `lane` into its column of the scratch; returns the number of words, the final
+// state in `state_out`.
+template <bool kVec, bool kPair, bool kLine>
+__device__ __forceinline__ uint32_t encode_lane(const Geo &g, uint32_t lane, const uint8_t *__restrict__ img,
+                                                const uint16_t *__restrict__ mu,
+                                                const int16_t *__restrict__ ls,
+                                                const int16_t *__restrict__ coef,
+                                                uint16_t *__restrict__ scratch, uint32_t lane_cap,
+                                                const LdsTables &tab, uint32_t &state_out)
 {
-    __shared__ LdsTables tab;
-    load_tables(tab);
-    const uint32_t lane = blockIdx.x * blockDim.x + threadIdx.x;
-    if (lane >= g.lanes) return;
     const LaneShape sh = lane_shape(g, lane);
     const uint32_t m_bits = g.prec_bits;
     const uint32_t spread = (1u << m_bits) - 256u, top = 1u << m_bits;
@@ -397,8 +396,254 @@ __global__ __launch_bounds__(kLaneMaxThreads) void k_encode_lanes(Geo g, const u
             encode_chunk(ck, cp);
         }
     }
-    lane_words[lane] = nwords;
-    lane_state[lane] = S;
+    state_out = S;
+    return nwords;
+}
+
+// --------------------------------------------------------------------------------------------
+// One-pass encode: the workgroup that has coded a group of lanes also places them in the
+// container.  It needs the bytes of all lanes before the group, which it gets by looking back over
+// the descriptors of the groups before it (a group's bytes are published as soon as they are
+// known, and the bytes of everything up to and including the group once its workgroup has looked
+// back).  Groups are handed out by a ticket counter, so every group with a smaller number has been
+// taken by a workgroup that is running, and no workgroup ever waits for a larger number: the
+// smallest unfinished group never waits at all.  A workgroup codes its next group before it looks
+// back for the one it has just coded, so the groups before that one have usually been coded by
+// then and the wait is short; the placing (memory) of one group overlaps the coding (arithmetic)
+// of others on the same compute unit.  The wait is bounded all the same: a workgroup that sees an
+// empty descriptor for longer than `wait_ticks` of the constant-rate clock raises ST_TIMEOUT, marks
+// its own descriptor as abandoned and leaves, and every workgroup that meets an abandoned
+// descriptor does the same, so the grid drains.
+// --------------------------------------------------------------------------------------------
+struct OnePass {
+    unsigned long long *desc;  // [groups], zero before the launch; null: two-pass encode
+    uint32_t *ticket;          // zero before the launch
+    Status *status;
+    uint8_t *coded;            // the container: header, offset table, payload
+    unsigned long long payload_capacity;  // bytes the payload may take
+    unsigned long long wait_ticks;
+    uint32_t groups;           // groups of blockDim.x lanes
+    uint32_t withhold_first;   // tests of the give-up path: group 0 publishes nothing
+    HeaderWords head;
+};
+constexpr unsigned long long kDescOwn = 1ull, kDescUpTo = 2ull, kDescAbandoned = 3ull;
+constexpr int kTailRows = 32;  // word numbers a wavefront moves through its LDS tile at a time
+
+__device__ __forceinline__ void desc_publish(const OnePass &op, uint32_t group, unsigned long long v,
+                                             unsigned long long flag)
+{
+    __hip_atomic_store(&op.desc[group], (v << 2) | flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Bytes of the workgroup's lanes before this thread's lane; *total = bytes of all its lanes.
+// Ends with a barrier (after which every word the workgroup's lanes stored is visible to it).
+__device__ __forceinline__ unsigned long long group_bytes_before(uint32_t t, unsigned long long bytes,
+                                                                 unsigned long long *total)
+{
+    __shared__ unsigned long long s_wave_sum[kLaneMaxThreads / 64];
+    const uint32_t wl = t & 63u, wv = t >> 6, nwaves = blockDim.x >> 6;
+    unsigned long long inc = bytes;
+    for (int d = 1; d < 64; d <<= 1) {
+        const unsigned long long o = __shfl_up(inc, d, 64);
+        if (wl >= (uint32_t)d) inc += o;
+    }
+    __syncthreads();  // the previous use of s_wave_sum is over
+    if (wl == 63u) s_wave_sum[wv] = inc;
+    __syncthreads();
+    unsigned long long before = 0, all = 0;
+    for (uint32_t i = 0; i < nwaves; ++i) {
+        if (i < wv) before += s_wave_sum[i];
+        all += s_wave_sum[i];
+    }
+    *total = all;
+    return before + inc - bytes;
+}
+
+// Looks back for group `group` (its own bytes: `total`), then every wavefront places its 64
+// lanes.  Returns false if the workgroup has to leave (abandoned wait).
+__device__ __forceinline__ bool place_group(const OnePass &op, const Geo &g, uint32_t t, uint32_t group,
+                                            unsigned long long total, unsigned long long before,
+                                            uint32_t nwords, uint32_t S, uint32_t lane_cap,
+                                            const uint16_t *__restrict__ scratch)
+{
+    __shared__ unsigned long long s_base;
+    __shared__ int s_abandon;
+    __shared__ __align__(4) uint16_t s_tile[kLaneMaxThreads / 64][kTailRows * kPackTileStride];
+    const uint32_t wl = t & 63u, wv = t >> 6;
+    const uint32_t lane = group * blockDim.x + t;
+    const bool active = lane < g.lanes;
+
+    if (wv == 0u) {
+        unsigned long long running = 0;
+        int abandon = 0;
+        if (group != 0u) {
+            long long pos = (long long)group;  // descriptors below pos are still to be added
+            const unsigned long long t0 = wall_clock64();
+            for (;;) {
+                const long long idx = pos - 1 - (long long)wl;
+                const unsigned long long d =
+                    idx >= 0 ? __hip_atomic_load(&op.desc[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                             : kDescUpTo;  // before the first group: nothing, and final
+                const unsigned long long f = d & 3ull;
+                const unsigned long long m_upto = __ballot(f == kDescUpTo);
+                // the descriptors that matter: from the nearest one back to the first final sum
+                const unsigned long long need =
+                    m_upto ? ((2ull << (__ffsll((long long)m_upto) - 1)) - 1ull) : ~0ull;
+                if (__ballot(f == kDescAbandoned) & need) {
+                    abandon = 1;
+                    break;
+                }
+                if (__ballot(f == 0ull) & need) {
+                    if (wall_clock64() - t0 > op.wait_ticks) {
+                        abandon = 2;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(4);
+                    continue;
+                }
+                unsigned long long v = ((need >> wl) & 1ull) ? d >> 2 : 0ull;
+                for (int dd = 32; dd >= 1; dd >>= 1) v += __shfl_xor(v, dd, 64);
+                running += v;
+                if (m_upto) break;
+                pos -= 64;
+            }
+            if (wl == 0u) {
+                if (abandon) {
+                    desc_publish(op, group, 0ull, kDescAbandoned);
+                    if (abandon == 2) atomicMax(&op.status->code, (int)ST_TIMEOUT);
+                } else {
+                    desc_publish(op, group, running + total, kDescUpTo);
+                }
+            }
+        }
+        if (wl == 0u) {
+            s_base = running;
+            s_abandon = abandon;
+        }
+    }
+    __syncthreads();
+    const unsigned long long base = s_base, upto = base + total;
+    const bool leave = s_abandon != 0;
+    __syncthreads();  // s_base and s_abandon may be written again
+    if (leave) return false;
+    uint32_t *offsets = reinterpret_cast<uint32_t *>(op.coded + kHeaderBytes);
+    uint16_t *payload = reinterpret_cast<uint16_t *>(op.coded + kHeaderBytes + 4ull * ((size_t)g.lanes + 1ull));
+    if (group + 1u == op.groups && t == 0u) {
+        // the last group knows the size of the payload: header and closing offset
+        uint32_t *h = reinterpret_cast<uint32_t *>(op.coded);
+        for (int i = 0; i < 12; ++i) h[i] = op.head.w[i];
+        h[12] = (uint32_t)upto;
+        h[13] = (uint32_t)(upto >> 32);
+        h[14] = 0u;
+        h[15] = 0u;
+        offsets[g.lanes] = (uint32_t)upto;
+        op.status->payload_bytes = upto;
+    }
+    if (upto >= (1ull << 32) || upto > op.payload_capacity) {
+        // this group's lanes do not fit: nothing of them is written (the groups before it that did
+        // fit have been written inside the capacity); later groups will find the same
+        if (t == 0u) atomicMax(&op.status->code, upto >= (1ull << 32) ? (int)ST_TOO_LARGE : (int)ST_CAPACITY);
+        return true;
+    }
+
+    // From here on a wavefront meets no other: the words of its 64 lanes are rows of 64 in the
+    // scratch ([word number][thread]); 32 rows at a time go through an LDS tile and leave as runs
+    // of 32 consecutive words of a lane, two lanes per instruction.
+    const uint32_t first = (uint32_t)((base + before) >> 1);  // payload word index of the lane's state
+    if (active) {
+        offsets[lane] = (uint32_t)(base + before);
+        payload[first] = (uint16_t)S;
+        payload[first + 1u] = (uint16_t)(S >> 16);
+    }
+    const uint32_t my_nw = active ? nwords : 0u;
+    uint32_t max_nw = my_nw;
+    for (int dd = 32; dd >= 1; dd >>= 1) max_nw = max(max_nw, (uint32_t)__shfl_xor((int)max_nw, dd, 64));
+    const uint16_t *rows = scratch + (size_t)(lane - wl) * lane_cap;
+    uint16_t *tile = s_tile[wv];
+    const uint32_t half = wl >> 5, u = wl & 31u;
+    for (uint32_t k0 = 0; k0 < max_nw; k0 += kTailRows) {
+        wave_lds_sync();
+#pragma unroll 4
+        for (int j = 0; j < kTailRows / 2; ++j) {  // two rows an instruction, a dword (two lanes) a thread
+            const uint32_t r = 2u * j + half;
+            if (k0 + r < max_nw)
+                *reinterpret_cast<uint32_t *>(&tile[r * kPackTileStride + 2u * u]) =
+                    *reinterpret_cast<const uint32_t *>(rows + (size_t)(k0 + r) * 64u + 2u * u);
+        }
+        wave_lds_sync();
+#pragma unroll 4
+        for (int j = 0; j < 32; ++j) {  // lanes 2 j and 2 j + 1; thread u of a half has word number k0 + u
+            const uint32_t i = 2u * j + half, k = k0 + u;
+            const uint32_t nw_i = (uint32_t)__shfl((int)my_nw, (int)i, 64);
+            const uint32_t first_i = (uint32_t)__shfl((int)first, (int)i, 64);
+            if (k < nw_i) payload[first_i + 2u + (nw_i - 1u - k)] = tile[u * kPackTileStride + i];
+        }
+    }
+    return true;
+}
+
+// kOnePass: the kernel also places the lanes in the container (`op`); otherwise it leaves word
+// counts and states for the scan and pack kernels.  (Three wavefronts per SIMD are asked for: the
+// one-pass whole-line variant would otherwise settle at 175 registers, two wavefronts.)
+template <bool kOnePass, bool kVec, bool kPair, bool kLine = false>
+__global__ __launch_bounds__(kLaneMaxThreads) __attribute__((amdgpu_waves_per_eu(3))) void k_encode_lanes(Geo g, const uint8_t *__restrict__ img,
+                               const uint16_t *__restrict__ mu, const int16_t *__restrict__ ls,
+                               const int16_t *__restrict__ coef, uint16_t *__restrict__ scratch,
+                               uint32_t lane_cap, uint32_t *__restrict__ lane_words,
+                               uint32_t *__restrict__ lane_state, OnePass op)
+{
+    __shared__ LdsTables tab;
+    load_tables(tab);  // ends with a barrier
+    if (!kOnePass) {
+        const uint32_t lane = blockIdx.x * blockDim.x + threadIdx.x;
+        if (lane >= g.lanes) return;
+        uint32_t S;
+        const uint32_t nwords = encode_lane<kVec, kPair, kLine>(g, lane, img, mu, ls, coef, scratch, lane_cap, tab, S);
+        lane_words[lane] = nwords;
+        lane_state[lane] = S;
+        return;
+    }
+    // what the group coded last still needs: kept in LDS while the next group is coded
+    __shared__ uint32_t s_ticket;
+    __shared__ uint32_t s_words[kLaneMaxThreads], s_state[kLaneMaxThreads];
+    __shared__ unsigned long long s_before[kLaneMaxThreads];
+    bool have = false;
+    uint32_t last_group = 0u;
+    unsigned long long last_total = 0ull;
+    for (;;) {
+        // the thread index afresh in every round: nothing derived from it (LDS addresses of the
+        // arrays below, wavefront numbers) is to be carried in registers through the coding
+        uint32_t t = threadIdx.x;
+        asm volatile("" : "+v"(t));
+        if (t == 0u) s_ticket = atomicAdd(op.ticket, 1u);
+        __syncthreads();
+        const uint32_t group = s_ticket;
+        if (group < op.groups) {
+            const uint32_t lane = group * blockDim.x + t;
+            uint32_t nwords = 0u, S = 0u;
+            if (lane < g.lanes)
+                nwords = encode_lane<kVec, kPair, kLine>(g, lane, img, mu, ls, coef, scratch, lane_cap, tab, S);
+            t = threadIdx.x;
+            asm volatile("" : "+v"(t));  // (as above: what follows starts from the thread index again)
+            unsigned long long total;
+            const bool coded = group * blockDim.x + t < g.lanes;
+            const unsigned long long before = group_bytes_before(t, coded ? 4ull + 2ull * nwords : 0ull, &total);
+            if (t == 0u && !(group == 0u && op.withhold_first))
+                desc_publish(op, group, total, group == 0u ? kDescUpTo : kDescOwn);
+            if (have && !place_group(op, g, t, last_group, last_total, s_before[t], s_words[t], s_state[t],
+                                     lane_cap, scratch))
+                return;
+            s_words[t] = nwords;  // a thread reads back only what it wrote itself
+            s_state[t] = S;
+            s_before[t] = before;
+            last_group = group;
+            last_total = total;
+            have = true;
+        } else {
+            if (have) place_group(op, g, t, last_group, last_total, s_before[t], s_words[t], s_state[t], lane_cap, scratch);
+            return;
+        }
+    }
 }
 
 // --------------------------------------------------------------------------------------------

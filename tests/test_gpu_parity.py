@@ -17,9 +17,10 @@ def _ogeom(wl):
     return orc.make_geom(*wl.geom)
 
 
-@pytest.fixture(params=[1, 2], ids=["thread-per-lane", "few-lane"])
+@pytest.fixture(params=[1, 2, 3], ids=["thread-per-lane", "few-lane", "thread-per-lane-one-pass"])
 def policy(request):
-    """Runs a test once with each lane-kernel family forced."""
+    """Runs a test once with each lane-kernel family forced (thread per lane: with the scan and
+    pack kernels, and with the encoder placing its lanes itself)."""
     pb.pilc_set_kernel_policy(request.param)
     yield request.param
     pb.pilc_set_kernel_policy(0)
@@ -108,6 +109,29 @@ def test_exact_capacity_is_enough_and_one_byte_less_is_not():
     small = torch.empty(1024, dtype=torch.uint8, device="cuda:0")
     rc, _ = pb.pilc_encode(d.geom, d.img, d.mu, d.log_scale, d.chan_coef, small, d.coded, check=False)
     assert rc == pb.PILC_E_WORKSPACE
+
+
+def test_one_pass_encoder_gives_up_a_wait_that_is_never_answered():
+    """The one-pass encoder's workgroups wait for the byte counts of the workgroups before
+    them.  The wait is bounded: with the first workgroup made to publish nothing (a switch that
+    exists for this test) and a bound of 20 microseconds, every other workgroup must give up, every
+    kernel must end, and the call must say PILC_E_TIMEOUT; the next ordinary call works."""
+    wl = synth.make_workload(2, 64)           # 4096 row lanes: 64 workgroups of 64
+    d = DeviceWorkload(wl)
+    pb.pilc_set_kernel_policy(3)
+    try:
+        _, nbytes = d.encode()
+        ref = d.coded_numpy()[:nbytes].copy()
+        pb.pilc_set_one_pass_wait(2000, True)
+        rc, _ = d.encode(check=False)
+        assert rc == pb.PILC_E_TIMEOUT
+        pb.pilc_set_one_pass_wait(0, False)
+        d.coded.zero_()
+        rc, nb2 = d.encode()
+        assert rc == pb.PILC_OK and nb2 == nbytes and np.array_equal(d.coded_numpy()[:nbytes], ref)
+    finally:
+        pb.pilc_set_one_pass_wait(0, False)
+        pb.pilc_set_kernel_policy(0)
 
 
 def test_damaged_containers_give_error_codes_never_faults(policy):

@@ -36,7 +36,7 @@ def _random_geometry(seed):
 
 
 @pytest.mark.parametrize("seed", range(24))
-@pytest.mark.parametrize("policy", [0, 1, 2], ids=["auto", "thread-per-lane", "few-lane"])
+@pytest.mark.parametrize("policy", [0, 1, 2, 3], ids=["auto", "thread-per-lane", "few-lane", "thread-per-lane-one-pass"])
 def test_random_geometry_matches_oracle(seed, policy):
     n, h, w, m, mode, la, lb = _random_geometry(seed)
     wl = synth.make_random_case(seed, n, h, w, m, mode, la, lb, wild=(seed % 3 == 0))
