@@ -117,6 +117,42 @@ __global__ __launch_bounds__(256) void k_twar_forward4(TwarK p, uint32_t groups,
     o[2] = out[2];
 }
 
+// Copies `total` dwords between contiguous memory and an LDS tile whose rows of `rd` dwords lie
+// `row_stride` bytes apart, one wavefront, element o = lane + 64 i.  Eight elements a turn: the
+// eight loads are under way together (taken one at a time, every load waits for the one before).
+template <bool kIn>
+__device__ __forceinline__ void tile_copy(uint8_t *tile, uint32_t row_stride, uint32_t rd, uint32_t total,
+                                          const uint32_t *__restrict__ src, uint32_t *__restrict__ dst,
+                                          uint32_t lane)
+{
+    uint32_t r = lane / rd, c = lane % rd;  // row and dword of element `lane`, then + 64 a turn
+    const uint32_t dc = 64u % rd, dr = 64u / rd;
+    for (uint32_t o = lane; o < total; o += 8u * 64u) {
+        uint32_t v[8], at[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            at[k] = r * row_stride + 4u * c;
+            const bool ok = o + 64u * k < total;
+            if (kIn)
+                v[k] = ok ? src[o + 64u * k] : 0u;
+            else
+                v[k] = ok ? *reinterpret_cast<const uint32_t *>(tile + at[k]) : 0u;
+            c += dc;
+            r += dr + (c >= rd ? 1u : 0u);
+            c -= c >= rd ? rd : 0u;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            if (o + 64u * k < total) {
+                if (kIn)
+                    *reinterpret_cast<uint32_t *>(tile + at[k]) = v[k];
+                else
+                    dst[o + 64u * k] = v[k];
+            }
+        }
+    }
+}
+
 // A wavefront per group of up to 64 rows: whole images when h <= 64 (64 / h of them side by side),
 // else the bands of 64 rows of one image one after the other, the last row's red values of a band
 // kept in LDS for the first row of the next.  kTile: the group's residuals are copied to LDS
@@ -166,15 +202,9 @@ __global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint3
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             if (dwords) {
-                const uint32_t rd = (uint32_t)row_bytes >> 2, total = rows_here * rd;
-                const uint32_t *src = reinterpret_cast<const uint32_t *>(res + first);
-                uint32_t r = lane / rd, c = lane % rd;  // row and dword of element `lane`, then + 64 a turn
-                for (uint32_t o = lane; o < total; o += 64u) {
-                    reinterpret_cast<uint32_t *>(tile + r * row_stride)[c] = src[o];
-                    c += 64u % rd;
-                    r += 64u / rd + (c >= rd ? 1u : 0u);
-                    c -= c >= rd ? rd : 0u;
-                }
+                const uint32_t rd = (uint32_t)row_bytes >> 2;
+                tile_copy<true>(tile, row_stride, rd, rows_here * rd, reinterpret_cast<const uint32_t *>(res + first),
+                                nullptr, lane);
             } else {
                 for (uint32_t r = 0; r < rows_here; ++r)
                     for (uint32_t c = lane; c < row_bytes; c += 64u)
@@ -244,15 +274,9 @@ __global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint3
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             if (dwords) {
-                const uint32_t rd = (uint32_t)row_bytes >> 2, total = rows_here * rd;
-                uint32_t *dst = reinterpret_cast<uint32_t *>(img + first);
-                uint32_t r = lane / rd, c = lane % rd;
-                for (uint32_t o = lane; o < total; o += 64u) {
-                    dst[o] = reinterpret_cast<const uint32_t *>(tile + r * row_stride)[c];
-                    c += 64u % rd;
-                    r += 64u / rd + (c >= rd ? 1u : 0u);
-                    c -= c >= rd ? rd : 0u;
-                }
+                const uint32_t rd = (uint32_t)row_bytes >> 2;
+                tile_copy<false>(tile, row_stride, rd, rows_here * rd, nullptr,
+                                 reinterpret_cast<uint32_t *>(img + first), lane);
             } else {
                 for (uint32_t r = 0; r < rows_here; ++r)
                     for (uint32_t c = lane; c < row_bytes; c += 64u)

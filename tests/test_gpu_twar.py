@@ -17,7 +17,10 @@ SHAPES = [(1, 1, 1), (3, 32, 32), (5, 7, 9), (2, 64, 64), (7, 16, 16), (2, 33, 5
           # taller than a wavefront with rows of whole 16-pixel chunks: a workgroup per image with all
           # bands under way at once; one band and a bit, a band boundary at the last row, three
           # rounds of a workgroup, a full-size frame
-          (3, 65, 16), (2, 128, 48), (1, 1600, 32), (2, 1080, 1920)]
+          (3, 65, 16), (2, 128, 48), (1, 1600, 32), (2, 1080, 1920),
+          # more groups of small images: eight images a group, rows of 27 dwords, an odd number of
+          # groups, 17-row images (13 idle threads), many groups with a single-image group at the end
+          (9, 8, 8), (40, 32, 36), (11, 64, 64), (100, 17, 16), (24577, 32, 32)]
 
 
 def models(rng):
