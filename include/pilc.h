@@ -20,7 +20,8 @@
  *     different streams may run concurrently, from any threads, if they use different workspaces.
  *     The library's only process-wide state: the constant tables (filled once per device under a
  *     lock), the knobs pilc_set_timing, pilc_set_kernel_policy and pilc_set_one_pass_wait (atomic
- *     integers, read once at the start of a call), and the scratch array of pilc_encode_static.
+ *     integers, read once at the start of a call), the scratch array of pilc_encode_static, and four
+ *     sets of progress counters that calls of pilc_twar_inverse on tall images take turns with.
  *   - Tensors are dense, row-major, channel-interleaved: index ((i*h + y)*w + x)*3 + c.
  */
 #ifndef PILC_H
@@ -192,7 +193,8 @@ int pilc_set_kernel_policy(int policy);
  * default, two seconds) and then gives up: the call returns PILC_E_TIMEOUT and every kernel still
  * ends.
  * `withhold_first` != 0 makes the first workgroup publish nothing, which forces that path: for
- * tests of the give-up path only.  Process-wide. */
+ * tests of the give-up path only.  The same bound and switch apply to the bands of
+ * pilc_twar_inverse.  Process-wide. */
 void pilc_set_one_pass_wait(uint64_t ticks, int withhold_first);
 
 /* ------------------------------------------------------------------------------------------
@@ -284,8 +286,11 @@ int pilc_twar_forward(uint32_t n, uint32_t h, uint32_t w, const uint8_t *img_dev
                       const pilc_twar_params *params_host, uint8_t *res_dev, void *hip_stream);
 
 /* The image back from the residual (Sec. 3.1: the anti-diagonal / column schedule of the paper's
- * decoding figure, here one walk along the anti-diagonals of 64 rows per wavefront).
- * Errors: PILC_E_ARG, PILC_E_TOO_LARGE, PILC_E_HIP. */
+ * decoding figure, here one walk along the anti-diagonals of 64 rows per wavefront).  Fewer than
+ * 256 images of more than 576 rows are cut into bands in workgroups of their own that follow each
+ * other through counters in the library's device globals; their wait for the band above is bounded
+ * like the one-pass encoder's (pilc_set_one_pass_wait) and ends in PILC_E_TIMEOUT.
+ * Errors: PILC_E_ARG, PILC_E_TOO_LARGE, PILC_E_HIP, PILC_E_TIMEOUT (img_dev contents undefined). */
 int pilc_twar_inverse(uint32_t n, uint32_t h, uint32_t w, const uint8_t *res_dev,
                       const pilc_twar_params *params_host, uint8_t *img_dev, void *hip_stream);
 

@@ -407,6 +407,206 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
     }
 }
 
+// The same for few tall images (video frames): an image is cut into bands of rows, a workgroup
+// per band, so that one image keeps several compute units busy.  The first row of a band needs the
+// red values of the last row of the band above, which belongs to another workgroup: that row's
+// thread publishes, after every chunk it has written back to the image, how many chunks of its row
+// are final (a counter per band in global memory, release / acquire at device scope), and three
+// threads of the band below fetch the chunk above their first row's next chunk from the image as
+// soon as the counter allows, one chunk turn ahead of its use.  Bands number themselves with a
+// ticket taken at their start (image-major), so the band above is always a workgroup that is
+// already running, and it never waits for the band below.  The wait is bounded by the
+// constant-rate clock; a band that gives up sets an abort word, every band that sees it while
+// waiting leaves too, and the host returns PILC_E_TIMEOUT.
+
+__global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_bands(
+    TwarK p, uint32_t h, uint32_t w, uint32_t bands, uint32_t band_rows, const uint8_t *__restrict__ res,
+    uint8_t *__restrict__ img, uint32_t *__restrict__ progress, uint32_t *__restrict__ ticket,
+    uint32_t *__restrict__ abort_word, unsigned long long wait_ticks, uint32_t withhold)
+{
+    extern __shared__ uint8_t twar_lds[];
+    __shared__ uint32_t s_id;
+    __shared__ int s_abort;
+    const uint32_t nt = blockDim.x, waves = nt >> 6;
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    if (threadIdx.x == 0u) {
+        s_id = atomicAdd(ticket, 1u);
+        s_abort = 0;
+    }
+    __syncthreads();
+    const uint32_t id = s_id, image = id / bands, band = id % bands;
+    uint8_t *my = twar_lds + (size_t)threadIdx.x * kTallStride;
+    uint8_t *hand = twar_lds + (size_t)nt * kTallStride;  // [wavefront][64]: red of its last row, by column mod 64
+    uint8_t *above_row = hand + waves * 64u;              // two chunks (2 x 48 bytes) of the row above the band
+    const size_t row_bytes = (size_t)w * 3u;
+    const int chunks = (int)(w >> 4);
+    const uint32_t lag = wave * (64u + kTallLag);
+    const uint32_t local_steps = kTallLead + w + 80u;
+    const uint32_t total = local_steps + (waves - 1u) * (64u + kTallLag);
+
+    const uint32_t u = band * band_rows + threadIdx.x;
+    const bool have = threadIdx.x < band_rows && u < h;
+    const size_t row_off = ((size_t)image * h + (have ? u : 0u)) * row_bytes;
+    const uint4 *src = reinterpret_cast<const uint4 *>(res + row_off);
+    uint4 *dst = reinterpret_cast<uint4 *>(img + row_off);
+    // the row whose progress the band below follows
+    const bool publishes = have && band + 1u < bands && (threadIdx.x + 1u == band_rows || u + 1u == h);
+    // the three threads that fetch the row above the band (16 bytes of a chunk each)
+    const bool fetches = band != 0u && wave == 0u && lane < 3u;
+    const uint4 *above_src =
+        reinterpret_cast<const uint4 *>(img + ((size_t)image * h + (band != 0u ? band * band_rows - 1u : 0u)) * row_bytes);
+    const uint32_t *above_progress = progress + (id - (band != 0u ? 1u : 0u));
+    uint4 above_ahead = make_uint4(0u, 0u, 0u, 0u);
+    uint32_t above_done = 0u;  // chunks of the row above known to be final
+
+    int rl = 0, rll = 0, gl = 0, bl = 0, first_prev = 0;
+    uint32_t ptr = 0;
+    int cur = (((int)-kTallLead - (int)lane) >> 4) - 1;
+    int cur3 = ((cur % 3) + 3) % 3;
+    uint4 ahead[3] = {};
+    for (uint32_t D = 0; D < total; ++D) {
+        if ((D & (kTallLag - 1)) == 0u) {
+            __syncthreads();
+            if (s_abort) return;  // the same for every thread: written before the barrier
+        }
+        const int d = (int)D - (int)lag - kTallLead;
+        if (d < -kTallLead || d >= (int)(w + 80u)) continue;
+        if ((d & 15) == 0) {
+            cur = (d - (int)lane) >> 4;
+            cur3 = cur3 == 2 ? 0 : cur3 + 1;
+            if (fetches) {
+                // thread 0 enters chunk T = d >> 4 now: what was fetched a turn ago goes to LDS, and
+                // chunk T + 1 of the row above is fetched as soon as it is final
+                const int T = d >> 4;
+                if (T >= 0 && T < chunks)
+                    reinterpret_cast<uint4 *>(above_row + (T & 1) * kTallChunk)[lane] = above_ahead;
+                if (T + 1 >= 0 && T + 1 < chunks) {
+                    const unsigned long long t0 = wall_clock64();
+                    while (above_done < (uint32_t)(T + 2)) {  // what is known to be final does not need asking
+                        const uint32_t done = __hip_atomic_load(above_progress, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+                        above_done = done;
+                        if (__hip_atomic_load(abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+                            s_abort = 1;
+                            break;
+                        }
+                        if (done >= (uint32_t)(T + 2)) break;
+                        if (wall_clock64() - t0 > wait_ticks) {
+                            s_abort = 1;
+                            __hip_atomic_store(abort_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(2);
+                    }
+                    if (!s_abort) above_ahead = above_src[3 * (T + 1) + (int)lane];
+                }
+            }
+            if (have) {
+                const int nxt3 = cur3 == 2 ? 0 : cur3 + 1, prv3 = cur3 == 0 ? 2 : cur3 - 1;
+                if (cur - 1 >= 0 && cur - 1 < chunks) {  // written back: it was left for good
+                    const uint32_t *q = reinterpret_cast<const uint32_t *>(my + prv3 * kTallChunk);
+#pragma unroll
+                    for (int i = 0; i < 3; ++i)
+                        dst[3 * (cur - 1) + i] = make_uint4(q[4 * i], q[4 * i + 1], q[4 * i + 2], q[4 * i + 3]);
+                    // chunks 0 .. cur - 1 of this row are final; said every fourth chunk and at the end
+                    // (a release at device scope writes the L2 back: too dear for every chunk)
+                    if (publishes && !withhold && ((cur & 3) == 0 || cur == chunks))
+                        __hip_atomic_store(progress + id, (uint32_t)cur, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                if (cur + 1 >= 0 && cur + 1 < chunks) {
+                    uint32_t *q = reinterpret_cast<uint32_t *>(my + nxt3 * kTallChunk);
+#pragma unroll
+                    for (int i = 0; i < 3; ++i) {
+                        q[4 * i] = ahead[i].x;
+                        q[4 * i + 1] = ahead[i].y;
+                        q[4 * i + 2] = ahead[i].z;
+                        q[4 * i + 3] = ahead[i].w;
+                    }
+                }
+                if (cur + 2 >= 0 && cur + 2 < chunks) {
+#pragma unroll
+                    for (int i = 0; i < 3; ++i) ahead[i] = src[3 * (cur + 2) + i];
+                }
+            }
+            if (fetches) wave_lds_sync();  // the chunk of the row above is in LDS before thread 0 reads it
+        }
+        const int v = d - (int)lane;
+        const bool on = have && v >= 0 && v < (int)w;
+        if (!__any(on)) continue;
+        int up = __builtin_amdgcn_update_dpp(0, rl, 0x138 /* wave_shr:1 */, 0xF, 0xF, true);
+        int upleft = __builtin_amdgcn_update_dpp(0, rll, 0x138, 0xF, 0xF, true);
+        if (lane == 0u && on) {
+            // the row above belongs to another wavefront, or to the band above, or is padding
+            int above = 0;
+            if (wave != 0u)
+                above = hand[(wave - 1u) * 64u + ((uint32_t)v & 63u)];
+            else if (band != 0u)
+                above = above_row[(((uint32_t)v >> 4) & 1u) * kTallChunk + 3u * ((uint32_t)v & 15u)];
+            up = above;
+            upleft = first_prev;
+            first_prev = above;
+        }
+        if (on) {
+            uint8_t *q = my + ptr;
+            const int xr = ((int)q[0] + twar_predict(p, 0, upleft, up, rl)) & 255;
+            const int xg = ((int)q[1] + twar_predict(p, 1, gl, rl, xr)) & 255;
+            const int xb = ((int)q[2] + twar_predict(p, 2, bl, gl, xg)) & 255;
+            q[0] = (uint8_t)xr;
+            q[1] = (uint8_t)xg;
+            q[2] = (uint8_t)xb;
+            ptr = ptr + 3u == (uint32_t)kTallRing ? 0u : ptr + 3u;
+            if (lane == 63u) hand[wave * 64u + ((uint32_t)v & 63u)] = (uint8_t)xr;
+            rll = rl;
+            rl = xr;
+            gl = xg;
+            bl = xb;
+        }
+    }
+}
+
+// Progress counters of the band kernel: a few sets in device globals (the entry points take no
+// workspace), handed out under a lock so that concurrent calls do not share one; a call that finds
+// none free uses the workgroup-per-image kernel instead.  Layout of a set: [kBandFlags] progress,
+// then the ticket and the abort word.
+constexpr int kBandSlots = 4;
+constexpr uint32_t kBandFlags = 4096;
+static __device__ uint32_t g_band_flags[kBandSlots][kBandFlags + 2];
+static std::mutex g_band_mutex;
+static bool g_band_in_use[kBandSlots];
+static std::map<int, uint32_t *> g_band_base;  // per device: address of g_band_flags there
+
+__global__ void k_band_clear(uint32_t *flags, uint32_t n)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) flags[i] = 0u;
+    if (i < 2u) flags[kBandFlags + i] = 0u;
+}
+
+// A free set of counters on the current device (null if none), and its release.
+static uint32_t *band_flags_acquire(int *slot_out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+    std::lock_guard<std::mutex> lock(g_band_mutex);
+    auto it = g_band_base.find(dev);
+    if (it == g_band_base.end()) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_band_flags)) != hipSuccess) return nullptr;
+        it = g_band_base.emplace(dev, static_cast<uint32_t *>(ptr)).first;
+    }
+    for (int i = 0; i < kBandSlots; ++i)
+        if (!g_band_in_use[i]) {
+            g_band_in_use[i] = true;
+            *slot_out = i;
+            return it->second + (size_t)i * (kBandFlags + 2);
+        }
+    return nullptr;
+}
+static void band_flags_release(int slot)
+{
+    std::lock_guard<std::mutex> lock(g_band_mutex);
+    g_band_in_use[slot] = false;
+}
+
 static int make_twar(const pilc_twar_params *in, uint32_t n, uint32_t h, uint32_t w, TwarK *k)
 {
     if (!in || n == 0 || h == 0 || w == 0) return PILC_E_ARG;
@@ -470,6 +670,42 @@ int pilc_twar_inverse(uint32_t n, uint32_t h, uint32_t w, const uint8_t *res_dev
     const size_t tile_lds = (size_t)kTwarWaves * (last_bytes + 64u * (size_t)row_stride);
     Timer timer(stream);
     const bool tall = h > 64 && w % 16 == 0 && w <= 16384 && ((((uintptr_t)img_dev) | ((uintptr_t)res_dev)) & 15) == 0;
+    // few tall images: bands of up to 576 rows in workgroups of their own (two bands of 540 rows
+    // and five of 216 take the same 1.5 ms on 30 frames of 1080 x 1920; one workgroup per frame 2.2)
+    uint32_t bands = tall && n < 256u ? (h + 575u) / 576u : 1u;
+    int slot = -1;
+    uint32_t *flags = nullptr;
+    if (bands > 1u && (uint64_t)n * bands <= kBandFlags) flags = band_flags_acquire(&slot);
+    if (tall && flags) {
+        const uint32_t band_rows = (h + bands - 1) / bands;
+        bands = (h + band_rows - 1) / band_rows;
+        const uint32_t nt = (band_rows + 63u) & ~63u;
+        const size_t lds = (size_t)nt * kTallStride + (nt / 64) * 64 + 2 * kTallChunk;
+        int dev = 0, khz = 0;
+        const unsigned long long wait = g_one_pass_wait.load(std::memory_order_relaxed);
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0)
+            khz = 100000;
+        rc = allow_large_lds(reinterpret_cast<const void *>(k_twar_inverse_bands));
+        uint32_t aborted = 0u;
+        if (rc == PILC_OK) {
+            k_band_clear<<<(n * bands + 255u) / 256u, 256, 0, stream>>>(flags, n * bands);
+            k_twar_inverse_bands<<<n * bands, nt, lds, stream>>>(
+                k, h, w, bands, band_rows, res_dev, img_dev, flags, flags + kBandFlags, flags + kBandFlags + 1,
+                wait ? wait : 2000ull * (unsigned long long)khz,
+                (uint32_t)g_one_pass_withhold.load(std::memory_order_relaxed));
+            timer.mark("k_twar_inverse");
+            hipError_t e = hipGetLastError();
+            if (e == hipSuccess)
+                e = hipMemcpyAsync(&aborted, flags + kBandFlags + 1, sizeof(aborted), hipMemcpyDeviceToHost, stream);
+            if (e == hipSuccess) e = hipStreamSynchronize(stream);
+            if (e != hipSuccess) rc = hip_fail(e, "k_twar_inverse_bands");
+        }
+        band_flags_release(slot);
+        if (rc != PILC_OK) return rc;
+        timer.finish();
+        return aborted ? PILC_E_TIMEOUT : PILC_OK;
+    }
     if (tall) {
         // as few rounds as the workgroup size allows, of equal size (three rounds of 512, 512 and 56
         // rows of a 1080-row frame took 2.8 ms where two rounds of 540 take 2.2)

@@ -18,6 +18,9 @@ SHAPES = [(1, 1, 1), (3, 32, 32), (5, 7, 9), (2, 64, 64), (7, 16, 16), (2, 33, 5
           # bands under way at once; one band and a bit, a band boundary at the last row, three
           # rounds of a workgroup, a full-size frame
           (3, 65, 16), (2, 128, 48), (1, 1600, 32), (2, 1080, 1920),
+          # few images taller than 576 rows: bands of an image in workgroups of their own that follow
+          # each other through counters in global memory (two bands of 350 rows; four of 525)
+          (2, 700, 64), (1, 2100, 160),
           # more groups of small images: eight images a group, rows of 27 dwords, an odd number of
           # groups, 17-row images (13 idle threads), many groups with a single-image group at the end
           (9, 8, 8), (40, 32, 36), (11, 64, 64), (100, 17, 16), (24577, 32, 32)]
@@ -51,6 +54,26 @@ def test_forward_and_inverse_match_the_reference(shape):
         d_noise = torch.from_numpy(noise).cuda()
         pb.pilc_twar_inverse(p, d_noise, d_back)
         assert np.array_equal(d_back.cpu().numpy(), to.inverse(to.make_params(wq, bq), noise)), name
+
+
+def test_bands_give_up_a_wait_that_is_never_answered():
+    """A band of a tall image waits for the last row of the band above.  With that row made to
+    publish nothing (a switch that exists for this test) and a bound of 20 microseconds the band
+    below must give up, every kernel must end, and the call must say PILC_E_TIMEOUT; the next
+    ordinary call works."""
+    rng = np.random.default_rng(5)
+    img = rng.integers(0, 256, (2, 700, 64, 3), dtype=np.uint8)
+    wq, bq = [[ONE // 2, ONE // 4, ONE // 4]] * 3, [0, 0, 0]
+    p = pb.make_twar_params(wq, bq)
+    d_res = torch.from_numpy(to.forward(to.make_params(wq, bq), img)).cuda()
+    d_back = torch.zeros_like(d_res)
+    try:
+        pb.pilc_set_one_pass_wait(2000, True)
+        assert pb.pilc_twar_inverse(p, d_res, d_back, check=False) == pb.PILC_E_TIMEOUT
+    finally:
+        pb.pilc_set_one_pass_wait(0, False)
+    assert pb.pilc_twar_inverse(p, d_res, d_back, check=False) == pb.PILC_OK
+    assert np.array_equal(d_back.cpu().numpy(), img)
 
 
 def test_bad_arguments():
