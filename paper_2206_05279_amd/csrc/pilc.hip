@@ -214,7 +214,7 @@ __global__ __launch_bounds__(256) void k_pack(Geo g, uint32_t lanes_per_block,
         const LaneShape sh = lane_shape(g, l0 + i);
         s_off[i] = begin;
         if (i + 1 == n) s_off[n] = end;
-        s_src[i] = sh.sym_base + 3u * sh.npx - ((end - begin - 4u) >> 1);
+        s_src[i] = block_slot_end(sh, l0 + i) - ((end - begin - 4u) >> 1);
         s_state[i] = lane_state[l0 + i];
     }
     __syncthreads();
@@ -497,7 +497,7 @@ static Workspace layout(const Geo &g)
     w.desc_off = off;  // one look-back descriptor per workgroup of the one-pass encoder (>= 64 lanes each)
     off = align256(off + 8 * (size_t)ceil_div64(g.lanes, 64));
     w.scratch_off = off;
-    // one 16-bit word per symbol, plus one dump word per lane for the branch-free encoder; the
+    // one 16-bit word per symbol, plus one spare word per lane for the branch-free encoder; the
     // thread-per-lane encoder gives every lane of a block of 64 the room of the longest lane
     const size_t linear = (size_t)g.total_px * 3 + g.lanes + 64;
     const size_t by_thread = (((size_t)g.lanes + 63) & ~(size_t)63) * max_lane_symbols(g);
@@ -776,8 +776,7 @@ static int encode_checked(const Geo &g, const uint8_t *img_dev, const pilc_param
     }
     if (few_lanes) {
         k_encode_block<<<(uint32_t)ceil_div64(g.lanes, kEncLanes), kEncThreads, 0, stream>>>(
-            g, img_dev, params->mu, params->log_scale, params->chan_coef, scratch, g.total_px * 3u,
-            lane_words, lane_state);
+            g, img_dev, params->mu, params->log_scale, params->chan_coef, scratch, lane_words, lane_state);
     } else {
         const int bt = lane_block_threads(g);
         uint32_t nb = (uint32_t)ceil_div64(g.lanes, bt);

@@ -7,8 +7,8 @@
 // pixels per lane (one pixel per thread) and leave, per symbol, one ready-made 16-byte record in
 // LDS (see
 // encode_record).  One barrier per batch hands a buffer over; the two roles never wait for each
-// other inside a batch.  The chain is branch-free: a word is stored on every step, to the
-// lane's stream when the state renormalises and to a per-lane dump word otherwise.
+// other inside a batch.  The chain is branch-free: a word is stored on every step, below the
+// lane's words so far, and counted only when the state renormalises.
 #pragma once
 
 #include "pilc_device.hpp"
@@ -51,7 +51,7 @@ __device__ __forceinline__ uint4 encode_record(uint32_t cum, uint32_t f, uint32_
 __global__ __launch_bounds__(kEncThreads) void k_encode_block(
     Geo g, const uint8_t *__restrict__ img, const uint16_t *__restrict__ mu,
     const int16_t *__restrict__ ls, const int16_t *__restrict__ coef, uint16_t *__restrict__ scratch,
-    uint32_t dump_base, uint32_t *__restrict__ lane_words, uint32_t *__restrict__ lane_state)
+    uint32_t *__restrict__ lane_words, uint32_t *__restrict__ lane_state)
 {
     __shared__ LdsTables tab;
     __shared__ uint4 rec[2][kEncSyms][kEncLanes];
@@ -77,7 +77,8 @@ __global__ __launch_bounds__(kEncThreads) void k_encode_block(
 
     // chain state (threads 0..nl-1 of wave 0)
     uint32_t S = 1u << 16;
-    const uint32_t slot_end = sh.sym_base + 3u * sh.npx;  // index into scratch, one past the slot
+    // index into scratch, one past the lane's slot (block_slot_end: one spare word below every slot)
+    const uint32_t slot_end = block_slot_end(sh, lane0 + (has_lane ? my : 0u));
     uint32_t wpos = slot_end;
 
     // producers: the nine input values of the pixel of batch b, loaded one batch ahead
@@ -119,8 +120,6 @@ __global__ __launch_bounds__(kEncThreads) void k_encode_block(
         }
     };
 
-    // where a step that does not renormalise leaves its (ignored) word: scratch[dump_base + lane]
-    const uint32_t dump_idx = dump_base + lane0 + my;
     auto consume = [&](uint32_t buf) {
         // all records of the batch first: the loads do not depend on the state
         uint4 r[kEncSyms];
@@ -128,9 +127,14 @@ __global__ __launch_bounds__(kEncThreads) void k_encode_block(
         for (int k = 0; k < kEncSyms; ++k) r[k] = rec[buf][k][my];
 #pragma unroll
         for (int k = 0; k < kEncSyms; ++k) {
+            // The word is stored on every step, just below the words already there, and counted
+            // only when the state renormalises: an uncounted word is overwritten by the next one
+            // or stays below the lane's first word.  After i symbols at most i words are counted
+            // and the slot has room for one per symbol, so the store stays in the slot, or, for the
+            // empty steps after a lane's last symbol, in the spare word below it.
             const bool emit = S > r[k].x;
+            scratch[wpos - 1u] = (uint16_t)(S & 0xFFFFu);
             wpos -= emit ? 1u : 0u;
-            scratch[emit ? wpos : dump_idx] = (uint16_t)(S & 0xFFFFu);
             S = emit ? S >> 16 : S;
             const uint32_t t = __umulhi(r[k].y, S);
             const uint32_t quo = (t + ((S - t) >> 1)) >> (r[k].w & 31u);

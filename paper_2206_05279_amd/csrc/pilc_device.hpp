@@ -92,6 +92,13 @@ __device__ __forceinline__ LaneShape lane_shape(const Geo &g, uint32_t lane)
     return s;
 }
 
+// Where lane `lane`'s words end in the scratch of the few-lane encoder: slots in lane order, one
+// word per symbol, and one spare word below every slot.
+__device__ __forceinline__ uint32_t block_slot_end(const LaneShape &sh, uint32_t lane)
+{
+    return sh.sym_base + 3u * sh.npx + lane + 1u;
+}
+
 // Flat pixel index of the t-th pixel of a lane (rows of sh.tw pixels, g.w apart).
 __device__ __forceinline__ uint32_t lane_pixel(const Geo &g, const LaneShape &sh, uint32_t t)
 {
