@@ -48,6 +48,22 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// 24-bit signed multiply and multiply-add as the single instructions they are.  (Written through
+// the 32-bit product, the compiler first sign-extends operands it cannot prove to be 24 bits wide,
+// which costs more instructions than the multiply.)  Operands must lie within +-2^23; only plain
+// vector ALU instructions consume the results.
+__device__ __forceinline__ int mul_i24(int a, int b)
+{
+    int r;
+    asm("v_mul_i32_i24 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ int mad_i24(int a, int b, int c)
+{
+    int r;
+    asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
 // Batch geometry as the kernels see it (derived on the host from pilc_geom).
 struct Geo {
     uint32_t n, h, w, hw;

@@ -73,22 +73,6 @@ __device__ __forceinline__ uint32_t row_next(uint32_t v)
     return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x12F /* row_ror:15 */, 0xF, 0xF, true);
 }
 
-// 24-bit signed multiply and multiply-add as the single instructions they are.  (Written through
-// the 32-bit product, the compiler first sign-extends operands it cannot prove to be 24 bits wide,
-// which costs more instructions than the multiply.)  Operands must lie within +-2^23; only plain
-// vector ALU instructions consume the results.
-__device__ __forceinline__ int mul_i24(int a, int b)
-{
-    int r;
-    asm("v_mul_i32_i24 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-    return r;
-}
-__device__ __forceinline__ int mad_i24(int a, int b, int c)
-{
-    int r;
-    asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-    return r;
-}
 // floor((a * e + 2^13) / 2^14) for a Q2.14 coefficient and an innovation e of at most 18 bits
 __device__ __forceinline__ int rsh14_mad(int a, int e) { return mad_i24(a, e, 8192) >> 14; }
 

@@ -290,15 +290,30 @@ __global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint3
 }
 
 // Images taller than 64 rows whose rows are whole 16-pixel chunks in 16-byte aligned arrays: a
-// workgroup per image, a thread per row, every wavefront a band of 64 rows, all bands under way at
-// once.  Thread t of the workgroup runs t + 16 (t / 64) positions behind thread 0, so inside a
-// wavefront a row still gets the two values it needs from the row above by a cross-lane shift, and
-// the first row of a band finds them in LDS, where the last row of the band above left them 17
-// steps earlier; a workgroup barrier every 16 steps separates the two.  Images with more rows than
-// a workgroup has threads go in rounds, the last row's red values of a round kept in LDS for the
-// first row of the next.  A thread reads and writes its row in chunks of 16 pixels (48 bytes,
-// three 16-byte accesses): the chunk it is in and the next wait in a three-chunk ring in LDS, the
-// one after that is on its way from memory in registers, the one it left is written back.
+// thread per row, every wavefront 64 rows, all wavefronts of a workgroup under way at once.
+// Thread t of the workgroup runs t + 16 (t / 64) positions behind thread 0, so inside a wavefront
+// a row still gets the two values it needs from the row above by a cross-lane shift, and the first
+// row of a wavefront finds them in LDS, where the last row of the wavefront above left them 17
+// steps earlier; a workgroup barrier every 16 steps separates the two.  A thread reads and writes
+// its row in chunks of 16 pixels (48 bytes, three 16-byte accesses): the chunk it is in and the
+// next wait in a three-chunk ring in LDS, the one after that is on its way from memory in
+// registers, the one it left is written back.  The work goes in blocks of 16 steps: barrier, chunk
+// turn, then 16 steps without a branch on anything but the loop count (a step used to spend more
+// time in its dozen branches than in its arithmetic).
+//
+// kBands false: a workgroup per image; images with more rows than a workgroup has threads go in
+// rounds, the last row's red values of a round kept in LDS for the first row of the next.
+// kBands true (few images): an image is cut into bands of rows, a workgroup per band, so that one
+// image keeps several compute units busy.  The first row of a band needs the red values of the last
+// row of the band above, which belongs to another workgroup: that row's thread publishes, after
+// every fourth chunk it has written back to the image, how many chunks of its row are final (a
+// counter per band in global memory, release / acquire at device scope), and three threads of the
+// band below fetch the chunk of that row two chunks ahead of their first row from the image as
+// soon as the counter allows.  Bands number themselves with a ticket taken at their start
+// (image-major), so the band above is always a workgroup that is already running, and it never
+// waits for the band below.  The wait is bounded by the constant-rate clock; a band that gives up
+// sets an abort word, every band that sees it while waiting leaves too, and the host returns
+// PILC_E_TIMEOUT.
 constexpr int kTallLag = 16;         // steps between barriers = extra lag per wavefront
 constexpr int kTallChunk = 48;       // bytes of a chunk of 16 pixels
 constexpr int kTallRing = 3 * kTallChunk;
@@ -306,31 +321,71 @@ constexpr int kTallStride = kTallRing + 4;  // LDS bytes per thread: 37 dwords, 
 constexpr int kTallMaxThreads = 768;
 constexpr int kTallLead = 32;        // steps a wavefront runs before its first pixel (two chunk turns)
 
+struct TallBands {
+    uint32_t bands, band_rows;
+    uint32_t *progress;   // [images * bands]: chunks of the band's last row that are final
+    uint32_t *ticket;
+    uint32_t *abort_word;
+    unsigned long long wait_ticks;
+    uint32_t withhold;    // tests of the give-up path: nothing is published
+};
+
+template <bool kBands>
 __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, uint32_t h, uint32_t w,
-                                                                       uint32_t rounds,
+                                                                       uint32_t rounds, TallBands tb,
                                                                        const uint8_t *__restrict__ res,
                                                                        uint8_t *__restrict__ img)
 {
     extern __shared__ uint8_t twar_lds[];
+    __shared__ uint32_t s_id;
+    __shared__ int s_abort;
     const uint32_t nt = blockDim.x, waves = nt >> 6;
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    uint32_t image = blockIdx.x, band = 0u, id = 0u;
+    if (kBands) {
+        if (threadIdx.x == 0u) {
+            s_id = atomicAdd(tb.ticket, 1u);
+            s_abort = 0;
+        }
+        __syncthreads();
+        id = s_id;
+        image = id / tb.bands;
+        band = id % tb.bands;
+    }
     uint8_t *my = twar_lds + (size_t)threadIdx.x * kTallStride;
     uint8_t *hand = twar_lds + (size_t)nt * kTallStride;  // [wavefront][64]: red of its last row, by column mod 64
-    uint8_t *carry = hand + waves * 64u;                  // [w]: red of the last row of the round before
+    // red of the row above the workgroup's first row: the whole row of the round before, or (bands) a
+    // ring of 32 values filled from the image
+    uint8_t *carry = hand + waves * 64u;
     const size_t row_bytes = (size_t)w * 3u;
     const int chunks = (int)(w >> 4);
-    const uint32_t lag = wave * (64u + kTallLag);
+    const int lag = (int)(wave * (64u + kTallLag));
     // local steps -kTallLead .. w + 63 + 16: the last lane's last chunk is written back by then
-    const uint32_t local_steps = kTallLead + w + 80u;
-    const uint32_t total = local_steps + (waves - 1u) * (64u + kTallLag);
+    const uint32_t total = kTallLead + w + 80u + (waves - 1u) * (64u + kTallLag);
+    const uint32_t rows_here = kBands ? tb.band_rows : nt;
+    // where the first thread of this wavefront finds the red values above its row
+    const uint8_t *above_ptr = wave != 0u ? hand + (wave - 1u) * 64u : carry;
+    const uint32_t above_mask = wave != 0u ? 63u : (kBands ? 31u : 0xFFFFFFFFu);
+    const bool first_lane = lane == 0u;
 
     for (uint32_t round = 0; round < rounds; ++round) {
-        const uint32_t u = round * nt + threadIdx.x;
-        const bool have = u < h;
-        const size_t row_off = ((size_t)blockIdx.x * h + (have ? u : 0u)) * row_bytes;
+        const uint32_t u = kBands ? band * tb.band_rows + threadIdx.x : round * nt + threadIdx.x;
+        const bool have = threadIdx.x < rows_here && u < h;
+        const size_t row_off = ((size_t)image * h + (have ? u : 0u)) * row_bytes;
         const uint4 *src = reinterpret_cast<const uint4 *>(res + row_off);
         uint4 *dst = reinterpret_cast<uint4 *>(img + row_off);
-        const bool last_row = have && (u + 1u == h || threadIdx.x + 1u == nt);
+        const bool last_row = have && (u + 1u == h || threadIdx.x + 1u == rows_here);
+        const bool keeps_row = !kBands && last_row;                          // leaves its red values for the next round
+        const bool publishes = kBands && last_row && band + 1u < tb.bands;   // tells the band below how far it is
+        const bool has_above = wave != 0u || (kBands ? band != 0u : round != 0u);
+        // (bands) the three threads that fetch the row above the band, 16 bytes of a chunk each
+        const bool fetches = kBands && band != 0u && wave == 0u && lane < 3u;
+        const uint4 *above_src = reinterpret_cast<const uint4 *>(
+            img + ((size_t)image * h + (kBands && band != 0u ? band * tb.band_rows - 1u : 0u)) * row_bytes);
+        const uint32_t *above_progress = tb.progress + (id - (band != 0u ? 1u : 0u));
+        uint4 above_ahead = make_uint4(0u, 0u, 0u, 0u);
+        uint32_t above_done = 0u;  // chunks of the row above known to be final
+
         int rl = 0, rll = 0, gl = 0, bl = 0, first_prev = 0;
         uint32_t ptr = 0;             // ring offset of the pixel about to be decoded
         // the chunk index before that of column -kTallLead - lane (the first chunk turn moves on to
@@ -338,166 +393,49 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
         int cur = (((int)-kTallLead - (int)lane) >> 4) - 1;
         int cur3 = ((cur % 3) + 3) % 3;
         uint4 ahead[3] = {};          // the chunk two after `cur`, on its way
-        for (uint32_t D = 0; D < total; ++D) {
-            if ((D & (kTallLag - 1)) == 0u) __syncthreads();
-            const int d = (int)D - (int)lag - kTallLead;  // this wavefront's step; lane 0 is at column d
-            if (d < -kTallLead || d >= (int)(w + 80u)) continue;
-            if ((d & 15) == 0) {
-                // a chunk turn: every lane moves one chunk on within the next 16 steps
-                cur = (d - (int)lane) >> 4;
-                cur3 = cur3 == 2 ? 0 : cur3 + 1;
-                if (have) {
-                    const int nxt3 = cur3 == 2 ? 0 : cur3 + 1, prv3 = cur3 == 0 ? 2 : cur3 - 1;
-                    if (cur - 1 >= 0 && cur - 1 < chunks) {  // written back: it was left for good
-                        const uint32_t *q = reinterpret_cast<const uint32_t *>(my + prv3 * kTallChunk);
-#pragma unroll
-                        for (int i = 0; i < 3; ++i)
-                            dst[3 * (cur - 1) + i] = make_uint4(q[4 * i], q[4 * i + 1], q[4 * i + 2], q[4 * i + 3]);
-                    }
-                    if (cur + 1 >= 0 && cur + 1 < chunks) {  // arrived: into the ring
-                        uint32_t *q = reinterpret_cast<uint32_t *>(my + nxt3 * kTallChunk);
-#pragma unroll
-                        for (int i = 0; i < 3; ++i) {
-                            q[4 * i] = ahead[i].x;
-                            q[4 * i + 1] = ahead[i].y;
-                            q[4 * i + 2] = ahead[i].z;
-                            q[4 * i + 3] = ahead[i].w;
-                        }
-                    }
-                    if (cur + 2 >= 0 && cur + 2 < chunks) {  // asked for
-#pragma unroll
-                        for (int i = 0; i < 3; ++i) ahead[i] = src[3 * (cur + 2) + i];
-                    }
-                }
-            }
-            const int v = d - (int)lane;
-            const bool on = have && v >= 0 && v < (int)w;
-            if (!__any(on)) continue;
-            int up = __builtin_amdgcn_update_dpp(0, rl, 0x138 /* wave_shr:1 */, 0xF, 0xF, true);
-            int upleft = __builtin_amdgcn_update_dpp(0, rll, 0x138, 0xF, 0xF, true);
-            if (lane == 0u && on) {
-                // the row above belongs to another wavefront, or to the round before, or is padding
-                int above = 0;
-                if (wave != 0u)
-                    above = hand[(wave - 1u) * 64u + ((uint32_t)v & 63u)];
-                else if (round != 0u)
-                    above = carry[v];
-                up = above;
-                upleft = first_prev;
-                first_prev = above;
-            }
-            if (on) {
-                uint8_t *q = my + ptr;
-                const int xr = ((int)q[0] + twar_predict(p, 0, upleft, up, rl)) & 255;
-                const int xg = ((int)q[1] + twar_predict(p, 1, gl, rl, xr)) & 255;
-                const int xb = ((int)q[2] + twar_predict(p, 2, bl, gl, xg)) & 255;
-                q[0] = (uint8_t)xr;
-                q[1] = (uint8_t)xg;
-                q[2] = (uint8_t)xb;
-                ptr = ptr + 3u == (uint32_t)kTallRing ? 0u : ptr + 3u;
-                if (lane == 63u) hand[wave * 64u + ((uint32_t)v & 63u)] = (uint8_t)xr;
-                if (last_row) carry[v] = (uint8_t)xr;
-                rll = rl;
-                rl = xr;
-                gl = xg;
-                bl = xb;
-            }
-        }
-        __syncthreads();
-    }
-}
-
-// The same for few tall images (video frames): an image is cut into bands of rows, a workgroup
-// per band, so that one image keeps several compute units busy.  The first row of a band needs the
-// red values of the last row of the band above, which belongs to another workgroup: that row's
-// thread publishes, after every chunk it has written back to the image, how many chunks of its row
-// are final (a counter per band in global memory, release / acquire at device scope), and three
-// threads of the band below fetch the chunk above their first row's next chunk from the image as
-// soon as the counter allows, one chunk turn ahead of its use.  Bands number themselves with a
-// ticket taken at their start (image-major), so the band above is always a workgroup that is
-// already running, and it never waits for the band below.  The wait is bounded by the
-// constant-rate clock; a band that gives up sets an abort word, every band that sees it while
-// waiting leaves too, and the host returns PILC_E_TIMEOUT.
-
-__global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_bands(
-    TwarK p, uint32_t h, uint32_t w, uint32_t bands, uint32_t band_rows, const uint8_t *__restrict__ res,
-    uint8_t *__restrict__ img, uint32_t *__restrict__ progress, uint32_t *__restrict__ ticket,
-    uint32_t *__restrict__ abort_word, unsigned long long wait_ticks, uint32_t withhold)
-{
-    extern __shared__ uint8_t twar_lds[];
-    __shared__ uint32_t s_id;
-    __shared__ int s_abort;
-    const uint32_t nt = blockDim.x, waves = nt >> 6;
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
-    if (threadIdx.x == 0u) {
-        s_id = atomicAdd(ticket, 1u);
-        s_abort = 0;
-    }
-    __syncthreads();
-    const uint32_t id = s_id, image = id / bands, band = id % bands;
-    uint8_t *my = twar_lds + (size_t)threadIdx.x * kTallStride;
-    uint8_t *hand = twar_lds + (size_t)nt * kTallStride;  // [wavefront][64]: red of its last row, by column mod 64
-    uint8_t *above_row = hand + waves * 64u;              // two chunks (2 x 48 bytes) of the row above the band
-    const size_t row_bytes = (size_t)w * 3u;
-    const int chunks = (int)(w >> 4);
-    const uint32_t lag = wave * (64u + kTallLag);
-    const uint32_t local_steps = kTallLead + w + 80u;
-    const uint32_t total = local_steps + (waves - 1u) * (64u + kTallLag);
-
-    const uint32_t u = band * band_rows + threadIdx.x;
-    const bool have = threadIdx.x < band_rows && u < h;
-    const size_t row_off = ((size_t)image * h + (have ? u : 0u)) * row_bytes;
-    const uint4 *src = reinterpret_cast<const uint4 *>(res + row_off);
-    uint4 *dst = reinterpret_cast<uint4 *>(img + row_off);
-    // the row whose progress the band below follows
-    const bool publishes = have && band + 1u < bands && (threadIdx.x + 1u == band_rows || u + 1u == h);
-    // the three threads that fetch the row above the band (16 bytes of a chunk each)
-    const bool fetches = band != 0u && wave == 0u && lane < 3u;
-    const uint4 *above_src =
-        reinterpret_cast<const uint4 *>(img + ((size_t)image * h + (band != 0u ? band * band_rows - 1u : 0u)) * row_bytes);
-    const uint32_t *above_progress = progress + (id - (band != 0u ? 1u : 0u));
-    uint4 above_ahead = make_uint4(0u, 0u, 0u, 0u);
-    uint32_t above_done = 0u;  // chunks of the row above known to be final
-
-    int rl = 0, rll = 0, gl = 0, bl = 0, first_prev = 0;
-    uint32_t ptr = 0;
-    int cur = (((int)-kTallLead - (int)lane) >> 4) - 1;
-    int cur3 = ((cur % 3) + 3) % 3;
-    uint4 ahead[3] = {};
-    for (uint32_t D = 0; D < total; ++D) {
-        if ((D & (kTallLag - 1)) == 0u) {
+        for (uint32_t D0 = 0; D0 < total; D0 += kTallLag) {
             __syncthreads();
-            if (s_abort) return;  // the same for every thread: written before the barrier
-        }
-        const int d = (int)D - (int)lag - kTallLead;
-        if (d < -kTallLead || d >= (int)(w + 80u)) continue;
-        if ((d & 15) == 0) {
-            cur = (d - (int)lane) >> 4;
+            if (kBands && s_abort) return;  // the same for every thread: written before the barrier
+            const int d0 = (int)D0 - lag - kTallLead;  // this wavefront's step; lane 0 is at column d0
+            if (d0 < -kTallLead || d0 >= (int)(w + 80u)) continue;  // (the same for the whole wavefront)
+            // ---- chunk turn: every lane moves one chunk on within the next 16 steps ----
+            cur = (d0 - (int)lane) >> 4;
             cur3 = cur3 == 2 ? 0 : cur3 + 1;
             if (fetches) {
-                // thread 0 enters chunk T = d >> 4 now: what was fetched a turn ago goes to LDS, and
-                // chunk T + 1 of the row above is fetched as soon as it is final
-                const int T = d >> 4;
-                if (T >= 0 && T < chunks)
-                    reinterpret_cast<uint4 *>(above_row + (T & 1) * kTallChunk)[lane] = above_ahead;
+                // thread 0 enters chunk T now: the red values of chunk T + 1 of the row above, fetched a
+                // turn ago, go to the ring (a whole turn before thread 0 gets there), and chunk T + 2
+                // is fetched as soon as it is final
+                const int T = d0 >> 4;
                 if (T + 1 >= 0 && T + 1 < chunks) {
+                    // this thread holds bytes 16 lane .. 16 lane + 15 of the chunk; red is every third
+                    const uint32_t wd[4] = {above_ahead.x, above_ahead.y, above_ahead.z, above_ahead.w};
+                    const uint32_t skip = (3u - (16u * lane) % 3u) % 3u;  // offset of the first red byte
+#pragma unroll
+                    for (uint32_t k = 0; k < 6u; ++k) {
+                        const uint32_t o = skip + 3u * k;  // byte within these 16
+                        if (o < 16u) {
+                            const uint32_t px = (16u * lane + o) / 3u;  // pixel within the chunk
+                            carry[(16u * (uint32_t)(T + 1) + px) & 31u] = (uint8_t)(wd[o >> 2] >> (8u * (o & 3u)));
+                        }
+                    }
+                }
+                if (T + 2 >= 0 && T + 2 < chunks) {
                     const unsigned long long t0 = wall_clock64();
-                    while (above_done < (uint32_t)(T + 2)) {  // what is known to be final does not need asking
-                        const uint32_t done = __hip_atomic_load(above_progress, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
-                        above_done = done;
-                        if (__hip_atomic_load(abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+                    while (above_done < (uint32_t)(T + 3)) {  // what is known to be final does not need asking
+                        above_done = __hip_atomic_load(above_progress, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+                        if (above_done >= (uint32_t)(T + 3)) break;
+                        if (__hip_atomic_load(tb.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
                             s_abort = 1;
                             break;
                         }
-                        if (done >= (uint32_t)(T + 2)) break;
-                        if (wall_clock64() - t0 > wait_ticks) {
+                        if (wall_clock64() - t0 > tb.wait_ticks) {
                             s_abort = 1;
-                            __hip_atomic_store(abort_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            __hip_atomic_store(tb.abort_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                             break;
                         }
                         __builtin_amdgcn_s_sleep(2);
                     }
-                    if (!s_abort) above_ahead = above_src[3 * (T + 1) + (int)lane];
+                    if (!s_abort) above_ahead = above_src[3 * (T + 2) + (int)lane];
                 }
             }
             if (have) {
@@ -509,10 +447,10 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_bands(
                         dst[3 * (cur - 1) + i] = make_uint4(q[4 * i], q[4 * i + 1], q[4 * i + 2], q[4 * i + 3]);
                     // chunks 0 .. cur - 1 of this row are final; said every fourth chunk and at the end
                     // (a release at device scope writes the L2 back: too dear for every chunk)
-                    if (publishes && !withhold && ((cur & 3) == 0 || cur == chunks))
-                        __hip_atomic_store(progress + id, (uint32_t)cur, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+                    if (publishes && !tb.withhold && ((cur & 3) == 0 || cur == chunks))
+                        __hip_atomic_store(tb.progress + id, (uint32_t)cur, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
                 }
-                if (cur + 1 >= 0 && cur + 1 < chunks) {
+                if (cur + 1 >= 0 && cur + 1 < chunks) {  // arrived: into the ring
                     uint32_t *q = reinterpret_cast<uint32_t *>(my + nxt3 * kTallChunk);
 #pragma unroll
                     for (int i = 0; i < 3; ++i) {
@@ -522,44 +460,46 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_bands(
                         q[4 * i + 3] = ahead[i].w;
                     }
                 }
-                if (cur + 2 >= 0 && cur + 2 < chunks) {
+                if (cur + 2 >= 0 && cur + 2 < chunks) {  // asked for
 #pragma unroll
                     for (int i = 0; i < 3; ++i) ahead[i] = src[3 * (cur + 2) + i];
                 }
             }
-            if (fetches) wave_lds_sync();  // the chunk of the row above is in LDS before thread 0 reads it
+            wave_lds_sync();
+            // ---- 16 steps ----
+            int v = d0 - (int)lane;
+#pragma unroll 2
+            for (int i = 0; i < kTallLag; ++i, ++v) {
+                const bool on = have && (uint32_t)v < w;
+                const uint32_t col = on ? (uint32_t)v : 0u;
+                int up = __builtin_amdgcn_update_dpp(0, rl, 0x138 /* wave_shr:1 */, 0xF, 0xF, true);
+                int upleft = __builtin_amdgcn_update_dpp(0, rll, 0x138, 0xF, 0xF, true);
+                // the first thread of a wavefront: the row above belongs to another wavefront, to the
+                // round or band before, or is padding
+                const int above = has_above ? (int)above_ptr[col & above_mask] : 0;
+                up = first_lane ? above : up;
+                upleft = first_lane ? first_prev : upleft;
+                first_prev = first_lane && on ? above : first_prev;
+                uint8_t *q = my + ptr;
+                const int xr = ((int)q[0] + twar_predict(p, 0, upleft, up, rl)) & 255;
+                const int xg = ((int)q[1] + twar_predict(p, 1, gl, rl, xr)) & 255;
+                const int xb = ((int)q[2] + twar_predict(p, 2, bl, gl, xg)) & 255;
+                if (on) {
+                    q[0] = (uint8_t)xr;
+                    q[1] = (uint8_t)xg;
+                    q[2] = (uint8_t)xb;
+                }
+                if (on && lane == 63u) hand[wave * 64u + (col & 63u)] = (uint8_t)xr;
+                if (on && keeps_row) carry[col] = (uint8_t)xr;
+                const uint32_t nptr = ptr + 3u == (uint32_t)kTallRing ? 0u : ptr + 3u;
+                ptr = on ? nptr : ptr;
+                rll = on ? rl : rll;
+                rl = on ? xr : rl;
+                gl = on ? xg : gl;
+                bl = on ? xb : bl;
+            }
         }
-        const int v = d - (int)lane;
-        const bool on = have && v >= 0 && v < (int)w;
-        if (!__any(on)) continue;
-        int up = __builtin_amdgcn_update_dpp(0, rl, 0x138 /* wave_shr:1 */, 0xF, 0xF, true);
-        int upleft = __builtin_amdgcn_update_dpp(0, rll, 0x138, 0xF, 0xF, true);
-        if (lane == 0u && on) {
-            // the row above belongs to another wavefront, or to the band above, or is padding
-            int above = 0;
-            if (wave != 0u)
-                above = hand[(wave - 1u) * 64u + ((uint32_t)v & 63u)];
-            else if (band != 0u)
-                above = above_row[(((uint32_t)v >> 4) & 1u) * kTallChunk + 3u * ((uint32_t)v & 15u)];
-            up = above;
-            upleft = first_prev;
-            first_prev = above;
-        }
-        if (on) {
-            uint8_t *q = my + ptr;
-            const int xr = ((int)q[0] + twar_predict(p, 0, upleft, up, rl)) & 255;
-            const int xg = ((int)q[1] + twar_predict(p, 1, gl, rl, xr)) & 255;
-            const int xb = ((int)q[2] + twar_predict(p, 2, bl, gl, xg)) & 255;
-            q[0] = (uint8_t)xr;
-            q[1] = (uint8_t)xg;
-            q[2] = (uint8_t)xb;
-            ptr = ptr + 3u == (uint32_t)kTallRing ? 0u : ptr + 3u;
-            if (lane == 63u) hand[wave * 64u + ((uint32_t)v & 63u)] = (uint8_t)xr;
-            rll = rl;
-            rl = xr;
-            gl = xg;
-            bl = xb;
-        }
+        __syncthreads();
     }
 }
 
@@ -680,20 +620,20 @@ int pilc_twar_inverse(uint32_t n, uint32_t h, uint32_t w, const uint8_t *res_dev
         const uint32_t band_rows = (h + bands - 1) / bands;
         bands = (h + band_rows - 1) / band_rows;
         const uint32_t nt = (band_rows + 63u) & ~63u;
-        const size_t lds = (size_t)nt * kTallStride + (nt / 64) * 64 + 2 * kTallChunk;
+        const size_t lds = (size_t)nt * kTallStride + (nt / 64) * 64 + 32;
         int dev = 0, khz = 0;
         const unsigned long long wait = g_one_pass_wait.load(std::memory_order_relaxed);
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0)
             khz = 100000;
-        rc = allow_large_lds(reinterpret_cast<const void *>(k_twar_inverse_bands));
+        rc = allow_large_lds(reinterpret_cast<const void *>(k_twar_inverse_tall<true>));
         uint32_t aborted = 0u;
         if (rc == PILC_OK) {
             k_band_clear<<<(n * bands + 255u) / 256u, 256, 0, stream>>>(flags, n * bands);
-            k_twar_inverse_bands<<<n * bands, nt, lds, stream>>>(
-                k, h, w, bands, band_rows, res_dev, img_dev, flags, flags + kBandFlags, flags + kBandFlags + 1,
-                wait ? wait : 2000ull * (unsigned long long)khz,
-                (uint32_t)g_one_pass_withhold.load(std::memory_order_relaxed));
+            const TallBands tb = {bands, band_rows, flags, flags + kBandFlags, flags + kBandFlags + 1,
+                                  wait ? wait : 2000ull * (unsigned long long)khz,
+                                  (uint32_t)g_one_pass_withhold.load(std::memory_order_relaxed)};
+            k_twar_inverse_tall<true><<<n * bands, nt, lds, stream>>>(k, h, w, 1u, tb, res_dev, img_dev);
             timer.mark("k_twar_inverse");
             hipError_t e = hipGetLastError();
             if (e == hipSuccess)
@@ -713,8 +653,8 @@ int pilc_twar_inverse(uint32_t n, uint32_t h, uint32_t w, const uint8_t *res_dev
         const uint32_t per = (h + rounds - 1) / rounds;
         const uint32_t nt = (per + 63u) & ~63u;
         const size_t lds = (size_t)nt * kTallStride + (nt / 64) * 64 + w;
-        if ((rc = allow_large_lds(reinterpret_cast<const void *>(k_twar_inverse_tall))) != PILC_OK) return rc;
-        k_twar_inverse_tall<<<n, nt, lds, stream>>>(k, h, w, rounds, res_dev, img_dev);
+        if ((rc = allow_large_lds(reinterpret_cast<const void *>(k_twar_inverse_tall<false>))) != PILC_OK) return rc;
+        k_twar_inverse_tall<false><<<n, nt, lds, stream>>>(k, h, w, rounds, TallBands{}, res_dev, img_dev);
     } else if (tile_lds <= 64 * 1024) {
         k_twar_inverse<true><<<blocks, 64 * kTwarWaves, tile_lds, stream>>>(k, n, h, w, row_stride, res_dev, img_dev);
     } else {

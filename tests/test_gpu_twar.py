@@ -21,6 +21,8 @@ SHAPES = [(1, 1, 1), (3, 32, 32), (5, 7, 9), (2, 64, 64), (7, 16, 16), (2, 33, 5
           # few images taller than 576 rows: bands of an image in workgroups of their own that follow
           # each other through counters in global memory (two bands of 350 rows; four of 525)
           (2, 700, 64), (1, 2100, 160),
+          # many images with more rows than a workgroup has threads: rounds within a workgroup
+          (256, 800, 16),
           # more groups of small images: eight images a group, rows of 27 dwords, an odd number of
           # groups, 17-row images (13 idle threads), many groups with a single-image group at the end
           (9, 8, 8), (40, 32, 36), (11, 64, 64), (100, 17, 16), (24577, 32, 32)]
