@@ -10,7 +10,7 @@ from paper_2206_05279_amd import synth
 
 pytestmark = pytest.mark.gpu
 
-from gpu_util import DeviceWorkload, first_difference, parse_container  # noqa: E402
+from gpu_util import DeviceWorkload, first_difference  # noqa: E402
 
 
 def _ogeom(wl):
