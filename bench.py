@@ -73,6 +73,10 @@ def parse_args():
     ap.add_argument("--no-traffic", action="store_true",
                     help="skip the two rocprofv3 --pmc child runs that measure HBM traffic")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
+    ap.add_argument("--lane-sweep", action="store_true",
+                    help="instead of the benchmark: the stress workload (config 4) on 256 random + 256 "
+                         "constant images over lanes per image 1..1024 and M = 12, 16, kernels chosen "
+                         "automatically and, at 8..64 lanes per image, forced either way; one JSON line")
     ap.add_argument("--pmc-child", action="store_true",
                     help="internal: one warm-up and one step of every workload of the run, each followed "
                          "by a plain device copy; prints nothing")
@@ -694,12 +698,70 @@ def report(run, r, seg, torch, with_copy=False):
     return out
 
 
+def lane_sweep():
+    """The stress workload over lanes per image: whole pilc_encode / pilc_decode calls, mean of
+    three after a warm-up, round trip checked in every row."""
+    import dataclasses
+    import torch
+    from paper_2206_05279_amd import binding as pb
+    from paper_2206_05279_amd import synth
+
+    wl = synth.make_workload(4, 512, prec_bits=12, lanes_per_image=64)
+    dev = torch.device("cuda:0")
+    img, mu, ls, coef = (torch.from_numpy(a).to(dev) for a in (wl.img, wl.mu, wl.log_scale, wl.chan_coef))
+    out = torch.empty_like(img)
+    px = wl.h * wl.w
+    rows = []
+
+    def one(m, per_image, policy):
+        pb.pilc_set_kernel_policy(policy)
+        geom = pb.make_geom(wl.n, wl.h, wl.w, m, 0, px // per_image, 0)
+        ws, mc = pb.pilc_workspace_size(geom)
+        work = torch.empty(ws, dtype=torch.uint8, device=dev)
+        coded = torch.empty(mc, dtype=torch.uint8, device=dev)
+        pb.pilc_set_timing(True)
+        enc, dec, nb, te, td = [], [], 0, None, None
+        for it in range(4):
+            _, nb = pb.pilc_encode(geom, img, mu, ls, coef, work, coded)
+            te = pb.pilc_last_timing()
+            pb.pilc_decode(geom, coded, nb, mu, ls, coef, work, out)
+            td = pb.pilc_last_timing()
+            if it:
+                enc.append(te[0][1])
+                dec.append(td[0][1])
+        raw = float(wl.subpixels)
+        rows.append({"M": m, "lanes_per_image": per_image, "lanes": wl.n * per_image,
+                     "policy": {0: "automatic", 1: "thread per lane", 2: "few-lane kernels"}[policy],
+                     "encode_kernel": te[1][0], "decode_kernel": td[-1][0],
+                     "encode_ms": float(np.mean(enc)), "decode_ms": float(np.mean(dec)),
+                     "compress_GB_s": raw / np.mean(enc) / 1e6, "decompress_GB_s": raw / np.mean(dec) / 1e6,
+                     "bits_per_subpixel": 8.0 * nb / raw, "round_trip_exact": bool(torch.equal(out, img))})
+
+    try:
+        for per_image in (1, 2, 4, 8, 16, 32, 64, 256, 1024):
+            one(12, per_image, 0)
+        for per_image in (1, 64, 1024):
+            one(16, per_image, 0)
+        for per_image in (8, 16, 32, 64):
+            one(12, per_image, 1)
+            one(12, per_image, 2)
+    finally:
+        pb.pilc_set_kernel_policy(0)
+    print(json.dumps({"workload": "cfg4 entropy extremes, 256 random + 256 constant images of 256x256x3 "
+                                  "(%.1f MB raw)" % (wl.subpixels / 1e6), "rows": rows}))
+    if not all(r["round_trip_exact"] for r in rows):
+        sys.exit(4)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU runs are not "
               "part of it", file=sys.stderr)
         sys.exit(2)
+    if args.lane_sweep:
+        lane_sweep()
+        return
     extras = not args.no_extra and args.images is None
 
     # children first: this process has not initialised HIP yet
