@@ -86,15 +86,15 @@ def parse_args():
 # ----------------------------------------------------------------------------------------------
 # HBM traffic from rocprofv3 counters (child processes, started before this process touches HIP)
 # ----------------------------------------------------------------------------------------------
-def _run_pmc(counter: str, argv):
-    """One rocprofv3 --pmc run of `bench.py --pmc-child <argv>`.  Returns the dispatches in launch
-    order as (kernel name, counter value in KiB), or None."""
+def _run_pmc(counters: str, argv):
+    """One rocprofv3 --pmc run of `bench.py --pmc-child <argv>` with the space-separated
+    `counters`.  Returns the dispatches in launch order as (kernel name, {counter: value}), or None."""
     exe = shutil.which("rocprofv3") or "/opt/rocm/bin/rocprofv3"
     if not os.path.exists(exe):
         return None
     out_dir = tempfile.mkdtemp(prefix="pilc_pmc_", dir="/tmp")
-    cmd = [exe, "--pmc", counter, "-d", out_dir, "-o", "pmc", "--output-format", "csv", "--",
-           sys.executable, os.path.join(HERE, "bench.py"), "--pmc-child"] + argv
+    cmd = [exe, "--pmc"] + counters.split() + ["-d", out_dir, "-o", "pmc", "--output-format", "csv", "--",
+                                               sys.executable, os.path.join(HERE, "bench.py"), "--pmc-child"] + argv
     env = dict(os.environ, TMPDIR="/tmp")
     try:
         proc = subprocess.Popen(cmd, cwd="/tmp", env=env, stdout=subprocess.DEVNULL,
@@ -107,17 +107,15 @@ def _run_pmc(counter: str, argv):
             return None
         if proc.returncode != 0:
             return None
-        rows = []
+        rows = {}
         for root, _, files in os.walk(out_dir):
             for f in files:
                 if f.endswith("counter_collection.csv"):
                     with open(os.path.join(root, f)) as fh:
                         for r in csv.DictReader(fh):
-                            if r["Counter_Name"] == counter:
-                                rows.append((int(r["Dispatch_Id"]), r["Kernel_Name"].split("(")[0],
-                                             float(r["Counter_Value"])))
-        rows.sort()
-        return [(name, value) for _, name, value in rows]
+                            d = rows.setdefault(int(r["Dispatch_Id"]), (r["Kernel_Name"].split("(")[0], {}))
+                            d[1][r["Counter_Name"]] = float(r["Counter_Value"])
+        return [rows[k] for k in sorted(rows)]
     except (OSError, KeyError, ValueError):
         return None
     finally:
@@ -134,30 +132,61 @@ def probe_copy_bytes(run):
     return float(min(int(run.probe_bytes // 2), PROBE_MAX_BYTES))
 
 
+# third pass: how busy the vector ALUs were (the thread-per-lane kernels are bound by them)
+VALU_COUNTERS = "SQ_INSTS_VALU SQ_ACTIVE_INST_VALU GRBM_GUI_ACTIVE"
+
+
 def measure_traffic(argv, count):
-    """HBM bytes per launch of the kernels of each of the `count` workloads of this run.  The
-    child runs them in order, each followed by a plain copy-like pass over a buffer of known
-    size, so those passes cut the launch sequence into one segment per workload.  Returns a list of
-    {"read": {kernel: KiB of its last launch}, "write": {...}, "read_copy_kib", "write_copy_kib"}
-    or None."""
+    """HBM bytes per launch of the kernels of each of the `count` workloads of this run, and their
+    vector-ALU counters.  The child runs the workloads in order, each followed by a plain
+    copy-like pass over a buffer of known size, so those passes cut the launch sequence into one
+    segment per workload.  Returns a list of {"read": {kernel: KiB of its last launch},
+    "write": {...}, "read_copy_kib", "write_copy_kib", "valu": {kernel: {counter: value}}} or None."""
     out = [dict() for _ in range(count)]
-    for counter, key in (("FETCH_SIZE", "read"), ("WRITE_SIZE", "write")):
-        rows = _run_pmc(counter, argv)
+    for counters, key in (("FETCH_SIZE", "read"), ("WRITE_SIZE", "write"), (VALU_COUNTERS, "valu")):
+        rows = _run_pmc(counters, argv)
         if not rows:
+            if key == "valu":
+                break              # the traffic figures stand without it
             return None
         seg, cur = [], {}
-        for name, value in rows:
+        for name, values in rows:
             if COPY_KERNEL in name:
-                seg.append((cur, value))
+                seg.append((cur, values))
                 cur = {}
             else:
-                cur[name] = value      # a later launch of the same kernel replaces the warm-up's
+                cur[name] = values     # a later launch of the same kernel replaces the warm-up's
         if len(seg) != count:
+            if key == "valu":
+                break
             return None
-        for i, (kernels, copy_kib) in enumerate(seg):
-            out[i][key] = kernels
-            out[i][key + "_copy_kib"] = copy_kib
+        for i, (kernels, copy_values) in enumerate(seg):
+            if key == "valu":
+                out[i][key] = kernels
+            else:
+                out[i][key] = {k: v[counters] for k, v in kernels.items()}
+                out[i][key + "_copy_kib"] = copy_values[counters]
     return out
+
+
+def _matches(kernel, name):
+    # the timing name is the kernel's, or its stem (k_twar_inverse: k_twar_inverse<..>, .._tall)
+    return ("::" + kernel) in name and not name.split("::" + kernel)[1][:1].isalpha()
+
+
+def valu_of(kernel, seg):
+    """Vector-ALU figures of the last launch of `kernel` from a segment of measure_traffic: wavefront
+    instructions issued, and the share of the chip's issue slots they took (an instruction
+    occupies a SIMD for 4 cycles; 1024 SIMDs; GRBM_GUI_ACTIVE sums the busy cycles of the 8 XCDs)."""
+    if not seg or "valu" not in seg:
+        return None
+    vals = [v for name, v in seg["valu"].items() if _matches(kernel, name)]
+    if not vals or not vals[-1].get("GRBM_GUI_ACTIVE"):
+        return None
+    v = vals[-1]
+    return {"wavefront_instructions": v.get("SQ_INSTS_VALU"),
+            "issue_frac": 4.0 * v.get("SQ_ACTIVE_INST_VALU", 0.0) / (1024.0 * v["GRBM_GUI_ACTIVE"] / 8.0),
+            "peak_wavefront_instructions_per_s": 256 * 4 * 2.4e9 / 4}
 
 
 def traffic_of(kernel, seg, copy_bytes):
@@ -170,9 +199,7 @@ def traffic_of(kernel, seg, copy_bytes):
         if not seg.get(key + "_copy_kib"):
             return None, None
         scale = copy_bytes / (seg[key + "_copy_kib"] * 1024.0)
-        # the timing name is the kernel's, or its stem (k_twar_inverse: k_twar_inverse<..>, .._tall)
-        vals = [v for name, v in seg[key].items()
-                if ("::" + kernel) in name and not name.split("::" + kernel)[1][:1].isalpha()]
+        vals = [v for name, v in seg[key].items() if _matches(kernel, name)]
         if not vals:
             return None, None
         detail[key + "_bytes"] = vals[-1] * 1024.0 * scale
@@ -685,7 +712,7 @@ def report(run, r, seg, torch, with_copy=False):
         "kernel_ms": kernel_ms,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_detail": detail,
-                     "algorithmic_bytes": algo, "avg_ms": kernel_ms[dom],
+                     "algorithmic_bytes": algo, "avg_ms": kernel_ms[dom], "valu": valu_of(dom, seg),
                      "calibration_copy_bytes": probe_copy_bytes(run)},
     }
     if not twar:
