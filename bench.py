@@ -77,6 +77,10 @@ def parse_args():
                     help="instead of the benchmark: the stress workload (config 4) on 256 random + 256 "
                          "constant images over lanes per image 1..1024 and M = 12, 16, kernels chosen "
                          "automatically and, at 8..64 lanes per image, forced either way; one JSON line")
+    ap.add_argument("--piece-sweep", action="store_true",
+                    help="instead of the benchmark: the table-driven coder over the number of pieces "
+                         "coded in parallel (the axis of the paper's Fig. 5), 64 .. 10^6 pieces of 1000 "
+                         "symbols, D = 8, M = 12; one JSON line")
     ap.add_argument("--pmc-child", action="store_true",
                     help="internal: one warm-up and one step of every workload of the run, each followed "
                          "by a plain device copy; prints nothing")
@@ -780,6 +784,50 @@ def lane_sweep():
         sys.exit(4)
 
 
+def piece_sweep():
+    """The table-driven coder over the number of pieces in flight (one thread each): whole
+    pilc_ansai_encode / pilc_ansai_decode calls, mean of three after a warm-up, round trip
+    checked in every row.  The recipe is that of the paper's Fig. 5 (Sec. 4.3)."""
+    import torch
+    from paper_2206_05279_amd import binding as pb
+    from paper_2206_05279_amd import synth_pieces
+
+    wl = synth_pieces.make_piece_workload(1, 1_000_000, threads=16)
+    dev = torch.device("cuda:0")
+    d, x = wl.mass.shape
+    sym_all, dist_all = torch.from_numpy(wl.sym).to(dev), torch.from_numpy(wl.dist).to(dev)
+    tables = torch.empty(pb.pilc_ansai_table_bytes(wl.prec_bits, d, x), dtype=torch.uint8, device=dev)
+    pb.pilc_ansai_build_tables(wl.prec_bits, d, x, torch.from_numpy(wl.mass).to(dev), tables)
+    pb.pilc_set_timing(True)
+    rows = []
+    for pieces in (64, 256, 1024, 4096, 16384, 65536, 262144, 1_000_000):
+        shape = pb.make_ansai_shape(pieces, wl.count, wl.prec_bits, d, x)
+        sym, dist = sym_all[:pieces].contiguous(), dist_all[:pieces].contiguous()
+        ws, mc = pb.pilc_ansai_workspace_size(shape)
+        work = torch.empty(ws, dtype=torch.uint8, device=dev)
+        coded = torch.empty(mc, dtype=torch.uint8, device=dev)
+        out = torch.empty_like(sym)
+        enc, dec, nb = [], [], 0
+        for it in range(4):
+            nb = pb.pilc_ansai_encode(shape, sym, dist, tables, work, coded)[1]
+            te = pb.pilc_last_timing()
+            pb.pilc_ansai_decode(shape, coded, nb, dist, tables, work, out)
+            td = pb.pilc_last_timing()
+            if it:
+                enc.append(te[0][1])
+                dec.append(td[0][1])
+        raw = float(pieces) * wl.count
+        rows.append({"pieces": pieces, "wavefronts": (pieces + 63) // 64,
+                     "encode_ms": float(np.mean(enc)), "decode_ms": float(np.mean(dec)),
+                     "encode_MB_s": raw / np.mean(enc) / 1e3, "decode_MB_s": raw / np.mean(dec) / 1e3,
+                     "bits_per_symbol": 8.0 * nb / raw, "round_trip_exact": bool(torch.equal(out, sym))})
+        del work, coded, out
+    print(json.dumps({"workload": "table-driven coder, pieces of %d symbols, D = %d, X = %d, M = %d"
+                                  % (wl.count, d, x, wl.prec_bits), "rows": rows}))
+    if not all(r["round_trip_exact"] for r in rows):
+        sys.exit(4)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -788,6 +836,9 @@ def main():
         sys.exit(2)
     if args.lane_sweep:
         lane_sweep()
+        return
+    if args.piece_sweep:
+        piece_sweep()
         return
     extras = not args.no_extra and args.images is None
 

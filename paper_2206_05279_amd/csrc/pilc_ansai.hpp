@@ -1015,7 +1015,7 @@ int pilc_ansai_decode(const pilc_ansai_shape *shape, const uint8_t *coded_dev, s
     const uint8_t *tb = static_cast<const uint8_t *>(tables_dev);
 
     // Workgroup shape: the decode tables in LDS when they leave room for at least four
-    // wavefronts' staging rows; as many wavefronts (<= 8) as then fit.
+    // wavefronts' staging rows; as many wavefronts (<= kAnsaiDecMaxWaves) as then fit.
     const size_t entries = (size_t)sh.D << sh.M;
     const size_t tab_lds = ((entries + 3) / 4 + (t.wide ? entries : (entries + 1) / 2)) * 4;
     const size_t row_lds = (size_t)64 * (kDecRow + kRingStride) * 4;
@@ -1025,6 +1025,14 @@ int pilc_ansai_decode(const pilc_ansai_shape *shape, const uint8_t *coded_dev, s
         // small tables: several workgroups per compute unit; large ones: one big workgroup
         size_t fit = (lds_max - tab_lds) / row_lds;
         waves = tab_lds <= 16384 ? 4u : (uint32_t)(fit > kAnsaiDecMaxWaves ? kAnsaiDecMaxWaves : fit);
+        // a batch too small to fill every compute unit that densely is spread over all of them
+        // (a piece is a serial chain: its pace falls with the wavefronts that share its SIMD)
+        int dev = 0, cus = 0;
+        if (waves > 4u && hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0) {
+            const uint32_t each = (uint32_t)ceil_div64(ws.waves, (uint64_t)cus);
+            waves = each < 4u ? 4u : (each < waves ? each : waves);
+        }
     }
     Timer timer(stream);
     k_ansai_begin<<<1, 1, 0, stream>>>(sh, reinterpret_cast<const ATabHeader *>(tb), status);

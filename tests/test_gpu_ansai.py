@@ -43,6 +43,8 @@ CASES = [
     ("255 distributions", 8, _random(8, 255, 256, 1.0), 64, 100, False),
     ("4096 pieces of 1000", 12, _logistic(12, 8), 4096, 1000, False),
     ("M14 random", 14, _random(14, 2, 256, 1.0), 77, 130, False),
+    # between one wavefront per SIMD and a full workgroup: seven wavefronts per decode workgroup
+    ("100,000 short pieces", 12, _logistic(12, 8), 100000, 24, False),
     # the stream of vector indices (Sec. 3.1): one static law, 16x16 indices per 32x32 image, K = 256
     ("vector-index stream", 12, lambda rng: sp.index_stream_masses(12), 3000, 256, False),
 ]
