@@ -985,6 +985,15 @@ static bool mix_params_ok(const pilc_mix_params *p)
            ((uintptr_t)p->chan_coef & 1) == 0;
 }
 
+// The component count a mixture kernel was built for (components in registers: even K, arrays on
+// 4-byte boundaries), or 0 for the kernels that take any K at run time.
+static int mix_built_for(const pilc_mix_params *p)
+{
+    const bool aligned =
+        (((uintptr_t)p->mu | (uintptr_t)p->log_scale | (uintptr_t)p->weight) & 3) == 0;
+    return aligned && p->num_comp == 10u ? 10 : 0;
+}
+
 int pilc_mix_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_mix_params *params,
                     void *workspace_dev, size_t workspace_bytes, uint8_t *coded_dev,
                     size_t coded_capacity, uint64_t *coded_bytes_host, void *hip_stream)
@@ -1012,13 +1021,15 @@ int pilc_mix_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_mi
     uint16_t *payload = reinterpret_cast<uint16_t *>(coded_dev + table_end);
     const MixArgs args = {params->mu, params->log_scale, params->weight, params->chan_coef,
                           params->num_comp};
-    const size_t lds = mix_lds_bytes(params->num_comp);
-    if ((rc = allow_large_lds(reinterpret_cast<const void *>(k_mix_encode))) != PILC_OK) return rc;
+    const int built = mix_built_for(params);
+    const size_t lds = mix_lds_bytes(params->num_comp, built == 0);
+    auto kern = built == 10 ? k_mix_encode<10> : k_mix_encode<0>;
+    if ((rc = allow_large_lds(reinterpret_cast<const void *>(kern))) != PILC_OK) return rc;
 
     Timer timer(stream);
     k_init_status<<<1, 1, 0, stream>>>(status);
     const uint32_t lane_cap = max_lane_symbols(g);
-    k_mix_encode<<<(uint32_t)ceil_div64(g.lanes, kMixThreads), kMixThreads, lds, stream>>>(
+    kern<<<(uint32_t)ceil_div64(g.lanes, kMixThreads), kMixThreads, lds, stream>>>(
         g, img_dev, args, scratch, lane_cap, lane_words, lane_state, &status->code);
     timer.mark("k_mix_encode");
     const ItemBytes lane_bytes = {4u, 2u, 0u, 0u};
@@ -1062,14 +1073,16 @@ int pilc_mix_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t code
     Status *status = reinterpret_cast<Status *>(static_cast<uint8_t *>(workspace_dev) + ws.status_off);
     const MixArgs args = {params->mu, params->log_scale, params->weight, params->chan_coef,
                           params->num_comp};
-    const size_t lds = mix_lds_bytes(params->num_comp);
-    if ((rc = allow_large_lds(reinterpret_cast<const void *>(k_mix_decode))) != PILC_OK) return rc;
+    const int built = mix_built_for(params);
+    const size_t lds = mix_lds_bytes(params->num_comp, built == 0);
+    auto kern = built == 10 ? k_mix_decode<10> : k_mix_decode<0>;
+    if ((rc = allow_large_lds(reinterpret_cast<const void *>(kern))) != PILC_OK) return rc;
 
     Timer timer(stream);
     k_check_header<<<1, 1, 0, stream>>>(g, kMagicMix, params->num_comp, coded_dev,
                                         (unsigned long long)coded_bytes, status);
     timer.mark("k_check_header");
-    k_mix_decode<<<(uint32_t)ceil_div64(g.lanes, kMixThreads), kMixThreads, lds, stream>>>(
+    kern<<<(uint32_t)ceil_div64(g.lanes, kMixThreads), kMixThreads, lds, stream>>>(
         g, coded_dev, args, img_out_dev, &status->code, &status->payload_bytes);
     timer.mark("k_mix_decode");
     HIP_TRY(hipGetLastError());

@@ -7,7 +7,8 @@
 // single-law edge CDF, and C(k) = k + floor(F(k) (2^M - 256) / 2^24); the channel conditioning
 // of Sec. 3.1 eqs. (3)-(4) shifts every component's mean with that component's own innovations.
 //
-// K is a run-time value, so nothing per component lives in registers.  A thread first copies
+// In the general kernels K is a run-time value, so nothing per component lives in registers
+// (the kernels built for one K, further down, keep the channel's components there).  A thread first copies
 // the 7 K 16-bit parameters of a pixel into its own LDS slots in one burst of loads (every
 // 128-byte line of the arrays is then asked for by one or two bursts rather than by dozens of
 // separate loads spread over the pixel's work), then, before a subpixel is coded, turns the
@@ -33,15 +34,16 @@ struct MixArgs {
 
 // Dynamic LDS of the mixture kernels: K {mean, 1/scale} pairs per thread as [component][thread]
 // 8-byte elements, then per thread the pixel's raw means (3 K halfwords), log-scales (3 K) and
-// weights (K), each rounded up to dwords, as [dword][thread].
+// weights (K), each rounded up to dwords, as [dword][thread].  The kernels built for one K have
+// neither the pairs nor the weights there.
 struct MixSlots {
     uint2 *pairs;    // this thread's column of the pairs
     uint32_t *base;  // this thread's column of the raw parameters
     uint32_t k, stride, raw_ls, raw_w;
     static constexpr uint32_t raw_mu = 0u;
-    __device__ __forceinline__ MixSlots(uint32_t *lds, uint32_t k_)
+    __device__ __forceinline__ MixSlots(uint32_t *lds, uint32_t k_, bool with_pairs = true)
         : pairs(reinterpret_cast<uint2 *>(lds) + threadIdx.x),
-          base(lds + 2u * k_ * blockDim.x + threadIdx.x), k(k_), stride(blockDim.x),
+          base(lds + (with_pairs ? 2u * k_ * blockDim.x : 0u) + threadIdx.x), k(k_), stride(blockDim.x),
           raw_ls((3u * k_ + 1u) / 2u), raw_w(2u * ((3u * k_ + 1u) / 2u))
     {
     }
@@ -61,9 +63,10 @@ struct MixSlots {
     }
 };
 
-static inline size_t mix_lds_bytes(uint32_t k)
+// with_pairs false: the kernels built for one K, which keep the pairs and the weights in registers.
+static inline size_t mix_lds_bytes(uint32_t k, bool with_pairs = true)
 {
-    return (size_t)kMixThreads * 4u * (2u * k + 2u * ((3u * k + 1u) / 2u) + (k + 1u) / 2u);
+    return (size_t)kMixThreads * 4u * ((with_pairs ? 2u * k + (k + 1u) / 2u : 0u) + 2u * ((3u * k + 1u) / 2u));
 }
 
 // The pixel's parameters into the slots; false if its weights do not sum to 2^15.
@@ -93,9 +96,19 @@ __device__ __forceinline__ bool mix_load_pixel(const MixArgs &a, uint32_t p, con
 // Even K with dword-aligned arrays: a pixel's raw parameters are 3 K / 2 + 3 K / 2 + K / 2 whole
 // dwords, and the kernels keep the NEXT pixel's dwords in registers while they work on the
 // current one, so that the loads have a pixel's worth of arithmetic to arrive in.
-constexpr int kMixPreMu = 3 * kMixMaxComp / 2, kMixPreW = kMixMaxComp / 2;
-struct MixAhead {
-    uint32_t m[kMixPreMu], l[kMixPreMu], w[kMixPreW];
+// kK is the component count a kernel was built for, 0 for the kernels that take it at run time.
+template <int kK> struct MixAhead {
+    static constexpr int kComp = kK > 0 ? kK : kMixMaxComp;
+    static constexpr int kMu = 3 * kComp / 2, kW = kComp / 2;
+    uint32_t m[kMu], l[kMu], w[kW];
+};
+
+// The components of the channel being coded, in registers: only in the kernels built for one K,
+// where every index into these arrays is a compile-time constant.
+template <int kK> struct MixRegs {
+    int c0[kK > 0 ? kK : 1];          // edge_offset of the shifted mean
+    uint32_t inv_s[kK > 0 ? kK : 1];  // 1 / scale
+    uint32_t w[kK > 0 ? kK : 1];      // the pixel's weights
 };
 
 __device__ __forceinline__ bool mix_can_run_ahead(const MixArgs &a)
@@ -104,39 +117,48 @@ __device__ __forceinline__ bool mix_can_run_ahead(const MixArgs &a)
                                  reinterpret_cast<uintptr_t>(a.weight)) & 3u) == 0u;
 }
 
-__device__ __forceinline__ void mix_fetch_ahead(const MixArgs &a, uint32_t p, MixAhead &r)
+template <int kK>
+__device__ __forceinline__ void mix_fetch_ahead(const MixArgs &a, uint32_t p, MixAhead<kK> &r)
 {
-    const size_t px = (size_t)p * 3u * a.k;
+    const uint32_t k = kK > 0 ? (uint32_t)kK : a.k;
+    const size_t px = (size_t)p * 3u * k;
     const uint32_t *gm = reinterpret_cast<const uint32_t *>(a.mu + px);
     const uint32_t *gl = reinterpret_cast<const uint32_t *>(a.ls + px);
-    const uint32_t *gw = reinterpret_cast<const uint32_t *>(a.weight + (size_t)p * a.k);
-    const uint32_t n3 = 3u * a.k / 2u, n1 = a.k / 2u;
+    const uint32_t *gw = reinterpret_cast<const uint32_t *>(a.weight + (size_t)p * k);
+    const uint32_t n3 = 3u * k / 2u, n1 = k / 2u;
 #pragma unroll
-    for (int i = 0; i < kMixPreMu; ++i)
+    for (int i = 0; i < MixAhead<kK>::kMu; ++i)
         if ((uint32_t)i < n3) r.m[i] = gm[i];
 #pragma unroll
-    for (int i = 0; i < kMixPreMu; ++i)
+    for (int i = 0; i < MixAhead<kK>::kMu; ++i)
         if ((uint32_t)i < n3) r.l[i] = gl[i];
 #pragma unroll
-    for (int i = 0; i < kMixPreW; ++i)
+    for (int i = 0; i < MixAhead<kK>::kW; ++i)
         if ((uint32_t)i < n1) r.w[i] = gw[i];
 }
 
-// The fetched pixel into the slots; false if its weights do not sum to 2^15.
-__device__ __forceinline__ bool mix_store_ahead(const MixAhead &r, const MixSlots &s)
+// The fetched pixel into the slots (and its weights into `regs` where the kernel keeps them
+// there); false if the weights do not sum to 2^15.
+template <int kK>
+__device__ __forceinline__ bool mix_store_ahead(const MixAhead<kK> &r, const MixSlots &s, MixRegs<kK> &regs)
 {
     const uint32_t n3 = 3u * s.k / 2u, n1 = s.k / 2u;
     uint32_t sum = 0;
 #pragma unroll
-    for (int i = 0; i < kMixPreMu; ++i)
+    for (int i = 0; i < MixAhead<kK>::kMu; ++i)
         if ((uint32_t)i < n3) s.dword(s.raw_mu + i) = r.m[i];
 #pragma unroll
-    for (int i = 0; i < kMixPreMu; ++i)
+    for (int i = 0; i < MixAhead<kK>::kMu; ++i)
         if ((uint32_t)i < n3) s.dword(s.raw_ls + i) = r.l[i];
 #pragma unroll
-    for (int i = 0; i < kMixPreW; ++i)
+    for (int i = 0; i < MixAhead<kK>::kW; ++i)
         if ((uint32_t)i < n1) {
-            s.dword(s.raw_w + i) = r.w[i];
+            if constexpr (kK > 0) {
+                regs.w[2 * i] = r.w[i] & 0xFFFFu;
+                regs.w[2 * i + 1] = r.w[i] >> 16;
+            } else {
+                s.dword(s.raw_w + i) = r.w[i];
+            }
             sum += (r.w[i] & 0xFFFFu) + (r.w[i] >> 16);
         }
     return sum == (1u << 15);
@@ -160,6 +182,39 @@ __device__ __forceinline__ void mix_load_channel(const MixSlots &s, int ch, int 
         }
         const int l = (int)(short)s.half(s.raw_ls, (uint32_t)ch * s.k + j);
         s.set_pair(j, me, inv_scale(l, tab));
+    }
+}
+
+// The same into registers, two components (one dword of each raw array) at a time.
+template <int kK>
+__device__ __forceinline__ void mix_load_channel(const MixSlots &s, MixRegs<kK> &regs, int ch, int x_r,
+                                                 int x_g, int a_gr, int a_br, int a_bg, const LdsTables &tab)
+{
+    static_assert(kK > 0 && kK % 2 == 0, "built for an even number of components");
+    const uint32_t *mu_r = s.base + s.raw_mu * s.stride;
+    const uint32_t *mu_g = mu_r + (kK / 2) * s.stride;
+    const uint32_t *mu_c = mu_r + (uint32_t)ch * (kK / 2) * s.stride;
+    const uint32_t *ls_c = s.base + (s.raw_ls + (uint32_t)ch * (kK / 2)) * s.stride;
+#pragma unroll
+    for (int jj = 0; jj < kK / 2; ++jj) {
+        const uint32_t m2 = mu_c[jj * s.stride], l2 = ls_c[jj * s.stride];
+        int me[2] = {(int)(m2 & 0xFFFFu), (int)(m2 >> 16)};
+        if (ch >= 1) {
+            const uint32_t r2 = mu_r[jj * s.stride];
+            const int e_r[2] = {x_r * 256 - (int)(r2 & 0xFFFFu), x_r * 256 - (int)(r2 >> 16)};
+            if (ch == 1) {
+                me[0] += rsh14_mul(a_gr, e_r[0]);
+                me[1] += rsh14_mul(a_gr, e_r[1]);
+            } else {
+                const uint32_t g2 = mu_g[jj * s.stride];
+                me[0] += rsh14_mul(a_br, e_r[0]) + rsh14_mul(a_bg, x_g * 256 - (int)(g2 & 0xFFFFu));
+                me[1] += rsh14_mul(a_br, e_r[1]) + rsh14_mul(a_bg, x_g * 256 - (int)(g2 >> 16));
+            }
+        }
+        regs.c0[2 * jj] = edge_offset(me[0]);
+        regs.c0[2 * jj + 1] = edge_offset(me[1]);
+        regs.inv_s[2 * jj] = inv_scale((int)(short)(l2 & 0xFFFFu), tab);
+        regs.inv_s[2 * jj + 1] = inv_scale((int)(short)(l2 >> 16), tab);
     }
 }
 
@@ -187,6 +242,21 @@ __device__ __forceinline__ uint32_t mix_cum_inner(int k, const MixSlots &s, uint
     return (uint32_t)k + scale_mass((uint32_t)(acc >> 15), spread);
 }
 
+// C(k), 1 <= k <= 255, from the registers: all kK table reads are in flight together.
+template <int kK>
+__device__ __forceinline__ uint32_t mix_cum_inner(int k, const MixRegs<kK> &regs, uint32_t spread,
+                                                  const LdsTables &tab)
+{
+    unsigned long long acc = 0ull;
+#pragma unroll
+    for (int j = 0; j < kK; ++j)
+        acc += (unsigned long long)regs.w[j] * edge_cdf(256 * k + regs.c0[j], regs.inv_s[j], tab);
+    return (uint32_t)k + scale_mass((uint32_t)(acc >> 15), spread);
+}
+
+// kK > 0: built for that many components (even, dword-aligned arrays: the host checks), which then
+// live in registers; kK == 0: any K, components in LDS.
+template <int kK>
 __global__ __launch_bounds__(kMixThreads) void k_mix_encode(
     Geo g, const uint8_t *__restrict__ img, MixArgs a, uint16_t *__restrict__ scratch,
     uint32_t lane_cap, uint32_t *__restrict__ lane_words, uint32_t *__restrict__ lane_state,
@@ -197,7 +267,7 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_encode(
     load_tables(tab);
     const uint32_t lane = blockIdx.x * blockDim.x + threadIdx.x;
     if (lane >= g.lanes) return;
-    const MixSlots slots(mix_lds, a.k);
+    const MixSlots slots(mix_lds, kK > 0 ? (uint32_t)kK : a.k, kK == 0);
     const LaneShape sh = lane_shape(g, lane);
     const uint32_t m_bits = g.prec_bits;
     const uint32_t spread = (1u << m_bits) - 256u, top = 1u << m_bits;
@@ -206,8 +276,9 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_encode(
     uint32_t nwords = 0, S = 1u << 16;
     bool ok = true;
     // pixels last-first, and B, G, R inside a pixel (App. A eq. (11) runs against the decoder)
-    const bool ahead = mix_can_run_ahead(a);
-    MixAhead pre;
+    const bool ahead = kK > 0 || mix_can_run_ahead(a);
+    MixAhead<kK> pre;
+    MixRegs<kK> regs;
     uint32_t pre_x = 0, im_now = 0xFFFFFFFFu;
     int a_gr = 0, a_br = 0, a_bg = 0;
     auto fetch_pixel_bytes = [&](uint32_t q) -> uint32_t {
@@ -228,7 +299,7 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_encode(
         }
         uint32_t xb;
         if (ahead) {
-            ok = mix_store_ahead(pre, slots) && ok;
+            ok = mix_store_ahead(pre, slots, regs) && ok;
             xb = pre_x;
             if (t != 0u) {
                 const uint32_t q = lane_pixel(g, sh, t - 1u);
@@ -242,10 +313,17 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_encode(
         const int x[3] = {(int)(xb & 0xFFu), (int)((xb >> 8) & 0xFFu), (int)(xb >> 16)};
 #pragma unroll 1
         for (int ch = 2; ch >= 0; --ch) {
-            mix_load_channel(slots, ch, x[0], x[1], a_gr, a_br, a_bg, tab);
             const int v = ch == 0 ? x[0] : (ch == 1 ? x[1] : x[2]);
-            const uint32_t lo = v == 0 ? 0u : mix_cum_inner(v, slots, spread, tab);
-            const uint32_t hi = v == 255 ? top : mix_cum_inner(v + 1, slots, spread, tab);
+            uint32_t lo, hi;
+            if constexpr (kK > 0) {
+                mix_load_channel(slots, regs, ch, x[0], x[1], a_gr, a_br, a_bg, tab);
+                lo = v == 0 ? 0u : mix_cum_inner(v, regs, spread, tab);
+                hi = v == 255 ? top : mix_cum_inner(v + 1, regs, spread, tab);
+            } else {
+                mix_load_channel(slots, ch, x[0], x[1], a_gr, a_br, a_bg, tab);
+                lo = v == 0 ? 0u : mix_cum_inner(v, slots, spread, tab);
+                hi = v == 255 ? top : mix_cum_inner(v + 1, slots, spread, tab);
+            }
             const uint32_t f = hi - lo;
             if (S >= (f << (32u - m_bits))) {
                 *wout = (uint16_t)(S & 0xFFFFu);
@@ -296,6 +374,7 @@ struct ByteRun {
     }
 };
 
+template <int kK>  // as k_mix_encode
 __global__ __launch_bounds__(kMixThreads) void k_mix_decode(
     Geo g, const uint8_t *__restrict__ coded, MixArgs a, uint8_t *__restrict__ out,
     int *__restrict__ status_code, const unsigned long long *__restrict__ status_payload)
@@ -306,7 +385,7 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_decode(
     if (*status_code != 0) return;  // uniform: written by an earlier kernel
     const uint32_t lane = blockIdx.x * blockDim.x + threadIdx.x;
     if (lane >= g.lanes) return;
-    const MixSlots slots(mix_lds, a.k);
+    const MixSlots slots(mix_lds, kK > 0 ? (uint32_t)kK : a.k, kK == 0);
     const LaneShape sh = lane_shape(g, lane);
     const uint32_t m_bits = g.prec_bits;
     const uint32_t spread = (1u << m_bits) - 256u, mask = (1u << m_bits) - 1u;
@@ -333,8 +412,9 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_decode(
     ByteRun run;
     run.begin(0);
     uint32_t p_next = 0xFFFFFFFFu;  // the pixel that would continue the current run of bytes
-    const bool ahead = mix_can_run_ahead(a);
-    MixAhead pre;
+    const bool ahead = kK > 0 || mix_can_run_ahead(a);
+    MixAhead<kK> pre;
+    MixRegs<kK> regs;
     uint32_t im_now = 0xFFFFFFFFu;
     int a_gr = 0, a_br = 0, a_bg = 0;
     if (ahead && sh.npx != 0u) mix_fetch_ahead(a, lane_pixel(g, sh, 0u), pre);
@@ -351,7 +431,7 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_decode(
             a_gr = a.coef[3 * im]; a_br = a.coef[3 * im + 1]; a_bg = a.coef[3 * im + 2];
         }
         if (ahead) {
-            ok = mix_store_ahead(pre, slots) && ok;
+            ok = mix_store_ahead(pre, slots, regs) && ok;
             if (t + 1u < sh.npx) mix_fetch_ahead(a, lane_pixel(g, sh, t + 1u), pre);
         } else {
             ok = mix_load_pixel(a, p, slots) && ok;
@@ -359,14 +439,21 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_decode(
         int x_r = 0, x_g = 0, x_b = 0;
 #pragma unroll 1
         for (int ch = 0; ch < 3; ++ch) {
-            mix_load_channel(slots, ch, x_r, x_g, a_gr, a_br, a_bg, tab);
+            if constexpr (kK > 0)
+                mix_load_channel(slots, regs, ch, x_r, x_g, a_gr, a_br, a_bg, tab);
+            else
+                mix_load_channel(slots, ch, x_r, x_g, a_gr, a_br, a_bg, tab);
             const uint32_t slot = S & mask;
             // the symbol is in lo .. lo + 2 * step - 1, and c_hi = C(lo + 2 * step)
             int lo = 0;
             uint32_t c_lo = 0u, c_hi = 1u << m_bits;
 #pragma unroll 1
             for (int step = 128; step >= 1; step >>= 1) {
-                const uint32_t cv = mix_cum_inner(lo + step, slots, spread, tab);
+                uint32_t cv;
+                if constexpr (kK > 0)
+                    cv = mix_cum_inner(lo + step, regs, spread, tab);
+                else
+                    cv = mix_cum_inner(lo + step, slots, spread, tab);
                 const bool ge = cv <= slot;
                 lo = ge ? lo + step : lo;
                 c_lo = ge ? cv : c_lo;

@@ -27,6 +27,14 @@ CASES = [
     ("wild-k9-flat-M10", lambda: synth_mix.from_base(
         synth.make_random_case(2, 37, 12, 10, 10, 0, 360, wild=True), 9, 2)),
     ("many-lanes-k2", lambda: synth_mix.from_base(synth.make_random_case(9, 70, 16, 16, 14, 0, 8), 2, 9)),
+    # K = 10 runs in kernels of its own (components in registers): the same corners again
+    ("wild-k10-ragged-tiles", lambda: synth_mix.from_base(
+        synth.make_random_case(13, 5, 37, 41, 13, 1, 8, 16, wild=True), 10, 13)),
+    ("wild-k10-flat-M10", lambda: synth_mix.from_base(
+        synth.make_random_case(12, 37, 12, 10, 10, 0, 360, wild=True), 10, 12)),
+    ("cfg1-k10-long-lanes", lambda: synth_mix.make_mix_workload(1, 16 * 2 + 5, 10)),
+    ("cfg4-k10-M16", lambda: synth_mix.make_mix_workload(4, 6, 10, h=32, w=32, prec_bits=16, lanes_per_image=16)),
+    ("many-lanes-k10", lambda: synth_mix.from_base(synth.make_random_case(19, 70, 16, 16, 14, 0, 8), 10, 19)),
 ]
 
 
@@ -47,6 +55,27 @@ def test_container_and_image_identical_to_oracle(name, make):
     assert np.array_equal(d.decoded_numpy(), wl.img)
 
 
+def test_ten_components_in_arrays_off_the_dword_grid_take_the_general_kernels():
+    wl = synth_mix.make_mix_workload(2, 4, 10)
+    g = orc.make_geom(*wl.geom)
+    rc, want = mx.encode(g, wl.num_comp, wl.img, wl.mu, wl.log_scale, wl.weight, wl.chan_coef)
+    assert rc == mx.OK
+    d = DeviceMix(wl)
+
+    def shifted(t):  # the same values at an address that is 2 but not 4 bytes aligned
+        buf = torch.empty(t.numel() + 1, dtype=t.dtype, device=t.device)
+        buf[1:] = t.reshape(-1)
+        assert buf[1:].data_ptr() % 4 == 2
+        return buf[1:].reshape(t.shape)
+
+    d.mu, d.log_scale, d.weight = shifted(d.mu), shifted(d.log_scale), shifted(d.weight)
+    rc, nbytes = d.encode()
+    got = d.coded_numpy()
+    assert nbytes == want.size and np.array_equal(got, want), first_difference(got, want)
+    assert d.decode() == pb.PILC_OK
+    assert np.array_equal(d.decoded_numpy(), wl.img)
+
+
 def test_one_component_matches_the_single_law_path():
     base = synth.make_workload(2, 6)
     wl = synth_mix.from_base(base, 1, 1)
@@ -59,8 +88,9 @@ def test_one_component_matches_the_single_law_path():
     assert np.array_equal(mix[64:], single[64:]) and np.array_equal(mix[8:44], single[8:44])
 
 
-def test_bad_weights_and_component_counts_are_rejected():
-    wl = synth_mix.make_mix_workload(0, 4, 3)
+@pytest.mark.parametrize("k", [3, 10])
+def test_bad_weights_and_component_counts_are_rejected(k):
+    wl = synth_mix.make_mix_workload(0, 4, k)
     d = DeviceMix(wl)
     rc, _ = d.encode()
     good = d.nbytes
