@@ -39,12 +39,13 @@ struct MixArgs {
 struct MixSlots {
     uint2 *pairs;    // this thread's column of the pairs
     uint32_t *base;  // this thread's column of the raw parameters
-    uint32_t k, stride, raw_ls, raw_w;
+    uint32_t k, stride, raw_ls, raw_w, image_block;
     static constexpr uint32_t raw_mu = 0u;
     __device__ __forceinline__ MixSlots(uint32_t *lds, uint32_t k_, bool with_pairs = true)
         : pairs(reinterpret_cast<uint2 *>(lds) + threadIdx.x),
           base(lds + (with_pairs ? 2u * k_ * blockDim.x : 0u) + threadIdx.x), k(k_), stride(blockDim.x),
-          raw_ls((3u * k_ + 1u) / 2u), raw_w(2u * ((3u * k_ + 1u) / 2u))
+          raw_ls((3u * k_ + 1u) / 2u), raw_w(2u * ((3u * k_ + 1u) / 2u)),
+          image_block(2u * ((3u * k_ + 1u) / 2u) + (with_pairs ? (k_ + 1u) / 2u : 0u))
     {
     }
     __device__ __forceinline__ uint32_t &dword(uint32_t i) const { return base[i * stride]; }
@@ -63,11 +64,52 @@ struct MixSlots {
     }
 };
 
+constexpr uint32_t kMixImageBlock = 32;  // bytes of the image a thread of the encoder keeps in LDS
+
 // with_pairs false: the kernels built for one K, which keep the pairs and the weights in registers.
-static inline size_t mix_lds_bytes(uint32_t k, bool with_pairs = true)
+// image_block: the encoder's block of image bytes (the last dwords of a thread's column).
+static inline size_t mix_lds_bytes(uint32_t k, bool with_pairs, bool image_block)
 {
-    return (size_t)kMixThreads * 4u * ((with_pairs ? 2u * k + (k + 1u) / 2u : 0u) + 2u * ((3u * k + 1u) / 2u));
+    return (size_t)kMixThreads * 4u *
+           ((with_pairs ? 2u * k + (k + 1u) / 2u : 0u) + 2u * ((3u * k + 1u) / 2u) +
+            (image_block ? kMixImageBlock / 4u : 0u));
 }
+
+// The encoder's image bytes: the aligned 32-byte block around the byte last asked for sits in the
+// thread's LDS column, so a 128-byte line of the image is asked for four times rather than once
+// per pixel (which a byte load per subpixel comes to, with the lines long gone from the L2 when the
+// lane reaches its next pixel).  A block that holds a byte of the image lies inside the image's
+// pages even where it reaches past its ends.
+struct PixelBytes {
+    uint32_t *col;
+    uint32_t stride;
+    uint32_t tag;  // low address bits of the block held (the image spans less than 4 GiB), 1: none
+    __device__ __forceinline__ PixelBytes(const MixSlots &s)
+        : col(s.base + s.image_block * s.stride), stride(s.stride), tag(1u)
+    {
+    }
+    __device__ __forceinline__ uint32_t byte(const uint8_t *a)
+    {
+        const uintptr_t at = reinterpret_cast<uintptr_t>(a);
+        const uint32_t blk = (uint32_t)at & ~(kMixImageBlock - 1u);
+        if (blk != tag) {
+            const uint4 *src = reinterpret_cast<const uint4 *>(at & ~(uintptr_t)(kMixImageBlock - 1u));
+            const uint4 v0 = src[0], v1 = src[1];
+            col[0] = v0.x; col[stride] = v0.y; col[2u * stride] = v0.z; col[3u * stride] = v0.w;
+            col[4u * stride] = v1.x; col[5u * stride] = v1.y; col[6u * stride] = v1.z; col[7u * stride] = v1.w;
+            tag = blk;
+        }
+        const uint32_t o = (uint32_t)at & (kMixImageBlock - 1u);
+        return (col[(o >> 2) * stride] >> (8u * (o & 3u))) & 0xFFu;
+    }
+    // R | G << 8 | B << 16 of pixel q, highest address first: the encoder walks its lane backwards
+    __device__ __forceinline__ uint32_t pixel(const uint8_t *img, uint32_t q)
+    {
+        const uint8_t *a = img + 3 * (size_t)q;
+        const uint32_t b = byte(a + 2), g = byte(a + 1), r = byte(a);
+        return r | (g << 8) | (b << 16);
+    }
+};
 
 // The pixel's parameters into the slots; false if its weights do not sum to 2^15.
 __device__ __forceinline__ bool mix_load_pixel(const MixArgs &a, uint32_t p, const MixSlots &s)
@@ -279,17 +321,10 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_encode(
     const bool ahead = kK > 0 || mix_can_run_ahead(a);
     MixAhead<kK> pre;
     MixRegs<kK> regs;
-    uint32_t pre_x = 0, im_now = 0xFFFFFFFFu;
+    PixelBytes bytes(slots);
+    uint32_t im_now = 0xFFFFFFFFu;
     int a_gr = 0, a_br = 0, a_bg = 0;
-    auto fetch_pixel_bytes = [&](uint32_t q) -> uint32_t {
-        const uint8_t *b = img + 3 * (size_t)q;
-        return (uint32_t)b[0] | ((uint32_t)b[1] << 8) | ((uint32_t)b[2] << 16);
-    };
-    if (ahead && sh.npx != 0u) {
-        const uint32_t q = lane_pixel(g, sh, sh.npx - 1u);
-        mix_fetch_ahead(a, q, pre);
-        pre_x = fetch_pixel_bytes(q);
-    }
+    if (ahead && sh.npx != 0u) mix_fetch_ahead(a, lane_pixel(g, sh, sh.npx - 1u), pre);
     for (uint32_t t = sh.npx; t-- > 0u;) {
         const uint32_t p = lane_pixel(g, sh, t);
         const uint32_t im = p / g.hw;
@@ -297,19 +332,13 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_encode(
             im_now = im;
             a_gr = a.coef[3 * im]; a_br = a.coef[3 * im + 1]; a_bg = a.coef[3 * im + 2];
         }
-        uint32_t xb;
         if (ahead) {
             ok = mix_store_ahead(pre, slots, regs) && ok;
-            xb = pre_x;
-            if (t != 0u) {
-                const uint32_t q = lane_pixel(g, sh, t - 1u);
-                mix_fetch_ahead(a, q, pre);
-                pre_x = fetch_pixel_bytes(q);
-            }
+            if (t != 0u) mix_fetch_ahead(a, lane_pixel(g, sh, t - 1u), pre);
         } else {
             ok = mix_load_pixel(a, p, slots) && ok;
-            xb = fetch_pixel_bytes(p);
         }
+        const uint32_t xb = bytes.pixel(img, p);
         const int x[3] = {(int)(xb & 0xFFu), (int)((xb >> 8) & 0xFFu), (int)(xb >> 16)};
 #pragma unroll 1
         for (int ch = 2; ch >= 0; --ch) {
