@@ -1022,7 +1022,7 @@ int pilc_mix_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_mi
     const MixArgs args = {params->mu, params->log_scale, params->weight, params->chan_coef,
                           params->num_comp};
     const int built = mix_built_for(params);
-    const size_t lds = mix_lds_bytes(params->num_comp, built == 0, true);
+    const size_t lds = mix_lds_bytes(params->num_comp, built == 0);
     auto kern = built == 10 ? k_mix_encode<10> : k_mix_encode<0>;
     if ((rc = allow_large_lds(reinterpret_cast<const void *>(kern))) != PILC_OK) return rc;
 
@@ -1074,7 +1074,7 @@ int pilc_mix_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t code
     const MixArgs args = {params->mu, params->log_scale, params->weight, params->chan_coef,
                           params->num_comp};
     const int built = mix_built_for(params);
-    const size_t lds = mix_lds_bytes(params->num_comp, built == 0, false);
+    const size_t lds = mix_lds_bytes(params->num_comp, built == 0);
     auto kern = built == 10 ? k_mix_decode<10> : k_mix_decode<0>;
     if ((rc = allow_large_lds(reinterpret_cast<const void *>(kern))) != PILC_OK) return rc;
 

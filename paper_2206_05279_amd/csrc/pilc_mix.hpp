@@ -36,16 +36,20 @@ struct MixArgs {
 // 8-byte elements, then per thread the pixel's raw means (3 K halfwords), log-scales (3 K) and
 // weights (K), each rounded up to dwords, as [dword][thread].  The kernels built for one K have
 // neither the pairs nor the weights there.
+constexpr uint32_t kMixImageBlock = 32;   // bytes of the image a thread of the encoder keeps in LDS
+constexpr uint32_t kMixWeightBlock = 64;  // bytes of the weights a thread keeps there (kernels built for one K)
+
 struct MixSlots {
     uint2 *pairs;    // this thread's column of the pairs
     uint32_t *base;  // this thread's column of the raw parameters
-    uint32_t k, stride, raw_ls, raw_w, image_block;
+    uint32_t k, stride, raw_ls, raw_w, image_block, weight_block;
     static constexpr uint32_t raw_mu = 0u;
     __device__ __forceinline__ MixSlots(uint32_t *lds, uint32_t k_, bool with_pairs = true)
         : pairs(reinterpret_cast<uint2 *>(lds) + threadIdx.x),
           base(lds + (with_pairs ? 2u * k_ * blockDim.x : 0u) + threadIdx.x), k(k_), stride(blockDim.x),
           raw_ls((3u * k_ + 1u) / 2u), raw_w(2u * ((3u * k_ + 1u) / 2u)),
-          image_block(2u * ((3u * k_ + 1u) / 2u) + (with_pairs ? (k_ + 1u) / 2u : 0u))
+          image_block(2u * ((3u * k_ + 1u) / 2u) + (with_pairs ? (k_ + 1u) / 2u : 0u)),
+          weight_block(image_block + kMixImageBlock / 4u)
     {
     }
     __device__ __forceinline__ uint32_t &dword(uint32_t i) const { return base[i * stride]; }
@@ -64,43 +68,55 @@ struct MixSlots {
     }
 };
 
-constexpr uint32_t kMixImageBlock = 32;  // bytes of the image a thread of the encoder keeps in LDS
-
 // with_pairs false: the kernels built for one K, which keep the pairs and the weights in registers.
-// image_block: the encoder's block of image bytes (the last dwords of a thread's column).
-static inline size_t mix_lds_bytes(uint32_t k, bool with_pairs, bool image_block)
+// The blocks of image bytes and of weights are the encoder's (the decoder's columns have them too,
+// unused: one layout for both).
+static inline size_t mix_lds_bytes(uint32_t k, bool with_pairs)
 {
     return (size_t)kMixThreads * 4u *
-           ((with_pairs ? 2u * k + (k + 1u) / 2u : 0u) + 2u * ((3u * k + 1u) / 2u) +
-            (image_block ? kMixImageBlock / 4u : 0u));
+           ((with_pairs ? 2u * k + (k + 1u) / 2u : kMixWeightBlock / 4u) + 2u * ((3u * k + 1u) / 2u) +
+            kMixImageBlock / 4u);
 }
 
-// The encoder's image bytes: the aligned 32-byte block around the byte last asked for sits in the
-// thread's LDS column, so a 128-byte line of the image is asked for four times rather than once
-// per pixel (which a byte load per subpixel comes to, with the lines long gone from the L2 when the
-// lane reaches its next pixel).  A block that holds a byte of the image lies inside the image's
-// pages even where it reaches past its ends.
-struct PixelBytes {
+// An aligned block of kBytes of global memory in a thread's LDS column ([dword][thread]), loaded
+// when an address outside it is asked for.  With the lines long gone from the L2 when a lane
+// reaches its next pixel, every separate load costs a fetch of its whole 128-byte line; through a
+// block a line is asked for 128 / kBytes times instead of once per pixel.  A block that holds a
+// byte of an array lies inside the array's pages even where it reaches past its ends.
+template <uint32_t kBytes> struct LdsBlock {
     uint32_t *col;
     uint32_t stride;
-    uint32_t tag;  // low address bits of the block held (the image spans less than 4 GiB), 1: none
-    __device__ __forceinline__ PixelBytes(const MixSlots &s)
-        : col(s.base + s.image_block * s.stride), stride(s.stride), tag(1u)
+    uintptr_t tag;  // address of the block held; 1: none
+    __device__ __forceinline__ LdsBlock(uint32_t *column, uint32_t stride_) : col(column), stride(stride_), tag(1u) {}
+    __device__ __forceinline__ uint32_t dword(uintptr_t at)  // the aligned dword that holds byte `at`
     {
+        const uintptr_t blk = at & ~(uintptr_t)(kBytes - 1u);
+        if (blk != tag) {
+            const uint4 *src = reinterpret_cast<const uint4 *>(blk);
+            uint4 v[kBytes / 16u];
+#pragma unroll
+            for (uint32_t i = 0; i < kBytes / 16u; ++i) v[i] = src[i];
+#pragma unroll
+            for (uint32_t i = 0; i < kBytes / 16u; ++i) {
+                col[(4u * i) * stride] = v[i].x;
+                col[(4u * i + 1u) * stride] = v[i].y;
+                col[(4u * i + 2u) * stride] = v[i].z;
+                col[(4u * i + 3u) * stride] = v[i].w;
+            }
+            tag = blk;
+        }
+        return col[(((uint32_t)at & (kBytes - 1u)) >> 2) * stride];
     }
+};
+
+// The encoder's image bytes.
+struct PixelBytes {
+    LdsBlock<kMixImageBlock> block;
+    __device__ __forceinline__ PixelBytes(const MixSlots &s) : block(s.base + s.image_block * s.stride, s.stride) {}
     __device__ __forceinline__ uint32_t byte(const uint8_t *a)
     {
         const uintptr_t at = reinterpret_cast<uintptr_t>(a);
-        const uint32_t blk = (uint32_t)at & ~(kMixImageBlock - 1u);
-        if (blk != tag) {
-            const uint4 *src = reinterpret_cast<const uint4 *>(at & ~(uintptr_t)(kMixImageBlock - 1u));
-            const uint4 v0 = src[0], v1 = src[1];
-            col[0] = v0.x; col[stride] = v0.y; col[2u * stride] = v0.z; col[3u * stride] = v0.w;
-            col[4u * stride] = v1.x; col[5u * stride] = v1.y; col[6u * stride] = v1.z; col[7u * stride] = v1.w;
-            tag = blk;
-        }
-        const uint32_t o = (uint32_t)at & (kMixImageBlock - 1u);
-        return (col[(o >> 2) * stride] >> (8u * (o & 3u))) & 0xFFu;
+        return (block.dword(at) >> (8u * ((uint32_t)at & 3u))) & 0xFFu;
     }
     // R | G << 8 | B << 16 of pixel q, highest address first: the encoder walks its lane backwards
     __device__ __forceinline__ uint32_t pixel(const uint8_t *img, uint32_t q)
@@ -159,7 +175,8 @@ __device__ __forceinline__ bool mix_can_run_ahead(const MixArgs &a)
                                  reinterpret_cast<uintptr_t>(a.weight)) & 3u) == 0u;
 }
 
-template <int kK>
+// kWeights false: the weights come some other way (the encoder built for one K has an LdsBlock).
+template <int kK, bool kWeights = true>
 __device__ __forceinline__ void mix_fetch_ahead(const MixArgs &a, uint32_t p, MixAhead<kK> &r)
 {
     const uint32_t k = kK > 0 ? (uint32_t)kK : a.k;
@@ -174,14 +191,34 @@ __device__ __forceinline__ void mix_fetch_ahead(const MixArgs &a, uint32_t p, Mi
 #pragma unroll
     for (int i = 0; i < MixAhead<kK>::kMu; ++i)
         if ((uint32_t)i < n3) r.l[i] = gl[i];
+    if constexpr (kWeights) {
 #pragma unroll
-    for (int i = 0; i < MixAhead<kK>::kW; ++i)
-        if ((uint32_t)i < n1) r.w[i] = gw[i];
+        for (int i = 0; i < MixAhead<kK>::kW; ++i)
+            if ((uint32_t)i < n1) r.w[i] = gw[i];
+    }
 }
 
-// The fetched pixel into the slots (and its weights into `regs` where the kernel keeps them
-// there); false if the weights do not sum to 2^15.
+// The weights of pixel p into `regs`, through the thread's block (dword-aligned array, even kK),
+// highest address first: the encoder walks its lane backwards.  False if they do not sum to 2^15.
 template <int kK>
+__device__ __forceinline__ bool mix_load_weights(const MixArgs &a, uint32_t p, LdsBlock<kMixWeightBlock> &block,
+                                                 MixRegs<kK> &regs)
+{
+    const uintptr_t at = reinterpret_cast<uintptr_t>(a.weight + (size_t)p * kK);
+    uint32_t sum = 0;
+#pragma unroll
+    for (int i = kK / 2 - 1; i >= 0; --i) {
+        const uint32_t w2 = block.dword(at + 4u * i);
+        regs.w[2 * i] = w2 & 0xFFFFu;
+        regs.w[2 * i + 1] = w2 >> 16;
+        sum += (w2 & 0xFFFFu) + (w2 >> 16);
+    }
+    return sum == (1u << 15);
+}
+
+// The fetched pixel into the slots, its weights into `regs` in the kernels built for one K; false
+// if the weights do not sum to 2^15.  kWeights as above (then true).
+template <int kK, bool kWeights = true>
 __device__ __forceinline__ bool mix_store_ahead(const MixAhead<kK> &r, const MixSlots &s, MixRegs<kK> &regs)
 {
     const uint32_t n3 = 3u * s.k / 2u, n1 = s.k / 2u;
@@ -192,6 +229,7 @@ __device__ __forceinline__ bool mix_store_ahead(const MixAhead<kK> &r, const Mix
 #pragma unroll
     for (int i = 0; i < MixAhead<kK>::kMu; ++i)
         if ((uint32_t)i < n3) s.dword(s.raw_ls + i) = r.l[i];
+    if constexpr (!kWeights) return true;
 #pragma unroll
     for (int i = 0; i < MixAhead<kK>::kW; ++i)
         if ((uint32_t)i < n1) {
@@ -322,9 +360,14 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_encode(
     MixAhead<kK> pre;
     MixRegs<kK> regs;
     PixelBytes bytes(slots);
+    LdsBlock<kMixWeightBlock> weights(slots.base + slots.weight_block * slots.stride, slots.stride);
     uint32_t im_now = 0xFFFFFFFFu;
     int a_gr = 0, a_br = 0, a_bg = 0;
-    if (ahead && sh.npx != 0u) mix_fetch_ahead(a, lane_pixel(g, sh, sh.npx - 1u), pre);
+    // built for one K: the weights reach the registers through a block in LDS, which costs a wait
+    // when the block runs out and saves most of their traffic (the decoder, bound by its
+    // arithmetic, keeps fetching them ahead with the other parameters)
+    constexpr bool kAheadW = kK == 0;
+    if (ahead && sh.npx != 0u) mix_fetch_ahead<kK, kAheadW>(a, lane_pixel(g, sh, sh.npx - 1u), pre);
     for (uint32_t t = sh.npx; t-- > 0u;) {
         const uint32_t p = lane_pixel(g, sh, t);
         const uint32_t im = p / g.hw;
@@ -333,8 +376,9 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_encode(
             a_gr = a.coef[3 * im]; a_br = a.coef[3 * im + 1]; a_bg = a.coef[3 * im + 2];
         }
         if (ahead) {
-            ok = mix_store_ahead(pre, slots, regs) && ok;
-            if (t != 0u) mix_fetch_ahead(a, lane_pixel(g, sh, t - 1u), pre);
+            ok = mix_store_ahead<kK, kAheadW>(pre, slots, regs) && ok;
+            if constexpr (!kAheadW) ok = mix_load_weights<kK>(a, p, weights, regs) && ok;
+            if (t != 0u) mix_fetch_ahead<kK, kAheadW>(a, lane_pixel(g, sh, t - 1u), pre);
         } else {
             ok = mix_load_pixel(a, p, slots) && ok;
         }
