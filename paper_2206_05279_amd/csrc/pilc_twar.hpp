@@ -117,53 +117,39 @@ __global__ __launch_bounds__(256) void k_twar_forward4(TwarK p, uint32_t groups,
     o[2] = out[2];
 }
 
-// Copies `total` dwords between contiguous memory and an LDS tile whose rows of `rd` dwords lie
-// `row_stride` bytes apart, one wavefront, element o = lane + 64 i.  Eight elements a turn: the
-// eight loads are under way together (taken one at a time, every load waits for the one before).
-template <bool kIn>
-__device__ __forceinline__ void tile_copy(uint8_t *tile, uint32_t row_stride, uint32_t rd, uint32_t total,
-                                          const uint32_t *__restrict__ src, uint32_t *__restrict__ dst,
-                                          uint32_t lane)
+// A flat copy by one wavefront: `total` >= 1 elements, element lane + 64 i, four of them a turn, so
+// that four loads are under way together (taken one at a time, every load waits for the one
+// before).  Loads past the end read the last element again instead of being skipped (a register
+// that is only sometimes written costs more in moves than the load it saves); stores past the end
+// are skipped.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <typename T>
+__device__ __forceinline__ void flat_copy(const T *__restrict__ src, T *__restrict__ dst, uint32_t total, uint32_t lane)
 {
-    uint32_t r = lane / rd, c = lane % rd;  // row and dword of element `lane`, then + 64 a turn
-    const uint32_t dc = 64u % rd, dr = 64u / rd;
-    for (uint32_t o = lane; o < total; o += 8u * 64u) {
-        uint32_t v[8], at[8];
+    for (uint32_t base = 0; base < total; base += 256u) {  // the same for the whole wavefront
+        T v[4];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            at[k] = r * row_stride + 4u * c;
-            const bool ok = o + 64u * k < total;
-            if (kIn)
-                v[k] = ok ? src[o + 64u * k] : 0u;
-            else
-                v[k] = ok ? *reinterpret_cast<const uint32_t *>(tile + at[k]) : 0u;
-            c += dc;
-            r += dr + (c >= rd ? 1u : 0u);
-            c -= c >= rd ? rd : 0u;
-        }
+        for (uint32_t k = 0; k < 4u; ++k) v[k] = src[min(base + lane + 64u * k, total - 1u)];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            if (o + 64u * k < total) {
-                if (kIn)
-                    *reinterpret_cast<uint32_t *>(tile + at[k]) = v[k];
-                else
-                    dst[o + 64u * k] = v[k];
-            }
-        }
+        for (uint32_t k = 0; k < 4u; ++k)
+            if (base + lane + 64u * k < total) dst[base + lane + 64u * k] = v[k];
     }
 }
 
 // A wavefront per group of up to 64 rows: whole images when h <= 64 (64 / h of them side by side),
 // else the bands of 64 rows of one image one after the other, the last row's red values of a band
 // kept in LDS for the first row of the next.  kTile: the group's residuals are copied to LDS
-// first and the pixels copied back at the end (rows of w * 3 bytes at a stride with an odd number
-// of dwords), so that global memory only sees whole, coalesced rows; without it every thread reads
-// and writes its row in place in global memory.
+// first and the pixels copied back at the end, so that global memory only sees whole, coalesced
+// rows; without it every thread reads and writes its row in place in global memory.  The tile is
+// the group exactly as it lies in memory (its rows are contiguous there), copied as a flat run of
+// elements of type T (16 bytes, 4 bytes or single bytes: what the sizes and addresses allow); the
+// skew between rows keeps the threads' accesses on different banks without any padding.
 constexpr int kTwarWaves = 4;
 
-template <bool kTile>
+template <bool kTile, typename T>
 __global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint32_t n, uint32_t h,
-                                                                  uint32_t w, uint32_t row_stride,
+                                                                  uint32_t w, uint32_t last_bytes,
                                                                   const uint8_t *__restrict__ res,
                                                                   uint8_t *__restrict__ img)
 {
@@ -174,13 +160,11 @@ __global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint3
     const uint32_t g = blockIdx.x * kTwarWaves + wave;
     if (g >= groups) return;
     const uint32_t bands = h <= 64u ? 1u : (h + 63u) / 64u;
-    // LDS of this wavefront: [w bytes: red values of the row above a band][tile]
-    const uint32_t last_bytes = (w + 3u) & ~3u;
+    // LDS of this wavefront: [last_bytes >= w, a multiple of 16: red values of the row above a band][tile]
+    const uint32_t row_stride = 3u * w;
     uint8_t *lastrow = twar_lds + (size_t)wave * (last_bytes + (kTile ? 64u * row_stride : 0u));
     uint8_t *tile = lastrow + last_bytes;
     const size_t row_bytes = (size_t)w * 3u;
-    // rows of whole dwords in 4-byte aligned arrays are copied a dword at a time
-    const bool dwords = (row_bytes & 3u) == 0u && (((uintptr_t)res | (uintptr_t)img) & 3u) == 0u;
 
     for (uint32_t band = 0; band < bands; ++band) {
         // this thread's row
@@ -199,20 +183,10 @@ __global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint3
         const uint32_t rows_here = h <= 64u ? min(per, n - g * per) * h : min(64u, h - band * 64u);
         if (kTile) {  // the group's rows are contiguous in memory: copy them row by row
             const size_t first = h <= 64u ? (size_t)g * per * h * row_bytes : ((size_t)g * h + band * 64u) * row_bytes;
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            if (dwords) {
-                const uint32_t rd = (uint32_t)row_bytes >> 2;
-                tile_copy<true>(tile, row_stride, rd, rows_here * rd, reinterpret_cast<const uint32_t *>(res + first),
-                                nullptr, lane);
-            } else {
-                for (uint32_t r = 0; r < rows_here; ++r)
-                    for (uint32_t c = lane; c < row_bytes; c += 64u)
-                        tile[r * row_stride + c] = res[first + r * row_bytes + c];
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            wave_lds_sync();
+            flat_copy(reinterpret_cast<const T *>(res + first), reinterpret_cast<T *>(tile),
+                      rows_here * row_stride / (uint32_t)sizeof(T), lane);
+            wave_lds_sync();
         }
         const bool top = u == 0u;                // the row above is padding
         const bool from_lds = lane == 0u && !top;  // the row above belongs to the previous band
@@ -221,7 +195,8 @@ __global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint3
         const uint32_t skew = h <= 64u ? lane % h : lane;
         const uint32_t steps = w + min(h, 64u) - 1u;
         for (uint32_t d = 0; d < steps; ++d) {
-            int up = __shfl_up(rl, 1, 64), upleft = __shfl_up(rll, 1, 64);
+            int up = __builtin_amdgcn_update_dpp(0, rl, 0x138 /* wave_shr:1 */, 0xF, 0xF, true);
+            int upleft = __builtin_amdgcn_update_dpp(0, rll, 0x138, 0xF, 0xF, true);
             const int v = (int)d - (int)skew;
             const bool on = have && v >= 0 && v < (int)w;
             if (top) {
@@ -270,22 +245,11 @@ __global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint3
         }
         if (kTile) {
             const size_t first = h <= 64u ? (size_t)g * per * h * row_bytes : ((size_t)g * h + band * 64u) * row_bytes;
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            if (dwords) {
-                const uint32_t rd = (uint32_t)row_bytes >> 2;
-                tile_copy<false>(tile, row_stride, rd, rows_here * rd, nullptr,
-                                 reinterpret_cast<uint32_t *>(img + first), lane);
-            } else {
-                for (uint32_t r = 0; r < rows_here; ++r)
-                    for (uint32_t c = lane; c < row_bytes; c += 64u)
-                        img[first + r * row_bytes + c] = tile[r * row_stride + c];
-            }
+            wave_lds_sync();
+            flat_copy(reinterpret_cast<const T *>(tile), reinterpret_cast<T *>(img + first),
+                      rows_here * row_stride / (uint32_t)sizeof(T), lane);
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        wave_lds_sync();
     }
 }
 
@@ -603,11 +567,15 @@ int pilc_twar_inverse(uint32_t n, uint32_t h, uint32_t w, const uint8_t *res_dev
     const uint32_t per = h <= 64 ? 64 / h : 1;
     const uint32_t groups = (n + per - 1) / per;
     const uint32_t blocks = (groups + kTwarWaves - 1) / kTwarWaves;
-    const uint32_t last_bytes = (w + 3u) & ~3u;
-    // a row stride with an odd number of dwords keeps the 64 rows on distinct LDS banks
-    uint32_t row_stride = (w * 3u + 3u) & ~3u;
-    if (((row_stride >> 2) & 1u) == 0u) row_stride += 4u;
-    const size_t tile_lds = (size_t)kTwarWaves * (last_bytes + 64u * (size_t)row_stride);
+    const uint32_t last_bytes = (w + 15u) & ~15u;
+    const size_t tile_lds = (size_t)kTwarWaves * (last_bytes + 64u * (size_t)w * 3u);
+    // the element of the tile copies: every group (whole images, or a band of 64 rows) must start
+    // and end on a multiple of it
+    const uint32_t row_bytes = w * 3u;
+    const uintptr_t both = (uintptr_t)img_dev | (uintptr_t)res_dev;
+    const bool whole_images = h <= 64;
+    const uint32_t unit_bytes = whole_images ? h * row_bytes : row_bytes;
+    const int elem = unit_bytes % 16u == 0u && (both & 15) == 0 ? 16 : unit_bytes % 4u == 0u && (both & 3) == 0 ? 4 : 1;
     Timer timer(stream);
     const bool tall = h > 64 && w % 16 == 0 && w <= 16384 && ((((uintptr_t)img_dev) | ((uintptr_t)res_dev)) & 15) == 0;
     // few tall images: bands of up to 576 rows in workgroups of their own (two bands of 540 rows
@@ -656,10 +624,15 @@ int pilc_twar_inverse(uint32_t n, uint32_t h, uint32_t w, const uint8_t *res_dev
         if ((rc = allow_large_lds(reinterpret_cast<const void *>(k_twar_inverse_tall<false>))) != PILC_OK) return rc;
         k_twar_inverse_tall<false><<<n, nt, lds, stream>>>(k, h, w, rounds, TallBands{}, res_dev, img_dev);
     } else if (tile_lds <= 64 * 1024) {
-        k_twar_inverse<true><<<blocks, 64 * kTwarWaves, tile_lds, stream>>>(k, n, h, w, row_stride, res_dev, img_dev);
+        if (elem == 16)
+            k_twar_inverse<true, u32x4><<<blocks, 64 * kTwarWaves, tile_lds, stream>>>(k, n, h, w, last_bytes, res_dev, img_dev);
+        else if (elem == 4)
+            k_twar_inverse<true, uint32_t><<<blocks, 64 * kTwarWaves, tile_lds, stream>>>(k, n, h, w, last_bytes, res_dev, img_dev);
+        else
+            k_twar_inverse<true, uint8_t><<<blocks, 64 * kTwarWaves, tile_lds, stream>>>(k, n, h, w, last_bytes, res_dev, img_dev);
     } else {
-        k_twar_inverse<false><<<blocks, 64 * kTwarWaves, (size_t)kTwarWaves * last_bytes, stream>>>(
-            k, n, h, w, row_stride, res_dev, img_dev);
+        k_twar_inverse<false, uint8_t><<<blocks, 64 * kTwarWaves, (size_t)kTwarWaves * last_bytes, stream>>>(
+            k, n, h, w, last_bytes, res_dev, img_dev);
     }
     timer.mark("k_twar_inverse");
     HIP_TRY(hipGetLastError());
