@@ -25,7 +25,10 @@ SHAPES = [(1, 1, 1), (3, 32, 32), (5, 7, 9), (2, 64, 64), (7, 16, 16), (2, 33, 5
           (256, 800, 16),
           # more groups of small images: eight images a group, rows of 27 dwords, an odd number of
           # groups, 17-row images (13 idle threads), many groups with a single-image group at the end
-          (9, 8, 8), (40, 32, 36), (11, 64, 64), (100, 17, 16), (24577, 32, 32)]
+          (9, 8, 8), (40, 32, 36), (11, 64, 64), (100, 17, 16), (24577, 32, 32),
+          # tiles copied a byte, 4 bytes or 16 bytes at a time (image sizes 105, 36 and 3960 bytes,
+          # the last with 33-row images), each with many groups and a short last one
+          (4001, 5, 7), (7001, 3, 4), (1300, 33, 40)]
 
 
 def models(rng):
