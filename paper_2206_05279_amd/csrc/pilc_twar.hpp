@@ -28,6 +28,16 @@ __device__ __forceinline__ int twar_predict(const TwarK &p, int ch, int a, int b
     return min(max(acc >> 14, 0), 255);  // arithmetic shift: floor
 }
 
+// (a + b) mod 256 for a pixel value: one instruction that adds and keeps the low byte.
+__device__ __forceinline__ int add_low_byte(int a, int b)
+{
+    int r;
+    asm("v_add_u32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:DWORD"
+        : "=v"(r)
+        : "v"(a), "v"(b));
+    return r;
+}
+
 // One thread per pixel.  A workgroup takes 256 / w whole rows (or one row, in steps of 256
 // pixels, when w > 256); neighbouring threads read neighbouring bytes and the row above comes from
 // the caches.
@@ -188,25 +198,26 @@ __global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint3
                       rows_here * row_stride / (uint32_t)sizeof(T), lane);
             wave_lds_sync();
         }
-        const bool top = u == 0u;                // the row above is padding
+        const bool top = u == 0u;                // the row above is padding: its two weights are zero here
+        const int w_upleft = top ? 0 : p.w[0][0], w_up = top ? 0 : p.w[0][1];
+        // the rounding biases in vector registers of their own: as scalar operands they would be
+        // copied into one at every use (a multiply-add takes one scalar operand, and has a weight)
+        int bias_r = p.bias[0] + 8192, bias_g = p.bias[1] + 8192, bias_b = p.bias[2] + 8192;
+        asm volatile("" : "+v"(bias_r), "+v"(bias_g), "+v"(bias_b));
+        // likewise the weights of the multiply-adds that are written out below
+        int w_g0 = p.w[1][0], w_g1 = p.w[1][1], w_b0 = p.w[2][0], w_b1 = p.w[2][1];
+        asm volatile("" : "+v"(w_g0), "+v"(w_g1), "+v"(w_b0), "+v"(w_b1));
         const bool from_lds = lane == 0u && !top;  // the row above belongs to the previous band
-        int rl = 0, rll = 0, gl = 0, bl = 0;
+        int rl = 0, gl = 0, bl = 0;
+        int above = 0;  // the red value above the pixel decoded last: above-left of the next one
         // row k of an image (or band) runs k positions behind row 0: w + rows - 1 steps in all
         const uint32_t skew = h <= 64u ? lane % h : lane;
         const uint32_t steps = w + min(h, 64u) - 1u;
         for (uint32_t d = 0; d < steps; ++d) {
             int up = __builtin_amdgcn_update_dpp(0, rl, 0x138 /* wave_shr:1 */, 0xF, 0xF, true);
-            int upleft = __builtin_amdgcn_update_dpp(0, rll, 0x138, 0xF, 0xF, true);
             const int v = (int)d - (int)skew;
             const bool on = have && v >= 0 && v < (int)w;
-            if (top) {
-                up = 0;
-                upleft = 0;
-            }
-            if (from_lds && on) {
-                up = lastrow[v];
-                upleft = v > 0 ? lastrow[v - 1] : 0;
-            }
+            if (from_lds && on) up = lastrow[v];
             if (on) {
                 int r0, r1, r2;
                 if (kTile) {
@@ -220,9 +231,16 @@ __global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint3
                     r1 = s[1];
                     r2 = s[2];
                 }
-                const int xr = (r0 + twar_predict(p, 0, upleft, up, rl)) & 255;
-                const int xg = (r1 + twar_predict(p, 1, gl, rl, xr)) & 255;
-                const int xb = (r2 + twar_predict(p, 2, bl, gl, xg)) & 255;
+                // Three multiply-adds each.  What only needs the pixel to the left comes first, so
+                // that each new value can take the place of the one it replaces; the operand that
+                // arrives last (the value just decoded) goes into the last multiply-add.
+                auto clamp8 = [](int acc) { return min(max(acc >> 14, 0), 255); };
+                const int tg = mad_i24(w_g1, rl, mad_i24(w_g0, gl, bias_g));
+                const int tb = mad_i24(w_b1, gl, mad_i24(w_b0, bl, bias_b));
+                const int tr = mad_i24(w_up, up, mad_i24(w_upleft, above, bias_r));
+                const int xr = add_low_byte(r0, clamp8(__mul24(p.w[0][2], rl) + tr));
+                const int xg = add_low_byte(r1, clamp8(__mul24(p.w[1][2], xr) + tg));
+                const int xb = add_low_byte(r2, clamp8(__mul24(p.w[2][2], xg) + tb));
                 if (kTile) {
                     uint8_t *o = tile + lane * row_stride + 3u * v;
                     o[0] = (uint8_t)xr;
@@ -237,7 +255,7 @@ __global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint3
                 // the last row of a band leaves its red values for the next band; it runs 63
                 // positions behind the first row's reads of the same buffer
                 if (bands > 1u && lane == 63u) lastrow[v] = (uint8_t)xr;
-                rll = rl;
+                above = up;
                 rl = xr;
                 gl = xg;
                 bl = xb;
