@@ -349,6 +349,12 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
     const uint8_t *above_ptr = wave != 0u ? hand + (wave - 1u) * 64u : carry;
     const uint32_t above_mask = wave != 0u ? 63u : (kBands ? 31u : 0xFFFFFFFFu);
     const bool first_lane = lane == 0u;
+    // the rounding biases and the weights of the multiply-adds written out below in vector
+    // registers of their own (as scalar operands they would be copied into one at every use)
+    int bias_r = p.bias[0] + 8192, bias_g = p.bias[1] + 8192, bias_b = p.bias[2] + 8192;
+    int w_r0 = p.w[0][0], w_r1 = p.w[0][1], w_g0 = p.w[1][0], w_g1 = p.w[1][1], w_b0 = p.w[2][0], w_b1 = p.w[2][1];
+    asm volatile("" : "+v"(bias_r), "+v"(bias_g), "+v"(bias_b));
+    asm volatile("" : "+v"(w_r0), "+v"(w_r1), "+v"(w_g0), "+v"(w_g1), "+v"(w_b0), "+v"(w_b1));
 
     for (uint32_t round = 0; round < rounds; ++round) {
         const uint32_t u = kBands ? band * tb.band_rows + threadIdx.x : round * nt + threadIdx.x;
@@ -368,7 +374,8 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
         uint4 above_ahead = make_uint4(0u, 0u, 0u, 0u);
         uint32_t above_done = 0u;  // chunks of the row above known to be final
 
-        int rl = 0, rll = 0, gl = 0, bl = 0, first_prev = 0;
+        int rl = 0, gl = 0, bl = 0;
+        int prev_up = 0;  // the red value above the pixel decoded last: above-left of the next one
         uint32_t ptr = 0;             // ring offset of the pixel about to be decoded
         // the chunk index before that of column -kTallLead - lane (the first chunk turn moves on to
         // it), and that index mod 3
@@ -455,17 +462,22 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
                 const bool on = have && (uint32_t)v < w;
                 const uint32_t col = on ? (uint32_t)v : 0u;
                 int up = __builtin_amdgcn_update_dpp(0, rl, 0x138 /* wave_shr:1 */, 0xF, 0xF, true);
-                int upleft = __builtin_amdgcn_update_dpp(0, rll, 0x138, 0xF, 0xF, true);
                 // the first thread of a wavefront: the row above belongs to another wavefront, to the
                 // round or band before, or is padding
                 const int above = has_above ? (int)above_ptr[col & above_mask] : 0;
                 up = first_lane ? above : up;
-                upleft = first_lane ? first_prev : upleft;
-                first_prev = first_lane && on ? above : first_prev;
+                const int upleft = prev_up;
+                prev_up = on ? up : prev_up;
                 uint8_t *q = my + ptr;
-                const int xr = ((int)q[0] + twar_predict(p, 0, upleft, up, rl)) & 255;
-                const int xg = ((int)q[1] + twar_predict(p, 1, gl, rl, xr)) & 255;
-                const int xb = ((int)q[2] + twar_predict(p, 2, bl, gl, xg)) & 255;
+                // three multiply-adds each; what only needs the pixel to the left comes first, the
+                // operand that arrives last (the value just decoded) goes into the last of them
+                auto clamp8 = [](int acc) { return min(max(acc >> 14, 0), 255); };
+                const int tg = mad_i24(w_g1, rl, mad_i24(w_g0, gl, bias_g));
+                const int tb = mad_i24(w_b1, gl, mad_i24(w_b0, bl, bias_b));
+                const int tr = mad_i24(w_r1, up, mad_i24(w_r0, upleft, bias_r));
+                const int xr = add_low_byte((int)q[0], clamp8(__mul24(p.w[0][2], rl) + tr));
+                const int xg = add_low_byte((int)q[1], clamp8(__mul24(p.w[1][2], xr) + tg));
+                const int xb = add_low_byte((int)q[2], clamp8(__mul24(p.w[2][2], xg) + tb));
                 if (on) {
                     q[0] = (uint8_t)xr;
                     q[1] = (uint8_t)xg;
@@ -475,7 +487,6 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
                 if (on && keeps_row) carry[col] = (uint8_t)xr;
                 const uint32_t nptr = ptr + 3u == (uint32_t)kTallRing ? 0u : ptr + 3u;
                 ptr = on ? nptr : ptr;
-                rll = on ? rl : rll;
                 rl = on ? xr : rl;
                 gl = on ? xg : gl;
                 bl = on ? xb : bl;
