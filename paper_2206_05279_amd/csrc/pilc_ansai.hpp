@@ -130,7 +130,6 @@ __global__ __launch_bounds__(256) void k_ansai_build(uint32_t M, uint32_t X,
 // i = 0..7, bytes [16c, 16c+16) of the line of row 8i + lane/8, with c = lane%8.  Every line is
 // thus requested once, whole.  The threads then pass the line through LDS in two halves of 64
 // bytes, where thread r finds the bytes of row r; the registers of the second half simply wait.
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr uint32_t kLine = 128;
 

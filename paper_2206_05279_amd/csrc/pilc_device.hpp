@@ -39,6 +39,10 @@ __device__ __forceinline__ void load_tables(LdsTables &t)
     __syncthreads();
 }
 
+// Sixteen bytes as the compiler's own vector type (arrays of it stay in registers where arrays of
+// the HIP struct type of the same size go to private memory).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 // Orders this wavefront's LDS accesses: LDS instructions of one wavefront execute in order, so
 // all that is needed is that the compiler keeps them in order too.
 __device__ __forceinline__ void wave_lds_sync()

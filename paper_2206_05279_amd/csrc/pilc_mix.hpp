@@ -7,8 +7,9 @@
 // single-law edge CDF, and C(k) = k + floor(F(k) (2^M - 256) / 2^24); the channel conditioning
 // of Sec. 3.1 eqs. (3)-(4) shifts every component's mean with that component's own innovations.
 //
-// In the general kernels K is a run-time value, so nothing per component lives in registers
-// (the kernels built for one K, further down, keep the channel's components there).  A thread first copies
+// In the general kernels K is a run-time value, so nothing per component lives in registers (the
+// kernels built for one K keep the channel's components and the pixel's weights there; they are
+// the same kernels with the component count as a template argument).  A thread first copies
 // the 7 K 16-bit parameters of a pixel into its own LDS slots in one burst of loads (every
 // 128-byte line of the arrays is then asked for by one or two bursts rather than by dozens of
 // separate loads spread over the pixel's work), then, before a subpixel is coded, turns the

@@ -132,8 +132,6 @@ __global__ __launch_bounds__(256) void k_twar_forward4(TwarK p, uint32_t groups,
 // before).  Loads past the end read the last element again instead of being skipped (a register
 // that is only sometimes written costs more in moves than the load it saves); stores past the end
 // are skipped.
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
 template <typename T>
 __device__ __forceinline__ void flat_copy(const T *__restrict__ src, T *__restrict__ dst, uint32_t total, uint32_t lane)
 {
