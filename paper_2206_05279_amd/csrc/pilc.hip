@@ -991,8 +991,27 @@ static int mix_built_for(const pilc_mix_params *p)
 {
     const bool aligned =
         (((uintptr_t)p->mu | (uintptr_t)p->log_scale | (uintptr_t)p->weight) & 3) == 0;
-    return aligned && p->num_comp == 10u ? 10 : 0;
+    return aligned && p->num_comp % 2u == 0u ? (int)p->num_comp : 0;
 }
+
+#define PILC_MIX_KERNEL_FOR(NAME)                                                                \
+    static decltype(&NAME<0>) NAME##_for(int built)                                              \
+    {                                                                                            \
+        switch (built) {                                                                         \
+        case 2: return NAME<2>;                                                                  \
+        case 4: return NAME<4>;                                                                  \
+        case 6: return NAME<6>;                                                                  \
+        case 8: return NAME<8>;                                                                  \
+        case 10: return NAME<10>;                                                                \
+        case 12: return NAME<12>;                                                                \
+        case 14: return NAME<14>;                                                                \
+        case 16: return NAME<16>;                                                                \
+        default: return NAME<0>;                                                                 \
+        }                                                                                        \
+    }
+PILC_MIX_KERNEL_FOR(k_mix_encode)
+PILC_MIX_KERNEL_FOR(k_mix_decode)
+#undef PILC_MIX_KERNEL_FOR
 
 int pilc_mix_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_mix_params *params,
                     void *workspace_dev, size_t workspace_bytes, uint8_t *coded_dev,
@@ -1023,7 +1042,7 @@ int pilc_mix_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_mi
                           params->num_comp};
     const int built = mix_built_for(params);
     const size_t lds = mix_lds_bytes(params->num_comp, built == 0);
-    auto kern = built == 10 ? k_mix_encode<10> : k_mix_encode<0>;
+    auto kern = k_mix_encode_for(built);
     if ((rc = allow_large_lds(reinterpret_cast<const void *>(kern))) != PILC_OK) return rc;
 
     Timer timer(stream);
@@ -1075,7 +1094,7 @@ int pilc_mix_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t code
                           params->num_comp};
     const int built = mix_built_for(params);
     const size_t lds = mix_lds_bytes(params->num_comp, built == 0);
-    auto kern = built == 10 ? k_mix_decode<10> : k_mix_decode<0>;
+    auto kern = k_mix_decode_for(built);
     if ((rc = allow_large_lds(reinterpret_cast<const void *>(kern))) != PILC_OK) return rc;
 
     Timer timer(stream);
