@@ -985,26 +985,34 @@ static bool mix_params_ok(const pilc_mix_params *p)
            ((uintptr_t)p->chan_coef & 1) == 0;
 }
 
-// The component count a mixture kernel was built for (components in registers: even K, arrays on
-// 4-byte boundaries), or 0 for the kernels that take any K at run time.
+// The component count a mixture kernel was built for (components in registers: arrays on 4-byte
+// boundaries), or 0 for the kernels that take any K at run time.
 static int mix_built_for(const pilc_mix_params *p)
 {
     const bool aligned =
         (((uintptr_t)p->mu | (uintptr_t)p->log_scale | (uintptr_t)p->weight) & 3) == 0;
-    return aligned && p->num_comp % 2u == 0u ? (int)p->num_comp : 0;
+    return aligned ? (int)p->num_comp : 0;
 }
 
 #define PILC_MIX_KERNEL_FOR(NAME)                                                                \
     static decltype(&NAME<0>) NAME##_for(int built)                                              \
     {                                                                                            \
         switch (built) {                                                                         \
+        case 1: return NAME<1>;                                                                  \
         case 2: return NAME<2>;                                                                  \
+        case 3: return NAME<3>;                                                                  \
         case 4: return NAME<4>;                                                                  \
+        case 5: return NAME<5>;                                                                  \
         case 6: return NAME<6>;                                                                  \
+        case 7: return NAME<7>;                                                                  \
         case 8: return NAME<8>;                                                                  \
+        case 9: return NAME<9>;                                                                  \
         case 10: return NAME<10>;                                                                \
+        case 11: return NAME<11>;                                                                \
         case 12: return NAME<12>;                                                                \
+        case 13: return NAME<13>;                                                                \
         case 14: return NAME<14>;                                                                \
+        case 15: return NAME<15>;                                                                \
         case 16: return NAME<16>;                                                                \
         default: return NAME<0>;                                                                 \
         }                                                                                        \

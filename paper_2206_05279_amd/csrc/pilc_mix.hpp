@@ -152,13 +152,16 @@ __device__ __forceinline__ bool mix_load_pixel(const MixArgs &a, uint32_t p, con
     return sum == (1u << 15);
 }
 
-// Even K with dword-aligned arrays: a pixel's raw parameters are 3 K / 2 + 3 K / 2 + K / 2 whole
-// dwords, and the kernels keep the NEXT pixel's dwords in registers while they work on the
-// current one, so that the loads have a pixel's worth of arithmetic to arrive in.
-// kK is the component count a kernel was built for, 0 for the kernels that take it at run time.
+// Dword-aligned arrays: a pixel's raw parameters lie in ceil(3 K / 2) + ceil(3 K / 2) + ceil(K / 2)
+// aligned dwords (for odd K the blocks of every other pixel start on the upper half of a dword and
+// end on a lower half: the same number of dwords, one halfword of a neighbour at either end), and
+// the kernels keep the NEXT pixel's dwords in registers while they work on the current one, so that
+// the loads have a pixel's worth of arithmetic to arrive in.
+// kK is the component count a kernel was built for, 0 for the kernels that take it at run time
+// (those run ahead for even K only).
 template <int kK> struct MixAhead {
     static constexpr int kComp = kK > 0 ? kK : kMixMaxComp;
-    static constexpr int kMu = 3 * kComp / 2, kW = kComp / 2;
+    static constexpr int kMu = (3 * kComp + 1) / 2, kW = (kComp + 1) / 2;
     uint32_t m[kMu], l[kMu], w[kW];
 };
 
@@ -181,11 +184,11 @@ template <int kK, bool kWeights = true>
 __device__ __forceinline__ void mix_fetch_ahead(const MixArgs &a, uint32_t p, MixAhead<kK> &r)
 {
     const uint32_t k = kK > 0 ? (uint32_t)kK : a.k;
-    const size_t px = (size_t)p * 3u * k;
-    const uint32_t *gm = reinterpret_cast<const uint32_t *>(a.mu + px);
-    const uint32_t *gl = reinterpret_cast<const uint32_t *>(a.ls + px);
-    const uint32_t *gw = reinterpret_cast<const uint32_t *>(a.weight + (size_t)p * k);
-    const uint32_t n3 = 3u * k / 2u, n1 = k / 2u;
+    const size_t px = (size_t)p * 3u * k;  // in halfwords: the aligned dwords from px / 2 on
+    const uint32_t *gm = reinterpret_cast<const uint32_t *>(a.mu) + (px >> 1);
+    const uint32_t *gl = reinterpret_cast<const uint32_t *>(a.ls) + (px >> 1);
+    const uint32_t *gw = reinterpret_cast<const uint32_t *>(a.weight) + (((size_t)p * k) >> 1);
+    const uint32_t n3 = (3u * k + 1u) / 2u, n1 = (k + 1u) / 2u;
 #pragma unroll
     for (int i = 0; i < MixAhead<kK>::kMu; ++i)
         if ((uint32_t)i < n3) r.m[i] = gm[i];
@@ -199,48 +202,72 @@ __device__ __forceinline__ void mix_fetch_ahead(const MixArgs &a, uint32_t p, Mi
     }
 }
 
-// The weights of pixel p into `regs`, through the thread's block (dword-aligned array, even kK),
-// highest address first: the encoder walks its lane backwards.  False if they do not sum to 2^15.
+// The weights of pixel p into `regs`, through the thread's block (dword-aligned array), highest
+// address first: the encoder walks its lane backwards.  False if they do not sum to 2^15.
 template <int kK>
 __device__ __forceinline__ bool mix_load_weights(const MixArgs &a, uint32_t p, LdsBlock<kMixWeightBlock> &block,
                                                  MixRegs<kK> &regs)
 {
     const uintptr_t at = reinterpret_cast<uintptr_t>(a.weight + (size_t)p * kK);
     uint32_t sum = 0;
+    if constexpr (kK % 2 == 0) {
 #pragma unroll
-    for (int i = kK / 2 - 1; i >= 0; --i) {
-        const uint32_t w2 = block.dword(at + 4u * i);
-        regs.w[2 * i] = w2 & 0xFFFFu;
-        regs.w[2 * i + 1] = w2 >> 16;
-        sum += (w2 & 0xFFFFu) + (w2 >> 16);
+        for (int i = kK / 2 - 1; i >= 0; --i) {
+            const uint32_t w2 = block.dword(at + 4u * i);
+            regs.w[2 * i] = w2 & 0xFFFFu;
+            regs.w[2 * i + 1] = w2 >> 16;
+        }
+    } else {  // a halfword at a time: the pixel's weights start on either half of a dword
+#pragma unroll
+        for (int j = kK - 1; j >= 0; --j) {
+            const uintptr_t b = at + 2u * j;
+            const uint32_t w2 = block.dword(b);
+            regs.w[j] = (b & 2u) ? w2 >> 16 : w2 & 0xFFFFu;
+        }
     }
+#pragma unroll
+    for (int j = 0; j < kK; ++j) sum += regs.w[j];
     return sum == (1u << 15);
 }
 
 // The fetched pixel into the slots, its weights into `regs` in the kernels built for one K; false
-// if the weights do not sum to 2^15.  kWeights as above (then true).
+// if the weights do not sum to 2^15.  kWeights as above (then true).  `upper`: the pixel's blocks
+// start on the upper half of the first dword fetched (odd K, every other pixel) and are moved down
+// by a halfword on the way.
 template <int kK, bool kWeights = true>
-__device__ __forceinline__ bool mix_store_ahead(const MixAhead<kK> &r, const MixSlots &s, MixRegs<kK> &regs)
+__device__ __forceinline__ bool mix_store_ahead(const MixAhead<kK> &r, const MixSlots &s, MixRegs<kK> &regs,
+                                                bool upper)
 {
-    const uint32_t n3 = 3u * s.k / 2u, n1 = s.k / 2u;
+    constexpr bool kOdd = kK % 2 != 0;
+    const uint32_t n3 = (3u * s.k + 1u) / 2u, n1 = (s.k + 1u) / 2u;
+    auto lowered = [&](const uint32_t *d, int i, int n) {  // dword i of the block, from the n fetched
+        if constexpr (!kOdd) return d[i];
+        const uint32_t next = i + 1 < n ? d[i + 1] : 0u;
+        return upper ? __builtin_amdgcn_alignbit(next, d[i], 16) : d[i];
+    };
     uint32_t sum = 0;
 #pragma unroll
     for (int i = 0; i < MixAhead<kK>::kMu; ++i)
-        if ((uint32_t)i < n3) s.dword(s.raw_mu + i) = r.m[i];
+        if ((uint32_t)i < n3) s.dword(s.raw_mu + i) = lowered(r.m, i, MixAhead<kK>::kMu);
 #pragma unroll
     for (int i = 0; i < MixAhead<kK>::kMu; ++i)
-        if ((uint32_t)i < n3) s.dword(s.raw_ls + i) = r.l[i];
+        if ((uint32_t)i < n3) s.dword(s.raw_ls + i) = lowered(r.l, i, MixAhead<kK>::kMu);
     if constexpr (!kWeights) return true;
 #pragma unroll
     for (int i = 0; i < MixAhead<kK>::kW; ++i)
         if ((uint32_t)i < n1) {
+            const uint32_t w2 = lowered(r.w, i, MixAhead<kK>::kW);
             if constexpr (kK > 0) {
-                regs.w[2 * i] = r.w[i] & 0xFFFFu;
-                regs.w[2 * i + 1] = r.w[i] >> 16;
+                regs.w[2 * i] = w2 & 0xFFFFu;
+                sum += w2 & 0xFFFFu;
+                if (2 * i + 1 < kK) {
+                    regs.w[2 * i + 1] = w2 >> 16;
+                    sum += w2 >> 16;
+                }
             } else {
-                s.dword(s.raw_w + i) = r.w[i];
+                s.dword(s.raw_w + i) = w2;
+                sum += (w2 & 0xFFFFu) + (w2 >> 16);
             }
-            sum += (r.w[i] & 0xFFFFu) + (r.w[i] >> 16);
         }
     return sum == (1u << 15);
 }
@@ -271,7 +298,23 @@ template <int kK>
 __device__ __forceinline__ void mix_load_channel(const MixSlots &s, MixRegs<kK> &regs, int ch, int x_r,
                                                  int x_g, int a_gr, int a_br, int a_bg, const LdsTables &tab)
 {
-    static_assert(kK > 0 && kK % 2 == 0, "built for an even number of components");
+    static_assert(kK > 0, "built for one component count");
+    if constexpr (kK % 2 != 0) {  // a channel's block starts on either half of a dword: halfword reads
+#pragma unroll
+        for (int j = 0; j < kK; ++j) {
+            int me = (int)s.half(s.raw_mu, (uint32_t)ch * kK + j);
+            if (ch >= 1) {
+                const int e_r = x_r * 256 - (int)s.half(s.raw_mu, j);
+                if (ch == 1)
+                    me += rsh14_mul(a_gr, e_r);
+                else
+                    me += rsh14_mul(a_br, e_r) + rsh14_mul(a_bg, x_g * 256 - (int)s.half(s.raw_mu, kK + j));
+            }
+            regs.c0[j] = edge_offset(me);
+            regs.inv_s[j] = inv_scale((int)(short)s.half(s.raw_ls, (uint32_t)ch * kK + j), tab);
+        }
+        return;
+    }
     const uint32_t *mu_r = s.base + s.raw_mu * s.stride;
     const uint32_t *mu_g = mu_r + (kK / 2) * s.stride;
     const uint32_t *mu_c = mu_r + (uint32_t)ch * (kK / 2) * s.stride;
@@ -377,7 +420,7 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_encode(
             a_gr = a.coef[3 * im]; a_br = a.coef[3 * im + 1]; a_bg = a.coef[3 * im + 2];
         }
         if (ahead) {
-            ok = mix_store_ahead<kK, kAheadW>(pre, slots, regs) && ok;
+            ok = mix_store_ahead<kK, kAheadW>(pre, slots, regs, (kK & 1) != 0 && (p & 1u) != 0u) && ok;
             if constexpr (!kAheadW) ok = mix_load_weights<kK>(a, p, weights, regs) && ok;
             if (t != 0u) mix_fetch_ahead<kK, kAheadW>(a, lane_pixel(g, sh, t - 1u), pre);
         } else {
@@ -505,7 +548,7 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_decode(
             a_gr = a.coef[3 * im]; a_br = a.coef[3 * im + 1]; a_bg = a.coef[3 * im + 2];
         }
         if (ahead) {
-            ok = mix_store_ahead(pre, slots, regs) && ok;
+            ok = mix_store_ahead(pre, slots, regs, (kK & 1) != 0 && (p & 1u) != 0u) && ok;
             if (t + 1u < sh.npx) mix_fetch_ahead(a, lane_pixel(g, sh, t + 1u), pre);
         } else {
             ok = mix_load_pixel(a, p, slots) && ok;
