@@ -605,9 +605,10 @@ int pilc_twar_inverse(uint32_t n, uint32_t h, uint32_t w, const uint8_t *res_dev
     const int elem = unit_bytes % 16u == 0u && (both & 15) == 0 ? 16 : unit_bytes % 4u == 0u && (both & 3) == 0 ? 4 : 1;
     Timer timer(stream);
     const bool tall = h > 64 && w % 16 == 0 && w <= 16384 && ((((uintptr_t)img_dev) | ((uintptr_t)res_dev)) & 15) == 0;
-    // few tall images: bands of up to 576 rows in workgroups of their own (two bands of 540 rows
-    // and five of 216 take the same 1.5 ms on 30 frames of 1080 x 1920; one workgroup per frame 2.2)
-    uint32_t bands = tall && n < 256u ? (h + 575u) / 576u : 1u;
+    // few tall images: bands of up to 384 rows in workgroups of their own (on 30 frames of
+    // 1080 x 1920: three bands of 360 rows 1.01 ms, four of 270 1.03, five of 216 1.07, six of 180
+    // 1.13, two of 540 1.14; one workgroup per frame 2.2)
+    uint32_t bands = tall && n < 256u ? (h + 383u) / 384u : 1u;
     int slot = -1;
     uint32_t *flags = nullptr;
     if (bands > 1u && (uint64_t)n * bands <= kBandFlags) flags = band_flags_acquire(&slot);
