@@ -19,8 +19,8 @@
  *   - Return value: 0 on success, a negative PILC_E_* code otherwise.  No exceptions.  Calls on
  *     different streams may run concurrently, from any threads, if they use different workspaces.
  *     The library's only process-wide state: the constant tables (filled once per device under a
- *     lock), the knobs pilc_set_timing, pilc_set_kernel_policy and pilc_set_one_pass_wait (atomic
- *     integers, read once at the start of a call), the scratch array of pilc_encode_static, and four
+ *     lock), the knobs pilc_set_timing, pilc_set_kernel_policy, pilc_set_one_pass_wait and
+ *     pilc_set_ansai_decode_waves (atomic integers, read once at the start of a call), the scratch array of pilc_encode_static, and four
  *     sets of progress counters that calls of pilc_twar_inverse on tall images take turns with.
  *   - Tensors are dense, row-major, channel-interleaved: index ((i*h + y)*w + x)*3 + c.
  */
@@ -265,6 +265,13 @@ int pilc_ansai_encode(const pilc_ansai_shape *shape, const uint8_t *sym_dev, con
 int pilc_ansai_decode(const pilc_ansai_shape *shape, const uint8_t *coded_dev, size_t coded_bytes,
                       const uint8_t *dist_dev, const void *tables_dev, void *workspace_dev,
                       size_t workspace_bytes, uint8_t *sym_out_dev, void *hip_stream);
+
+/* How many wavefronts a workgroup of pilc_ansai_decode's kernel has: 0 = chosen from the batch and
+ * the table size (default: as many as fit beside the tables in LDS, fewer for a batch that would
+ * not fill every compute unit that densely), 1 .. 12 = that many (less if fewer fit).  Every
+ * choice decodes the same symbols; the knob exists for tuning and for testing every workgroup
+ * shape on the same input.  Process-wide.  Errors: PILC_E_ARG for any other value. */
+int pilc_set_ansai_decode_waves(int waves);
 
 /* ------------------------------------------------------------------------------------------
  * The Three-Way Auto-regressive residual transform (Sec. 3.1, eqs. (2)-(4)): every subpixel is

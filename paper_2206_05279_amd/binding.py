@@ -28,7 +28,7 @@ PILC_E_TIMEOUT = -8
 EXPORTS = [
     "pilc_lane_count", "pilc_workspace_size", "pilc_encode", "pilc_encode_static", "pilc_decode",
     "pilc_symbol_tables",
-    "pilc_set_timing", "pilc_set_kernel_policy", "pilc_set_one_pass_wait", "pilc_last_timing", "pilc_timing_name", "pilc_strerror",
+    "pilc_set_timing", "pilc_set_kernel_policy", "pilc_set_one_pass_wait", "pilc_set_ansai_decode_waves", "pilc_last_timing", "pilc_timing_name", "pilc_strerror",
     "pilc_last_hip_error", "pilc_version",
     "pilc_ansai_table_bytes", "pilc_ansai_build_tables", "pilc_ansai_workspace_size", "pilc_ansai_encode",
     "pilc_ansai_decode", "pilc_ansai_center", "pilc_twar_forward", "pilc_twar_inverse",
@@ -104,6 +104,8 @@ def lib():
         L.pilc_set_timing.argtypes = [C.c_int]
         L.pilc_set_kernel_policy.restype = C.c_int
         L.pilc_set_kernel_policy.argtypes = [C.c_int]
+        L.pilc_set_ansai_decode_waves.restype = C.c_int
+        L.pilc_set_ansai_decode_waves.argtypes = [C.c_int]
         L.pilc_set_one_pass_wait.restype = None
         L.pilc_set_one_pass_wait.argtypes = [C.c_uint64, C.c_int]
         L.pilc_last_timing.restype = C.c_int
@@ -240,6 +242,12 @@ def pilc_set_kernel_policy(policy: int) -> None:
     rc = lib().pilc_set_kernel_policy(int(policy))
     if rc != PILC_OK:
         raise PilcError(rc, "pilc_set_kernel_policy")
+
+
+def pilc_set_ansai_decode_waves(waves: int) -> None:
+    rc = lib().pilc_set_ansai_decode_waves(int(waves))
+    if rc != PILC_OK:
+        raise PilcError(rc, "pilc_set_ansai_decode_waves")
 
 
 def pilc_set_one_pass_wait(ticks: int = 0, withhold_first: bool = False) -> None:

@@ -361,6 +361,7 @@ namespace pilc {
 // 0 chosen from the lane count, 1 thread per lane, 2 the kernels for few long lanes, 3 thread per
 // lane with the one-pass encoder (the lane kernel also scans and packs)
 static std::atomic<int> g_kernel_policy{0};
+static std::atomic<int> g_ansai_decode_waves{0};  // 0: chosen per call
 // Bound of a look-back wait of the one-pass encoder in ticks of the constant-rate clock (0: two
 // seconds), and the switch that makes its first workgroup publish nothing (tests only).
 static std::atomic<unsigned long long> g_one_pass_wait{0};

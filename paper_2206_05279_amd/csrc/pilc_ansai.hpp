@@ -991,6 +991,13 @@ int pilc_ansai_encode(const pilc_ansai_shape *shape, const uint8_t *sym_dev, con
     return PILC_OK;
 }
 
+int pilc_set_ansai_decode_waves(int waves)
+{
+    if (waves < 0 || waves > kAnsaiDecMaxWaves) return PILC_E_ARG;
+    g_ansai_decode_waves.store(waves, std::memory_order_relaxed);
+    return PILC_OK;
+}
+
 int pilc_ansai_decode(const pilc_ansai_shape *shape, const uint8_t *coded_dev, size_t coded_bytes,
                       const uint8_t *dist_dev, const void *tables_dev, void *workspace_dev,
                       size_t workspace_bytes, uint8_t *sym_out_dev, void *hip_stream)
@@ -1032,6 +1039,11 @@ int pilc_ansai_decode(const pilc_ansai_shape *shape, const uint8_t *coded_dev, s
             const uint32_t each = (uint32_t)ceil_div64(ws.waves, (uint64_t)cus);
             waves = each < 4u ? 4u : (each < waves ? each : waves);
         }
+    }
+    const uint32_t asked = (uint32_t)g_ansai_decode_waves.load(std::memory_order_relaxed);
+    if (asked != 0u) {  // pilc_set_ansai_decode_waves: that many, if they fit
+        const size_t fit = tab_in_lds ? (lds_max - tab_lds) / row_lds : (size_t)kAnsaiDecMaxWaves;
+        waves = asked < fit ? asked : (uint32_t)fit;
     }
     Timer timer(stream);
     k_ansai_begin<<<1, 1, 0, stream>>>(sh, reinterpret_cast<const ATabHeader *>(tb), status);

@@ -91,6 +91,29 @@ def test_decode_returns_the_symbols(case):
     assert np.array_equal(dp.decoded_numpy(), dp.sym_np)
 
 
+def test_every_workgroup_shape_of_the_decoder_gives_the_same_symbols():
+    """One input through workgroups of 1 .. 12 wavefronts (as many as fit beside the tables), for
+    tables in LDS with 16-bit and with 32-bit entries and for tables in global memory."""
+    for m, d, pieces, count in ((12, 8, 2000, 300), (13, 1, 1500, 200), (15, 2, 1500, 200)):
+        mass = sp.logistic_masses(m, d)
+        sym, dist = sp.draw_pieces(mass, m, pieces, count, seed=77 + m, threads=1)
+        dp = DevicePieces(m, mass, sym, dist)
+        rc, ref = ao.encode(m, mass, sym, dist)
+        assert rc == ao.OK
+        dp.encode()
+        assert np.array_equal(dp.coded_numpy(), ref)
+        try:
+            for waves in range(1, 13):
+                print("M", m, "D", d, "wavefronts per workgroup", waves, flush=True)
+                pb.pilc_set_ansai_decode_waves(waves)
+                dp.decode()
+                assert np.array_equal(dp.decoded_numpy(), sym), waves
+        finally:
+            pb.pilc_set_ansai_decode_waves(0)
+    with pytest.raises(pb.PilcError):
+        pb.pilc_set_ansai_decode_waves(13)
+
+
 # ---------------------------------------------------------------- errors
 @pytest.fixture(scope="module")
 def small():
