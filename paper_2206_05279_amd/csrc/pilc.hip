@@ -219,30 +219,44 @@ __global__ __launch_bounds__(256) void k_pack(Geo g, uint32_t lanes_per_block,
     }
     __syncthreads();
     const uint32_t w_begin = s_off[0] >> 1, w_end = s_off[n] >> 1;
-    for (uint32_t w = w_begin + threadIdx.x; w < w_end; w += blockDim.x) {
-        const uint32_t byte = 2u * w;
-        uint32_t lo = 0, hi = n - 1;  // largest i with s_off[i] <= byte
-        while (lo < hi) {
-            const uint32_t mid = (lo + hi + 1) >> 1;
-            if (s_off[mid] <= byte)
-                lo = mid;
-            else
-                hi = mid - 1;
+    if (w_begin == w_end) return;
+    // four words per thread and turn, so that four loads are under way together (words past the
+    // end read the last one again and are not written)
+    for (uint32_t w0 = w_begin + threadIdx.x; w0 - threadIdx.x < w_end; w0 += 4u * blockDim.x) {
+        uint16_t v[4];
+#pragma unroll
+        for (uint32_t k = 0; k < 4u; ++k) {
+            const uint32_t byte = 2u * min(w0 + k * blockDim.x, w_end - 1u);
+            uint32_t lo = 0, hi = n - 1;  // largest i with s_off[i] <= byte
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi + 1) >> 1;
+                if (s_off[mid] <= byte)
+                    lo = mid;
+                else
+                    hi = mid - 1;
+            }
+            const uint32_t local = byte - s_off[lo];
+            // a lane's state is its first four bytes; for those the load goes to the word below the
+            // lane's words (inside its slot: a lane has a pixel or more) and is not used
+            const uint16_t word = scratch[local < 4u ? s_src[lo] - 1u : s_src[lo] + ((local - 4u) >> 1)];
+            v[k] = local < 4u ? (uint16_t)(s_state[lo] >> (8u * local)) : word;
         }
-        const uint32_t local = byte - s_off[lo];
-        payload[w] = local < 4u ? (uint16_t)(s_state[lo] >> (8u * local))
-                                : scratch[s_src[lo] + ((local - 4u) >> 1)];
+#pragma unroll
+        for (uint32_t k = 0; k < 4u; ++k)
+            if (w0 + k * blockDim.x < w_end) payload[w0 + k * blockDim.x] = v[k];
     }
 }
 
 // The packer for the thread-per-lane encoder, whose scratch is [word number][thread] per 64
 // lanes with room for lane_cap words each, the words of a lane in the reverse of the stream
-// order.  A workgroup owns 64 lanes: it reads 64 word numbers at a time as whole 128-byte rows
-// into an LDS tile and writes every lane's piece of the stream from there, 64 consecutive words
-// per wavefront instruction.
-constexpr int kPackTile = 64;
+// order.  A workgroup owns 64 lanes: it reads kPackTile word numbers at a time as whole 128-byte
+// rows into an LDS tile and writes every lane's piece of the stream from there, 64 consecutive words
+// per wavefront instruction.  kPackTile word numbers a turn: the more, the longer the runs a lane's
+// words are written in (128 for lanes of up to 256 symbols, where more would mostly be read in
+// vain, 256 for longer ones; on the stress workload 64 / 128 / 256 take 0.61 / 0.52 / 0.47 ms).
 constexpr int kPackTileStride = 66;  // 16-bit elements: 33 dwords, odd, so a column read spreads over the banks
 
+template <int kPackTile>
 __global__ __launch_bounds__(256) void k_pack_by_thread(uint32_t lanes, uint32_t lane_cap,
                                                         const uint16_t *__restrict__ scratch,
                                                         const uint32_t *__restrict__ lane_state,
@@ -277,23 +291,29 @@ __global__ __launch_bounds__(256) void k_pack_by_thread(uint32_t lanes, uint32_t
     const uint32_t max_nw = s_max;
     const uint16_t *rows = scratch + (size_t)l0 * lane_cap;
     for (uint32_t k0 = 0; k0 < max_nw; k0 += kPackTile) {
-        // rows k0 .. k0 + 63 of the block, two lanes (one dword) per thread and 8 rows apart
+        // rows k0 .. k0 + 63 of the block, two lanes (one dword) per thread and 8 rows apart; all
+        // eight are asked for before the first is stored (guarded one by one, every load would wait
+        // for the one before); rows past the last one repeat it and are never read
+        uint32_t v[kPackTile / 8];
 #pragma unroll
         for (int j = 0; j < kPackTile / 8; ++j) {
-            const uint32_t r = (t >> 5) + 8u * j, c2 = t & 31u;
-            if (k0 + r < max_nw) {
-                const uint32_t v =
-                    *reinterpret_cast<const uint32_t *>(rows + (size_t)(k0 + r) * 64u + 2u * c2);
-                *reinterpret_cast<uint32_t *>(&tile[r * kPackTileStride + 2u * c2]) = v;
-            }
+            const uint32_t r = min(k0 + (t >> 5) + 8u * j, max_nw - 1u);
+            v[j] = *reinterpret_cast<const uint32_t *>(rows + (size_t)r * 64u + 2u * (t & 31u));
         }
+#pragma unroll
+        for (int j = 0; j < kPackTile / 8; ++j)
+            *reinterpret_cast<uint32_t *>(&tile[((t >> 5) + 8u * j) * kPackTileStride + 2u * (t & 31u)]) = v[j];
         __syncthreads();
-        // wavefront w writes lanes 16 w .. 16 w + 15; its thread u has word number k0 + u
+        // wavefront w writes lanes 16 w .. 16 w + 15; its thread u has word numbers k0 + u, k0 + 64 + u, ...
 #pragma unroll 4
         for (int j = 0; j < 16; ++j) {
-            const uint32_t i = (t >> 6) * 16u + j, k = k0 + (t & 63u);
+            const uint32_t i = (t >> 6) * 16u + j;
             const uint32_t nw = s_nw[i];
-            if (k < nw) payload[s_first[i] + 2u + (nw - 1u - k)] = tile[(t & 63u) * kPackTileStride + i];
+#pragma unroll
+            for (uint32_t part = 0; part < (uint32_t)kPackTile; part += 64u) {
+                const uint32_t row = part + (t & 63u), k = k0 + row;
+                if (k < nw) payload[s_first[i] + 2u + (nw - 1u - k)] = tile[row * kPackTileStride + i];
+            }
         }
         __syncthreads();
     }
@@ -825,7 +845,7 @@ static int encode_checked(const Geo &g, const uint8_t *img_dev, const pilc_param
         uint32_t pack_lanes = 16384u / (lane_sym ? lane_sym : 1u);
         pack_lanes = pack_lanes < 1 ? 1 : (pack_lanes > (uint32_t)kPackMaxLanes ? kPackMaxLanes : pack_lanes);
         if (lane_cap != 0u)
-            k_pack_by_thread<<<(uint32_t)ceil_div64(g.lanes, 64), 256, 0, stream>>>(
+            (lane_cap <= 256u ? k_pack_by_thread<128> : k_pack_by_thread<256>)<<<(uint32_t)ceil_div64(g.lanes, 64), 256, 0, stream>>>(
                 g.lanes, lane_cap, scratch, lane_state, offsets, payload, status);
         else
             k_pack<<<(uint32_t)ceil_div64(g.lanes, pack_lanes), 256, 0, stream>>>(
@@ -1069,7 +1089,7 @@ int pilc_mix_encode(const pilc_geom *geom, const uint8_t *img_dev, const pilc_mi
     k_scan_apply<<<ws.scan_blocks, kScanThreads, 0, stream>>>(g.lanes, lane_bytes, lane_words, sums,
                                                               offsets);
     timer.mark("scan");
-    k_pack_by_thread<<<(uint32_t)ceil_div64(g.lanes, 64), 256, 0, stream>>>(
+    (lane_cap <= 256u ? k_pack_by_thread<128> : k_pack_by_thread<256>)<<<(uint32_t)ceil_div64(g.lanes, 64), 256, 0, stream>>>(
         g.lanes, lane_cap, scratch, lane_state, offsets, payload, status);
     timer.mark("k_pack_by_thread");
     HIP_TRY(hipGetLastError());

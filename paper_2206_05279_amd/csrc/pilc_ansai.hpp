@@ -389,7 +389,7 @@ __global__ __launch_bounds__(64 * kAnsaiEncWaves) void k_ansai_encode(
 // Pack: scratch [wavefront][word][thread] -> records {state, bit count, words} at the offsets
 // ---------------------------------------------------------------------------------------------
 constexpr int kAnsaiPackWaves = 4;
-constexpr int kAnsaiPackRows = 16;
+constexpr int kAnsaiPackRows = 64;
 
 __global__ __launch_bounds__(64 * kAnsaiPackWaves) void k_ansai_pack(
     AShape sh, const uint32_t *__restrict__ scratch, uint32_t maxw,
@@ -419,15 +419,26 @@ __global__ __launch_bounds__(64 * kAnsaiPackWaves) void k_ansai_pack(
     for (int d = 32; d >= 1; d >>= 1) most = max(most, (uint32_t)__shfl_xor((int)most, d, 64));
     const uint32_t *src = scratch + (size_t)gw * maxw * 64u + lane;
     uint32_t *mine = tile[wave] + lane * (kAnsaiPackRows + 1);
+    // A turn moves kAnsaiPackRows words of every piece.  All rows of a turn are asked for before the
+    // first is stored (guarded one by one, every load would wait for the one before; rows past the
+    // last one repeat it and are never read), and the next turn's rows are asked for before this
+    // turn's words are written out, so that they arrive meanwhile.
+    uint32_t v[kAnsaiPackRows];
+    auto fetch = [&](uint32_t j0) {
+#pragma unroll
+        for (int jj = 0; jj < kAnsaiPackRows; ++jj) v[jj] = src[(size_t)min(j0 + jj, most - 1u) * 64u];
+    };
+    if (most != 0u) fetch(0u);
     for (uint32_t j0 = 0; j0 < most; j0 += kAnsaiPackRows) {
         wave_lds_sync();
 #pragma unroll
-        for (int jj = 0; jj < kAnsaiPackRows; ++jj)
-            if (j0 + jj < most) mine[jj] = src[(size_t)(j0 + jj) * 64u];
+        for (int jj = 0; jj < kAnsaiPackRows; ++jj) mine[jj] = v[jj];
         wave_lds_sync();
+        if (j0 + kAnsaiPackRows < most) fetch(j0 + kAnsaiPackRows);
+        constexpr uint32_t kPer = 64u / kAnsaiPackRows;  // pieces per pass, kAnsaiPackRows threads each
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {  // 4 pieces per pass, 16 threads each
-            const uint32_t r = i * 4 + (lane >> 4), jj = lane & 15u, j = j0 + jj;
+        for (int i = 0; i < kAnsaiPackRows; ++i) {
+            const uint32_t r = i * kPer + lane / kAnsaiPackRows, jj = lane % kAnsaiPackRows, j = j0 + jj;
             if (j < s_nw[wave][r]) payload[s_dst[wave][r] + j] = tile[wave][r * (kAnsaiPackRows + 1) + jj];
         }
     }
