@@ -182,7 +182,7 @@ const char *pilc_timing_name(int index_in_last_call);
  * thread per lane, 2 = the kernels for few long lanes (workgroup-cooperative encode, a row of 16
  * threads per lane in decode), 3 = one thread per lane with the one-pass encoder (the lane kernel
  * also computes the offsets and places its lanes in the container, instead of leaving that to the
- * scan and pack kernels; measured slower, kept for comparison).  All choices produce the same
+ * scan and pack kernels; measured no faster, kept for comparison).  All choices produce the same
  * bytes; the knob exists for tuning and for testing every kernel on the same input.  Process-wide.
  * Errors: PILC_E_ARG for any other value. */
 int pilc_set_kernel_policy(int policy);

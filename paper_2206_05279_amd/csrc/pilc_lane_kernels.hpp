@@ -563,20 +563,27 @@ __device__ __forceinline__ bool place_group(const OnePass &op, const Geo &g, uin
     const uint32_t half = wl >> 5, u = wl & 31u;
     for (uint32_t k0 = 0; k0 < max_nw; k0 += kTailRows) {
         wave_lds_sync();
-#pragma unroll 4
-        for (int j = 0; j < kTailRows / 2; ++j) {  // two rows an instruction, a dword (two lanes) a thread
-            const uint32_t r = 2u * j + half;
-            if (k0 + r < max_nw)
-                *reinterpret_cast<uint32_t *>(&tile[r * kPackTileStride + 2u * u]) =
-                    *reinterpret_cast<const uint32_t *>(rows + (size_t)(k0 + r) * 64u + 2u * u);
-        }
+        // two rows an instruction, a dword (two lanes) a thread; all rows of the turn are asked for
+        // before the first is stored (guarded one by one, every load would wait for the one before);
+        // rows past the last one repeat it and are never read
+        uint32_t v[kTailRows / 2];
+#pragma unroll
+        for (int j = 0; j < kTailRows / 2; ++j)
+            v[j] = *reinterpret_cast<const uint32_t *>(rows + (size_t)min(k0 + 2u * j + half, max_nw - 1u) * 64u + 2u * u);
+#pragma unroll
+        for (int j = 0; j < kTailRows / 2; ++j)
+            *reinterpret_cast<uint32_t *>(&tile[(2u * j + half) * kPackTileStride + 2u * u]) = v[j];
         wave_lds_sync();
 #pragma unroll 4
-        for (int j = 0; j < 32; ++j) {  // lanes 2 j and 2 j + 1; thread u of a half has word number k0 + u
-            const uint32_t i = 2u * j + half, k = k0 + u;
+        for (int j = 0; j < 32; ++j) {  // lanes 2 j and 2 j + 1; thread u of a half has word numbers k0 + u, + 32, ...
+            const uint32_t i = 2u * j + half;
             const uint32_t nw_i = (uint32_t)__shfl((int)my_nw, (int)i, 64);
             const uint32_t first_i = (uint32_t)__shfl((int)first, (int)i, 64);
-            if (k < nw_i) payload[first_i + 2u + (nw_i - 1u - k)] = tile[u * kPackTileStride + i];
+#pragma unroll
+            for (uint32_t part = 0; part < (uint32_t)kTailRows; part += 32u) {
+                const uint32_t k = k0 + part + u;
+                if (k < nw_i) payload[first_i + 2u + (nw_i - 1u - k)] = tile[(part + u) * kPackTileStride + i];
+            }
         }
     }
     return true;
