@@ -398,23 +398,21 @@ __global__ __launch_bounds__(64 * kAnsaiPackWaves) void k_ansai_pack(
     const Status *__restrict__ status)
 {
     if (status->code != ST_OK) return;
+    static_assert(kAnsaiPackRows == 64, "a pass writes 64 words of one piece, one per thread");
     __shared__ uint32_t tile[kAnsaiPackWaves][64 * (kAnsaiPackRows + 1)];
-    __shared__ uint32_t s_dst[kAnsaiPackWaves][64];  // payload dword index of the piece's words
-    __shared__ uint32_t s_nw[kAnsaiPackWaves][64];
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
     const uint32_t gw = blockIdx.x * kAnsaiPackWaves + wave;
     const uint32_t p0 = gw * 64u;
     if (p0 >= sh.pieces) return;
     const uint32_t np = min(64u, sh.pieces - p0);
-    uint32_t nw = 0;
+    uint32_t nw = 0, dst = 0;  // words of this thread's piece and the payload dword index of the first
     if (lane < np) {
         const uint32_t bits = piece_bits[p0 + lane], at = offsets[p0 + lane] >> 2;
         nw = (bits + 31u) >> 5;
         payload[at] = piece_state[p0 + lane];
         payload[at + 1u] = bits;
-        s_dst[wave][lane] = at + 2u;
+        dst = at + 2u;
     }
-    s_nw[wave][lane] = nw;
     uint32_t most = nw;
     for (int d = 32; d >= 1; d >>= 1) most = max(most, (uint32_t)__shfl_xor((int)most, d, 64));
     const uint32_t *src = scratch + (size_t)gw * maxw * 64u + lane;
@@ -435,11 +433,20 @@ __global__ __launch_bounds__(64 * kAnsaiPackWaves) void k_ansai_pack(
         for (int jj = 0; jj < kAnsaiPackRows; ++jj) mine[jj] = v[jj];
         wave_lds_sync();
         if (j0 + kAnsaiPackRows < most) fetch(j0 + kAnsaiPackRows);
-        constexpr uint32_t kPer = 64u / kAnsaiPackRows;  // pieces per pass, kAnsaiPackRows threads each
+        // pass i writes words j0 .. j0 + 63 of piece i, a word per thread; the piece's length and
+        // place come from its thread's registers, and eight tile reads are under way at a time
+        const uint32_t j = j0 + lane;
 #pragma unroll
-        for (int i = 0; i < kAnsaiPackRows; ++i) {
-            const uint32_t r = i * kPer + lane / kAnsaiPackRows, jj = lane % kAnsaiPackRows, j = j0 + jj;
-            if (j < s_nw[wave][r]) payload[s_dst[wave][r] + j] = tile[wave][r * (kAnsaiPackRows + 1) + jj];
+        for (int i0 = 0; i0 < 64; i0 += 8) {
+            uint32_t word[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) word[k] = tile[wave][(i0 + k) * (kAnsaiPackRows + 1) + lane];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const uint32_t nw_i = (uint32_t)__builtin_amdgcn_readlane((int)nw, i0 + k);
+                const uint32_t dst_i = (uint32_t)__builtin_amdgcn_readlane((int)dst, i0 + k);
+                if (j < nw_i) payload[dst_i + j] = word[k];
+            }
         }
     }
 }
