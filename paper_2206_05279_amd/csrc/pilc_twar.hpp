@@ -82,14 +82,16 @@ __device__ __forceinline__ int byte_at(uint32_t prev, uint32_t c0, uint32_t c1, 
 
 // Four pixels (12 bytes, three dwords) per thread, for rows that are a whole number of such
 // groups in 4-byte aligned arrays: dword loads and stores only.
-__global__ __launch_bounds__(256) void k_twar_forward4(TwarK p, uint32_t groups, uint32_t h,
-                                                       uint32_t groups_per_row,
+__global__ __launch_bounds__(256) void k_twar_forward4(TwarK p, uint32_t groups, FastDiv by_h,
+                                                       FastDiv by_groups_per_row,
                                                        const uint32_t *__restrict__ img,
                                                        uint32_t *__restrict__ res)
 {
     const uint32_t gi = blockIdx.x * blockDim.x + threadIdx.x;
     if (gi >= groups) return;
-    const uint32_t row = gi / groups_per_row, k = gi % groups_per_row, u = row % h;
+    const uint32_t groups_per_row = by_groups_per_row.d;
+    const uint32_t row = by_groups_per_row.div(gi), k = gi - row * groups_per_row;
+    const uint32_t u = row - by_h.div(row) * by_h.d;
     const uint32_t *x = img + (size_t)gi * 3u;
     const uint32_t c0 = x[0], c1 = x[1], c2 = x[2];
     const uint32_t prev = k > 0 ? x[-1] : 0u;  // the pixel to the left of the group (its last 3 bytes)
@@ -572,7 +574,7 @@ int pilc_twar_forward(uint32_t n, uint32_t h, uint32_t w, const uint8_t *img_dev
     const uint64_t groups = rows * (w / 4);
     if (w % 4 == 0 && ((((uintptr_t)img_dev) | ((uintptr_t)res_dev)) & 3) == 0 && groups < (1ull << 32))
         k_twar_forward4<<<(uint32_t)((groups + 255) / 256), 256, 0, stream>>>(
-            k, (uint32_t)groups, h, w / 4, reinterpret_cast<const uint32_t *>(img_dev),
+            k, (uint32_t)groups, FastDiv::make(h), FastDiv::make(w / 4), reinterpret_cast<const uint32_t *>(img_dev),
             reinterpret_cast<uint32_t *>(res_dev));
     else
         k_twar_forward<<<blocks, 256, 0, stream>>>(k, (uint32_t)rows, h, w, rpb, img_dev, res_dev);
