@@ -67,7 +67,7 @@ __global__ void k_symbol_tables(Geo g, const uint8_t *__restrict__ img,
     uint32_t p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= g.total_px) return;
     size_t s = (size_t)p * 3;
-    uint32_t im = p / g.hw;
+    uint32_t im = g.by_hw.div(p);
     int x[3] = {img[s], img[s + 1], img[s + 2]};
     int m[3] = {mu[s], mu[s + 1], mu[s + 2]};
     int me[3];
@@ -483,6 +483,7 @@ static int make_geo(const pilc_geom *in, Geo *g)
         in->lane_mode == 1 ? (uint32_t)(ceil_div64(in->h, in->lane_a) * g->tiles_x) : 1u;
     g->total_px = (uint32_t)total;
     g->lanes = (uint32_t)lanes;
+    g->by_hw = FastDiv::make(g->hw);
     return PILC_OK;
 }
 

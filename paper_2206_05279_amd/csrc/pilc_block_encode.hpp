@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kEncThreads) void k_encode_block(
         const uint32_t row = t / sh.tw;
         const uint32_t p = sh.first + row * g.w + (t - row * sh.tw);
         const size_t s = (size_t)p * 3;
-        const uint32_t im = p / g.hw;
+        const uint32_t im = g.by_hw.div(p);
 #pragma unroll
         for (int c = 0; c < 3; ++c) {
             in.x[c] = img[s + c];

@@ -101,6 +101,7 @@ struct Geo {
     uint32_t tiles_x, tiles_per_img;  // mode 1
     uint32_t total_px;                // n*h*w   (< 2^32 / 3)
     uint32_t lanes;
+    FastDiv by_hw;                    // which image a pixel belongs to: once a chunk or pixel in every kernel
 };
 
 // One lane's pixel set: `npx` pixels starting at flat pixel `first`, laid out as rows of `tw`
@@ -147,6 +148,7 @@ __device__ __forceinline__ uint32_t block_slot_end(const LaneShape &sh, uint32_t
 // Flat pixel index of the t-th pixel of a lane (rows of sh.tw pixels, g.w apart).
 __device__ __forceinline__ uint32_t lane_pixel(const Geo &g, const LaneShape &sh, uint32_t t)
 {
+    if (g.lane_mode == 0) return sh.first + t;  // a flat lane is one run of pixels (the same for every thread)
     uint32_t row = t / sh.tw;
     return sh.first + row * g.w + (t - row * sh.tw);
 }

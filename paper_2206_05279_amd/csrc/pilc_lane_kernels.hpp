@@ -312,7 +312,7 @@ __device__ __forceinline__ uint32_t encode_lane(const Geo &g, uint32_t lane, con
 
     auto encode_chunk = [&](const Chunk &ck, const ChunkPos cp) {
         // a chunk never straddles two images when kVec; otherwise take the image per pixel
-        uint32_t im = cp.p / g.hw;
+        uint32_t im = g.by_hw.div(cp.p);
         int a_gr = coef[3 * im], a_br = coef[3 * im + 1], a_bg = coef[3 * im + 2];
         // The chunk in two halves of four pixels, the later half first.  Phase 1 of a half:
         // (cum | freq << 16) of its 12 symbols; nothing there depends on the state, so the
@@ -327,7 +327,7 @@ __device__ __forceinline__ uint32_t encode_lane(const Geo &g, uint32_t lane, con
             for (int ii = 0; ii < kHalf; ++ii) {
                 const int i = kHalf * hb + ii;
                 if (!kVec && (uint32_t)i < cp.len) {
-                    const uint32_t im_i = (cp.p + i) / g.hw;
+                    const uint32_t im_i = g.by_hw.div(cp.p + i);
                     if (im_i != im) {
                         im = im_i;
                         a_gr = coef[3 * im]; a_br = coef[3 * im + 1]; a_bg = coef[3 * im + 2];
@@ -826,6 +826,8 @@ __global__ __launch_bounds__(kLaneMaxThreads) void k_decode_lanes(Geo g, const u
     // decodes the chunk into its 24 bytes (6 dwords)
     // tiles and flat lanes no longer than an image lie in one image: its coefficients are loaded once
     auto decode_chunk = [&](const Chunk &ck, const ChunkPos cp, uint32_t *wout) {
+        // (the plain division on purpose: with g.by_hw the whole-line variant needs 171 registers
+        // instead of 167 and loses its third wavefront per SIMD)
         uint32_t im = cp.p / g.hw;
         int a_gr = coef[3 * im], a_br = coef[3 * im + 1], a_bg = coef[3 * im + 2];
 #pragma unroll

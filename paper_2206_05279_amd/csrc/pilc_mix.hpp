@@ -414,7 +414,7 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_encode(
     if (ahead && sh.npx != 0u) mix_fetch_ahead<kK, kAheadW>(a, lane_pixel(g, sh, sh.npx - 1u), pre);
     for (uint32_t t = sh.npx; t-- > 0u;) {
         const uint32_t p = lane_pixel(g, sh, t);
-        const uint32_t im = p / g.hw;
+        const uint32_t im = g.by_hw.div(p);
         if (im != im_now) {
             im_now = im;
             a_gr = a.coef[3 * im]; a_br = a.coef[3 * im + 1]; a_bg = a.coef[3 * im + 2];
@@ -542,7 +542,7 @@ __global__ __launch_bounds__(kMixThreads) void k_mix_decode(
             run.begin(3 * (size_t)p);
         }
         p_next = p + 1u;
-        const uint32_t im = p / g.hw;
+        const uint32_t im = g.by_hw.div(p);
         if (im != im_now) {
             im_now = im;
             a_gr = a.coef[3 * im]; a_br = a.coef[3 * im + 1]; a_bg = a.coef[3 * im + 2];

@@ -162,7 +162,7 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_decode_rows(
         const uint32_t t = t0 + j;
         const uint32_t p = lane_pixel(g, sh, t < npx ? t : 0u);
         const size_t s = (size_t)p * 3;
-        const uint32_t im = p / g.hw;
+        const uint32_t im = g.by_hw.div(p);
 #pragma unroll
         for (int c = 0; c < 3; ++c) {
             r.m[c] = mu[s + c];
