@@ -276,26 +276,31 @@ __global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint3
 // Thread t of the workgroup runs t + 16 (t / 64) positions behind thread 0, so inside a wavefront
 // a row still gets the two values it needs from the row above by a cross-lane shift, and the first
 // row of a wavefront finds them in LDS, where the last row of the wavefront above left them 17
-// steps earlier; a workgroup barrier every 16 steps separates the two.  A thread reads and writes
-// its row in chunks of 16 pixels (48 bytes, three 16-byte accesses): the chunk it is in and the
-// next wait in a three-chunk ring in LDS, the one after that is on its way from memory in
-// registers, the one it left is written back.  The work goes in blocks of 16 steps: barrier, chunk
-// turn, then 16 steps without a branch on anything but the loop count (a step used to spend more
-// time in its dozen branches than in its arithmetic).
+// steps earlier; a workgroup barrier every 16 steps separates the two.  A row passes through a
+// three-chunk ring in LDS (a chunk is 16 pixels, 48 bytes): the chunk the row is in, the next one,
+// and the one it left, which is written back and then filled again; what is to fill it was asked
+// for a turn earlier and waits in registers.  The chunks of a wavefront's 64 rows are moved as 192
+// pieces of 16 bytes, three neighbouring threads taking the 48 contiguous bytes of one row.  The
+// work goes in blocks of 16 steps: barrier, chunk turn, then 16 steps without a branch on anything
+// but the loop count (a step used to spend more time in its dozen branches than in its arithmetic).
 //
-// kBands false: a workgroup per image; images with more rows than a workgroup has threads go in
-// rounds, the last row's red values of a round kept in LDS for the first row of the next.
+// kBands false: a workgroup per image, every wavefront turns the chunks of its own rows before its
+// 16 steps; images with more rows than a workgroup has threads go in rounds, the last row's red
+// values of a round kept in LDS for the first row of the next.
 // kBands true (few images): an image is cut into bands of rows, a workgroup per band, so that one
-// image keeps several compute units busy.  The first row of a band needs the red values of the last
-// row of the band above, which belongs to another workgroup: that row's thread publishes, after
-// every fourth chunk it has written back to the image, how many chunks of its row are final (a
+// image keeps several compute units busy.  Here the workgroup has a second set of wavefronts, the
+// movers: mover k turns the chunks of wavefront k's rows while wavefront k decodes (with one
+// or two decoding wavefronts on a SIMD a turn's trip to memory and back, a third of a block's
+// time, is not hidden by anything else).  The first row of a band needs the red values of the last
+// row of the band above, which belongs to another workgroup: the mover of that row publishes, after
+// every fourth chunk it has written back to the image, how many chunks of the row are final (a
 // counter per band in global memory, release / acquire at device scope), and three threads of the
-// band below fetch the chunk of that row two chunks ahead of their first row from the image as
-// soon as the counter allows.  Bands number themselves with a ticket taken at their start
-// (image-major), so the band above is always a workgroup that is already running, and it never
-// waits for the band below.  The wait is bounded by the constant-rate clock; a band that gives up
-// sets an abort word, every band that sees it while waiting leaves too, and the host returns
-// PILC_E_TIMEOUT.
+// first mover of the band below fetch the chunk of that row two chunks ahead of their first row
+// from the image as soon as the counter allows.  Bands number themselves with a ticket taken at
+// their start (image-major), so the band above is always a workgroup that is already running, and
+// it never waits for the band below.  The wait is bounded by the constant-rate clock; a band that
+// gives up sets an abort word, every band that sees it while waiting leaves too, and the host
+// returns PILC_E_TIMEOUT.
 constexpr int kTallLag = 16;         // steps between barriers = extra lag per wavefront
 constexpr int kTallChunk = 48;       // bytes of a chunk of 16 pixels
 constexpr int kTallRing = 3 * kTallChunk;
@@ -321,8 +326,12 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
     extern __shared__ uint8_t twar_lds[];
     __shared__ uint32_t s_id;
     __shared__ int s_abort;
-    const uint32_t nt = blockDim.x, waves = nt >> 6;
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    // (bands) the second half of the workgroup are the movers: wavefront waves + k moves the chunks of
+    // wavefront k's rows between memory and the ring while wavefront k decodes
+    const uint32_t nt = kBands ? blockDim.x >> 1 : blockDim.x, waves = nt >> 6;
+    const bool mover = kBands && threadIdx.x >= nt;
+    const uint32_t wave = (threadIdx.x >> 6) - (mover ? waves : 0u), lane = threadIdx.x & 63u;
+    const uint32_t thread = wave * 64u + lane;  // the row of the workgroup this thread decodes (a mover: none)
     uint32_t image = blockIdx.x, band = 0u, id = 0u;
     if (kBands) {
         if (threadIdx.x == 0u) {
@@ -334,7 +343,7 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
         image = id / tb.bands;
         band = id % tb.bands;
     }
-    uint8_t *my = twar_lds + (size_t)threadIdx.x * kTallStride;
+    uint8_t *my = twar_lds + (size_t)thread * kTallStride;
     uint8_t *hand = twar_lds + (size_t)nt * kTallStride;  // [wavefront][64]: red of its last row, by column mod 64
     // red of the row above the workgroup's first row: the whole row of the round before, or (bands) a
     // ring of 32 values filled from the image
@@ -342,8 +351,10 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
     const size_t row_bytes = (size_t)w * 3u;
     const int chunks = (int)(w >> 4);
     const int lag = (int)(wave * (64u + kTallLag));
-    // local steps -kTallLead .. w + 63 + 16: the last lane's last chunk is written back by then
-    const uint32_t total = kTallLead + w + 80u + (waves - 1u) * (64u + kTallLag);
+    // a mover asks for a chunk three turns before its row enters it, a decoding wavefront two
+    constexpr int kLead = kBands ? kTallLead + kTallLag : kTallLead;
+    // local steps -kLead .. w + 63 + 16: the last lane's last chunk is written back by then
+    const uint32_t total = kLead + w + 80u + (waves - 1u) * (64u + kTallLag);
     const uint32_t rows_here = kBands ? tb.band_rows : nt;
     // where the first thread of this wavefront finds the red values above its row
     const uint8_t *above_ptr = wave != 0u ? hand + (wave - 1u) * 64u : carry;
@@ -357,43 +368,111 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
     asm volatile("" : "+v"(w_r0), "+v"(w_r1), "+v"(w_g0), "+v"(w_g1), "+v"(w_b0), "+v"(w_b1));
 
     for (uint32_t round = 0; round < rounds; ++round) {
-        const uint32_t u = kBands ? band * tb.band_rows + threadIdx.x : round * nt + threadIdx.x;
-        const bool have = threadIdx.x < rows_here && u < h;
-        const size_t row_off = ((size_t)image * h + (have ? u : 0u)) * row_bytes;
-        const uint4 *src = reinterpret_cast<const uint4 *>(res + row_off);
-        uint4 *dst = reinterpret_cast<uint4 *>(img + row_off);
-        const bool last_row = have && (u + 1u == h || threadIdx.x + 1u == rows_here);
-        const bool keeps_row = !kBands && last_row;                          // leaves its red values for the next round
-        const bool publishes = kBands && last_row && band + 1u < tb.bands;   // tells the band below how far it is
+        const uint32_t u = kBands ? band * tb.band_rows + thread : round * nt + thread;
+        const bool have = !mover && thread < rows_here && u < h;
+        const bool last_row = have && (u + 1u == h || thread + 1u == rows_here);
+        const bool keeps_row = !kBands && last_row;  // leaves its red values for the next round
         const bool has_above = wave != 0u || (kBands ? band != 0u : round != 0u);
         // (bands) the three threads that fetch the row above the band, 16 bytes of a chunk each
-        const bool fetches = kBands && band != 0u && wave == 0u && lane < 3u;
+        const bool fetches = mover && band != 0u && wave == 0u && lane < 3u;
         const uint4 *above_src = reinterpret_cast<const uint4 *>(
             img + ((size_t)image * h + (kBands && band != 0u ? band * tb.band_rows - 1u : 0u)) * row_bytes);
         const uint32_t *above_progress = tb.progress + (id - (band != 0u ? 1u : 0u));
         uint4 above_ahead = make_uint4(0u, 0u, 0u, 0u);
         uint32_t above_done = 0u;  // chunks of the row above known to be final
 
+        // The 64 rows of a wavefront move one chunk on per turn, as 192 pieces of 16 bytes: piece k of
+        // the turn is piece k mod 3 of row k / 3, so three neighbouring threads move the 48 contiguous
+        // bytes of one row's chunk.  These are this thread's three pieces.
+        uint32_t piece_row[3];
+        bool piece_have[3];
+        const uint4 *piece_src[3];
+        uint4 *piece_dst[3];
+        uint8_t *piece_lds[3];
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const uint32_t k = 64u * i + lane, r = (k * 171u) >> 9, part = k - 3u * r;  // r = k / 3 for k < 192
+            const uint32_t t = wave * 64u + r;
+            const uint32_t ur = kBands ? band * tb.band_rows + t : round * nt + t;
+            piece_row[i] = r;
+            piece_have[i] = t < rows_here && ur < h;
+            const size_t off = ((size_t)image * h + (piece_have[i] ? ur : 0u)) * row_bytes + 16u * part;
+            piece_src[i] = reinterpret_cast<const uint4 *>(res + off);
+            piece_dst[i] = reinterpret_cast<uint4 *>(img + off);
+            piece_lds[i] = twar_lds + (size_t)t * kTallStride + 16u * part;
+        }
+        // (bands) the thread of the band's last row, which the band below waits for
+        const uint32_t pub_thread = kBands ? min(rows_here, h - band * tb.band_rows) - 1u : 0u;
+        const uint32_t pub_wave = kBands && band + 1u < tb.bands ? pub_thread >> 6 : 0xFFFFFFFFu;
+        const uint32_t pub_lane = pub_thread & 63u;
+        uint4 ahead[3] = {};  // this thread's three pieces of the chunks asked for in the last turn
+
+        // One chunk turn of the rows of this wavefront, whose thread 0 stands at column d0: row r is in
+        // chunk c = (d0 - r) >> 4.  Chunk c - 1 was left for good and is written back; chunk c + kFill,
+        // asked for a turn ago, goes into the ring; chunk c + kFill + 1 is asked for.  The ring has
+        // three slots (chunk mod 3): a decoding wavefront that turns its own rows fills the slot its
+        // rows enter during the coming 16 steps (kFill 1); a mover works beside the wavefront that is
+        // in chunks c and c + 1, so it fills the slot it has just read out (kFill 2), a turn before
+        // that wavefront needs it.  What is written back is read out of the ring first, and the
+        // stores are issued last: loads and stores share one counter of outstanding accesses, and
+        // a wait for last turn's loads placed after this turn's stores would wait for the stores too.
+        auto turn = [&](int d0, int kFill) {
+            uint4 back[3];
+            bool backs[3];
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                const int c_prev = ((d0 - (int)piece_row[i]) >> 4) - 1;
+                backs[i] = piece_have[i] && c_prev >= 0 && c_prev < chunks;
+                const uint32_t *q = reinterpret_cast<const uint32_t *>(
+                    piece_lds[i] + ((uint32_t)(c_prev + 48) % 3u) * kTallChunk);
+                back[i] = make_uint4(q[0], q[1], q[2], q[3]);
+            }
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                const int c_fill = ((d0 - (int)piece_row[i]) >> 4) + kFill;
+                if (piece_have[i] && c_fill >= 0 && c_fill < chunks) {
+                    uint32_t *q = reinterpret_cast<uint32_t *>(piece_lds[i] + ((uint32_t)(c_fill + 48) % 3u) * kTallChunk);
+                    q[0] = ahead[i].x;
+                    q[1] = ahead[i].y;
+                    q[2] = ahead[i].z;
+                    q[3] = ahead[i].w;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                const int c_ask = ((d0 - (int)piece_row[i]) >> 4) + kFill + 1;
+                // (a piece with nothing to ask for reads the row's first chunk: no branch round a load)
+                const bool asks = piece_have[i] && c_ask >= 0 && c_ask < chunks;
+                ahead[i] = piece_src[i][asks ? 3 * c_ask : 0];
+            }
+#pragma unroll
+            for (int i = 0; i < 3; ++i)
+                if (backs[i]) piece_dst[i][3 * (((d0 - (int)piece_row[i]) >> 4) - 1)] = back[i];
+            if (kBands && wave == pub_wave && !tb.withhold) {
+                // chunks 0 .. c - 1 of the band's last row are final; said every fourth chunk and at the
+                // end (a release at device scope writes the L2 back: too dear for every chunk).  The
+                // row's pieces were stored by threads of this wavefront: the fence is the wavefront's.
+                const int c = (d0 - (int)pub_lane) >> 4;
+                if (c >= 1 && c <= chunks && ((c & 3) == 0 || c == chunks)) {
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                    if (lane == pub_lane)
+                        __hip_atomic_store(tb.progress + id, (uint32_t)c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        };
+
         int rl = 0, gl = 0, bl = 0;
         int prev_up = 0;  // the red value above the pixel decoded last: above-left of the next one
         uint32_t ptr = 0;             // ring offset of the pixel about to be decoded
-        // the chunk index before that of column -kTallLead - lane (the first chunk turn moves on to
-        // it), and that index mod 3
-        int cur = (((int)-kTallLead - (int)lane) >> 4) - 1;
-        int cur3 = ((cur % 3) + 3) % 3;
-        uint4 ahead[3] = {};          // the chunk two after `cur`, on its way
         for (uint32_t D0 = 0; D0 < total; D0 += kTallLag) {
             __syncthreads();
             if (kBands && s_abort) return;  // the same for every thread: written before the barrier
-            const int d0 = (int)D0 - lag - kTallLead;  // this wavefront's step; lane 0 is at column d0
-            if (d0 < -kTallLead || d0 >= (int)(w + 80u)) continue;  // (the same for the whole wavefront)
-            // ---- chunk turn: every lane moves one chunk on within the next 16 steps ----
-            cur = (d0 - (int)lane) >> 4;
-            cur3 = cur3 == 2 ? 0 : cur3 + 1;
+            const int d0 = (int)D0 - lag - kLead;  // this wavefront's step; lane 0 is at column d0
+            if (d0 < -kLead || d0 >= (int)(w + 80u)) continue;  // (the same for the whole wavefront)
             if (fetches) {
-                // thread 0 enters chunk T now: the red values of chunk T + 1 of the row above, fetched a
-                // turn ago, go to the ring (a whole turn before thread 0 gets there), and chunk T + 2
-                // is fetched as soon as it is final
+                // thread 0 of the band enters chunk T now: the red values of chunk T + 1 of the row
+                // above, fetched a turn ago, go to the ring (the half that thread is not reading), and
+                // chunk T + 2 is fetched as soon as it is final
                 const int T = d0 >> 4;
                 if (T + 1 >= 0 && T + 1 < chunks) {
                     // this thread holds bytes 16 lane .. 16 lane + 15 of the chunk; red is every third
@@ -427,69 +506,65 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
                     if (!s_abort) above_ahead = above_src[3 * (T + 2) + (int)lane];
                 }
             }
-            if (have) {
-                const int nxt3 = cur3 == 2 ? 0 : cur3 + 1, prv3 = cur3 == 0 ? 2 : cur3 - 1;
-                if (cur - 1 >= 0 && cur - 1 < chunks) {  // written back: it was left for good
-                    const uint32_t *q = reinterpret_cast<const uint32_t *>(my + prv3 * kTallChunk);
-#pragma unroll
-                    for (int i = 0; i < 3; ++i)
-                        dst[3 * (cur - 1) + i] = make_uint4(q[4 * i], q[4 * i + 1], q[4 * i + 2], q[4 * i + 3]);
-                    // chunks 0 .. cur - 1 of this row are final; said every fourth chunk and at the end
-                    // (a release at device scope writes the L2 back: too dear for every chunk)
-                    if (publishes && !tb.withhold && ((cur & 3) == 0 || cur == chunks))
-                        __hip_atomic_store(tb.progress + id, (uint32_t)cur, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-                }
-                if (cur + 1 >= 0 && cur + 1 < chunks) {  // arrived: into the ring
-                    uint32_t *q = reinterpret_cast<uint32_t *>(my + nxt3 * kTallChunk);
-#pragma unroll
-                    for (int i = 0; i < 3; ++i) {
-                        q[4 * i] = ahead[i].x;
-                        q[4 * i + 1] = ahead[i].y;
-                        q[4 * i + 2] = ahead[i].z;
-                        q[4 * i + 3] = ahead[i].w;
-                    }
-                }
-                if (cur + 2 >= 0 && cur + 2 < chunks) {  // asked for
-#pragma unroll
-                    for (int i = 0; i < 3; ++i) ahead[i] = src[3 * (cur + 2) + i];
-                }
+            if (mover) {
+                turn(d0, 2);
+                continue;
             }
-            wave_lds_sync();
+            if (!kBands) {
+                turn(d0, 1);
+                wave_lds_sync();
+            }
             // ---- 16 steps ----
+            // A step's LDS reads (the pixel's three residual bytes, and for a wavefront's first
+            // thread the value above it) are asked for a step ahead: with one or two wavefronts on a
+            // SIMD nothing else covers their latency.  The next pixel's ring offset is never this
+            // pixel's, and the value above was written before the last barrier (17 steps earlier);
+            // what the last step asks for is not used.
             int v = d0 - (int)lane;
+            bool on = have && (uint32_t)v < w;
+            int e_r = my[ptr], e_g = my[ptr + 1u], e_b = my[ptr + 2u];
+            int above = has_above ? (int)above_ptr[(on ? (uint32_t)v : 0u) & above_mask] : 0;
+            uint8_t *const spare = my + kTallRing;  // the four bytes after the ring: where writes of idle steps go
 #pragma unroll 2
             for (int i = 0; i < kTallLag; ++i, ++v) {
-                const bool on = have && (uint32_t)v < w;
                 const uint32_t col = on ? (uint32_t)v : 0u;
+                const bool on_next = have && (uint32_t)(v + 1) < w;
+                const uint32_t nptr = ptr + 3u == (uint32_t)kTallRing ? 0u : ptr + 3u;
+                const uint32_t ptr_next = on ? nptr : ptr;
+                const int n_r = my[ptr_next], n_g = my[ptr_next + 1u], n_b = my[ptr_next + 2u];
+                const int above_next = has_above ? (int)above_ptr[(on_next ? (uint32_t)(v + 1) : 0u) & above_mask] : 0;
+                __builtin_amdgcn_sched_barrier(0);
                 int up = __builtin_amdgcn_update_dpp(0, rl, 0x138 /* wave_shr:1 */, 0xF, 0xF, true);
                 // the first thread of a wavefront: the row above belongs to another wavefront, to the
                 // round or band before, or is padding
-                const int above = has_above ? (int)above_ptr[col & above_mask] : 0;
                 up = first_lane ? above : up;
                 const int upleft = prev_up;
                 prev_up = on ? up : prev_up;
-                uint8_t *q = my + ptr;
+                uint8_t *q = on ? my + ptr : spare;
                 // three multiply-adds each; what only needs the pixel to the left comes first, the
                 // operand that arrives last (the value just decoded) goes into the last of them
                 auto clamp8 = [](int acc) { return min(max(acc >> 14, 0), 255); };
                 const int tg = mad_i24(w_g1, rl, mad_i24(w_g0, gl, bias_g));
                 const int tb = mad_i24(w_b1, gl, mad_i24(w_b0, bl, bias_b));
                 const int tr = mad_i24(w_r1, up, mad_i24(w_r0, upleft, bias_r));
-                const int xr = add_low_byte((int)q[0], clamp8(__mul24(p.w[0][2], rl) + tr));
-                const int xg = add_low_byte((int)q[1], clamp8(__mul24(p.w[1][2], xr) + tg));
-                const int xb = add_low_byte((int)q[2], clamp8(__mul24(p.w[2][2], xg) + tb));
-                if (on) {
-                    q[0] = (uint8_t)xr;
-                    q[1] = (uint8_t)xg;
-                    q[2] = (uint8_t)xb;
-                }
-                if (on && lane == 63u) hand[wave * 64u + (col & 63u)] = (uint8_t)xr;
+                const int xr = add_low_byte(e_r, clamp8(__mul24(p.w[0][2], rl) + tr));
+                const int xg = add_low_byte(e_g, clamp8(__mul24(p.w[1][2], xr) + tg));
+                const int xb = add_low_byte(e_b, clamp8(__mul24(p.w[2][2], xg) + tb));
+                q[0] = (uint8_t)xr;
+                q[1] = (uint8_t)xg;
+                q[2] = (uint8_t)xb;
+                uint8_t *const to_next_wave = on && lane == 63u ? hand + wave * 64u + (col & 63u) : spare + 3;
+                *to_next_wave = (uint8_t)xr;
                 if (on && keeps_row) carry[col] = (uint8_t)xr;
-                const uint32_t nptr = ptr + 3u == (uint32_t)kTallRing ? 0u : ptr + 3u;
-                ptr = on ? nptr : ptr;
+                ptr = ptr_next;
                 rl = on ? xr : rl;
                 gl = on ? xg : gl;
                 bl = on ? xb : bl;
+                e_r = n_r;
+                e_g = n_g;
+                e_b = n_b;
+                above = above_next;
+                on = on_next;
             }
         }
         __syncthreads();
@@ -608,8 +683,8 @@ int pilc_twar_inverse(uint32_t n, uint32_t h, uint32_t w, const uint8_t *res_dev
     Timer timer(stream);
     const bool tall = h > 64 && w % 16 == 0 && w <= 16384 && ((((uintptr_t)img_dev) | ((uintptr_t)res_dev)) & 15) == 0;
     // few tall images: bands of up to 384 rows in workgroups of their own (on 30 frames of
-    // 1080 x 1920: three bands of 360 rows 1.01 ms, four of 270 1.03, five of 216 1.07, six of 180
-    // 1.13, two of 540 1.14; one workgroup per frame 2.2)
+    // 1080 x 1920: three bands of 360 rows 0.74 ms, four of 270 0.77, five of 216 0.75, six of 180
+    // 0.79; one workgroup per frame 2.2)
     uint32_t bands = tall && n < 256u ? (h + 383u) / 384u : 1u;
     int slot = -1;
     uint32_t *flags = nullptr;
@@ -631,7 +706,8 @@ int pilc_twar_inverse(uint32_t n, uint32_t h, uint32_t w, const uint8_t *res_dev
             const TallBands tb = {bands, band_rows, flags, flags + kBandFlags, flags + kBandFlags + 1,
                                   wait ? wait : 2000ull * (unsigned long long)khz,
                                   (uint32_t)g_one_pass_withhold.load(std::memory_order_relaxed)};
-            k_twar_inverse_tall<true><<<n * bands, nt, lds, stream>>>(k, h, w, 1u, tb, res_dev, img_dev);
+            // a decoding and a moving wavefront per 64 rows
+            k_twar_inverse_tall<true><<<n * bands, 2u * nt, lds, stream>>>(k, h, w, 1u, tb, res_dev, img_dev);
             timer.mark("k_twar_inverse");
             hipError_t e = hipGetLastError();
             if (e == hipSuccess)
