@@ -294,7 +294,7 @@ int pilc_twar_forward(uint32_t n, uint32_t h, uint32_t w, const uint8_t *img_dev
 
 /* The image back from the residual (Sec. 3.1: the anti-diagonal / column schedule of the paper's
  * decoding figure, here one walk along the anti-diagonals of 64 rows per wavefront).  Fewer than
- * 256 images of more than 384 rows are cut into bands in workgroups of their own that follow each
+ * 256 images of more than 256 rows are cut into bands in workgroups of their own that follow each
  * other through counters in the library's device globals; their wait for the band above is bounded
  * like the one-pass encoder's (pilc_set_one_pass_wait) and ends in PILC_E_TIMEOUT.
  * Errors: PILC_E_ARG, PILC_E_TOO_LARGE, PILC_E_HIP, PILC_E_TIMEOUT (img_dev contents undefined). */

@@ -38,6 +38,20 @@ __device__ __forceinline__ int add_low_byte(int a, int b)
     return r;
 }
 
+// (byte kByte of a + b) mod 256
+template <int kByte>
+__device__ __forceinline__ int add_byte_of(uint32_t a, int b)
+{
+    int r;
+    if (kByte == 0)
+        asm("v_add_u32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:BYTE_0 src1_sel:DWORD" : "=v"(r) : "v"(a), "v"(b));
+    else if (kByte == 1)
+        asm("v_add_u32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:DWORD" : "=v"(r) : "v"(a), "v"(b));
+    else
+        asm("v_add_u32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:BYTE_2 src1_sel:DWORD" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
 // One thread per pixel.  A workgroup takes 256 / w whole rows (or one row, in steps of 256
 // pixels, when w > 256); neighbouring threads read neighbouring bytes and the row above comes from
 // the caches.
@@ -293,10 +307,11 @@ __global__ __launch_bounds__(64 * kTwarWaves) void k_twar_inverse(TwarK p, uint3
 // or two decoding wavefronts on a SIMD a turn's trip to memory and back, a third of a block's
 // time, is not hidden by anything else).  The first row of a band needs the red values of the last
 // row of the band above, which belongs to another workgroup: the mover of that row publishes, after
-// every fourth chunk it has written back to the image, how many chunks of the row are final (a
-// counter per band in global memory, release / acquire at device scope), and three threads of the
-// first mover of the band below fetch the chunk of that row two chunks ahead of their first row
-// from the image as soon as the counter allows.  Bands number themselves with a ticket taken at
+// every chunk it has written back to the image, how many chunks of the row are final (a counter per
+// band in global memory; the row's bytes and the count are stored at device scope, the count once
+// no store of the wavefront is outstanding), and three threads of the first mover of the band below
+// fetch the chunk of that row two chunks ahead of their first row from the image as soon as the
+// counter allows (acquire at device scope).  Bands number themselves with a ticket taken at
 // their start (image-major), so the band above is always a workgroup that is already running, and
 // it never waits for the band below.  The wait is bounded by the constant-rate clock; a band that
 // gives up sets an abort word, every band that sees it while waiting leaves too, and the host
@@ -405,6 +420,9 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
         const uint32_t pub_thread = kBands ? min(rows_here, h - band * tb.band_rows) - 1u : 0u;
         const uint32_t pub_wave = kBands && band + 1u < tb.bands ? pub_thread >> 6 : 0xFFFFFFFFu;
         const uint32_t pub_lane = pub_thread & 63u;
+        bool piece_published[3];
+#pragma unroll
+        for (int i = 0; i < 3; ++i) piece_published[i] = wave == pub_wave && piece_row[i] == pub_lane;
         uint4 ahead[3] = {};  // this thread's three pieces of the chunks asked for in the last turn
 
         // One chunk turn of the rows of this wavefront, whose thread 0 stands at column d0: row r is in
@@ -413,9 +431,10 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
         // three slots (chunk mod 3): a decoding wavefront that turns its own rows fills the slot its
         // rows enter during the coming 16 steps (kFill 1); a mover works beside the wavefront that is
         // in chunks c and c + 1, so it fills the slot it has just read out (kFill 2), a turn before
-        // that wavefront needs it.  What is written back is read out of the ring first, and the
-        // stores are issued last: loads and stores share one counter of outstanding accesses, and
-        // a wait for last turn's loads placed after this turn's stores would wait for the stores too.
+        // that wavefront needs it.  What is written back is read out of the ring first; the ring is
+        // filled before the stores are issued: loads and stores share one counter of outstanding
+        // accesses, and a wait for last turn's loads placed after this turn's stores would wait for
+        // the stores too.
         auto turn = [&](int d0, int kFill) {
             uint4 back[3];
             bool backs[3];
@@ -440,24 +459,38 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
             }
 #pragma unroll
             for (int i = 0; i < 3; ++i) {
+                if (!backs[i]) continue;
+                uint4 *to = piece_dst[i] + 3 * (((d0 - (int)piece_row[i]) >> 4) - 1);
+                if (kBands && piece_published[i]) {
+                    // the band's last row, which another workgroup reads: stores at device scope go
+                    // through to memory, so that no write-back of the whole L2 is needed to publish them
+                    uint32_t *t32 = reinterpret_cast<uint32_t *>(to);
+                    __hip_atomic_store(t32 + 0, back[i].x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(t32 + 1, back[i].y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(t32 + 2, back[i].z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(t32 + 3, back[i].w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    *to = back[i];
+                }
+            }
+            if (kBands && wave == pub_wave && !tb.withhold) {
+                // chunks 0 .. c - 1 of the band's last row are final.  Its pieces were stored by threads
+                // of this wavefront, at device scope; once the wavefront has no store outstanding they
+                // are in memory, and the count may follow (a release fence would do the same and also
+                // write the whole L2 back: 2.5 us each, a third of a block of 16 steps).
+                const int c = (d0 - (int)pub_lane) >> 4;
+                if (c >= 1 && c <= chunks) {
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                    if (lane == pub_lane)
+                        __hip_atomic_store(tb.progress + id, (uint32_t)c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
                 const int c_ask = ((d0 - (int)piece_row[i]) >> 4) + kFill + 1;
                 // (a piece with nothing to ask for reads the row's first chunk: no branch round a load)
                 const bool asks = piece_have[i] && c_ask >= 0 && c_ask < chunks;
                 ahead[i] = piece_src[i][asks ? 3 * c_ask : 0];
-            }
-#pragma unroll
-            for (int i = 0; i < 3; ++i)
-                if (backs[i]) piece_dst[i][3 * (((d0 - (int)piece_row[i]) >> 4) - 1)] = back[i];
-            if (kBands && wave == pub_wave && !tb.withhold) {
-                // chunks 0 .. c - 1 of the band's last row are final; said every fourth chunk and at the
-                // end (a release at device scope writes the L2 back: too dear for every chunk).  The
-                // row's pieces were stored by threads of this wavefront: the fence is the wavefront's.
-                const int c = (d0 - (int)pub_lane) >> 4;
-                if (c >= 1 && c <= chunks && ((c & 3) == 0 || c == chunks)) {
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-                    if (lane == pub_lane)
-                        __hip_atomic_store(tb.progress + id, (uint32_t)c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
             }
         };
 
@@ -519,20 +552,33 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
             // thread the value above it) are asked for a step ahead: with one or two wavefronts on a
             // SIMD nothing else covers their latency.  The next pixel's ring offset is never this
             // pixel's, and the value above was written before the last barrier (17 steps earlier);
-            // what the last step asks for is not used.
+            // what the last step asks for is not used.  They are read as the aligned dwords that hold
+            // them (two for the pixel: the second may be the spare bytes behind the ring) and taken
+            // apart when used: a byte read is widened where it is read, and that use would put the
+            // wait for it right behind the read.
             int v = d0 - (int)lane;
             bool on = have && (uint32_t)v < w;
-            int e_r = my[ptr], e_g = my[ptr + 1u], e_b = my[ptr + 2u];
-            int above = has_above ? (int)above_ptr[(on ? (uint32_t)v : 0u) & above_mask] : 0;
+            auto ring_dwords = [&](uint32_t at) { return reinterpret_cast<const uint32_t *>(my + (at & ~3u)); };
+            auto above_dword = [&](bool live, int column) {
+                const uint32_t at = (live ? (uint32_t)column : 0u) & above_mask;
+                return has_above ? reinterpret_cast<const uint32_t *>(above_ptr)[at >> 2] : 0u;
+            };
+            uint32_t e_lo = ring_dwords(ptr)[0], e_hi = ring_dwords(ptr)[1];
+            uint32_t above_in = above_dword(on, v);
             uint8_t *const spare = my + kTallRing;  // the four bytes after the ring: where writes of idle steps go
-#pragma unroll 2
+#pragma unroll
             for (int i = 0; i < kTallLag; ++i, ++v) {
+                // the wait for what the last step asked for stands here, before this step asks: LDS
+                // answers in order, and placed after the new reads it would wait for the first of them
+                asm volatile("" : "+v"(e_lo), "+v"(e_hi), "+v"(above_in));
                 const uint32_t col = on ? (uint32_t)v : 0u;
+                const uint32_t e = __builtin_amdgcn_alignbyte(e_hi, e_lo, ptr & 3u);  // bytes ptr .. ptr + 3 of the ring
+                const int above = (int)((above_in >> (8u * (col & above_mask & 3u))) & 0xFFu);
                 const bool on_next = have && (uint32_t)(v + 1) < w;
                 const uint32_t nptr = ptr + 3u == (uint32_t)kTallRing ? 0u : ptr + 3u;
                 const uint32_t ptr_next = on ? nptr : ptr;
-                const int n_r = my[ptr_next], n_g = my[ptr_next + 1u], n_b = my[ptr_next + 2u];
-                const int above_next = has_above ? (int)above_ptr[(on_next ? (uint32_t)(v + 1) : 0u) & above_mask] : 0;
+                const uint32_t n_lo = ring_dwords(ptr_next)[0], n_hi = ring_dwords(ptr_next)[1];
+                const uint32_t above_next = above_dword(on_next, v + 1);
                 __builtin_amdgcn_sched_barrier(0);
                 int up = __builtin_amdgcn_update_dpp(0, rl, 0x138 /* wave_shr:1 */, 0xF, 0xF, true);
                 // the first thread of a wavefront: the row above belongs to another wavefront, to the
@@ -547,9 +593,9 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
                 const int tg = mad_i24(w_g1, rl, mad_i24(w_g0, gl, bias_g));
                 const int tb = mad_i24(w_b1, gl, mad_i24(w_b0, bl, bias_b));
                 const int tr = mad_i24(w_r1, up, mad_i24(w_r0, upleft, bias_r));
-                const int xr = add_low_byte(e_r, clamp8(__mul24(p.w[0][2], rl) + tr));
-                const int xg = add_low_byte(e_g, clamp8(__mul24(p.w[1][2], xr) + tg));
-                const int xb = add_low_byte(e_b, clamp8(__mul24(p.w[2][2], xg) + tb));
+                const int xr = add_byte_of<0>(e, clamp8(__mul24(p.w[0][2], rl) + tr));
+                const int xg = add_byte_of<1>(e, clamp8(__mul24(p.w[1][2], xr) + tg));
+                const int xb = add_byte_of<2>(e, clamp8(__mul24(p.w[2][2], xg) + tb));
                 q[0] = (uint8_t)xr;
                 q[1] = (uint8_t)xg;
                 q[2] = (uint8_t)xb;
@@ -560,10 +606,9 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
                 rl = on ? xr : rl;
                 gl = on ? xg : gl;
                 bl = on ? xb : bl;
-                e_r = n_r;
-                e_g = n_g;
-                e_b = n_b;
-                above = above_next;
+                e_lo = n_lo;
+                e_hi = n_hi;
+                above_in = above_next;
                 on = on_next;
             }
         }
@@ -682,10 +727,10 @@ int pilc_twar_inverse(uint32_t n, uint32_t h, uint32_t w, const uint8_t *res_dev
     const int elem = unit_bytes % 16u == 0u && (both & 15) == 0 ? 16 : unit_bytes % 4u == 0u && (both & 3) == 0 ? 4 : 1;
     Timer timer(stream);
     const bool tall = h > 64 && w % 16 == 0 && w <= 16384 && ((((uintptr_t)img_dev) | ((uintptr_t)res_dev)) & 15) == 0;
-    // few tall images: bands of up to 384 rows in workgroups of their own (on 30 frames of
-    // 1080 x 1920: three bands of 360 rows 0.74 ms, four of 270 0.77, five of 216 0.75, six of 180
-    // 0.79; one workgroup per frame 2.2)
-    uint32_t bands = tall && n < 256u ? (h + 383u) / 384u : 1u;
+    // few tall images: bands of up to 256 rows in workgroups of their own, four decoding wavefronts
+    // (one per SIMD) and their four movers (on 30 frames of 1080 x 1920: five bands of 216 rows
+    // 0.58 ms, six of 180 0.61, three of 360 0.62, four of 270 0.63; one workgroup per frame 2.2)
+    uint32_t bands = tall && n < 256u ? (h + 255u) / 256u : 1u;
     int slot = -1;
     uint32_t *flags = nullptr;
     if (bands > 1u && (uint64_t)n * bands <= kBandFlags) flags = band_flags_acquire(&slot);

@@ -18,10 +18,10 @@ SHAPES = [(1, 1, 1), (3, 32, 32), (5, 7, 9), (2, 64, 64), (7, 16, 16), (2, 33, 5
           # bands under way at once; one band and a bit, a band boundary at the last row, three
           # rounds of a workgroup, a full-size frame
           (3, 65, 16), (2, 128, 48), (1, 1600, 32), (2, 1080, 1920),
-          # few images taller than 384 rows: bands of an image in workgroups of their own that follow
-          # each other through counters in global memory (two bands of 350 rows; six of 350; two of
-          # 193, the second of which ends with a wavefront of a single row)
-          (2, 700, 64), (1, 2100, 160), (3, 385, 32),
+          # few images taller than 256 rows: bands of an image in workgroups of their own that follow
+          # each other through counters in global memory (three bands of 234 rows; nine of 234; two
+          # of 193 and two of 129, whose last wavefront has a single row; two full bands of 256)
+          (2, 700, 64), (1, 2100, 160), (3, 385, 32), (3, 257, 32), (2, 512, 48),
           # many images with more rows than a workgroup has threads: rounds within a workgroup
           (256, 800, 16),
           # more groups of small images: eight images a group, rows of 27 dwords, an odd number of
