@@ -959,11 +959,11 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
                                               (g.lane_a * g.lane_b) % kRowBatch == 0);
         const uint32_t nblk = (uint32_t)ceil_div64(g.lanes, kRowLanes);
         if (even)
-            k_decode_rows<false><<<nblk, 64 * kRowWaves, 0, stream>>>(
+            k_decode_rows<false><<<nblk, 2 * 64 * kRowWaves, 0, stream>>>(
                 g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev,
                 &status->code, &status->payload_bytes);
         else
-            k_decode_rows<true><<<nblk, 64 * kRowWaves, 0, stream>>>(
+            k_decode_rows<true><<<nblk, 2 * 64 * kRowWaves, 0, stream>>>(
                 g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev,
                 &status->code, &status->payload_bytes);
     } else {

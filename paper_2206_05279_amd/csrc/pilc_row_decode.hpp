@@ -23,8 +23,13 @@
 //   - per-pixel parameters are prepared 16 pixels at a time, one pixel per thread, two batches
 //     ahead of their use, and handed over through LDS; the 96 stream words a batch can reach are
 //     fetched a batch ahead and wait in LDS, and the word a refill would take is read ahead of
-//     time.
-// Every loop has a trip count fixed by the geometry.
+//     time;
+//   - none of that, nor the stores of the decoded pixels, is done by the wavefront that decodes:
+//     every decoding wavefront has a second wavefront on its SIMD, its stager, which does it a
+//     batch ahead in the issue slots the decoder leaves empty (a decoder that staged its own
+//     batches spent 6 % of its time on it).  The two hand over through counts in LDS.
+// Every loop has a trip count fixed by the geometry; the waits of the hand-over are bounded by the
+// constant-rate clock and end in a time-out error.
 #pragma once
 
 #include <type_traits>
@@ -93,8 +98,10 @@ struct RowCand {
     bool ok;  // the 24-bit evaluation is exact for this window
 };
 
+constexpr unsigned long long kRowWaitTicks = 200000000ull;  // 2 s of the 100 MHz clock: a partner that never answers
+
 template <bool kRagged>
-__global__ __launch_bounds__(64 * kRowWaves) void k_decode_rows(
+__global__ __launch_bounds__(2 * 64 * kRowWaves) void k_decode_rows(
     Geo g, const uint8_t *__restrict__ coded, const uint16_t *__restrict__ mu,
     const int16_t *__restrict__ ls, const int16_t *__restrict__ coef, uint8_t *__restrict__ out,
     int *__restrict__ status_code, const unsigned long long *__restrict__ status_payload)
@@ -102,12 +109,30 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_decode_rows(
     __shared__ LdsTables tab;
     __shared__ RowPixel stage[2][kRowLanes][kRowBatch];
     __shared__ uint16_t words[2][kRowLanes][kRowWords];
-    load_tables(tab);
+    // The workgroup has two wavefronts per four lanes: one decodes, the other (its stager) prepares
+    // the next batch's parameters and stream words in LDS meanwhile.  What passes between them:
+    __shared__ uint32_t s_word_base[2][kRowLanes];  // stream position of words[buf][lane][0]
+    // Of batch b, in slot b & 1: the lane's stream position at its start and its 16 decoded pixels.
+    // (The decoder writes a slot again two batches later, and cannot start that batch before the
+    // stager, which reads the slot first, has staged it.)
+    __shared__ uint32_t s_pos[2][kRowLanes];
+    __shared__ uint32_t s_out[2][kRowLanes][kRowBatch];
+    __shared__ uint32_t s_posted[kRowWaves];        // batches the decoding wavefront has finished
+    __shared__ uint32_t s_staged[kRowWaves];        // batches the stager has made ready
+    __shared__ uint32_t s_abort;                    // a wait was given up: everybody leaves
+    if (threadIdx.x < (uint32_t)kRowWaves) {
+        s_posted[threadIdx.x] = 0u;
+        s_staged[threadIdx.x] = 0u;
+    }
+    if (threadIdx.x == 0u) s_abort = 0u;
+    load_tables(tab);  // ends with a barrier
     if (*status_code != 0) return;
 
-    const uint32_t tid = threadIdx.x & 63u;
+    const bool stager = threadIdx.x >= 64u * kRowWaves;
+    const uint32_t tix = threadIdx.x - (stager ? 64u * kRowWaves : 0u);  // index among the threads of its kind
+    const uint32_t tid = tix & 63u, wv = tix >> 6;
     const uint32_t j = tid & 15u, gbase = tid & 48u;
-    const uint32_t lrow = threadIdx.x >> 4;  // lane slot of the workgroup
+    const uint32_t lrow = tix >> 4;  // lane slot of the workgroup
     // a row beyond the last lane decodes the last lane once more and keeps the result to itself,
     // so that every row of a wavefront always does valid work
     const bool has_lane = blockIdx.x * kRowLanes + lrow < g.lanes;
@@ -289,31 +314,81 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_decode_rows(
         return (uint32_t)kb + n - 1u;
     };
 
-    uint32_t search_batches = 0;  // wavefront-uniform: batches still to decode by search alone
-    // ---- prologue: batch 0 staged, batch 1 in flight ----
-    put_stage(fetch_raw(0), 0);
-    Raw raw_next = fetch_raw(kRowBatch);
-    Ahead ahead = fetch_words(pos);
-    uint32_t ahead_base = pos;
+    // Hand-over between a decoding wavefront and its stager: a count in LDS, raised by one thread
+    // after the wavefront's LDS writes are done, and waited for by the whole partner wavefront.  A
+    // wait is bounded by the constant-rate clock; who gives up says so to everybody (no wavefront
+    // is left waiting) and the call ends in a time-out error.
+    auto raise = [&](uint32_t *count, uint32_t value) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        if (tid == 0u) __hip_atomic_store(count, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+    auto wait_for = [&](uint32_t *count, uint32_t value) -> bool {
+        if (__hip_atomic_load(count, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) >= value) return true;
+        const unsigned long long since = wall_clock64();
+        for (;;) {
+            if (__hip_atomic_load(count, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) >= value) return true;
+            if (__hip_atomic_load(&s_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) != 0u) return false;
+            if (wall_clock64() - since > kRowWaitTicks) {
+                __hip_atomic_store(&s_abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (tid == 0u) atomicMax(status_code, 8);
+                return false;
+            }
+            __builtin_amdgcn_s_sleep(8);
+        }
+    };
+    auto put_words = [&](const Ahead &a, uint32_t buf, uint32_t from) {
+#pragma unroll
+        for (int r = 0; r < kRowWords / 16; ++r) words[buf][lrow][16 * r + j] = (uint16_t)a.w[r];
+        if (j == 0u) s_word_base[buf][lrow] = from;
+    };
 
+    // the pixels of the batch that began at pixel t0 of the lane, from slot `slot`, to the image
+    auto store_batch = [&](uint32_t t0, uint32_t slot) {
+        const uint32_t nb = t0 < npx ? min((uint32_t)kRowBatch, npx - t0) : 0u;
+        if (j < nb && has_lane) {
+            const uint32_t v = s_out[slot][lrow][j];
+            const size_t s = (size_t)lane_pixel(g, sh, t0 + j) * 3;
+            out[s] = (uint8_t)v;
+            out[s + 1] = (uint8_t)(v >> 8);
+            out[s + 2] = (uint8_t)(v >> 16);
+        }
+    };
+
+    if (stager) {
+        // Batch 0 first; then, while the partner decodes batch b, the parameters of batch b + 1 (loaded
+        // a batch ago) and its stream words: the 112 words from where the stream stood when batch b
+        // began, of which batch b takes at most 48 and batch b + 1 at most 48 more; and the pixels of
+        // batch b - 1 go to the image.
+        put_stage(fetch_raw(0), 0);
+        Raw raw_next = fetch_raw(kRowBatch);
+        put_words(fetch_words(pos), 0u, pos);
+        raise(&s_staged[wv], 1u);
+        uint32_t from = pos, t0 = 0, b = 0;
+        for (; __any(t0 < npx); t0 += kRowBatch, ++b) {
+            const uint32_t buf = b & 1u;
+            if (b != 0u) {
+                // the partner has finished batch b - 1: buffer buf ^ 1 is free, and the position is known
+                if (!wait_for(&s_posted[wv], b)) return;
+                from = s_pos[buf][lrow];
+                store_batch(t0 - kRowBatch, buf ^ 1u);
+            }
+            const Ahead ahead = fetch_words(from);
+            put_stage(raw_next, buf ^ 1u);
+            raw_next = fetch_raw(t0 + 2 * kRowBatch);
+            put_words(ahead, buf ^ 1u, from);
+            raise(&s_staged[wv], b + 2u);
+        }
+        if (b != 0u && wait_for(&s_posted[wv], b)) store_batch(t0 - kRowBatch, (b & 1u) ^ 1u);  // the last batch's pixels
+        return;
+    }
+
+    uint32_t search_batches = 0;  // wavefront-uniform: batches still to decode by search alone
     for (uint32_t t0 = 0, b = 0; __any(t0 < npx); t0 += kRowBatch, ++b) {
         const uint32_t buf = b & 1u;
         const uint32_t nb = t0 < npx ? min((uint32_t)kRowBatch, npx - t0) : 0u;
-        // this batch's words (fetched a batch ago, from where the stream stood then) into LDS, and
-        // the next batch's requested, from where the stream stands now
+        if (!wait_for(&s_staged[wv], b + 1u)) break;
         my_words = words[buf][lrow];
-        wbase = ahead_base;
-#pragma unroll
-        for (int r = 0; r < kRowWords / 16; ++r) words[buf][lrow][16 * r + j] = (uint16_t)ahead.w[r];
-        ahead = fetch_words(pos);
-        ahead_base = pos;
-        // the next batch's parameters: staged now from the registers loaded a batch ago, and the
-        // batch after that requested
-        put_stage(raw_next, buf ^ 1u);
-        raw_next = fetch_raw(t0 + 2 * kRowBatch);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        wbase = s_word_base[buf][lrow];
         wnext = my_words[pos - wbase];
 
         const RowPixel *px = stage[buf][lrow];
@@ -401,12 +476,10 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_decode_rows(
             }
             if (redone >= (uint32_t)kRowRedoLimit) search_batches = kRowSearchBatches;
         }
-        if (j < nb && has_lane) {
-            const size_t s = (size_t)lane_pixel(g, sh, t0 + j) * 3;
-            out[s] = (uint8_t)v_out;
-            out[s + 1] = (uint8_t)(v_out >> 8);
-            out[s + 2] = (uint8_t)(v_out >> 16);
-        }
+        // the pixels and the position go to the stager, which may then go on to the batch after next
+        s_out[buf][lrow][j] = v_out;
+        if (j == 0u) s_pos[buf ^ 1u][lrow] = pos;
+        raise(&s_posted[wv], b + 1u);
     }
     if (has_lane && npx != 0u && (S != (1u << 16) || pos != stop) && j == 0) atomicMax(status_code, 6);
 }
