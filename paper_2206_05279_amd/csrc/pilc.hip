@@ -958,14 +958,21 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
                                            : (g.h % g.lane_a == 0 && g.w % g.lane_b == 0 &&
                                               (g.lane_a * g.lane_b) % kRowBatch == 0);
         const uint32_t nblk = (uint32_t)ceil_div64(g.lanes, kRowLanes);
-        if (even)
-            k_decode_rows<false><<<nblk, 2 * 64 * kRowWaves, 0, stream>>>(
-                g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev,
-                &status->code, &status->payload_bytes);
-        else
-            k_decode_rows<true><<<nblk, 2 * 64 * kRowWaves, 0, stream>>>(
-                g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev,
-                &status->code, &status->payload_bytes);
+        // a stager beside every decoding wavefront while one workgroup per compute unit holds all lanes
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        const bool staged = nblk <= (uint32_t)cus;
+#define PILC_DECODE_ROWS(RAGGED, STAGED)                                                              \
+    k_decode_rows<RAGGED, STAGED><<<nblk, (STAGED ? 2 : 1) * 64 * kRowWaves, 0, stream>>>(           \
+        g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev, &status->code,   \
+        &status->payload_bytes)
+        if (even && staged) PILC_DECODE_ROWS(false, true);
+        else if (even) PILC_DECODE_ROWS(false, false);
+        else if (staged) PILC_DECODE_ROWS(true, true);
+        else PILC_DECODE_ROWS(true, false);
+#undef PILC_DECODE_ROWS
     } else {
         const int bt = lane_block_threads(g);
         const uint32_t nb = (uint32_t)ceil_div64(g.lanes, bt);

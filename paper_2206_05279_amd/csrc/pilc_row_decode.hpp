@@ -87,7 +87,7 @@ struct RowPixel {
     uint4 r;  // m_r (Q8.8), 1/s of R split, 1/s of R whole
     uint4 a;  // m_g, m_b (Q8.8), a_gr, a_br (Q2.14, sign-extended)
     uint4 b;  // a_bg, 1/s of G split, 1/s of B >> 17
-    uint4 c;  // 1/s of B & 0x1FFFF, 1/s of G whole, 1/s of B whole, unused
+    uint4 c;  // 1/s of B & 0x1FFFF, 1/s of G whole, 1/s of B whole, window of R: base | exact << 16
 };
 
 // The candidates of one symbol as a thread holds them: C(k) at k = base + 2 j and base + 2 j + 1
@@ -100,8 +100,12 @@ struct RowCand {
 
 constexpr unsigned long long kRowWaitTicks = 200000000ull;  // 2 s of the 100 MHz clock: a partner that never answers
 
-template <bool kRagged>
-__global__ __launch_bounds__(2 * 64 * kRowWaves) void k_decode_rows(
+// kStaged: with a stager per decoding wavefront (see above).  That form keeps twice the LDS per
+// lane (the first channel's candidates of two batches), so only one workgroup of 16 lanes fits a
+// compute unit; it is for batches of up to 16 lanes per compute unit.  Without it a decoding
+// wavefront stages its own batches, and two workgroups share a compute unit.
+template <bool kRagged, bool kStaged>
+__global__ __launch_bounds__((kStaged ? 2 : 1) * 64 * kRowWaves) void k_decode_rows(
     Geo g, const uint8_t *__restrict__ coded, const uint16_t *__restrict__ mu,
     const int16_t *__restrict__ ls, const int16_t *__restrict__ coef, uint8_t *__restrict__ out,
     int *__restrict__ status_code, const unsigned long long *__restrict__ status_payload)
@@ -109,6 +113,9 @@ __global__ __launch_bounds__(2 * 64 * kRowWaves) void k_decode_rows(
     __shared__ LdsTables tab;
     __shared__ RowPixel stage[2][kRowLanes][kRowBatch];
     __shared__ uint16_t words[2][kRowLanes][kRowWords];
+    // C(k) at the two candidates of every thread for the first channel of every pixel of a batch,
+    // 16 bits each (a candidate is at most 255, so C is below 2^M <= 2^16)
+    __shared__ uint32_t first_cand[kStaged ? 2 : 1][kStaged ? kRowLanes : 1][kRowBatch][16];
     // The workgroup has two wavefronts per four lanes: one decodes, the other (its stager) prepares
     // the next batch's parameters and stream words in LDS meanwhile.  What passes between them:
     __shared__ uint32_t s_word_base[2][kRowLanes];  // stream position of words[buf][lane][0]
@@ -116,7 +123,7 @@ __global__ __launch_bounds__(2 * 64 * kRowWaves) void k_decode_rows(
     // (The decoder writes a slot again two batches later, and cannot start that batch before the
     // stager, which reads the slot first, has staged it.)
     __shared__ uint32_t s_pos[2][kRowLanes];
-    __shared__ uint32_t s_out[2][kRowLanes][kRowBatch];
+    __shared__ uint32_t s_out[2][kStaged ? kRowLanes : 1][kRowBatch];
     __shared__ uint32_t s_posted[kRowWaves];        // batches the decoding wavefront has finished
     __shared__ uint32_t s_staged[kRowWaves];        // batches the stager has made ready
     __shared__ uint32_t s_abort;                    // a wait was given up: everybody leaves
@@ -128,7 +135,7 @@ __global__ __launch_bounds__(2 * 64 * kRowWaves) void k_decode_rows(
     load_tables(tab);  // ends with a barrier
     if (*status_code != 0) return;
 
-    const bool stager = threadIdx.x >= 64u * kRowWaves;
+    const bool stager = kStaged && threadIdx.x >= 64u * kRowWaves;
     const uint32_t tix = threadIdx.x - (stager ? 64u * kRowWaves : 0u);  // index among the threads of its kind
     const uint32_t tid = tix & 63u, wv = tix >> 6;
     const uint32_t j = tid & 15u, gbase = tid & 48u;
@@ -196,13 +203,16 @@ __global__ __launch_bounds__(2 * 64 * kRowWaves) void k_decode_rows(
         }
         return r;
     };
+    auto window_base = [](int me) { return min(max((me - (256 * (kRowWindow / 2 - 1) - 128)) >> 8, 0), kRowBaseMax); };
+    auto window_exact = [](int me) { return (uint32_t)(me + 8576) <= (uint32_t)(73600 + 8576); };
     auto put_stage = [&](const Raw &r, uint32_t buf) {
         const uint32_t i0 = inv_scale(r.l[0], tab), i1 = inv_scale(r.l[1], tab), i2 = inv_scale(r.l[2], tab);
         RowPixel px;
         px.r = make_uint4(r.m[0], i0 >> 17, i0 & 0x1FFFFu, i0);
         px.a = make_uint4(r.m[1], r.m[2], (uint32_t)r.a[0], (uint32_t)r.a[1]);
         px.b = make_uint4((uint32_t)r.a[2], i1 >> 17, i1 & 0x1FFFFu, i2 >> 17);
-        px.c = make_uint4(i2 & 0x1FFFFu, i1, i2, 0u);
+        px.c = make_uint4(i2 & 0x1FFFFu, i1, i2,
+                          (uint32_t)window_base((int)r.m[0]) | (window_exact((int)r.m[0]) ? 1u << 16 : 0u));
         stage[buf][lrow][j] = px;
     };
 
@@ -223,8 +233,8 @@ __global__ __launch_bounds__(2 * 64 * kRowWaves) void k_decode_rows(
     const int j2 = 2 * (int)j;
     auto aim = [&](int me, uint32_t inv_hi, uint32_t inv_lo) {
         RowAim am;
-        am.base = min(max((me - (256 * (kRowWindow / 2 - 1) - 128)) >> 8, 0), kRowBaseMax);
-        am.ok = (uint32_t)(me + 8576) <= (uint32_t)(73600 + 8576);
+        am.base = window_base(me);
+        am.ok = window_exact(me);
         am.k0 = am.base + j2;
         const int d0 = 256 * am.k0 - 128 - me;
 #pragma unroll
@@ -236,9 +246,8 @@ __global__ __launch_bounds__(2 * 64 * kRowWaves) void k_decode_rows(
         }
         return am;
     };
-    auto finish = [&](const RowAim &am) {
-        RowCand cd;
-        uint32_t cv[2];
+    // C(k) at the thread's two candidates, from the cells `aim` asked for
+    auto cum_pair = [&](const RowAim &am, uint32_t cv[2]) {
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
             const uint32_t f24 =
@@ -246,19 +255,41 @@ __global__ __launch_bounds__(2 * 64 * kRowWaves) void k_decode_rows(
             cv[c] = (uint32_t)(am.k0 + c) + ((uint32_t)__umul24(f24, sp8) >> 16);
         }
         cv[0] = am.k0 == 0 ? 0u : cv[0];  // C(0) = 0
-        // the second candidate is followed by the next thread's first; candidate 31 by C(base + 32),
-        // which is known only when it is C(256) = 2^M
-        const uint32_t from_next = row_next(cv[0]);
-        const uint32_t after = j == 15u ? (am.base == kRowBaseMax ? top : cv[1]) : from_next;
-        cd.cv0 = cv[0];
-        cd.cv1 = cv[1];
-        cd.f0 = cv[1] - cv[0];
-        cd.f1 = after - cv[1];
-        cd.base = am.base;
-        cd.ok = am.ok;
+    };
+    // The candidates of a symbol from its two values of C.  The second candidate is followed by the
+    // next thread's first; candidate 31 by C(base + 32), which is known only when it is C(256) = 2^M.
+    auto with_masses = [&](uint32_t cv0, uint32_t cv1, int base, bool ok) {
+        RowCand cd;
+        const uint32_t from_next = row_next(cv0);
+        const uint32_t after = j == 15u ? (base == kRowBaseMax ? top : cv1) : from_next;
+        cd.cv0 = cv0;
+        cd.cv1 = cv1;
+        cd.f0 = cv1 - cv0;
+        cd.f1 = after - cv1;
+        cd.base = base;
+        cd.ok = ok;
         return cd;
     };
-    auto candidates = [&](int me, uint32_t inv_hi, uint32_t inv_lo) { return finish(aim(me, inv_hi, inv_lo)); };
+    auto finish = [&](const RowAim &am) {
+        uint32_t cv[2];
+        cum_pair(am, cv);
+        return with_masses(cv[0], cv[1], am.base, am.ok);
+    };
+    // the same for a pixel's first channel, whose two values of C the stager has left in LDS
+    auto first_channel = [&](uint32_t pair, uint32_t window) {
+        return with_masses(pair & 0xFFFFu, pair >> 16, (int)(window & 0xFFFFu), (window >> 16) != 0u);
+    };
+    // (stager) the first channel of the 16 pixels staged in `buf`, every thread its two candidates
+    auto put_first_cand = [&](uint32_t buf) {
+        wave_lds_sync();  // the parameters were written by this wavefront
+#pragma unroll 4
+        for (int i = 0; i < kRowBatch; ++i) {
+            const uint4 r = stage[buf][lrow][i].r;
+            uint32_t cv[2];
+            cum_pair(aim((int)r.x, r.y, r.z), cv);
+            first_cand[buf][lrow][i][j] = cv[0] | (cv[1] << 16);
+        }
+    };
 
     const uint32_t xw0 = 2u * j | 256u, xw1 = xw0 | 1u;  // what a winning candidate contributes
     const uint16_t *my_words = words[0][lrow];  // the current batch's words, from `wbase` on
@@ -354,13 +385,14 @@ __global__ __launch_bounds__(2 * 64 * kRowWaves) void k_decode_rows(
         }
     };
 
-    if (stager) {
+    if (kStaged && stager) {
         // Batch 0 first; then, while the partner decodes batch b, the parameters of batch b + 1 (loaded
         // a batch ago) and its stream words: the 112 words from where the stream stood when batch b
         // began, of which batch b takes at most 48 and batch b + 1 at most 48 more; and the pixels of
         // batch b - 1 go to the image.
         put_stage(fetch_raw(0), 0);
         Raw raw_next = fetch_raw(kRowBatch);
+        put_first_cand(0u);
         put_words(fetch_words(pos), 0u, pos);
         raise(&s_staged[wv], 1u);
         uint32_t from = pos, t0 = 0, b = 0;
@@ -375,6 +407,7 @@ __global__ __launch_bounds__(2 * 64 * kRowWaves) void k_decode_rows(
             const Ahead ahead = fetch_words(from);
             put_stage(raw_next, buf ^ 1u);
             raw_next = fetch_raw(t0 + 2 * kRowBatch);
+            put_first_cand(buf ^ 1u);
             put_words(ahead, buf ^ 1u, from);
             raise(&s_staged[wv], b + 2u);
         }
@@ -383,12 +416,36 @@ __global__ __launch_bounds__(2 * 64 * kRowWaves) void k_decode_rows(
     }
 
     uint32_t search_batches = 0;  // wavefront-uniform: batches still to decode by search alone
+    // (without a stager) batch 0 staged, batch 1 in flight
+    Raw raw_next = {};
+    Ahead ahead = {};
+    uint32_t ahead_base = pos;
+    if (!kStaged) {
+        put_stage(fetch_raw(0), 0);
+        raw_next = fetch_raw(kRowBatch);
+        ahead = fetch_words(pos);
+    }
     for (uint32_t t0 = 0, b = 0; __any(t0 < npx); t0 += kRowBatch, ++b) {
         const uint32_t buf = b & 1u;
         const uint32_t nb = t0 < npx ? min((uint32_t)kRowBatch, npx - t0) : 0u;
-        if (!wait_for(&s_staged[wv], b + 1u)) break;
-        my_words = words[buf][lrow];
-        wbase = s_word_base[buf][lrow];
+        if (kStaged) {
+            if (!wait_for(&s_staged[wv], b + 1u)) break;
+            my_words = words[buf][lrow];
+            wbase = s_word_base[buf][lrow];
+        } else {
+            // this batch's words (fetched a batch ago, from where the stream stood then) into LDS, the
+            // next batch's requested from where the stream stands now; the next batch's parameters
+            // staged from the registers loaded a batch ago, and the batch after that requested
+            my_words = words[buf][lrow];
+            wbase = ahead_base;
+#pragma unroll
+            for (int r = 0; r < kRowWords / 16; ++r) words[buf][lrow][16 * r + j] = (uint16_t)ahead.w[r];
+            ahead = fetch_words(pos);
+            ahead_base = pos;
+            put_stage(raw_next, buf ^ 1u);
+            raw_next = fetch_raw(t0 + 2 * kRowBatch);
+            wave_lds_sync();
+        }
         wnext = my_words[pos - wbase];
 
         const RowPixel *px = stage[buf][lrow];
@@ -424,6 +481,7 @@ __global__ __launch_bounds__(2 * 64 * kRowWaves) void k_decode_rows(
             auto pixel = [&](uint32_t i, const RowPixel &cur, RowPixel &nxt, RowCand &cr) {
                 const bool act = i < nb;
                 nxt = px[(i + 1u) & (kRowBatch - 1)];
+                const uint32_t next_pair = kStaged ? first_cand[buf][lrow][(i + 1u) & (kRowBatch - 1)][j] : 0u;
                 __builtin_amdgcn_sched_barrier(0);  // asked for here, used a pixel later
                 const int m_r = (int)cur.r.x, m_g = (int)cur.a.x, m_b = (int)cur.a.y;
                 const int a_gr = (int)cur.a.z, a_br = (int)cur.a.w, a_bg = (int)cur.b.x;
@@ -435,18 +493,28 @@ __global__ __launch_bounds__(2 * 64 * kRowWaves) void k_decode_rows(
                 const int me_g = m_g + rsh14_mad(a_gr, e_r);
                 const RowAim ag = aim(me_g, cur.b.y, cur.b.z);
                 __builtin_amdgcn_sched_barrier(0);
-                // the next pixel's first channel depends on no decoded value: its arithmetic fills
-                // the waits for the table cells of the two channels that do
-                const RowAim an = aim((int)nxt.r.x, nxt.r.y, nxt.r.z);
                 const int mb1 = m_b + rsh14_mad(a_br, e_r);
+                // The next pixel's first channel depends on no decoded value.  The stager has evaluated
+                // it, and what is left to do fills the wait for this channel's table cells; without a
+                // stager its evaluation fills the waits of the two channels that do depend.
+                RowCand cr_next = {};
+                RowAim an = {};
+                if (kStaged)
+                    cr_next = first_channel(next_pair, nxt.c.w);
+                else
+                    an = aim((int)nxt.r.x, nxt.r.y, nxt.r.z);
                 __builtin_amdgcn_sched_barrier(0);
                 const RowCand cg = finish(ag);
                 uint32_t x_g = decode_symbol(act, cg, seen);
                 const int me_b = mb1 + rsh14_mad(a_bg, (int)(x_g << 8) - m_g);
                 const RowAim ab = aim(me_b, cur.b.w, cur.c.x);
                 __builtin_amdgcn_sched_barrier(0);
-                cr = finish(an);
-                __builtin_amdgcn_sched_barrier(0);
+                if (kStaged) {
+                    cr = cr_next;
+                } else {
+                    cr = finish(an);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
                 const RowCand cb = finish(ab);
                 uint32_t x_b = decode_symbol(act, cb, seen);
 
@@ -469,17 +537,25 @@ __global__ __launch_bounds__(2 * 64 * kRowWaves) void k_decode_rows(
                 v_out = j == i ? (x_r | (x_g << 8) | (x_b << 16)) : v_out;
             };
             RowPixel pe = px[0], po;
-            RowCand cr = candidates((int)pe.r.x, pe.r.y, pe.r.z);
+            RowCand cr = kStaged ? first_channel(first_cand[buf][lrow][0][j], pe.c.w)
+                                 : finish(aim((int)pe.r.x, pe.r.y, pe.r.z));
             for (uint32_t i = 0; kRagged ? __any(i < nb) : i < (uint32_t)kRowBatch; i += 2) {
                 pixel(i, pe, po, cr);
                 pixel(i + 1u, po, pe, cr);
             }
             if (redone >= (uint32_t)kRowRedoLimit) search_batches = kRowSearchBatches;
         }
-        // the pixels and the position go to the stager, which may then go on to the batch after next
-        s_out[buf][lrow][j] = v_out;
-        if (j == 0u) s_pos[buf ^ 1u][lrow] = pos;
-        raise(&s_posted[wv], b + 1u);
+        if (kStaged) {
+            // the pixels and the position go to the stager, which may then go on to the batch after next
+            s_out[buf][lrow][j] = v_out;
+            if (j == 0u) s_pos[buf ^ 1u][lrow] = pos;
+            raise(&s_posted[wv], b + 1u);
+        } else if (j < nb && has_lane) {
+            const size_t s = (size_t)lane_pixel(g, sh, t0 + j) * 3;
+            out[s] = (uint8_t)v_out;
+            out[s + 1] = (uint8_t)(v_out >> 8);
+            out[s + 2] = (uint8_t)(v_out >> 16);
+        }
     }
     if (has_lane && npx != 0u && (S != (1u << 16) || pos != stop) && j == 0) atomicMax(status_code, 6);
 }

@@ -56,6 +56,9 @@ SMALL_CASES = [
     ("wild-single-pixel-lanes", lambda: synth.make_random_case(5, 2, 7, 9, 14, 0, 1, wild=True)),
     ("one-pixel", lambda: synth.make_random_case(6, 1, 1, 1, 12, 0, 1, wild=True)),
     ("one-lane-whole-batch", lambda: synth.make_random_case(7, 4, 16, 16, 15, 0, 4 * 256)),
+    # more lanes than one workgroup of the few-lane decoder per compute unit can hold, of uneven length:
+    # the form of that decoder whose wavefronts stage their own batches
+    ("wild-5720-clipped-tile-lanes", lambda: synth.make_random_case(8, 40, 37, 41, 13, 1, 3, 4, wild=True)),
 ]
 
 
