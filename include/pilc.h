@@ -46,8 +46,8 @@ enum {
     PILC_E_CORRUPT = -6,   /* decode: offsets not monotone or out of bounds, a lane runs
                               past its end, or does not return to its initial state         */
     PILC_E_HIP = -7,       /* HIP runtime failure (see pilc_last_hip_error)                 */
-    PILC_E_TIMEOUT = -8    /* encode: a bounded wait between workgroups ran out (see
-                              pilc_set_one_pass_wait); coded_dev contents undefined         */
+    PILC_E_TIMEOUT = -8    /* a bounded wait between workgroups or wavefronts ran out (see
+                              pilc_set_one_pass_wait); outputs undefined                    */
 };
 
 /* Geometry of a batch.  M = prec_bits is the constant of Sec. 3.2 for which every
@@ -194,7 +194,9 @@ int pilc_set_kernel_policy(int policy);
  * ends.
  * `withhold_first` != 0 makes the first workgroup publish nothing, which forces that path: for
  * tests of the give-up path only.  The same bound and switch apply to the bands of
- * pilc_twar_inverse.  Process-wide. */
+ * pilc_twar_inverse and to pilc_decode with few lanes, where every decoding wavefront waits for
+ * a second one that prepares its next batch (the switch: nothing is ever said to be ready).
+ * Process-wide. */
 void pilc_set_one_pass_wait(uint64_t ticks, int withhold_first);
 
 /* ------------------------------------------------------------------------------------------

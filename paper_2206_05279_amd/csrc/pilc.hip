@@ -959,15 +959,20 @@ int pilc_decode(const pilc_geom *geom, const uint8_t *coded_dev, size_t coded_by
                                               (g.lane_a * g.lane_b) % kRowBatch == 0);
         const uint32_t nblk = (uint32_t)ceil_div64(g.lanes, kRowLanes);
         // a stager beside every decoding wavefront while one workgroup per compute unit holds all lanes
-        int dev = 0, cus = 0;
+        int dev = 0, cus = 0, khz = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
             cus = 256;
+        if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0) khz = 100000;
         const bool staged = nblk <= (uint32_t)cus;
+        // the bound of the waits between a decoding wavefront and its stager, and the test switch
+        const unsigned long long asked = g_one_pass_wait.load(std::memory_order_relaxed);
+        const unsigned long long wait_ticks = asked ? asked : 2000ull * (unsigned long long)khz;
+        const uint32_t withhold = (uint32_t)g_one_pass_withhold.load(std::memory_order_relaxed);
 #define PILC_DECODE_ROWS(RAGGED, STAGED)                                                              \
     k_decode_rows<RAGGED, STAGED><<<nblk, (STAGED ? 2 : 1) * 64 * kRowWaves, 0, stream>>>(           \
         g, coded_dev, params->mu, params->log_scale, params->chan_coef, img_out_dev, &status->code,   \
-        &status->payload_bytes)
+        &status->payload_bytes, wait_ticks, withhold)
         if (even && staged) PILC_DECODE_ROWS(false, true);
         else if (even) PILC_DECODE_ROWS(false, false);
         else if (staged) PILC_DECODE_ROWS(true, true);

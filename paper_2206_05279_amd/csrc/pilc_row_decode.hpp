@@ -98,8 +98,6 @@ struct RowCand {
     bool ok;  // the 24-bit evaluation is exact for this window
 };
 
-constexpr unsigned long long kRowWaitTicks = 200000000ull;  // 2 s of the 100 MHz clock: a partner that never answers
-
 // kStaged: with a stager per decoding wavefront (see above).  That form keeps twice the LDS per
 // lane (the first channel's candidates of two batches), so only one workgroup of 16 lanes fits a
 // compute unit; it is for batches of up to 16 lanes per compute unit.  Without it a decoding
@@ -108,8 +106,12 @@ template <bool kRagged, bool kStaged>
 __global__ __launch_bounds__((kStaged ? 2 : 1) * 64 * kRowWaves) void k_decode_rows(
     Geo g, const uint8_t *__restrict__ coded, const uint16_t *__restrict__ mu,
     const int16_t *__restrict__ ls, const int16_t *__restrict__ coef, uint8_t *__restrict__ out,
-    int *__restrict__ status_code, const unsigned long long *__restrict__ status_payload)
+    int *__restrict__ status_code, const unsigned long long *__restrict__ status_payload,
+    unsigned long long wait_ticks, uint32_t withhold)
 {
+    // wait_ticks: the bound of a wait between a decoding wavefront and its stager, in ticks of the
+    // constant-rate clock; withhold: the stagers never say that a batch is ready (tests of the
+    // give-up path)
     __shared__ LdsTables tab;
     __shared__ RowPixel stage[2][kRowLanes][kRowBatch];
     __shared__ uint16_t words[2][kRowLanes][kRowWords];
@@ -359,7 +361,7 @@ __global__ __launch_bounds__((kStaged ? 2 : 1) * 64 * kRowWaves) void k_decode_r
         for (;;) {
             if (__hip_atomic_load(count, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) >= value) return true;
             if (__hip_atomic_load(&s_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) != 0u) return false;
-            if (wall_clock64() - since > kRowWaitTicks) {
+            if (wall_clock64() - since > wait_ticks) {
                 __hip_atomic_store(&s_abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 if (tid == 0u) atomicMax(status_code, 8);
                 return false;
@@ -394,7 +396,7 @@ __global__ __launch_bounds__((kStaged ? 2 : 1) * 64 * kRowWaves) void k_decode_r
         Raw raw_next = fetch_raw(kRowBatch);
         put_first_cand(0u);
         put_words(fetch_words(pos), 0u, pos);
-        raise(&s_staged[wv], 1u);
+        if (!withhold) raise(&s_staged[wv], 1u);
         uint32_t from = pos, t0 = 0, b = 0;
         for (; __any(t0 < npx); t0 += kRowBatch, ++b) {
             const uint32_t buf = b & 1u;
@@ -409,7 +411,7 @@ __global__ __launch_bounds__((kStaged ? 2 : 1) * 64 * kRowWaves) void k_decode_r
             raw_next = fetch_raw(t0 + 2 * kRowBatch);
             put_first_cand(buf ^ 1u);
             put_words(ahead, buf ^ 1u, from);
-            raise(&s_staged[wv], b + 2u);
+            if (!withhold) raise(&s_staged[wv], b + 2u);
         }
         if (b != 0u && wait_for(&s_posted[wv], b)) store_batch(t0 - kRowBatch, (b & 1u) ^ 1u);  // the last batch's pixels
         return;

@@ -137,6 +137,27 @@ def test_one_pass_encoder_gives_up_a_wait_that_is_never_answered():
         pb.pilc_set_kernel_policy(0)
 
 
+def test_few_lane_decoder_gives_up_a_wait_that_is_never_answered():
+    """A decoding wavefront of the few-lane decoder waits for its stager to say that a batch is
+    ready.  With the stagers made silent (a switch that exists for this test) and a bound of 20
+    microseconds every decoding wavefront must give up, the kernel must end, and the call must say
+    PILC_E_TIMEOUT; the next ordinary call works."""
+    wl = synth.make_workload(1, 16 * 9)
+    d = DeviceWorkload(wl)
+    rc, _ = d.encode()
+    assert rc == pb.PILC_OK
+    pb.pilc_set_kernel_policy(2)
+    try:
+        pb.pilc_set_one_pass_wait(2000, True)
+        assert d.decode(check=False) == pb.PILC_E_TIMEOUT
+        pb.pilc_set_one_pass_wait(0, False)
+        assert d.decode() == pb.PILC_OK
+        assert np.array_equal(d.decoded_numpy(), wl.img)
+    finally:
+        pb.pilc_set_one_pass_wait(0, False)
+        pb.pilc_set_kernel_policy(0)
+
+
 def test_damaged_containers_give_error_codes_never_faults(policy):
     wl = synth.make_workload(0, 4)
     d = DeviceWorkload(wl)
