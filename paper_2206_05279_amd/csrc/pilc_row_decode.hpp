@@ -133,9 +133,16 @@ __global__ __launch_bounds__((kStaged ? 2 : 1) * 64 * kRowWaves) void k_decode_r
         s_posted[threadIdx.x] = 0u;
         s_staged[threadIdx.x] = 0u;
     }
-    if (threadIdx.x == 0u) s_abort = 0u;
+    // Whether the call has failed already is looked at once for the whole workgroup: were every
+    // wavefront to look for itself, another workgroup's error could come between the looks, and a
+    // wavefront would wait for a partner that has left.
+    __shared__ int s_failed;
+    if (threadIdx.x == 0u) {
+        s_abort = 0u;
+        s_failed = *status_code;
+    }
     load_tables(tab);  // ends with a barrier
-    if (*status_code != 0) return;
+    if (s_failed != 0) return;
 
     const bool stager = kStaged && threadIdx.x >= 64u * kRowWaves;
     const uint32_t tix = threadIdx.x - (stager ? 64u * kRowWaves : 0u);  // index among the threads of its kind
