@@ -62,6 +62,26 @@ def test_forward_and_inverse_match_the_reference(shape):
         assert np.array_equal(d_back.cpu().numpy(), to.inverse(to.make_params(wq, bq), noise)), name
 
 
+def test_thirty_frames_come_back_every_time():
+    """The workload bench.py times (30 frames of 1080 x 1920, five bands each, 150 workgroups that
+    follow each other through the image itself): the inverse of the forward transform is the
+    image, on five calls in a row into a buffer poisoned before each, compared on the device.  A
+    band that read a row of the band above before it was there would pick up the poison."""
+    g = torch.Generator().manual_seed(11)
+    img = torch.randint(0, 256, (30, 1080, 1920, 3), dtype=torch.uint8, generator=g).cuda()
+    p = pb.make_twar_params([[-ONE, ONE, ONE], [ONE // 2, -ONE // 2, ONE], [ONE // 2, -ONE // 2, ONE]], [0, 0, 0])
+    res = torch.empty_like(img)
+    back = torch.empty_like(img)
+    pb.pilc_twar_forward(p, img, res)
+    # two frames of the residual against the CPU reference
+    assert np.array_equal(res[:2].cpu().numpy(), to.forward(to.make_params(
+        [[-ONE, ONE, ONE], [ONE // 2, -ONE // 2, ONE], [ONE // 2, -ONE // 2, ONE]], [0, 0, 0]), img[:2].cpu().numpy()))
+    for turn in range(5):
+        back.fill_(0xA5 ^ turn)
+        pb.pilc_twar_inverse(p, res, back)
+        assert torch.equal(back, img), turn
+
+
 def test_bands_give_up_a_wait_that_is_never_answered():
     """A band of a tall image waits for the last row of the band above.  With that row made to
     publish nothing (a switch that exists for this test) and a bound of 20 microseconds the band
