@@ -31,7 +31,17 @@ __device__ __forceinline__ uint32_t frac32(uint32_t a, uint32_t f)
     return (q1 << 16) | q0;
 }
 
-// Record of one symbol for the chain: { T, m, add, sh | k << 8 } such that one step is
+// v >> (top byte of w): one instruction that takes its shift count from byte 3 of a register
+__device__ __forceinline__ uint32_t shift_right_by_top_byte(uint32_t v, uint32_t w)
+{
+    uint32_t r;
+    asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3 src1_sel:DWORD"
+        : "=v"(r)
+        : "v"(w), "v"(v));
+    return r;
+}
+
+// Record of one symbol for the chain: { T, m, add, k | sh << 24 } such that one step is
 //     if (S > T) { emit low 16 bits; S >>= 16; }
 //     t = mulhi(m, S);  q = (t + ((S - t) >> 1)) >> sh;  S = S + add + q * k.
 // For f >= 2 this is App. A eq. (11) with the division by f done by multiplication (Granlund &
@@ -39,13 +49,15 @@ __device__ __forceinline__ uint32_t frac32(uint32_t a, uint32_t f)
 // T = (f << (32-M)) - 1, add = cum, k = 2^M - f, since (q << M) + (S - q f) + cum = S + cum + q k.
 // For f = 1 the same formula with m = 2^32 - 1, sh = 0 yields q = S - 1, so add = cum + 2^M - 1
 // makes up for the missing k.  An all-identity record (T = 2^32 - 1, add = k = 0) skips a slot.
+// k and sh share a word without any unpacking: the 24-bit multiply looks at the low 24 bits only,
+// and the shift takes its count from the top byte.
 __device__ __forceinline__ uint4 encode_record(uint32_t cum, uint32_t f, uint32_t m_bits)
 {
     const uint32_t k = (1u << m_bits) - f;
-    if (f == 1u) return make_uint4((1u << (32u - m_bits)) - 1u, 0xFFFFFFFFu, cum + k, k << 8);
+    if (f == 1u) return make_uint4((1u << (32u - m_bits)) - 1u, 0xFFFFFFFFu, cum + k, k);
     const uint32_t l = 32u - (uint32_t)__clz(f - 1u);
     const uint32_t magic = frac32((1u << l) - f, f) + 1u;
-    return make_uint4((f << (32u - m_bits)) - 1u, magic, cum, (l - 1u) | (k << 8));
+    return make_uint4((f << (32u - m_bits)) - 1u, magic, cum, k | ((l - 1u) << 24));
 }
 
 __global__ __launch_bounds__(kEncThreads) void k_encode_block(
@@ -79,7 +91,7 @@ __global__ __launch_bounds__(kEncThreads) void k_encode_block(
     uint32_t S = 1u << 16;
     // index into scratch, one past the lane's slot (block_slot_end: one spare word below every slot)
     const uint32_t slot_end = block_slot_end(sh, lane0 + (has_lane ? my : 0u));
-    uint32_t wpos = slot_end;
+    uint32_t wat = slot_end - 1u;  // where the next word goes: just below the lane's words so far
 
     // producers: the nine input values of the pixel of batch b, loaded one batch ahead
     struct PixelIn {
@@ -133,12 +145,14 @@ __global__ __launch_bounds__(kEncThreads) void k_encode_block(
             // and the slot has room for one per symbol, so the store stays in the slot, or, for the
             // empty steps after a lane's last symbol, in the spare word below it.
             const bool emit = S > r[k].x;
-            scratch[wpos - 1u] = (uint16_t)(S & 0xFFFFu);
-            wpos -= emit ? 1u : 0u;
+            scratch[wat] = (uint16_t)(S & 0xFFFFu);
+            wat -= emit ? 1u : 0u;
             S = emit ? S >> 16 : S;
             const uint32_t t = __umulhi(r[k].y, S);
-            const uint32_t quo = (t + ((S - t) >> 1)) >> (r[k].w & 31u);
-            S = S + r[k].z + __umul24(quo, r[k].w >> 8);
+            // the shift count is the top byte of the record's last word (picked by the shift itself),
+            // the multiplier its low 24 bits (all the 24-bit multiply looks at)
+            const uint32_t quo = shift_right_by_top_byte(t + ((S - t) >> 1), r[k].w);
+            S = S + r[k].z + __umul24(quo, r[k].w);
         }
     };
 
@@ -160,7 +174,7 @@ __global__ __launch_bounds__(kEncThreads) void k_encode_block(
         __syncthreads();
     }
     if (!producer && has_lane) {
-        lane_words[lane0 + my] = slot_end - wpos;
+        lane_words[lane0 + my] = slot_end - 1u - wat;
         lane_state[lane0 + my] = S;
     }
 }
