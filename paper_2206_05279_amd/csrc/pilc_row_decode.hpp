@@ -318,6 +318,9 @@ __global__ __launch_bounds__((kStaged ? 2 : 1) * 64 * kRowWaves) void k_decode_r
         uint32_t s_new = (win0 ? s0 : 0u) | (win1 ? s1 : 0u);
         uint32_t xw = (win0 ? xw0 : 0u) | (win1 ? xw1 : 0u);
         row_or2(xw, s_new);
+        // (kept as one value: left free, the compiler splits the last step of the reduction into a
+        // move, an OR and a three-operand AND for the two uses of xw below, four instructions for two)
+        asm("" : "+v"(xw));
         seen &= cd.ok ? xw : 0u;
         const bool refill = s_new < (1u << 16);
         const uint32_t s_ref = (s_new << 16) | wnext;
