@@ -548,37 +548,39 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
                 wave_lds_sync();
             }
             // ---- 16 steps ----
-            // A step's LDS reads (the pixel's three residual bytes, and for a wavefront's first
-            // thread the value above it) are asked for a step ahead: with one or two wavefronts on a
-            // SIMD nothing else covers their latency.  The next pixel's ring offset is never this
-            // pixel's, and the value above was written before the last barrier (17 steps earlier);
-            // what the last step asks for is not used.  They are read as the aligned dwords that hold
-            // them (two for the pixel: the second may be the spare bytes behind the ring) and taken
-            // apart when used: a byte read is widened where it is read, and that use would put the
-            // wait for it right behind the read.
+            // A step's LDS reads (the pixel's three residual bytes) are asked for a step ahead: with
+            // one or two wavefronts on a SIMD nothing else covers their latency.  The next pixel's
+            // ring offset is never this pixel's; what the last step asks for is not used.  They are
+            // read as the two aligned dwords that hold them (the second may be the spare bytes
+            // behind the ring) and taken apart when used: a byte read is widened where it is read,
+            // and that use would put the wait for it right behind the read.
+            // The values above the 16 pixels that the wavefront's first thread decodes in this block
+            // (columns d0 .. d0 + 15: 16 neighbouring bytes, all written before the last barrier, the
+            // last of them 17 steps ago) are read once, by every thread alike.
             int v = d0 - (int)lane;
             bool on = have && (uint32_t)v < w;
             auto ring_dwords = [&](uint32_t at) { return reinterpret_cast<const uint32_t *>(my + (at & ~3u)); };
-            auto above_dword = [&](bool live, int column) {
-                const uint32_t at = (live ? (uint32_t)column : 0u) & above_mask;
-                return has_above ? reinterpret_cast<const uint32_t *>(above_ptr)[at >> 2] : 0u;
-            };
+            uint32_t above16[4] = {0u, 0u, 0u, 0u};
+            if (has_above) {
+                const uint32_t at = (d0 >= 0 && (uint32_t)d0 < w ? (uint32_t)d0 : 0u) & above_mask;
+                const uint32_t *a = reinterpret_cast<const uint32_t *>(above_ptr + at);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) above16[k] = a[k];
+            }
             uint32_t e_lo = ring_dwords(ptr)[0], e_hi = ring_dwords(ptr)[1];
-            uint32_t above_in = above_dword(on, v);
             uint8_t *const spare = my + kTallRing;  // the four bytes after the ring: where writes of idle steps go
 #pragma unroll
             for (int i = 0; i < kTallLag; ++i, ++v) {
                 // the wait for what the last step asked for stands here, before this step asks: LDS
                 // answers in order, and placed after the new reads it would wait for the first of them
-                asm volatile("" : "+v"(e_lo), "+v"(e_hi), "+v"(above_in));
+                asm volatile("" : "+v"(e_lo), "+v"(e_hi));
                 const uint32_t col = on ? (uint32_t)v : 0u;
                 const uint32_t e = __builtin_amdgcn_alignbyte(e_hi, e_lo, ptr & 3u);  // bytes ptr .. ptr + 3 of the ring
-                const int above = (int)((above_in >> (8u * (col & above_mask & 3u))) & 0xFFu);
+                const int above = (int)((above16[i >> 2] >> (8 * (i & 3))) & 0xFFu);
                 const bool on_next = have && (uint32_t)(v + 1) < w;
                 const uint32_t nptr = ptr + 3u == (uint32_t)kTallRing ? 0u : ptr + 3u;
                 const uint32_t ptr_next = on ? nptr : ptr;
                 const uint32_t n_lo = ring_dwords(ptr_next)[0], n_hi = ring_dwords(ptr_next)[1];
-                const uint32_t above_next = above_dword(on_next, v + 1);
                 __builtin_amdgcn_sched_barrier(0);
                 int up = __builtin_amdgcn_update_dpp(0, rl, 0x138 /* wave_shr:1 */, 0xF, 0xF, true);
                 // the first thread of a wavefront: the row above belongs to another wavefront, to the
@@ -608,7 +610,6 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
                 bl = on ? xb : bl;
                 e_lo = n_lo;
                 e_hi = n_hi;
-                above_in = above_next;
                 on = on_next;
             }
         }
