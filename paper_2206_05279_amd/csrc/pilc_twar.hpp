@@ -548,12 +548,18 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
                 wave_lds_sync();
             }
             // ---- 16 steps ----
-            // A step's LDS reads (the pixel's three residual bytes) are asked for a step ahead: with
-            // one or two wavefronts on a SIMD nothing else covers their latency.  The next pixel's
-            // ring offset is never this pixel's; what the last step asks for is not used.  They are
-            // read as the two aligned dwords that hold them (the second may be the spare bytes
-            // behind the ring) and taken apart when used: a byte read is widened where it is read,
-            // and that use would put the wait for it right behind the read.
+            // The 16 steps.  Within a pixel green waits for red and blue for green, three chains of
+            // dependent instructions one after the other, and a wavefront alone on its SIMD has
+            // nothing else to issue meanwhile; red of the next pixel, however, only needs red.  So
+            // the channels run skewed: turn i decodes red of pixel i, green of pixel i - 1 and blue
+            // of pixel i - 2, which do not depend on each other, and two more turns drain the block
+            // (at its end every pixel is whole, as the chunk turns and the barrier expect).
+            // A pixel's three residual bytes are asked for a step ahead, as the two aligned dwords
+            // that hold them (the second may be the spare bytes behind the ring), and taken apart
+            // when used: a byte read is widened where it is read, and that use would put the wait for
+            // it right behind the read; the wait stands before the next reads are issued, because
+            // LDS answers in order.  The next pixel's ring offset is never this pixel's; what the
+            // last step asks for is not used.
             // The values above the 16 pixels that the wavefront's first thread decodes in this block
             // (columns d0 .. d0 + 15: 16 neighbouring bytes, all written before the last barrier, the
             // last of them 17 steps ago) are read once, by every thread alike.
@@ -569,48 +575,78 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
             }
             uint32_t e_lo = ring_dwords(ptr)[0], e_hi = ring_dwords(ptr)[1];
             uint8_t *const spare = my + kTallRing;  // the four bytes after the ring: where writes of idle steps go
+            auto clamp8 = [](int acc) { return min(max(acc >> 14, 0), 255); };
+            // what a pixel's later channels need from its earlier ones, one and two turns later
+            struct InFlight {
+                uint32_t e;     // its residual bytes
+                uint8_t *q;     // where it goes in the ring (the spare bytes for an idle step)
+                bool on;
+                int left_r, xr; // red to its left, its own red
+                int left_g, xg; // green to its left, its own green
+            };
+            InFlight one = {}, two = {};  // the pixels of one and two turns ago
 #pragma unroll
-            for (int i = 0; i < kTallLag; ++i, ++v) {
-                // the wait for what the last step asked for stands here, before this step asks: LDS
-                // answers in order, and placed after the new reads it would wait for the first of them
-                asm volatile("" : "+v"(e_lo), "+v"(e_hi));
-                const uint32_t col = on ? (uint32_t)v : 0u;
-                const uint32_t e = __builtin_amdgcn_alignbyte(e_hi, e_lo, ptr & 3u);  // bytes ptr .. ptr + 3 of the ring
-                const int above = (int)((above16[i >> 2] >> (8 * (i & 3))) & 0xFFu);
-                const bool on_next = have && (uint32_t)(v + 1) < w;
-                const uint32_t nptr = ptr + 3u == (uint32_t)kTallRing ? 0u : ptr + 3u;
-                const uint32_t ptr_next = on ? nptr : ptr;
-                const uint32_t n_lo = ring_dwords(ptr_next)[0], n_hi = ring_dwords(ptr_next)[1];
-                __builtin_amdgcn_sched_barrier(0);
-                int up = __builtin_amdgcn_update_dpp(0, rl, 0x138 /* wave_shr:1 */, 0xF, 0xF, true);
-                // the first thread of a wavefront: the row above belongs to another wavefront, to the
-                // round or band before, or is padding
-                up = first_lane ? above : up;
-                const int upleft = prev_up;
-                prev_up = on ? up : prev_up;
-                uint8_t *q = on ? my + ptr : spare;
+            for (int i = 0; i < kTallLag + 2; ++i) {
+                InFlight now = {};
+                int xr = 0;
+                if (i < kTallLag) {
+                    // the wait for what the last step asked for stands here, before this step asks
+                    asm volatile("" : "+v"(e_lo), "+v"(e_hi));
+                    now.on = on;
+                    now.e = __builtin_amdgcn_alignbyte(e_hi, e_lo, ptr & 3u);  // bytes ptr .. ptr + 3 of the ring
+                    now.q = on ? my + ptr : spare;
+                    const uint32_t nptr = ptr + 3u == (uint32_t)kTallRing ? 0u : ptr + 3u;
+                    ptr = on ? nptr : ptr;
+                    e_lo = ring_dwords(ptr)[0];
+                    e_hi = ring_dwords(ptr)[1];
+                }
+                // ---- red of this turn's pixel, green of the one before, blue of the one before that:
                 // three multiply-adds each; what only needs the pixel to the left comes first, the
                 // operand that arrives last (the value just decoded) goes into the last of them
-                auto clamp8 = [](int acc) { return min(max(acc >> 14, 0), 255); };
-                const int tg = mad_i24(w_g1, rl, mad_i24(w_g0, gl, bias_g));
-                const int tb = mad_i24(w_b1, gl, mad_i24(w_b0, bl, bias_b));
-                const int tr = mad_i24(w_r1, up, mad_i24(w_r0, upleft, bias_r));
-                const int xr = add_byte_of<0>(e, clamp8(__mul24(p.w[0][2], rl) + tr));
-                const int xg = add_byte_of<1>(e, clamp8(__mul24(p.w[1][2], xr) + tg));
-                const int xb = add_byte_of<2>(e, clamp8(__mul24(p.w[2][2], xg) + tb));
-                q[0] = (uint8_t)xr;
-                q[1] = (uint8_t)xg;
-                q[2] = (uint8_t)xb;
-                uint8_t *const to_next_wave = on && lane == 63u ? hand + wave * 64u + (col & 63u) : spare + 3;
-                *to_next_wave = (uint8_t)xr;
-                if (on && keeps_row) carry[col] = (uint8_t)xr;
-                ptr = ptr_next;
-                rl = on ? xr : rl;
-                gl = on ? xg : gl;
-                bl = on ? xb : bl;
-                e_lo = n_lo;
-                e_hi = n_hi;
-                on = on_next;
+                int acc_r = 0, acc_g = 0, acc_b = 0;
+                if (i < kTallLag) {
+                    const int above = (int)((above16[i >> 2] >> (8 * (i & 3))) & 0xFFu);
+                    int up = __builtin_amdgcn_update_dpp(0, rl, 0x138 /* wave_shr:1 */, 0xF, 0xF, true);
+                    // the first thread of a wavefront: the row above belongs to another wavefront, to
+                    // the round or band before, or is padding
+                    up = first_lane ? above : up;
+                    const int upleft = prev_up;
+                    prev_up = on ? up : prev_up;
+                    acc_r = mad_i24(p.w[0][2], rl, mad_i24(w_r1, up, mad_i24(w_r0, upleft, bias_r)));
+                }
+                if (i >= 1 && i <= kTallLag)
+                    acc_g = mad_i24(p.w[1][2], one.xr, mad_i24(w_g1, one.left_r, mad_i24(w_g0, gl, bias_g)));
+                if (i >= 2)
+                    acc_b = mad_i24(p.w[2][2], two.xg, mad_i24(w_b1, two.left_g, mad_i24(w_b0, bl, bias_b)));
+                if (i < kTallLag) {
+                    xr = add_byte_of<0>(now.e, clamp8(acc_r));
+                    now.left_r = rl;
+                    now.xr = xr;
+                    const uint32_t col = on ? (uint32_t)v : 0u;
+                    uint8_t *const to_next_wave = on && lane == 63u ? hand + wave * 64u + (col & 63u) : spare + 3;
+                    *to_next_wave = (uint8_t)xr;
+                    if (on && keeps_row) carry[col] = (uint8_t)xr;
+                    rl = on ? xr : rl;
+                }
+                if (i >= 1 && i <= kTallLag) {
+                    const int xg = add_byte_of<1>(one.e, clamp8(acc_g));
+                    one.left_g = gl;
+                    one.xg = xg;
+                    gl = one.on ? xg : gl;
+                }
+                if (i >= 2) {
+                    const int xb = add_byte_of<2>(two.e, clamp8(acc_b));
+                    bl = two.on ? xb : bl;
+                    two.q[0] = (uint8_t)two.xr;
+                    two.q[1] = (uint8_t)two.xg;
+                    two.q[2] = (uint8_t)xb;
+                }
+                two = one;
+                one = now;
+                if (i < kTallLag) {
+                    ++v;
+                    on = have && (uint32_t)v < w;
+                }
             }
         }
         __syncthreads();
