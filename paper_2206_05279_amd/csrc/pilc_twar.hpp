@@ -322,6 +322,9 @@ constexpr int kTallRing = 3 * kTallChunk;
 constexpr int kTallStride = kTallRing + 4;  // LDS bytes per thread: 37 dwords, odd
 constexpr int kTallMaxThreads = 768;
 constexpr int kTallLead = 32;        // steps a wavefront runs before its first pixel (two chunk turns)
+// a band's progress counter has a 128-byte line to itself (32 words): the band below polls it while
+// the band's own mover writes it
+constexpr uint32_t kBandStride = 32;
 
 struct TallBands {
     uint32_t bands, band_rows;
@@ -392,7 +395,7 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
         const bool fetches = mover && band != 0u && wave == 0u && lane < 3u;
         const uint4 *above_src = reinterpret_cast<const uint4 *>(
             img + ((size_t)image * h + (kBands && band != 0u ? band * tb.band_rows - 1u : 0u)) * row_bytes);
-        const uint32_t *above_progress = tb.progress + (id - (band != 0u ? 1u : 0u));
+        const uint32_t *above_progress = tb.progress + (size_t)(id - (band != 0u ? 1u : 0u)) * kBandStride;
         uint4 above_ahead = make_uint4(0u, 0u, 0u, 0u);
         uint32_t above_done = 0u;  // chunks of the row above known to be final
 
@@ -482,7 +485,8 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
                 if (c >= 1 && c <= chunks) {
                     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                     if (lane == pub_lane)
-                        __hip_atomic_store(tb.progress + id, (uint32_t)c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        __hip_atomic_store(tb.progress + (size_t)id * kBandStride, (uint32_t)c, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
 #pragma unroll
@@ -534,7 +538,7 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
                             __hip_atomic_store(tb.abort_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                             break;
                         }
-                        __builtin_amdgcn_s_sleep(2);
+                        __builtin_amdgcn_s_sleep(32);
                     }
                     if (!s_abort) above_ahead = above_src[3 * (T + 2) + (int)lane];
                 }
@@ -655,10 +659,11 @@ __global__ __launch_bounds__(kTallMaxThreads) void k_twar_inverse_tall(TwarK p, 
 
 // Progress counters of the band kernel: a few sets in device globals (the entry points take no
 // workspace), handed out under a lock so that concurrent calls do not share one; a call that finds
-// none free uses the workgroup-per-image kernel instead.  Layout of a set: [kBandFlags] progress,
-// then the ticket and the abort word.
+// none free uses the workgroup-per-image kernel instead.  Layout of a set: the progress counters of
+// up to 4096 bands, kBandStride words apart (2 MB for the four sets), then the ticket and the abort
+// word.
 constexpr int kBandSlots = 4;
-constexpr uint32_t kBandFlags = 4096;
+constexpr uint32_t kBandFlags = 4096 * kBandStride;
 static __device__ uint32_t g_band_flags[kBandSlots][kBandFlags + 2];
 static std::mutex g_band_mutex;
 static bool g_band_in_use[kBandSlots];
@@ -770,7 +775,7 @@ int pilc_twar_inverse(uint32_t n, uint32_t h, uint32_t w, const uint8_t *res_dev
     uint32_t bands = tall && n < 256u ? (h + 255u) / 256u : 1u;
     int slot = -1;
     uint32_t *flags = nullptr;
-    if (bands > 1u && (uint64_t)n * bands <= kBandFlags) flags = band_flags_acquire(&slot);
+    if (bands > 1u && (uint64_t)n * bands * kBandStride <= kBandFlags) flags = band_flags_acquire(&slot);
     if (tall && flags) {
         const uint32_t band_rows = (h + bands - 1) / bands;
         bands = (h + band_rows - 1) / band_rows;
@@ -784,7 +789,7 @@ int pilc_twar_inverse(uint32_t n, uint32_t h, uint32_t w, const uint8_t *res_dev
         rc = allow_large_lds(reinterpret_cast<const void *>(k_twar_inverse_tall<true>));
         uint32_t aborted = 0u;
         if (rc == PILC_OK) {
-            k_band_clear<<<(n * bands + 255u) / 256u, 256, 0, stream>>>(flags, n * bands);
+            k_band_clear<<<(n * bands * kBandStride + 255u) / 256u, 256, 0, stream>>>(flags, n * bands * kBandStride);
             const TallBands tb = {bands, band_rows, flags, flags + kBandFlags, flags + kBandFlags + 1,
                                   wait ? wait : 2000ull * (unsigned long long)khz,
                                   (uint32_t)g_one_pass_withhold.load(std::memory_order_relaxed)};
