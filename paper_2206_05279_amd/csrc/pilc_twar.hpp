@@ -771,7 +771,7 @@ int pilc_twar_inverse(uint32_t n, uint32_t h, uint32_t w, const uint8_t *res_dev
     const bool tall = h > 64 && w % 16 == 0 && w <= 16384 && ((((uintptr_t)img_dev) | ((uintptr_t)res_dev)) & 15) == 0;
     // few tall images: bands of up to 256 rows in workgroups of their own, four decoding wavefronts
     // (one per SIMD) and their four movers (on 30 frames of 1080 x 1920: five bands of 216 rows
-    // 0.58 ms, six of 180 0.61, three of 360 0.62, four of 270 0.63; one workgroup per frame 2.2)
+    // 0.49 ms, six of 180 0.50, three of 360 0.57; one workgroup per frame 2.2)
     uint32_t bands = tall && n < 256u ? (h + 255u) / 256u : 1u;
     int slot = -1;
     uint32_t *flags = nullptr;
